@@ -1,0 +1,17 @@
+"""CPU oracle for the dq8 codec -- test infrastructure, not the product.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this
+package.  It shares nothing with the HIP library.
+"""
+from .dq8_oracle import (  # noqa: F401
+    DYNAMIC_TREE,
+    LINEAR,
+    STATIC_TREE,
+    absmax,
+    build,
+    codebook,
+    decode,
+    decode_accumulate_avg,
+    encode,
+    set_threads,
+)

@@ -1,0 +1,145 @@
+"""numpy front end of the C oracle (dq8_oracle.c) -- test infrastructure, not the product.
+
+Argument marshalling only: every number comes out of the C file, which is built
+with ``gcc -O2 -fno-fast-math -ffp-contract=off`` so that each fp32 operation is
+rounded once and never fused.  The functions follow Sec. 3.1 (data types, absmax
+normalisation), Sec. 3.2 (compression / decompression) and Sec. 2.1 (averaging)
+of arXiv 1511.04561.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+DYNAMIC_TREE, LINEAR, STATIC_TREE = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dq8_oracle.c")
+_LIB = os.path.join(_HERE, "libdq8_oracle.so")
+_CFLAGS = ["-O2", "-fno-fast-math", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+           "-Wall", "-Wextra"]
+_lib = None
+
+
+def build(force=False):
+    """Compile dq8_oracle.c next to its source; returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc"] + _CFLAGS + ["-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c_sz, c_f, c_u8 = ctypes.c_size_t, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint8)
+        lib.dq8o_codebook.argtypes = [ctypes.c_int, c_f]
+        lib.dq8o_absmax.argtypes = [c_f, c_sz, c_sz, c_f]
+        lib.dq8o_encode.argtypes = [ctypes.c_int, c_f, c_sz, c_sz, c_f, c_u8, ctypes.c_int]
+        lib.dq8o_decode.argtypes = [ctypes.c_int, c_u8, c_f, c_sz, c_sz, c_f]
+        lib.dq8o_decode_accumulate_avg.argtypes = [ctypes.c_int, ctypes.POINTER(c_u8), ctypes.POINTER(c_f),
+                                                   ctypes.c_int, c_sz, c_sz, c_f]
+        lib.dq8o_set_threads.argtypes = [ctypes.c_int]
+        for f in (lib.dq8o_codebook, lib.dq8o_absmax, lib.dq8o_encode, lib.dq8o_decode,
+                  lib.dq8o_decode_accumulate_avg, lib.dq8o_set_threads, lib.dq8o_get_threads):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _fp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _bp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s failed with status %d" % (what, rc))
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError("expected float32, got %s" % a.dtype)
+    return a.reshape(-1)
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint8:
+        raise TypeError("expected uint8, got %s" % a.dtype)
+    return a.reshape(-1)
+
+
+def n_blocks(n, block):
+    if n == 0:
+        return 0
+    b = n if block == 0 else block
+    return (n + b - 1) // b
+
+
+def set_threads(t):
+    """Threads used for the block loop (timing only; results do not depend on it)."""
+    return _load().dq8o_set_threads(int(t))
+
+
+def codebook(kind):
+    cb = np.empty(256, dtype=np.float32)
+    _check(_load().dq8o_codebook(int(kind), _fp(cb)), "codebook")
+    return cb
+
+
+def absmax(x, block=0):
+    x = _f32(x)
+    scales = np.empty(n_blocks(x.size, block), dtype=np.float32)
+    _check(_load().dq8o_absmax(_fp(x), x.size, int(block), _fp(scales)), "absmax")
+    return scales
+
+
+def encode(kind, x, block=0, scales=None):
+    """Returns (codes uint8[n], scales float32[nb]).  scales given -> used as input."""
+    x = _f32(x)
+    given = scales is not None
+    if given:
+        scales = _f32(scales).copy()
+        if scales.size != n_blocks(x.size, block):
+            raise ValueError("scales has %d entries, want %d" % (scales.size, n_blocks(x.size, block)))
+    else:
+        scales = np.empty(n_blocks(x.size, block), dtype=np.float32)
+    codes = np.empty(x.size, dtype=np.uint8)
+    _check(_load().dq8o_encode(int(kind), _fp(x), x.size, int(block), _fp(scales), _bp(codes), int(given)),
+           "encode")
+    return codes, scales
+
+
+def decode(kind, codes, scales, block=0):
+    codes, scales = _u8(codes), _f32(scales)
+    if scales.size != n_blocks(codes.size, block):
+        raise ValueError("scales has %d entries, want %d" % (scales.size, n_blocks(codes.size, block)))
+    out = np.empty(codes.size, dtype=np.float32)
+    _check(_load().dq8o_decode(int(kind), _bp(codes), _fp(scales), codes.size, int(block), _fp(out)), "decode")
+    return out
+
+
+def decode_accumulate_avg(kind, codes_list, scales_list, block=0):
+    K = len(codes_list)
+    if K != len(scales_list):
+        raise ValueError("codes_list and scales_list differ in length")
+    codes_list = [_u8(c) for c in codes_list]
+    scales_list = [_f32(s) for s in scales_list]
+    n = codes_list[0].size if K else 0
+    for c, s in zip(codes_list, scales_list):
+        if c.size != n or s.size != n_blocks(n, block):
+            raise ValueError("worker buffers differ in size")
+    cp = (ctypes.POINTER(ctypes.c_uint8) * max(K, 1))(*[_bp(c) for c in codes_list])
+    sp = (ctypes.POINTER(ctypes.c_float) * max(K, 1))(*[_fp(s) for s in scales_list])
+    out = np.empty(n, dtype=np.float32)
+    _check(_load().dq8o_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), _fp(out)),
+           "decode_accumulate_avg")
+    return out

@@ -1,0 +1,315 @@
+"""Pins for the oracle's absmax / encode / decode / averaging (Sec. 3.1, 3.2, 2.1).
+
+None of these tests re-types the oracle's scan: they reach the expected result by a
+sorted-table search over exact midpoints, by exact rational arithmetic, by numpy's
+float32 primitives, by closed-form special cases and by error bounds.
+"""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1511_04561_amd import workloads
+from tests.exact import codebook_exact, nearest_code_exact, round_to_f32
+
+KINDS = [oracle.DYNAMIC_TREE, oracle.LINEAR, oracle.STATIC_TREE]
+ONE = np.ones(1, np.float32)
+
+
+def sorted_table_codes(kind, xn):
+    """Sec. 3.2: search of |xn| in the sorted table of the 128 positive values, sign kept apart.
+
+    Nearest value with ties to the lower one == number of midpoints strictly below |xn|.
+    Midpoints of neighbouring binary32 values are exact in float64.
+    """
+    cb = oracle.codebook(kind)[:128].astype(np.float64)
+    mid = (cb[:-1] + cb[1:]) / 2
+    assert np.all((cb[:-1] + cb[1:]) == 2 * mid)
+    idx = np.searchsorted(mid, np.abs(xn).astype(np.float64), side="left")
+    return (idx | (np.signbit(xn).astype(np.int64) << 7)).astype(np.uint8)
+
+
+def ulp_neighbourhood(values, radius):
+    bits = np.asarray(values, np.float32).view(np.int32).astype(np.int64)
+    out = (bits[:, None] + np.arange(-radius, radius + 1)[None, :]).reshape(-1)
+    out = out[(out >= 0) & (out < 0x7F800000)]
+    return out.astype(np.int32).view(np.float32)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_brute_force_equals_sorted_table_search(kind):
+    cb = oracle.codebook(kind)[:128]
+    mid32 = ((cb[:-1].astype(np.float64) + cb[1:].astype(np.float64)) / 2).astype(np.float32)
+    near_mid = ulp_neighbourhood(mid32, 64)
+    near_cb = ulp_neighbourhood(cb[cb > 0], 3)
+    coarse = (np.arange(0, 0x4000, dtype=np.int64) << 16).astype(np.int32).view(np.float32)  # 0 .. 2.0
+    rng = np.random.Generator(np.random.PCG64(11))
+    rnd = rng.integers(0, 0x3F800001, 300000).astype(np.int32).view(np.float32)
+    uni = rng.random(200000).astype(np.float32)
+    pos = np.concatenate([near_mid, near_cb, coarse, rnd, uni, np.array([0.0, 1.0, 1.5], np.float32)])
+    x = np.concatenate([pos, -pos])
+    codes, scales = oracle.encode(kind, x, 0, scales=ONE)
+    assert scales[0] == 1.0
+    want = sorted_table_codes(kind, x)
+    bad = np.nonzero(codes != want)[0]
+    assert bad.size == 0, (x[bad[:5]], codes[bad[:5]], want[bad[:5]])
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_sign_bit_follows_the_input(kind):
+    x = np.array([0.0, -0.0, 1e-30, -1e-30, 0.5, -0.5, 1.0, -1.0], np.float32)
+    codes, _ = oracle.encode(kind, x, 0, scales=ONE)
+    assert np.all((codes >> 7) == np.signbit(x))
+    assert np.all((codes[0::2] | 0x80) == codes[1::2])
+
+
+def test_linear_is_round_half_down_of_127_times_xn():
+    rng = np.random.Generator(np.random.PCG64(5))
+    x = np.concatenate([rng.random(20000), -rng.random(20000), [0.0, 1.0, -1.0]]).astype(np.float32)
+    codes, _ = oracle.encode(oracle.LINEAR, x, 0, scales=ONE)
+    checked = 0
+    for xi, c in zip(x, codes):
+        v = abs(Fraction(float(xi))) * 127
+        frac = v - int(v)
+        if abs(frac - Fraction(1, 2)) < Fraction(1, 10 ** 4):
+            continue  # the table holds fp32(j/127), not j/127: skip a sliver around the half points
+        k = int(v) + (1 if frac > Fraction(1, 2) else 0)
+        assert (c & 127) == k and (c >> 7) == int(np.signbit(xi))
+        checked += 1
+    assert checked > 39000
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_normalisation_is_one_binary32_division_by_the_block_absmax(kind):
+    for block, n in [(0, 3000), (256, 3000), (7, 100), (4096, 4096 * 2 + 5)]:
+        x = (workloads.edge_case_block("wide", n, seed=block)).astype(np.float32)
+        codes, scales = oracle.encode(kind, x, block)
+        B = n if block == 0 else block
+        nb = (n + B - 1) // B
+        want_s = np.array([np.max(np.abs(x[b * B:(b + 1) * B])) for b in range(nb)], np.float32)
+        assert scales.tobytes() == want_s.tobytes()
+        assert oracle.absmax(x, block).tobytes() == want_s.tobytes()
+        xn = (x / np.repeat(want_s, B)[:n]).astype(np.float32)  # numpy float32 divide: one IEEE rounding
+        assert np.max(np.abs(xn)) <= 1.0
+        assert np.array_equal(codes, sorted_table_codes(kind, xn))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("s", [1.0, 3.0, 1e-3, float(np.float32(1) - np.float32(2.0 ** -24)), 1e30, 1e-37])
+def test_encode_of_decode_is_the_identity_on_codes(kind, s):
+    codes = np.arange(256, dtype=np.uint8)
+    if kind == oracle.STATIC_TREE and s < 1e-29:
+        s = 1e-29  # keep the smallest magnitude (1.3e-8) times the scale a normal binary32 number
+    sc = np.array([s], np.float32)
+    vals = oracle.decode(kind, codes, sc, 0)
+    back, sc2 = oracle.encode(kind, vals, 0, scales=sc)
+    assert sc2.tobytes() == sc.tobytes()
+    assert np.array_equal(back, codes)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_decode_is_table_times_scale_in_binary32(kind):
+    rng = np.random.Generator(np.random.PCG64(3))
+    n, B = 10000, 128
+    codes = rng.integers(0, 256, n).astype(np.uint8)
+    scales = np.exp(rng.uniform(-30, 30, (n + B - 1) // B)).astype(np.float32)
+    out = oracle.decode(kind, codes, scales, B)
+    cb = oracle.codebook(kind)
+    want = cb[codes] * np.repeat(scales, B)[:n]  # numpy float32 multiply
+    assert want.dtype == np.float32 and out.tobytes() == want.tobytes()
+    # and against exact rationals on a sample
+    for i in range(0, n, 997):
+        w = round_to_f32(Fraction(float(cb[codes[i]])) * Fraction(float(scales[i // B])))
+        assert np.float32(w) == out[i]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_round_trip_error_is_at_most_half_the_local_gap_times_absmax(kind):
+    rng = np.random.Generator(np.random.PCG64(7))
+    n, B = 1 << 16, 4096
+    x = (rng.standard_t(3, n) * 1e-3).astype(np.float32)
+    codes, scales = oracle.encode(kind, x, B)
+    out = oracle.decode(kind, codes, scales, B)
+    cb = oracle.codebook(kind)[:128].astype(np.float64)
+    s = np.repeat(scales, B)[:n].astype(np.float64)
+    j = (codes & 127).astype(np.int64)
+    below = np.where(j > 0, cb[j] - cb[np.maximum(j - 1, 0)], 0.0)
+    above = np.where(j < 127, cb[np.minimum(j + 1, 127)] - cb[j], 1.0 - cb[127])
+    if kind == oracle.STATIC_TREE:  # no zero: values under the smallest magnitude are at most that far away
+        below = np.where(j == 0, 2 * cb[0], below)
+    half_gap = 0.5 * np.maximum(below, above)
+    half_gap = np.where(j == 127, np.maximum(half_gap, 1.0 - cb[127]), half_gap)
+    err = np.abs(out.astype(np.float64) - x.astype(np.float64))
+    slack = 3 * np.spacing(np.abs(x)).astype(np.float64) + 1e-45  # roundings of the divide and the multiply
+    assert np.all(err <= half_gap * s + slack)
+    assert np.all(np.signbit(out) == np.signbit(x))
+    assert np.all(np.abs(out) <= s)
+
+
+def test_tree_types_bound_inside_a_decade():
+    # inside decade n of the dynamic tree the error of the normalised value is at most 0.45 * 10^-n / 2^(6-n)
+    for n in range(7):
+        lo, hi = 0.1 * 10.0 ** -n, 10.0 ** -n
+        xn = np.linspace(lo, hi, 4001, dtype=np.float64)[1:-1].astype(np.float32)
+        codes, _ = oracle.encode(oracle.DYNAMIC_TREE, xn, 0, scales=ONE)
+        back = oracle.decode(oracle.DYNAMIC_TREE, codes, ONE, 0).astype(np.float64)
+        bound = 0.45 * 10.0 ** -n / 2 ** (6 - n)
+        assert np.max(np.abs(back - xn.astype(np.float64))) <= bound * (1 + 1e-5)  # fp32 rounding of the table
+
+
+def _exhaustive_values(kind):
+    cb = oracle.codebook(kind)
+    mids = [(float(cb[j]) + float(cb[j + 1])) / 2 for j in (0, 1, 63, 64, 100, 126)]
+    rep = [m for m in mids if float(np.float32(m)) == m]  # representable tie points
+    vals = [-1.0, -0.5, -0.0, 0.0, 0.5, 1.0, 3e-45, -1e-39, 0.3] + rep[:2] + [-r for r in rep[:1]]
+    return [np.float32(v) for v in vals]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_exhaustive_tiny_inputs_against_exact_rationals(kind):
+    vals = _exhaustive_values(kind)
+    cbf = oracle.codebook(kind)
+    # the exact table: tree walk, rounded to binary32
+    table = [Fraction(float(round_to_f32(v))) for v in codebook_exact(kind)]
+    assert [float(t) for t in table[:128]] == [float(v) for v in cbf[:128]]
+    signs = [0] * 128 + [1] * 128
+    cache = {}
+    for m in (1, 2, 3):
+        for vec in itertools.product(vals, repeat=m):
+            x = np.array(vec, np.float32)
+            for block in (1, 2, 3):
+                if block > m and block != 3:
+                    continue
+                codes, scales = oracle.encode(kind, x, block)
+                nb = (m + block - 1) // block
+                for b in range(nb):
+                    seg = x[b * block:(b + 1) * block]
+                    s = max(abs(Fraction(float(v))) for v in seg)
+                    assert Fraction(float(scales[b])) == s and not np.signbit(scales[b])
+                    for i, v in enumerate(seg):
+                        key = (float(v), bool(np.signbit(v)), s)
+                        if key not in cache:
+                            xn = Fraction(float(v)) if s == 0 else Fraction(float(round_to_f32(Fraction(float(v)) / s)))
+                            cache[key] = nearest_code_exact(table, signs, xn, int(np.signbit(v)))
+                        assert codes[b * block + i] == cache[key], (vec, block, b, i)
+
+
+def test_tie_midpoints_go_to_the_lower_magnitude():
+    for kind in KINDS:
+        cb = oracle.codebook(kind)
+        hit = 0
+        for j in range(127):
+            m = (float(cb[j]) + float(cb[j + 1])) / 2
+            if float(np.float32(m)) != m:
+                continue
+            hit += 1
+            x = np.array([m, -m, np.nextafter(np.float32(m), np.float32(2)), np.nextafter(np.float32(m), np.float32(0))],
+                         np.float32)
+            codes, _ = oracle.encode(kind, x, 0, scales=ONE)
+            assert list(codes) == [j, j | 128, j + 1, j]
+        assert hit > 0
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_zero_blocks_and_degenerate_scales(kind):
+    x = np.array([0.0, -0.0, 0.0, -0.0, 0.0], np.float32)
+    codes, scales = oracle.encode(kind, x, 2)
+    assert scales.tobytes() == np.zeros(3, np.float32).tobytes()
+    assert list(codes) == [0, 128, 0, 128, 0]  # code 0 = smallest magnitude of every type
+    out = oracle.decode(kind, codes, scales, 2)
+    assert np.all(out == 0) and list(np.signbit(out)) == [False, True, False, True, False]
+    # n == 0
+    c0, s0 = oracle.encode(kind, np.zeros(0, np.float32), 16)
+    assert c0.size == 0 and s0.size == 0
+
+
+def test_averaging_special_cases():
+    rng = np.random.Generator(np.random.PCG64(21))
+    n, B = 5000, 512
+    kind = oracle.DYNAMIC_TREE
+    codes = rng.integers(0, 256, n).astype(np.uint8)
+    scales = np.exp(rng.uniform(-8, 2, (n + B - 1) // B)).astype(np.float32)
+    dec = oracle.decode(kind, codes, scales, B)
+    one = oracle.decode_accumulate_avg(kind, [codes], [scales], B)
+    assert np.array_equal(one, dec) and not np.any(np.signbit(one[dec == 0]))  # K=1: decode, -0 -> +0
+    two = oracle.decode_accumulate_avg(kind, [codes, codes], [scales, scales], B)
+    assert np.array_equal(two, dec)  # (v + v) / 2 is exact
+    flipped = codes ^ np.uint8(0x80)
+    zero = oracle.decode_accumulate_avg(kind, [codes, flipped], [scales, scales], B)
+    assert zero.tobytes() == np.zeros(n, np.float32).tobytes()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("K", [1, 2, 3, 5, 8])
+def test_averaging_is_sequential_binary32_arithmetic(kind, K):
+    rng = np.random.Generator(np.random.PCG64(100 + K))
+    n, B = 4099, 256
+    nb = (n + B - 1) // B
+    cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+    sl = [np.exp(rng.uniform(-6, 6, nb)).astype(np.float32) for _ in range(K)]
+    got = oracle.decode_accumulate_avg(kind, cl, sl, B)
+    cb = oracle.codebook(kind)
+    acc = np.zeros(n, np.float32)
+    for k in range(K):  # numpy float32: the product and the sum are rounded one after the other
+        prod = cb[cl[k]] * np.repeat(sl[k], B)[:n]
+        acc = acc + prod
+    want = acc / np.float32(K)
+    assert want.dtype == np.float32 and got.tobytes() == want.tobytes()
+    for i in range(0, n, 811):  # exact rationals, rounding after every operation
+        a = Fraction(0)
+        for k in range(K):
+            p = Fraction(float(round_to_f32(Fraction(float(cb[cl[k][i]])) * Fraction(float(sl[k][i // B])))))
+            a = Fraction(float(round_to_f32(a + p)))
+        assert np.float32(round_to_f32(a / K)) == got[i]
+
+
+def test_averaging_order_is_worker_0_first():
+    # big, -big, small: only the order ((big + -big) + small) keeps the small term
+    kind = oracle.LINEAR  # cb[127] == 1, so the decoded value is the scale itself
+    c_pos, c_neg = np.array([127], np.uint8), np.array([255], np.uint8)
+    big, small = np.array([1e8], np.float32), np.array([1.0], np.float32)
+    out = oracle.decode_accumulate_avg(kind, [c_pos, c_neg, c_pos], [big, big, small], 0)
+    assert out[0] == np.float32(1.0) / np.float32(3.0)
+    out = oracle.decode_accumulate_avg(kind, [c_pos, c_pos, c_neg], [big, small, big], 0)
+    assert out[0] == 0.0  # 1e8 + 1 rounds back to 1e8 in binary32
+
+
+def test_relative_error_ordering_matches_table_2(golden_dir):
+    """Table 2: dynamic tree < linear < static tree in mean relative error; values in the paper's ballpark.
+
+    The paper's search was evidently not exactly nearest (its errors are about 1.3x ours), and its static
+    types used a decimal exponent offset instead of absmax, so only the ordering and a loose band are pinned.
+    """
+    paper = {}
+    for l in open(os.path.join(golden_dir, "table2_mre.txt")):
+        if l.strip() and l[0] != "#":
+            dist, typ, v = l.split()
+            paper[(dist, typ)] = float(v)
+    rng = np.random.Generator(np.random.PCG64(2))
+    n = 1 << 20
+    data = {"U(0,1)": rng.random(n).astype(np.float32), "N(0,1)": rng.standard_normal(n).astype(np.float32)}
+    names = {oracle.DYNAMIC_TREE: "dynamic_tree", oracle.LINEAR: "linear", oracle.STATIC_TREE: "static_tree"}
+    for dist, x in data.items():
+        x = x[x != 0]
+        mre = {}
+        for kind in KINDS:
+            codes, scales = oracle.encode(kind, x, 0)
+            out = oracle.decode(kind, codes, scales, 0).astype(np.float64)
+            mre[kind] = 100 * np.mean(np.abs(out - x) / np.abs(x))
+        assert mre[oracle.DYNAMIC_TREE] < mre[oracle.LINEAR] < mre[oracle.STATIC_TREE], (dist, mre)
+        for kind in KINDS:
+            ratio = mre[kind] / paper[(dist, names[kind])]
+            assert 0.55 < ratio < 1.05, (dist, names[kind], mre[kind], ratio)
+
+
+def test_results_do_not_depend_on_thread_count():
+    x = workloads.tensor(3, 2, limit=50000)
+    oracle.set_threads(1)
+    a = oracle.encode(oracle.DYNAMIC_TREE, x, 4096)
+    oracle.set_threads(4)
+    b = oracle.encode(oracle.DYNAMIC_TREE, x, 4096)
+    oracle.set_threads(1)
+    assert np.array_equal(a[0], b[0]) and a[1].tobytes() == b[1].tobytes()
