@@ -1,0 +1,131 @@
+/*
+ * dq8 -- 8-bit approximation codec for fp32 gradients and activations on AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "8-Bit Approximations for Parallelism in Deep Learning"
+ * (arXiv 1511.04561): fp32 values are normalised by the absolute maximum of their block,
+ * replaced by the nearest entry of a 256-entry table (one sign bit + 128 sorted magnitudes)
+ * and sent as one byte each; the receiver looks the byte up and multiplies by the maximum.
+ *
+ * Conventions shared by every call
+ *   - All `x`, `codes`, `scales`, `out` pointers are DEVICE pointers owned by the caller,
+ *     unless a parameter is explicitly marked host.  The library allocates no memory the
+ *     caller sees and keeps only small immutable per-device tables.
+ *   - `n` is the number of elements.  `block` is the number of consecutive elements that
+ *     share one scale: block == 0 means one scale for the whole array (the paper's
+ *     per-matrix maximum); a row-major matrix gets one scale per row with block == row
+ *     length.  nb = ceil(n / block) scales are read or written; the last block may be short.
+ *   - `hip_stream` is a hipStream_t passed as void*; NULL is the default stream.  Work is
+ *     enqueued on that stream and the call returns without waiting for it.  The first call
+ *     for a given device and kind uploads that kind's tables with a blocking copy; call
+ *     dq8_init() beforehand where that must not happen (e.g. before stream capture).
+ *   - Every function returns DQ8_OK or an error code and never throws or aborts.  After an
+ *     error dq8_last_error() describes it.  n == 0 is DQ8_OK and launches nothing.
+ *   - Inputs must be finite.  With DQ8_SCALES_GIVEN the quotient x / scale must be finite.
+ *   - Any pointer alignment and any n / block are accepted.  The fast kernels need
+ *     16-byte aligned `x` / `out`, 4-byte aligned `codes`, and block % 4 == 0 (or a single
+ *     block); anything else runs on slower kernels with the same results.
+ *   - Results are deterministic and independent of launch configuration: codes and scales
+ *     are exact functions of the input, and the average adds workers in index order.
+ *
+ * Code layout: bit 7 of a code is the sign, bits 6..0 index the 128 magnitudes in
+ * ascending order.  This is this library's own layout; the paper's figure of the bit
+ * fields is not reproduced and no wire compatibility with other implementations is claimed.
+ */
+#ifndef DQ8_H
+#define DQ8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    DQ8_OK = 0,
+    DQ8_ERR_NULL = 1,   /* a required pointer is NULL */
+    DQ8_ERR_KIND = 2,   /* unknown data type */
+    DQ8_ERR_ARG = 3,    /* bad K, overlapping buffers, size overflow */
+    DQ8_ERR_DEVICE = 4  /* a HIP call failed; text in dq8_last_error() */
+};
+
+/* The 8-bit data types of Sec. 3.1. */
+enum {
+    DQ8_DYNAMIC_TREE = 0, /* dynamic exponent + bisection tree over (0.1, 1) */
+    DQ8_LINEAR = 1,       /* linear quantisation, magnitudes j / 127 */
+    DQ8_STATIC_TREE = 2   /* 3-bit static exponent + 4-bit bisection tree */
+};
+
+/* dq8_encode flag: `scales` is an input computed elsewhere (e.g. by dq8_absmax). */
+#define DQ8_SCALES_GIVEN 1u
+
+/* Largest number of worker buffers dq8_decode_accumulate_avg accepts. */
+#define DQ8_MAX_K 32
+
+/*
+ * The table of a data type (Sec. 3.1): cb256_host[c] is the value code c stands for when the
+ * scale is 1.  HOST pointer to 256 floats, written by the call.  Entries 0..127 are the
+ * magnitudes in ascending order, entry c + 128 is the negation of entry c (so entry 128 is
+ * -0.0f where entry 0 is 0).  Pure host computation, needs no device.
+ *   dynamic tree: entry 0 is 0; an entry whose 7-bit index has n leading zeros, then a one,
+ *     then t = 6 - n bits read as k, is (0.1 + 0.9 (k + 1/2) / 2^t) * 10^-n;
+ *   linear: j / 127;
+ *   static tree: index = 16 E + k, value (0.1 + 0.9 (k + 1/2) / 16) * 10^(E - 7).
+ * Each entry is the exact ratio rounded once to binary32.
+ */
+int dq8_codebook(int kind, float *cb256_host);
+
+/*
+ * Uploads the tables of every data type to the current device (blocking).  Optional: the
+ * other calls do it on first use.  Safe to call repeatedly and from several threads.
+ */
+int dq8_init(void);
+
+/*
+ * Block-wise absolute maximum (Sec. 3.1, last paragraph: a matrix is normalised by its
+ * absolute maximum).  scales[b] = max |x[i]| over block b, exact, +0 for an all-zero block.
+ * x: n floats (read).  scales: nb floats (written).
+ */
+int dq8_absmax(const float *x, size_t n, size_t block, float *scales, void *hip_stream);
+
+/*
+ * Compression (Sec. 3.1 last paragraph, Sec. 3.2 first paragraph).  For every element of
+ * block b: xn = x[i] / scales[b] rounded once to binary32 (not divided when the scale is 0),
+ * then codes[i] = the code whose table value is nearest to xn in real arithmetic; a value
+ * exactly half way between two magnitudes takes the smaller one; bit 7 is the sign bit of xn.
+ * x: n floats (read).  codes: n bytes (written).  scales: nb floats, written with the block
+ * maxima unless flags has DQ8_SCALES_GIVEN, in which case they are read.
+ * `codes` and `scales` must not overlap `x`.
+ */
+int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
+               unsigned flags, void *hip_stream);
+
+/*
+ * Decompression (Sec. 3.2 third paragraph, Sec. 3.1 last paragraph):
+ * out[i] = table[codes[i]] * scales[b], one binary32 multiplication.
+ * codes: n bytes (read).  scales: nb floats (read).  out: n floats (written), must not
+ * overlap the inputs.
+ */
+int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, size_t block,
+               float *out, void *hip_stream);
+
+/*
+ * Decompress K workers' buffers and average them (Sec. 2.1: data parallelism averages the
+ * exchanged gradients) in one pass:
+ *   acc = +0;  for k = 0 .. K-1 in this order: acc = acc + table[codes[k][i]] * scales[k][b];
+ *   out[i] = acc / K
+ * with the product, each sum and the quotient rounded to binary32 separately (no fused
+ * multiply-add).  `codes` and `scales` are HOST arrays of K device pointers, read before the
+ * call returns; buffer k holds n bytes / nb floats.  1 <= K <= DQ8_MAX_K.
+ * out: n floats (written), must not overlap any input.
+ */
+int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float *const *scales,
+                              int K, size_t n, size_t block, float *out, void *hip_stream);
+
+/* Text of the calling thread's most recent error ("" if none).  Static storage, never NULL. */
+const char *dq8_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DQ8_H */

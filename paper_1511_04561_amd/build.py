@@ -1,0 +1,58 @@
+"""Builds libdq8.so (HIP kernels + C ABI) for gfx950 next to this file.
+
+hipcc cross-compiles without a GPU.  Flags that matter for the results:
+  -ffp-contract=off   the decode-and-average sum rounds product and sum separately;
+  no fast-math        divisions are the correctly rounded ones;
+  -packed-fp32-ops off (target feature) as required for the test machines.
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libdq8.so")
+SOURCES = ["dq8.hip", "dq8_tables.cpp"]
+HEADERS = ["dq8_internal.h", "dq8_tables.hpp", os.path.join(ROOT, "include", "dq8.h")]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unknown-cuda-version"]
+
+
+def hipcc():
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
+            return cand
+    return "hipcc"
+
+
+def command(out=LIB, extra=()):
+    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    return [hipcc()] + FLAGS + list(extra) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", out] + srcs
+
+
+def stale():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, s) for s in SOURCES] + [h if os.path.isabs(h) else os.path.join(CSRC, h) for h in HEADERS]
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force=True, verbose=False, extra=()):
+    """Compiles the library; with force=False only when it is missing or older than a source."""
+    if not force and not stale():
+        return LIB
+    tmp = LIB + ".tmp%d" % os.getpid()
+    cmd = command(tmp, extra)
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(force=True, verbose=True, extra=sys.argv[1:])
+    print(LIB)

@@ -1,0 +1,139 @@
+// Host-side table construction for the dq8 kernels (see dq8_tables.hpp).
+#include "dq8_tables.hpp"
+
+#include <cmath>
+#include <cstring>
+
+namespace dq8 {
+namespace {
+
+uint32_t f2u(float f)
+{
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    return u;
+}
+
+float u2f(uint32_t u)
+{
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// num / den rounded once to binary32 (nearest, ties to even), in integer arithmetic.
+// Requires 0 <= num / den <= 1 and a result that is zero or a normal number.
+float ratio_to_f32(uint64_t num, uint64_t den)
+{
+    if (num == 0) return 0.0f;
+    // scale so that q = floor(num * 2^sh / den) has exactly 25 significant bits
+    int sh = 0;
+    unsigned __int128 n = num;
+    while (n / den < ((unsigned __int128)1 << 24)) {
+        n <<= 1;
+        ++sh;
+    }
+    unsigned __int128 q = n / den, r = n % den;
+    uint32_t m = (uint32_t)(q >> 1);  // 24-bit significand candidate
+    bool half = (q & 1) != 0, sticky = r != 0;
+    if (half && (sticky || (m & 1))) ++m;
+    // value = m * 2^-(sh-1); m == 2^24 after a carry is still exact in ldexp
+    return std::ldexp((float)m, -(sh - 1));
+}
+
+uint64_t pow10u(int e)
+{
+    uint64_t p = 1;
+    while (e-- > 0) p *= 10;
+    return p;
+}
+
+// Magnitude j of each data type of Sec. 3.1 as an exact ratio num / den.
+bool magnitude_ratio(int kind, int j, uint64_t *num, uint64_t *den)
+{
+    if (kind == 0) {  // dynamic tree: [n zeros][1][t tree bits]
+        if (j == 0) {
+            *num = 0;
+            *den = 1;
+            return true;
+        }
+        int flag = 6;  // bit position of the flag inside the 7-bit field
+        while (!((j >> flag) & 1)) --flag;
+        int t = flag, n = 6 - flag;
+        uint64_t leaf = (uint64_t)j & ((1u << t) - 1);  // path through the bisection tree
+        // middle of leaf `leaf` of 2^t equal pieces of (0.1, 1):  1/10 + 9/10 * (2 leaf + 1) / 2^(t+1)
+        *num = (1ull << (t + 1)) + 9 * (2 * leaf + 1);
+        *den = (1ull << (t + 1)) * 10 * pow10u(n);
+        return true;
+    }
+    if (kind == 1) {  // linear quantisation on [0, 1]
+        *num = (uint64_t)j;
+        *den = 127;
+        return true;
+    }
+    if (kind == 2) {  // static tree: 3 exponent bits, 4 tree bits; decade 10^(E-7)
+        int E = j >> 4;
+        uint64_t leaf = (uint64_t)(j & 15);
+        *num = 32 + 9 * (2 * leaf + 1);
+        *den = 32ull * 10 * pow10u(7 - E);
+        return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+int build_tables(int kind, Tables *t)
+{
+    for (int j = 0; j < 128; ++j) {
+        uint64_t num, den;
+        if (!magnitude_ratio(kind, j, &num, &den)) return 2;
+        t->cb[j] = ratio_to_f32(num, den);
+        t->cb[j + 128] = u2f(f2u(t->cb[j]) | 0x80000000u);
+    }
+    for (int j = 0; j < 127; ++j) {
+        if (!(t->cb[j] < t->cb[j + 1])) return 5;
+        // the midpoint of two nearby binary32 numbers is exact in binary64
+        double mid = ((double)t->cb[j] + (double)t->cb[j + 1]) * 0.5;
+        float f = (float)mid;
+        if ((double)f <= mid) f = std::nextafterf(f, 2.0f);
+        t->thr[j] = f;  // smallest binary32 strictly above the midpoint
+        if (j > 0 && !(t->thr[j - 1] < f)) return 5;
+    }
+    const uint32_t hi_key = f2u(1.0f) >> 16;  // every threshold is below 1
+    if (!(t->thr[126] < 1.0f)) return 5;
+    uint32_t lo_key = (f2u(t->thr[0]) >> 16);
+    if (lo_key == 0) return 5;
+    lo_key -= 1;  // one bucket that lies entirely below the first threshold
+    uint32_t nb = hi_key - lo_key + 1;
+    if (nb > (uint32_t)(kTableWords - kBucketOff)) return 5;
+    t->lo_key = lo_key;
+    t->n_bucket = nb;
+    int j = 0;  // next threshold not yet passed
+    for (uint32_t key = lo_key; key <= hi_key; ++key) {
+        uint32_t first = key << 16, last = first | 0xFFFFu;
+        uint32_t base = (uint32_t)j, tlow = 0x10000u;
+        int inside = 0;
+        while (j < 127 && f2u(t->thr[j]) <= last) {
+            if (f2u(t->thr[j]) < first) return 5;  // cannot happen: thresholds ascend
+            tlow = f2u(t->thr[j]) & 0xFFFFu;
+            ++inside;
+            ++j;
+        }
+        if (inside > 1) return 5;  // two thresholds in one bucket: scheme not applicable
+        t->bucket[key - lo_key] = (base << 16) + (0x10000u - tlow);
+    }
+    if (j != 127) return 5;
+    return 0;
+}
+
+void pack_tables(const Tables &t, uint32_t *words)
+{
+    std::memset(words, 0, sizeof(uint32_t) * kTableWords);
+    for (int c = 0; c < 256; ++c) words[kCbOff + c] = f2u(t.cb[c]);
+    words[kLoKeyOff] = t.lo_key;
+    words[kNBucketOff] = t.n_bucket;
+    for (uint32_t i = 0; i < t.n_bucket; ++i) words[kBucketOff + i] = t.bucket[i];
+}
+
+}  // namespace dq8

@@ -1,0 +1,156 @@
+"""Python binding of the dq8 C ABI (include/dq8.h): argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory) and enqueues the library's
+HIP kernels on torch's current stream.  Nothing is computed here and there is no
+fallback: if libdq8.so is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+DYNAMIC_TREE, LINEAR, STATIC_TREE = 0, 1, 2
+SCALES_GIVEN = 1
+MAX_K = 32
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdq8.so")
+_lib = None
+
+
+class Dq8Error(RuntimeError):
+    pass
+
+
+def lib():
+    """The loaded shared library (loaded on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise Dq8Error("%s not found: build it with `python -m paper_1511_04561_amd.build` "
+                           "(there is no fallback path)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.dq8_codebook.argtypes = [ci, vp]
+        L.dq8_init.argtypes = []
+        L.dq8_absmax.argtypes = [vp, sz, sz, vp, vp]
+        L.dq8_encode.argtypes = [ci, vp, sz, sz, vp, vp, ctypes.c_uint, vp]
+        L.dq8_decode.argtypes = [ci, vp, vp, sz, sz, vp, vp]
+        L.dq8_decode_accumulate_avg.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, sz, sz, vp, vp]
+        for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg):
+            f.restype = ci
+        L.dq8_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise Dq8Error("%s failed (status %d): %s" % (what, rc, lib().dq8_last_error().decode()))
+
+
+def n_blocks(n, block):
+    if n == 0:
+        return 0
+    b = n if (block == 0 or block > n) else block
+    return (n + b - 1) // b
+
+
+def _dev(t, dtype, what):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA tensor" % what)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (what, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % what)
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def codebook(kind):
+    """The 256 table values of a data type as a CPU float32 tensor."""
+    cb = torch.empty(256, dtype=torch.float32)
+    _check(lib().dq8_codebook(int(kind), cb.data_ptr()), "dq8_codebook")
+    return cb
+
+
+def init():
+    _check(lib().dq8_init(), "dq8_init")
+
+
+def absmax(x, block=0, scales=None):
+    x = _dev(x, torch.float32, "x")
+    n = x.numel()
+    if scales is None:
+        scales = torch.empty(n_blocks(n, block), dtype=torch.float32, device=x.device)
+    _dev(scales, torch.float32, "scales")
+    if scales.numel() < n_blocks(n, block):
+        raise ValueError("scales too small")
+    with torch.cuda.device(x.device):
+        _check(lib().dq8_absmax(x.data_ptr(), n, int(block), scales.data_ptr(), _stream()), "dq8_absmax")
+    return scales
+
+
+def encode(kind, x, block=0, scales=None, codes=None, scales_given=False):
+    """Returns (codes, scales).  With scales_given the passed scales are used as they are."""
+    x = _dev(x, torch.float32, "x")
+    n = x.numel()
+    if scales is None:
+        if scales_given:
+            raise ValueError("scales_given needs scales")
+        scales = torch.empty(n_blocks(n, block), dtype=torch.float32, device=x.device)
+    if codes is None:
+        codes = torch.empty(n, dtype=torch.uint8, device=x.device)
+    _dev(scales, torch.float32, "scales")
+    _dev(codes, torch.uint8, "codes")
+    if scales.numel() < n_blocks(n, block) or codes.numel() < n:
+        raise ValueError("output buffers too small")
+    with torch.cuda.device(x.device):
+        _check(lib().dq8_encode(int(kind), x.data_ptr(), n, int(block), scales.data_ptr(), codes.data_ptr(),
+                                SCALES_GIVEN if scales_given else 0, _stream()), "dq8_encode")
+    return codes, scales
+
+
+def decode(kind, codes, scales, block=0, out=None):
+    codes = _dev(codes, torch.uint8, "codes")
+    scales = _dev(scales, torch.float32, "scales")
+    n = codes.numel()
+    if scales.numel() < n_blocks(n, block):
+        raise ValueError("scales too small")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "out")
+    if out.numel() < n:
+        raise ValueError("out too small")
+    with torch.cuda.device(codes.device):
+        _check(lib().dq8_decode(int(kind), codes.data_ptr(), scales.data_ptr(), n, int(block), out.data_ptr(),
+                                _stream()), "dq8_decode")
+    return out
+
+
+def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None):
+    K = len(codes_list)
+    if K != len(scales_list):
+        raise ValueError("codes_list and scales_list differ in length")
+    if K == 0:
+        raise ValueError("need at least one worker buffer")
+    n = codes_list[0].numel()
+    for c, s in zip(codes_list, scales_list):
+        _dev(c, torch.uint8, "codes")
+        _dev(s, torch.float32, "scales")
+        if c.numel() != n or s.numel() < n_blocks(n, block):
+            raise ValueError("worker buffers differ in size")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes_list[0].device)
+    _dev(out, torch.float32, "out")
+    if out.numel() < n:
+        raise ValueError("out too small")
+    cp = (ctypes.c_void_p * K)(*[c.data_ptr() for c in codes_list])
+    sp = (ctypes.c_void_p * K)(*[s.data_ptr() for s in scales_list])
+    with torch.cuda.device(out.device):
+        _check(lib().dq8_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), out.data_ptr(), _stream()),
+               "dq8_decode_accumulate_avg")
+    return out

@@ -1,0 +1,109 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration the benchmark times.
+
+C3: the 61 100 840-element AlexNet-shaped gradient bucket, block 4096, dynamic tree: every
+code, scale and decoded value is compared with the oracle.
+C5: eight workers' buckets -> encode, fused decode-and-average, re-encode.  The oracle checks
+a sample of blocks end to end (its own encode of each worker's block, its own average of
+those codes, its own re-encode of that average); oracle inputs are the seeded tensors and
+the oracle's own outputs only.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1511_04561_amd import workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+B = workloads.C3_BLOCK
+KIND = oracle.DYNAMIC_TREE
+
+
+@pytest.fixture(scope="module")
+def dq8():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (select them with -m gpu on a GPU box)")
+    from paper_1511_04561_amd import dq8 as mod
+    mod.lib()
+    mod.init()
+    oracle.set_threads(16)
+    return mod
+
+
+def bits_equal(got, want, what):
+    got = got.cpu().numpy()
+    if got.tobytes() != want.tobytes():
+        g = got.view(np.uint8 if got.dtype == np.uint8 else np.uint32)
+        w = want.view(np.uint8 if want.dtype == np.uint8 else np.uint32)
+        bad = np.nonzero(g != w)[0]
+        raise AssertionError("%s: %d of %d differ, first at %d (%r vs %r)" % (what, bad.size, g.size, bad[0],
+                                                                             got[bad[0]], want[bad[0]]))
+
+
+def test_config3_full_bucket(dq8):
+    print("C3: generating bucket", flush=True)
+    x = workloads.bucket(3)
+    assert x.size == workloads.C3_NUMEL
+    xd = torch.from_numpy(x).cuda()
+    print("C3: gpu encode/decode", flush=True)
+    codes, scales = dq8.encode(KIND, xd, B)
+    amax = dq8.absmax(xd, B)
+    out = dq8.decode(KIND, codes, scales, B)
+    torch.cuda.synchronize()
+    print("C3: oracle encode (brute force over 61.1M elements)", flush=True)
+    want_codes, want_scales = oracle.encode(KIND, x, B)
+    bits_equal(scales, want_scales, "C3 scales")
+    bits_equal(amax, want_scales, "C3 absmax")
+    bits_equal(codes, want_codes, "C3 codes")
+    want_out = oracle.decode(KIND, want_codes, want_scales, B)
+    # the decoder is fed the oracle's codes
+    out2 = dq8.decode(KIND, torch.from_numpy(want_codes).cuda(), torch.from_numpy(want_scales).cuda(), B)
+    bits_equal(out2, want_out, "C3 decode")
+    bits_equal(out, want_out, "C3 decode of gpu codes")
+    # properties that hold at any size
+    err = np.abs(want_out.astype(np.float64) - x)
+    s = np.repeat(want_scales, B)[:x.size].astype(np.float64)
+    assert np.all(err <= 0.5 * 0.9 / 64 * s * 1.0001 + 1e-30)  # never worse than half the widest leaf (top decade)
+
+
+def test_config5_aggregation_pipeline(dq8):
+    K = workloads.C5_WORKERS
+    n = workloads.C3_NUMEL
+    nb = (n + B - 1) // B
+    rng = np.random.Generator(np.random.PCG64(workloads.BASE_SEED + 5))
+    sample = np.unique(np.concatenate([rng.integers(0, nb, 160), [0, 1, nb - 2, nb - 1]]))
+    codes_d, scales_d, xs = [], [], []
+    for w in range(K):
+        print("C5: worker %d generate + gpu encode" % w, flush=True)
+        x = workloads.bucket(5, worker=w)
+        c, s = dq8.encode(KIND, torch.from_numpy(x).cuda(), B)
+        codes_d.append(c)
+        scales_d.append(s)
+        xs.append([x[b * B:(b + 1) * B].copy() for b in sample])
+        del x
+    print("C5: gpu decode_accumulate_avg + re-encode", flush=True)
+    mean = dq8.decode_accumulate_avg(KIND, codes_d, scales_d, B)
+    rcodes, rscales = dq8.encode(KIND, mean, B)
+    torch.cuda.synchronize()
+    print("C5: oracle on %d sampled blocks" % sample.size, flush=True)
+    mean_h, rcodes_h, rscales_h = mean.cpu().numpy(), rcodes.cpu().numpy(), rscales.cpu().numpy()
+    codes_h = [c.cpu().numpy() for c in codes_d]
+    scales_h = [s.cpu().numpy() for s in scales_d]
+    for i, b in enumerate(sample):
+        lo, hi = b * B, min((b + 1) * B, n)
+        oc, os_ = [], []
+        for w in range(K):
+            c, s = oracle.encode(KIND, xs[w][i], B)
+            assert codes_h[w][lo:hi].tobytes() == c.tobytes(), ("codes", w, b)
+            assert scales_h[w][b:b + 1].tobytes() == s.tobytes(), ("scales", w, b)
+            oc.append(c)
+            os_.append(s)
+        m = oracle.decode_accumulate_avg(KIND, oc, os_, B)
+        assert mean_h[lo:hi].tobytes() == m.tobytes(), ("mean", b)
+        rc, rs = oracle.encode(KIND, m, B)
+        assert rcodes_h[lo:hi].tobytes() == rc.tobytes() and rscales_h[b:b + 1].tobytes() == rs.tobytes(), ("re-encode", b)
+    # whole-array properties: the mean never exceeds the mean of the scales, signs of re-encoded codes follow it
+    bound = np.repeat(np.mean(np.stack(scales_h).astype(np.float64), axis=0), B)[:n]
+    assert np.all(np.abs(mean_h) <= bound * (1 + 1e-6))
+    assert np.array_equal((rcodes_h >> 7).astype(bool), np.signbit(mean_h))

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+
+Codes and scales are compared byte for byte; decoded and averaged fp32 values are compared
+as raw bit patterns (0 ulp, -0 differs from +0).  Every input comes from the seeded
+generators or from the oracle's own outputs, never from the HIP path.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1511_04561_amd import workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+KINDS = [0, 1, 2]
+NAMES = {0: "dynamic_tree", 1: "linear", 2: "static_tree"}
+
+
+@pytest.fixture(scope="module")
+def dq8():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (select them with -m gpu on a GPU box)")
+    from paper_1511_04561_amd import dq8 as mod
+    mod.lib()  # a missing library is an error, not a skip
+    mod.init()
+    oracle.set_threads(16)
+    return mod
+
+
+def dev(a, offset=0):
+    """Device copy of a numpy array whose first element sits `offset` elements past an aligned address."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if offset == 0:
+        return t.cuda()
+    buf = torch.empty(t.numel() + offset, dtype=t.dtype, device="cuda")
+    view = buf[offset:]
+    view.copy_(t)
+    assert view.data_ptr() == buf.data_ptr() + offset * t.element_size()
+    return view
+
+
+def same_bits(got, want, what):
+    got = got.cpu().numpy() if hasattr(got, "cpu") else got
+    assert got.dtype == want.dtype and got.shape == want.shape, (what, got.dtype, got.shape, want.shape)
+    if got.tobytes() != want.tobytes():
+        gi, wi = got.view(np.uint8 if got.dtype == np.uint8 else np.uint32), want.view(
+            np.uint8 if want.dtype == np.uint8 else np.uint32)
+        bad = np.nonzero(gi != wi)[0]
+        raise AssertionError("%s: %d of %d differ, first at %d: got %r want %r" % (
+            what, bad.size, got.size, bad[0], got[bad[0]], want[bad[0]]))
+
+
+def check_encode_decode(dq8, kind, x, block, x_off=0, c_off=0, tag=""):
+    print("case %s kind=%d n=%d block=%d x_off=%d c_off=%d" % (tag, kind, x.size, block, x_off, c_off), flush=True)
+    want_codes, want_scales = oracle.encode(kind, x, block)
+    want_out = oracle.decode(kind, want_codes, want_scales, block)
+    xd = dev(x, x_off)
+    codes_buf = torch.empty(x.size + c_off, dtype=torch.uint8, device="cuda")
+    codes, scales = dq8.encode(kind, xd, block, codes=codes_buf[c_off:])
+    same_bits(scales, want_scales, "scales " + tag)
+    same_bits(codes, want_codes, "codes " + tag)
+    same_bits(dq8.absmax(xd, block), want_scales, "absmax " + tag)
+    # encode with the scales handed in goes through the non-fused kernel
+    codes2, _ = dq8.encode(kind, xd, block, scales=dev(want_scales), scales_given=True)
+    same_bits(codes2, want_codes, "codes(scales given) " + tag)
+    # decode takes the oracle's codes as input
+    out_buf = torch.empty(x.size + x_off, dtype=torch.float32, device="cuda")
+    out = dq8.decode(kind, dev(want_codes, c_off), dev(want_scales), block, out=out_buf[x_off:])
+    same_bits(out, want_out, "decode " + tag)
+
+
+SHAPES = [  # (n, block)
+    (3 * 4096 + 808, 4096),   # whole units and a ragged last block
+    (4096, 4096), (4095, 4096), (4097, 4096), (1, 0), (3, 0), (5, 2), (63, 64), (65, 64),
+    (100003, 0),              # one scale for the array, many units, tail not a multiple of 4
+    (50 * 1000, 1000),        # rows shorter than a unit
+    (7 * 6000 + 17, 6000),    # blocks of one full unit plus a partial one
+    (5 * 8192 + 100, 8192),   # two units per block
+    (1000, 7), (257, 1),      # tiny blocks
+    (20000, 10 ** 9),         # block larger than the array
+]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_shapes_blocks_and_tails(dq8, kind):
+    for i, (n, block) in enumerate(SHAPES):
+        x = workloads.edge_case_block("wide", n, seed=1000 * kind + i)
+        check_encode_decode(dq8, kind, x, block, tag="shape%d" % i)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_misaligned_pointers(dq8, kind):
+    n = 2 * 4096 + 100
+    x = workloads.edge_case_block("wide", n, seed=50 + kind)
+    for x_off, c_off in [(1, 0), (0, 1), (3, 2), (2, 3)]:
+        check_encode_decode(dq8, kind, x, 4096, x_off=x_off, c_off=c_off, tag="misaligned")
+        check_encode_decode(dq8, kind, x, 0, x_off=x_off, c_off=c_off, tag="misaligned-pertensor")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_degenerate_blocks(dq8, kind):
+    B = 4096
+    parts = [workloads.edge_case_block(c, B, seed=kind) for c in
+             ("zeros", "neg_zeros", "denormal_absmax", "single_nonzero", "huge", "tiny", "wide")]
+    parts.append(np.array([0.0, -0.0, 1e-45, -1e-45], np.float32))
+    x = np.concatenate(parts)
+    check_encode_decode(dq8, kind, x, B, tag="degenerate")
+    check_encode_decode(dq8, kind, x, 0, tag="degenerate-pertensor")
+    check_encode_decode(dq8, kind, x, 64, tag="degenerate-64")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_values_on_and_next_to_every_decision_point(dq8, kind):
+    cb = oracle.codebook(kind)[:128]
+    mid = ((cb[:-1].astype(np.float64) + cb[1:]) / 2).astype(np.float32).view(np.int32).astype(np.int64)
+    near = (mid[:, None] + np.arange(-3, 4)[None, :]).reshape(-1).astype(np.int32).view(np.float32)
+    pos = np.concatenate([near, cb, np.array([1.0], np.float32)])
+    for scale in (1.0, 0.37, 3e-3, 1e20):
+        x = np.concatenate([pos, -pos]) * np.float32(scale)
+        x = np.concatenate([x, np.array([scale], np.float32)]).astype(np.float32)  # pins the absmax to `scale`
+        check_encode_decode(dq8, kind, x, 0, tag="decision-points s=%g" % scale)
+
+
+def test_all_codes_decode_and_reencode(dq8):
+    for kind in KINDS:
+        codes = np.arange(256, dtype=np.uint8)
+        for s in (1.0, 3.0, 1e-3, 1e30):
+            sc = np.array([s], np.float32)
+            want = oracle.decode(kind, codes, sc, 0)
+            got = dq8.decode(kind, dev(codes), dev(sc), 0)
+            same_bits(got, want, "decode all codes")
+            back, _ = dq8.encode(kind, dev(want), 0, scales=dev(sc), scales_given=True)
+            same_bits(back, codes, "encode(decode(c)) == c")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 32])
+def test_decode_accumulate_avg(dq8, kind, K):
+    rng = np.random.Generator(np.random.PCG64(900 + 10 * K + kind))
+    for n, block, off in [(2 * 4096 + 333, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1), (100, 7, 0)]:
+        print("avg kind=%d K=%d n=%d block=%d off=%d" % (kind, K, n, block, off), flush=True)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
+        want = oracle.decode_accumulate_avg(kind, cl, sl, block)
+        out_buf = torch.empty(n + off, dtype=torch.float32, device="cuda")
+        got = dq8.decode_accumulate_avg(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block, out=out_buf[off:])
+        same_bits(got, want, "avg")
+
+
+def test_average_order_is_worker_zero_first(dq8):
+    c_pos, c_neg = np.full(5000, 127, np.uint8), np.full(5000, 255, np.uint8)
+    big, small = np.array([1e8], np.float32), np.array([1.0], np.float32)
+    for cl, sl in [([c_pos, c_neg, c_pos], [big, big, small]), ([c_pos, c_pos, c_neg], [big, small, big])]:
+        want = oracle.decode_accumulate_avg(oracle.LINEAR, cl, sl, 0)
+        got = dq8.decode_accumulate_avg(oracle.LINEAR, [dev(c) for c in cl], [dev(s) for s in sl], 0)
+        same_bits(got, want, "order")
+
+
+def test_config1_mnist_mlp_gradients(dq8):
+    for name, x in workloads.tensors(1):
+        check_encode_decode(dq8, 0, x, 0, tag="C1 " + name)
+
+
+def test_config2_convnet_gradients_all_types(dq8):
+    for kind in KINDS:
+        for name, x in workloads.tensors(2):
+            check_encode_decode(dq8, kind, x, 0, tag="C2 %s %s" % (NAMES[kind], name))
+
+
+def test_config4_activations_per_row(dq8):
+    for name, x in workloads.tensors(4):
+        check_encode_decode(dq8, 0, x, 4096, tag="C4 " + name)
+        # a rectified row of zeros encodes to code 0 and decodes to +0
+        assert np.mean(x == 0) > 0.45
+
+
+def test_errors_are_reported(dq8):
+    x = torch.zeros(100, device="cuda")
+    with pytest.raises(dq8.Dq8Error):
+        dq8.encode(7, x)
+    codes = torch.zeros(400, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dq8.Dq8Error):  # out overlapping an input
+        dq8.lib().dq8_last_error()
+        rc = dq8.lib().dq8_decode(0, x.data_ptr(), x.data_ptr(), 100, 0, x.data_ptr(), None)
+        dq8._check(rc, "dq8_decode")
+    del codes
