@@ -147,6 +147,31 @@ __global__ void k_fill_zero(float *p, size_t n)
     if (i < n) p[i] = 0.0f;
 }
 
+// Plain fp32 copy with the access pattern of the codec kernels (one unit per wavefront step,
+// 128-bit accesses).  Exists to calibrate bandwidth and hardware-counter readings against a
+// kernel whose traffic is known exactly: 4 bytes read and 4 bytes written per element.
+__global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, float *__restrict__ dst, size_t n,
+                                             size_t n_units, size_t n_waves)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    for (size_t u = first_unit(); u < n_units; u += n_waves) {
+        Unit un = unit_of(u, n, n, 0);
+        const float *ps = src + un.start;
+        float *pd = dst + un.start;
+        if (un.len == kUnit && (((uintptr_t)ps | (uintptr_t)pd) & 15) == 0) {
+            const float4 *s4 = reinterpret_cast<const float4 *>(ps);
+            float4 *d4 = reinterpret_cast<float4 *>(pd);
+            float4 v[kQuadIters];
+#pragma unroll
+            for (int it = 0; it < kQuadIters; ++it) v[it] = s4[it * kWave + lane];
+#pragma unroll
+            for (int it = 0; it < kQuadIters; ++it) d4[it * kWave + lane] = v[it];
+        } else {
+            for (uint32_t i = lane; i < un.len; i += kWave) pd[i] = ps[i];
+        }
+    }
+}
+
 // Block maxima.  upb == 1: each unit is a whole block and stores its maximum.
 // upb > 1: scales[] was zeroed and the units of a block merge with an integer atomic max
 // (non-negative binary32 numbers order like their bit patterns).
@@ -654,6 +679,19 @@ int dq8_internal_plan(size_t n, size_t block, int cus, size_t *out6)
     out6[4] = p.n_waves;
     out6[5] = p.grid;
     return DQ8_OK;
+}
+
+int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
+{
+    if (n == 0) return DQ8_OK;
+    if (!dst || !src) return fail(DQ8_ERR_NULL, "dq8_internal_copy: NULL pointer");
+    DeviceState *st;
+    int rc = device_state(&st);
+    if (rc) return rc;
+    Plan p = make_plan(n, 0, *st);
+    hipLaunchKernelGGL(k_copy, dim3(p.grid), dim3(kWg), 0, static_cast<hipStream_t>(hip_stream), src, dst, n, p.n_units,
+                       p.n_waves);
+    return after_launch("k_copy");
 }
 
 static int host_search(int kind, Search *sr, const dq8::Tables **tp)

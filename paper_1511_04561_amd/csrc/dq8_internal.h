@@ -25,6 +25,10 @@ int dq8_internal_check_search(int kind, uint64_t *mismatches);
 // The kernels' code search on the host for an array of already normalised values.
 int dq8_internal_search(int kind, const float *xn, size_t n, uint8_t *codes);
 
+// Copies n floats device to device with the codec kernels' access pattern (bandwidth and
+// counter calibration: exactly 4 bytes read and 4 written per element).
+int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

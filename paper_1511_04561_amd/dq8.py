@@ -40,6 +40,8 @@ def lib():
         for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg):
             f.restype = ci
         L.dq8_last_error.restype = ctypes.c_char_p
+        L.dq8_internal_copy.argtypes = [vp, vp, sz, vp]
+        L.dq8_internal_copy.restype = ci
         _lib = L
     return _lib
 
@@ -154,3 +156,14 @@ def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None):
         _check(lib().dq8_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), out.data_ptr(), _stream()),
                "dq8_decode_accumulate_avg")
     return out
+
+
+def calibration_copy(dst, src):
+    """Plain fp32 device copy with the kernels' access pattern (bandwidth / counter calibration only)."""
+    src = _dev(src, torch.float32, "src")
+    dst = _dev(dst, torch.float32, "dst")
+    if dst.numel() < src.numel():
+        raise ValueError("dst too small")
+    with torch.cuda.device(src.device):
+        _check(lib().dq8_internal_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream()), "dq8_internal_copy")
+    return dst
