@@ -32,15 +32,19 @@ using dq8::kBucketOff;
 using dq8::kCbOff;
 using dq8::kLoKeyOff;
 using dq8::kNBucketOff;
+using dq8::kNearWindow;
 using dq8::kTableWords;
 
 constexpr int kWave = 64;
 constexpr int kWavesPerWg = 4;
 constexpr int kWg = kWave * kWavesPerWg;
-constexpr int kUnit = 4096;            // elements per unit
-constexpr int kQuadIters = kUnit / (4 * kWave);  // 16 quads per lane per unit
+constexpr int kUnit = 4096;                      // elements per unit
+constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
 constexpr int kKinds = 3;
-constexpr int kLutCopies = 32;         // one copy of the decode table per LDS bank
+constexpr int kLutCopies = 32;                   // one copy of the decode table per LDS bank
+constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
+
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 // Tables of the three data types, one image per device (each GPU holds its own copy).
 __device__ __align__(256) uint32_t g_tables[kKinds][kTableWords];
@@ -52,6 +56,26 @@ struct WorkerPtrs {
 
 // ---------------------------------------------------------------- device helpers
 
+// Streaming accesses: every byte is touched once, so loads and stores carry the
+// non-temporal hint (NT) and do not displace each other in the caches.
+template <bool NT, typename T>
+__device__ __forceinline__ T ldg(const T *p)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void stg(T *p, T v)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
 #pragma unroll
@@ -62,7 +86,30 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
 
-__device__ __forceinline__ uint32_t abs_bits(float f) { return __float_as_uint(f) & 0x7FFFFFFFu; }
+__host__ __device__ __forceinline__ uint32_t f2u(float f)
+{
+    uint32_t u;
+    __builtin_memcpy(&u, &f, 4);
+    return u;
+}
+
+__host__ __device__ __forceinline__ float u2f(uint32_t u)
+{
+    float f;
+    __builtin_memcpy(&f, &u, 4);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t abs_bits(float f) { return f2u(f) & 0x7FFFFFFFu; }
+
+__device__ __forceinline__ uint32_t max4_abs(v4f v, uint32_t m)
+{
+    uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
+    a = a > b ? a : b;
+    c = c > d ? c : d;
+    a = a > c ? a : c;
+    return m > a ? m : a;
+}
 
 // Geometry of unit u.  All values are wave-uniform.
 struct Unit {
@@ -94,50 +141,98 @@ __device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t upb
     return r;
 }
 
-// Search state for the encoder: bucket table in LDS plus its key range.
+// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range.
 struct Search {
-    const uint32_t *bucket;  // LDS
-    uint32_t lo_key, hi_key;
+    const uint32_t *bucket;  // LDS on the device
+    uint32_t lo_key, lo_bits, hi_bits;
 };
 
-// Code of the normalised value xn: magnitude index = number of thresholds <= |xn|
-// (nearest table magnitude, ties to the smaller), bit 7 = sign bit of xn.
-__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, float xn)
+__host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket)
 {
-    uint32_t bits;
-    __builtin_memcpy(&bits, &xn, 4);
-    uint32_t key = (bits >> 16) & 0x7FFFu;
-    key = key < s.lo_key ? s.lo_key : key;
-    key = key > s.hi_key ? s.hi_key : key;
-    uint32_t e = s.bucket[key - s.lo_key];
-    uint32_t mag = (e + (bits & 0xFFFFu)) >> 16;
-    return mag | ((bits >> 24) & 0x80u);
+    Search s;
+    s.bucket = bucket;
+    s.lo_key = lo_key;
+    s.lo_bits = (lo_key << 16) + 0x8000u;
+    s.hi_bits = ((lo_key + n_bucket - 1) << 16) + 0x8000u;
+    return s;
 }
 
-__device__ __forceinline__ void load_bucket_table(const uint32_t *tab, uint32_t *lds, Search *s)
+// sum >> 16 = number of thresholds <= |xn|; the low half of sum measures the distance to
+// the threshold of the bucket.
+__host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
+{
+    uint32_t a = f2u(xn) & 0x7FFFFFFFu;
+    a = a < s.lo_bits ? s.lo_bits : a;
+    a = a > s.hi_bits ? s.hi_bits : a;
+    return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
+}
+
+// (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
+__host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (sum + kNearWindow) & 0xFFFFu; }
+
+// Code = magnitude index, bit 7 = sign bit of the input (the divisor is positive).
+__host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
+
+__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_from(search_sum(s, x / d), x); }
+
+// A scale qualifies for the reciprocal path when 1/d and every product x * (1/d) that can
+// reach a threshold are normal numbers: 2^-100 <= d <= 2^100.
+__host__ __device__ __forceinline__ bool reciprocal_ok(float d)
+{
+    uint32_t b = f2u(d);
+    return b >= 0x0D800000u && b <= 0x71800000u;
+}
+
+// Four codes packed into one word.  With `recip` the quotients are first taken as x * r with
+// r = fl(1/d): that differs from the correctly rounded x / d by at most 3 binary32 steps, so
+// the code is already right unless the product lies within kNearWindow steps of a threshold;
+// if any lane of the wavefront sees such a value the quad is redone with true divisions.
+template <bool FASTDIV>
+__device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d, float r, bool recip)
+{
+    if (FASTDIV && recip) {
+        uint32_t s0 = search_sum(sr, v.x * r), s1 = search_sum(sr, v.y * r);
+        uint32_t s2 = search_sum(sr, v.z * r), s3 = search_sum(sr, v.w * r);
+        uint32_t k0 = near_key(s0), k1 = near_key(s1), k2 = near_key(s2), k3 = near_key(s3);
+        k0 = k0 < k1 ? k0 : k1;
+        k2 = k2 < k3 ? k2 : k3;
+        k0 = k0 < k2 ? k0 : k2;
+        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0)
+            return code_from(s0, v.x) | (code_from(s1, v.y) << 8) | (code_from(s2, v.z) << 16) | (code_from(s3, v.w) << 24);
+    }
+    return code_exact(sr, v.x, d) | (code_exact(sr, v.y, d) << 8) | (code_exact(sr, v.z, d) << 16) |
+           (code_exact(sr, v.w, d) << 24);
+}
+
+template <bool FASTDIV>
+__device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float d, float r, bool recip)
+{
+    if (FASTDIV && recip) {
+        uint32_t s0 = search_sum(sr, x * r);
+        if (near_key(s0) > 2 * kNearWindow) return code_from(s0, x);
+    }
+    return code_exact(sr, x, d);
+}
+
+__device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds)
 {
     uint32_t nbk = tab[kNBucketOff];
     for (uint32_t i = threadIdx.x; i < nbk; i += kWg) lds[i] = tab[kBucketOff + i];
-    s->bucket = lds;
-    s->lo_key = tab[kLoKeyOff];
-    s->hi_key = s->lo_key + nbk - 1;
     __syncthreads();
+    return make_search(lds, tab[kLoKeyOff], nbk);
 }
 
 // Decode table replicated once per LDS bank: entry (code, copy) at code * 32 + copy.
 __device__ __forceinline__ void load_lut(const uint32_t *tab, float *lds)
 {
-    for (uint32_t i = threadIdx.x; i < 256 * kLutCopies; i += kWg)
-        lds[i] = __uint_as_float(tab[kCbOff + (i / kLutCopies)]);
+    for (uint32_t i = threadIdx.x; i < 256 * kLutCopies; i += kWg) lds[i] = u2f(tab[kCbOff + (i / kLutCopies)]);
     __syncthreads();
 }
 
+__device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
-__device__ __forceinline__ size_t first_unit()
-{
-    uint32_t w = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    return (size_t)blockIdx.x * kWavesPerWg + w;
-}
+__device__ __forceinline__ size_t first_unit() { return (size_t)blockIdx.x * kWavesPerWg + wave_in_wg(); }
 
 // ---------------------------------------------------------------- kernels
 
@@ -150,6 +245,7 @@ __global__ void k_fill_zero(float *p, size_t n)
 // Plain fp32 copy with the access pattern of the codec kernels (one unit per wavefront step,
 // 128-bit accesses).  Exists to calibrate bandwidth and hardware-counter readings against a
 // kernel whose traffic is known exactly: 4 bytes read and 4 bytes written per element.
+template <int Q, bool NT>
 __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, float *__restrict__ dst, size_t n,
                                              size_t n_units, size_t n_waves)
 {
@@ -159,22 +255,26 @@ __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, flo
         const float *ps = src + un.start;
         float *pd = dst + un.start;
         if (un.len == kUnit && (((uintptr_t)ps | (uintptr_t)pd) & 15) == 0) {
-            const float4 *s4 = reinterpret_cast<const float4 *>(ps);
-            float4 *d4 = reinterpret_cast<float4 *>(pd);
-            float4 v[kQuadIters];
+            const v4f *s4 = reinterpret_cast<const v4f *>(ps);
+            v4f *d4 = reinterpret_cast<v4f *>(pd);
+#pragma clang loop unroll(disable)
+            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
+                v4f v[Q];
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) v[it] = s4[it * kWave + lane];
+                for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(s4 + (sub * Q + j) * kWave + lane);
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) d4[it * kWave + lane] = v[it];
+                for (int j = 0; j < Q; ++j) stg<NT>(d4 + (sub * Q + j) * kWave + lane, v[j]);
+            }
         } else {
             for (uint32_t i = lane; i < un.len; i += kWave) pd[i] = ps[i];
         }
     }
 }
 
-// Block maxima.  upb == 1: each unit is a whole block and stores its maximum.
-// upb > 1: scales[] was zeroed and the units of a block merge with an integer atomic max
-// (non-negative binary32 numbers order like their bit patterns).
+// Block maxima.  One wavefront per unit, Q quads per lane in flight.  upb == 1: each unit is
+// a whole block and stores its maximum.  upb > 1: scales[] was zeroed and the units of a block
+// merge with an integer atomic max (non-negative binary32 numbers order like their bits).
+template <int Q, bool NT>
 __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t upb,
                                                size_t n_units, size_t n_waves, float *__restrict__ scales)
 {
@@ -184,17 +284,14 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
         const float *px = x + un.start;
         uint32_t m = 0;
         if (un.len == kUnit && ((uintptr_t)px & 15) == 0) {
-            const float4 *p4 = reinterpret_cast<const float4 *>(px);
-            float4 v[kQuadIters];
+            const v4f *p4 = reinterpret_cast<const v4f *>(px);
+#pragma clang loop unroll(disable)
+            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
+                v4f v[Q];
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) v[it] = p4[it * kWave + lane];
+                for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(p4 + (sub * Q + j) * kWave + lane);
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) {
-                uint32_t a = abs_bits(v[it].x), b = abs_bits(v[it].y), c = abs_bits(v[it].z), d = abs_bits(v[it].w);
-                a = a > b ? a : b;
-                c = c > d ? c : d;
-                a = a > c ? a : c;
-                m = m > a ? m : a;
+                for (int j = 0; j < Q; ++j) m = max4_abs(v[j], m);
             }
         } else {
             for (uint32_t i = lane; i < un.len; i += kWave) {
@@ -205,78 +302,87 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
         m = wave_max_u32(m);
         if (lane == 0) {
             if (upb == 1)
-                scales[un.block] = __uint_as_float(m);
+                scales[un.block] = u2f(m);
             else
                 atomicMax(reinterpret_cast<unsigned int *>(scales) + un.block, m);
         }
     }
 }
 
-// Compression.  FUSED: a unit is a whole block (upb == 1); the wave reduces the block's
-// maximum from registers, stores it and quantises the same registers.  Otherwise the
-// scale of the unit's block is read from scales[].
-template <bool FUSED>
+// Compression.  A team of WPB wavefronts owns a unit: WPB == 1, each wavefront of the
+// workgroup walks its own units with 16 quads per lane; WPB == 4, the workgroup's four
+// wavefronts share a unit, 4 quads per lane, and combine their maxima through LDS.
+// FUSED: a unit is a whole block (upb == 1); the team reduces the block's maximum from
+// registers, stores it and quantises the same registers.  Otherwise the scale of the unit's
+// block is read from scales[].
+template <int WPB, bool NT, bool FUSED, bool FASTDIV>
 __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
-                                               size_t B, size_t upb, size_t n_units, size_t n_waves,
+                                               size_t B, size_t upb, size_t n_units, size_t n_teams,
                                                float *__restrict__ scales, uint8_t *__restrict__ codes)
 {
-    extern __shared__ uint32_t lds_bucket[];
-    Search sr;
-    load_bucket_table(tab, lds_bucket, &sr);
+    static_assert(WPB == 1 || WPB == kWavesPerWg, "a team is one wavefront or the whole workgroup");
+    constexpr int Q = kUnitQuads / WPB;
+    constexpr uint32_t TEAM = kWave * WPB;
+    extern __shared__ uint32_t lds[];
+    uint32_t *slots = lds;  // kTeamSlots words
+    const Search sr = load_bucket_table(tab, lds + kTeamSlots);
     const uint32_t lane = threadIdx.x & 63;
-    for (size_t u = first_unit(); u < n_units; u += n_waves) {
+    const uint32_t wave = wave_in_wg();
+    const uint32_t tl = WPB == 1 ? lane : threadIdx.x;  // index inside the team
+    uint32_t phase = 0;
+    for (size_t u = (WPB == 1 ? first_unit() : (size_t)blockIdx.x); u < n_units; u += n_teams) {
         Unit un = unit_of(u, n, B, upb);
         const float *px = x + un.start;
         uint8_t *pc = codes + un.start;
-        if (un.len == kUnit && ((uintptr_t)px & 15) == 0 && ((uintptr_t)pc & 3) == 0) {
-            const float4 *p4 = reinterpret_cast<const float4 *>(px);
-            uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
-            float4 v[kQuadIters];
+        const bool fast = un.len == kUnit && ((uintptr_t)px & 15) == 0 && ((uintptr_t)pc & 3) == 0;
+        v4f v[Q];
+        uint32_t m = 0;
+        if (fast) {
+            const v4f *p4 = reinterpret_cast<const v4f *>(px);
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) v[it] = p4[it * kWave + lane];
-            float s;
+            for (int it = 0; it < Q; ++it) v[it] = ldg<NT>(p4 + it * TEAM + tl);
             if (FUSED) {
-                uint32_t m = 0;
 #pragma unroll
-                for (int it = 0; it < kQuadIters; ++it) {
-                    uint32_t a = abs_bits(v[it].x), b = abs_bits(v[it].y), c = abs_bits(v[it].z), d = abs_bits(v[it].w);
-                    a = a > b ? a : b;
-                    c = c > d ? c : d;
-                    a = a > c ? a : c;
-                    m = m > a ? m : a;
-                }
-                s = __uint_as_float(wave_max_u32(m));
-                if (lane == 0) scales[un.block] = s;
-            } else {
-                s = scales[un.block];
+                for (int it = 0; it < Q; ++it) m = max4_abs(v[it], m);
             }
-            const float d = s == 0.0f ? 1.0f : s;  // a zero scale leaves the value as it is
-#pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) {
-                uint32_t w = code_of(sr, v[it].x / d) | (code_of(sr, v[it].y / d) << 8) |
-                             (code_of(sr, v[it].z / d) << 16) | (code_of(sr, v[it].w / d) << 24);
-                c4[it * kWave + lane] = w;
+        } else if (FUSED) {
+            for (uint32_t i = tl; i < un.len; i += TEAM) {
+                uint32_t a = abs_bits(px[i]);
+                m = m > a ? m : a;
             }
+        }
+        float s;
+        if (FUSED) {
+            m = wave_max_u32(m);
+            if (WPB > 1) {
+                if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
+                __syncthreads();  // every wavefront of the workgroup walks the same units
+                const uint32_t *sl = slots + phase * kWavesPerWg;
+                uint32_t a = sl[0] > sl[1] ? sl[0] : sl[1], b = sl[2] > sl[3] ? sl[2] : sl[3];
+                m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+                phase ^= 1;  // the other half of slots next time: one barrier per unit is enough
+            }
+            s = u2f(m);
+            if (tl == 0) scales[un.block] = s;
         } else {
-            float s;
-            if (FUSED) {
-                uint32_t m = 0;
-                for (uint32_t i = lane; i < un.len; i += kWave) {
-                    uint32_t a = abs_bits(px[i]);
-                    m = m > a ? m : a;
-                }
-                s = __uint_as_float(wave_max_u32(m));
-                if (lane == 0) scales[un.block] = s;
-            } else {
-                s = scales[un.block];
-            }
-            const float d = s == 0.0f ? 1.0f : s;
-            for (uint32_t i = lane; i < un.len; i += kWave) pc[i] = (uint8_t)code_of(sr, px[i] / d);
+            s = scales[un.block];
+        }
+        const float d = s == 0.0f ? 1.0f : s;  // a zero scale leaves the value as it is
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        if (fast) {
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
+#pragma unroll
+            for (int it = 0; it < Q; ++it) stg<NT>(c4 + it * TEAM + tl, encode_quad<FASTDIV>(sr, v[it], d, r, recip));
+        } else {
+            for (uint32_t i = tl; i < un.len; i += TEAM) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
         }
     }
 }
 
-// Decompression of one buffer: out = table[code] * scale.
+// Decompression of one buffer: out = table[code] * scale.  Q code words (4 codes each) per
+// lane in flight.
+template <int Q, bool NT>
 __global__ __launch_bounds__(kWg) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
                                                const float *__restrict__ scales, size_t n, size_t B, size_t upb,
                                                size_t n_units, size_t n_waves, float *__restrict__ out)
@@ -292,18 +398,21 @@ __global__ __launch_bounds__(kWg) void k_decode(const uint32_t *__restrict__ tab
         const float s = scales[un.block];
         if (un.len == kUnit && ((uintptr_t)po & 15) == 0 && ((uintptr_t)pc & 3) == 0) {
             const uint32_t *c4 = reinterpret_cast<const uint32_t *>(pc);
-            float4 *o4 = reinterpret_cast<float4 *>(po);
-            uint32_t w[kQuadIters];
+            v4f *o4 = reinterpret_cast<v4f *>(po);
+#pragma clang loop unroll(disable)
+            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
+                uint32_t w[Q];
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) w[it] = c4[it * kWave + lane];
+                for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + (sub * Q + j) * kWave + lane);
 #pragma unroll
-            for (int it = 0; it < kQuadIters; ++it) {
-                float4 r;
-                r.x = my[(w[it] & 0xFFu) * kLutCopies] * s;
-                r.y = my[((w[it] >> 8) & 0xFFu) * kLutCopies] * s;
-                r.z = my[((w[it] >> 16) & 0xFFu) * kLutCopies] * s;
-                r.w = my[(w[it] >> 24) * kLutCopies] * s;
-                o4[it * kWave + lane] = r;
+                for (int j = 0; j < Q; ++j) {
+                    v4f r;
+                    r.x = my[(w[j] & 0xFFu) * kLutCopies] * s;
+                    r.y = my[((w[j] >> 8) & 0xFFu) * kLutCopies] * s;
+                    r.z = my[((w[j] >> 16) & 0xFFu) * kLutCopies] * s;
+                    r.w = my[(w[j] >> 24) * kLutCopies] * s;
+                    stg<NT>(o4 + (sub * Q + j) * kWave + lane, r);
+                }
             }
         } else {
             for (uint32_t i = lane; i < un.len; i += kWave) po[i] = my[(uint32_t)pc[i] * kLutCopies] * s;
@@ -312,8 +421,9 @@ __global__ __launch_bounds__(kWg) void k_decode(const uint32_t *__restrict__ tab
 }
 
 // Decompress K buffers and average: acc = +0; acc += table[code_k] * scale_k for k = 0..K-1
-// in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled), KT == 0 reads it.
-template <int KT>
+// in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled, Q code words per
+// lane and worker in flight), KT == 0 reads K from the argument.
+template <int KT, int Q, bool NT>
 __global__ __launch_bounds__(kWg) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt, size_t n,
                                                    size_t B, size_t upb, size_t n_units, size_t n_waves,
                                                    float *__restrict__ out)
@@ -324,36 +434,32 @@ __global__ __launch_bounds__(kWg) void k_decode_avg(const uint32_t *__restrict__
     const float fk = (float)K;
     const uint32_t lane = threadIdx.x & 63;
     const float *my = lut + (lane & (kLutCopies - 1));
-    constexpr int kSub = 4;  // quads per lane kept in flight per worker
+    constexpr int KA = KT > 0 ? KT : 1;
     for (size_t u = first_unit(); u < n_units; u += n_waves) {
         Unit un = unit_of(u, n, B, upb);
         float *po = out + un.start;
         bool fast = un.len == kUnit && ((uintptr_t)po & 15) == 0;
-        if (KT > 0) {
-#pragma unroll
-            for (int k = 0; k < KT; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
-        } else {
-            for (int k = 0; k < K; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
-        }
+        for (int k = 0; k < K; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
         if (fast) {
-            float4 *o4 = reinterpret_cast<float4 *>(po);
+            v4f *o4 = reinterpret_cast<v4f *>(po);
             if (KT > 0) {
-                float sc[KT > 0 ? KT : 1];
+                float sc[KA];
 #pragma unroll
-                for (int k = 0; k < KT; ++k) sc[k] = p.scales[k][un.block];
-                for (int sub = 0; sub < kQuadIters / kSub; ++sub) {
-                    uint32_t w[KT > 0 ? KT : 1][kSub];
+                for (int k = 0; k < KA; ++k) sc[k] = p.scales[k][un.block];
+#pragma clang loop unroll(disable)
+                for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
+                    uint32_t w[KA][Q];
 #pragma unroll
-                    for (int k = 0; k < KT; ++k) {
+                    for (int k = 0; k < KA; ++k) {
                         const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
 #pragma unroll
-                        for (int j = 0; j < kSub; ++j) w[k][j] = c4[(sub * kSub + j) * kWave + lane];
+                        for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + (sub * Q + j) * kWave + lane);
                     }
 #pragma unroll
-                    for (int j = 0; j < kSub; ++j) {
-                        float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    for (int j = 0; j < Q; ++j) {
+                        v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                        for (int k = 0; k < KT; ++k) {
+                        for (int k = 0; k < KA; ++k) {
                             a.x = a.x + my[(w[k][j] & 0xFFu) * kLutCopies] * sc[k];
                             a.y = a.y + my[((w[k][j] >> 8) & 0xFFu) * kLutCopies] * sc[k];
                             a.z = a.z + my[((w[k][j] >> 16) & 0xFFu) * kLutCopies] * sc[k];
@@ -363,14 +469,14 @@ __global__ __launch_bounds__(kWg) void k_decode_avg(const uint32_t *__restrict__
                         a.y = a.y / fk;
                         a.z = a.z / fk;
                         a.w = a.w / fk;
-                        o4[(sub * kSub + j) * kWave + lane] = a;
+                        stg<NT>(o4 + (sub * Q + j) * kWave + lane, a);
                     }
                 }
             } else {
-                for (int it = 0; it < kQuadIters; ++it) {
-                    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                for (int it = 0; it < kUnitQuads; ++it) {
+                    v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
                     for (int k = 0; k < K; ++k) {
-                        const uint32_t w = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start)[it * kWave + lane];
+                        const uint32_t w = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + it * kWave + lane);
                         const float s = p.scales[k][un.block];
                         a.x = a.x + my[(w & 0xFFu) * kLutCopies] * s;
                         a.y = a.y + my[((w >> 8) & 0xFFu) * kLutCopies] * s;
@@ -381,7 +487,7 @@ __global__ __launch_bounds__(kWg) void k_decode_avg(const uint32_t *__restrict__
                     a.y = a.y / fk;
                     a.z = a.z / fk;
                     a.w = a.w / fk;
-                    o4[it * kWave + lane] = a;
+                    stg<NT>(o4 + it * kWave + lane, a);
                 }
             }
         } else {
@@ -454,23 +560,32 @@ int device_state(DeviceState **out)
     return DQ8_OK;
 }
 
-int tune_waves_per_cu()
-{
-    static int v = [] {
-        const char *e = getenv("DQ8_WAVES_PER_CU");
-        int w = e ? atoi(e) : 0;
-        return (w >= 1 && w <= 32) ? w : 16;
-    }();
-    return v;
-}
+// Launch shape of each kernel.  Defaults come from measurements on MI355X (bandwidth peaks
+// at roughly 16-32 KiB of loads in flight per compute unit); dq8_internal_tune() changes them
+// for experiments.  None of them affects results.
+struct Tuning {
+    int nt = 1;          // non-temporal loads and stores
+    int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
+    int enc_wpb = 1;     // wavefronts per unit in the encoder: 1 or 4
+    int enc_wpc = 8;     // encoder wavefronts per compute unit
+    int amax_q = 4;      // absmax: quads per lane in flight
+    int amax_wpc = 8;
+    int dec_q = 4;       // decode: code words per lane in flight
+    int dec_wpc = 8;
+    int avg_q = 2;       // decode-and-average: code words per lane and worker in flight
+    int avg_wpc = 8;
+    int copy_q = 4;
+    int copy_wpc = 8;
+};
+Tuning g_tune;
 
 struct Plan {
-    size_t B, nb, upb, n_units, n_waves;
+    size_t B, nb, upb, n_units, n_teams;
     unsigned grid;
 };
 
-// Units, and a grid in which every wavefront walks the same number of them.
-Plan make_plan(size_t n, size_t block, const DeviceState &st)
+// Units, and a grid in which every team (wpb wavefronts) walks the same number of them.
+Plan make_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb)
 {
     Plan p;
     p.B = (block == 0 || block > n) ? n : block;
@@ -482,12 +597,14 @@ Plan make_plan(size_t n, size_t block, const DeviceState &st)
         size_t last = n - (p.nb - 1) * p.B;  // the last block may be short
         p.n_units = (p.nb - 1) * p.upb + (last + kUnit - 1) / kUnit;
     }
-    size_t max_waves = (size_t)st.cus * (size_t)tune_waves_per_cu();
-    size_t per_wave = (p.n_units + max_waves - 1) / max_waves;
-    size_t waves = (p.n_units + per_wave - 1) / per_wave;
-    size_t grid = (waves + kWavesPerWg - 1) / kWavesPerWg;
+    size_t max_teams = (size_t)cus * (size_t)waves_per_cu / (size_t)wpb;
+    if (max_teams < 1) max_teams = 1;
+    size_t per_team = (p.n_units + max_teams - 1) / max_teams;
+    size_t teams = (p.n_units + per_team - 1) / per_team;
+    size_t teams_per_wg = kWavesPerWg / wpb;
+    size_t grid = (teams + teams_per_wg - 1) / teams_per_wg;
     p.grid = (unsigned)grid;
-    p.n_waves = grid * kWavesPerWg;
+    p.n_teams = grid * teams_per_wg;
     return p;
 }
 
@@ -512,15 +629,73 @@ int after_launch(const char *what)
 
 int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block, float *scales, hipStream_t stream)
 {
-    Plan p = make_plan(n, block, st);
+    Plan p = make_plan(n, block, st.cus, g_tune.amax_wpc, 1);
     if (p.upb > 1) {
         unsigned g = (unsigned)((p.nb + 255) / 256);
         hipLaunchKernelGGL(k_fill_zero, dim3(g), dim3(256), 0, stream, scales, p.nb);
         int rc = after_launch("k_fill_zero");
         if (rc) return rc;
     }
-    hipLaunchKernelGGL(k_absmax, dim3(p.grid), dim3(kWg), 0, stream, x, n, p.B, p.upb, p.n_units, p.n_waves, scales);
+#define DQ8_AMAX(Q, NT)                                                                                          \
+    hipLaunchKernelGGL((k_absmax<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, x, n, p.B, p.upb, p.n_units, p.n_teams, \
+                       scales)
+#define DQ8_AMAX_Q(NT)                      \
+    switch (g_tune.amax_q) {                \
+    case 1: DQ8_AMAX(1, NT); break;         \
+    case 2: DQ8_AMAX(2, NT); break;         \
+    case 8: DQ8_AMAX(8, NT); break;         \
+    case 16: DQ8_AMAX(16, NT); break;       \
+    default: DQ8_AMAX(4, NT); break;        \
+    }
+    if (g_tune.nt) {
+        DQ8_AMAX_Q(true)
+    } else {
+        DQ8_AMAX_Q(false)
+    }
+#undef DQ8_AMAX_Q
+#undef DQ8_AMAX
     return after_launch("k_absmax");
+}
+
+int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
+                  bool fused, hipStream_t stream)
+{
+    const int wpb = g_tune.enc_wpb == 4 ? 4 : 1;
+    Plan p = make_plan(n, block, st.cus, g_tune.enc_wpc, wpb);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = ((size_t)st.n_bucket[kind] + kTeamSlots) * sizeof(uint32_t);
+#define DQ8_ENC(WPB, NT, FUSED, FD)                                                                              \
+    hipLaunchKernelGGL((k_encode<WPB, NT, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.upb, \
+                       p.n_units, p.n_teams, scales, codes)
+#define DQ8_ENC_FD(WPB, NT, FUSED)       \
+    if (g_tune.fastdiv) {                \
+        DQ8_ENC(WPB, NT, FUSED, true);   \
+    } else {                             \
+        DQ8_ENC(WPB, NT, FUSED, false);  \
+    }
+#define DQ8_ENC_NT(WPB, FUSED)           \
+    if (g_tune.nt) {                     \
+        DQ8_ENC_FD(WPB, true, FUSED)     \
+    } else {                             \
+        DQ8_ENC_FD(WPB, false, FUSED)    \
+    }
+    if (wpb == 4) {
+        if (fused) {
+            DQ8_ENC_NT(4, true)
+        } else {
+            DQ8_ENC_NT(4, false)
+        }
+    } else {
+        if (fused) {
+            DQ8_ENC_NT(1, true)
+        } else {
+            DQ8_ENC_NT(1, false)
+        }
+    }
+#undef DQ8_ENC_NT
+#undef DQ8_ENC_FD
+#undef DQ8_ENC
+    return after_launch("k_encode");
 }
 
 }  // namespace
@@ -569,25 +744,18 @@ int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, 
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, block, *st);
-    if (overlaps(x, n * 4, codes, n) || overlaps(x, n * 4, scales, p.nb * 4) || overlaps(codes, n, scales, p.nb * 4))
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t nbq = (n + Bq - 1) / Bq;
+    if (overlaps(x, n * 4, codes, n) || overlaps(x, n * 4, scales, nbq * 4) || overlaps(codes, n, scales, nbq * 4))
         return fail(DQ8_ERR_ARG, "dq8_encode: buffers overlap");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
-    const size_t lds = (size_t)st->n_bucket[kind] * sizeof(uint32_t);
     const bool given = (flags & DQ8_SCALES_GIVEN) != 0;
-    if (!given && p.upb == 1) {
-        hipLaunchKernelGGL(k_encode<true>, dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.upb, p.n_units,
-                           p.n_waves, scales, codes);
-        return after_launch("k_encode<fused>");
-    }
-    if (!given) {
+    const bool fused = !given && Bq <= (size_t)kUnit;  // the block fits one unit: absmax and encode in one kernel
+    if (!given && !fused) {
         rc = launch_absmax(*st, x, n, block, scales, stream);
         if (rc) return rc;
     }
-    hipLaunchKernelGGL(k_encode<false>, dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.upb, p.n_units,
-                       p.n_waves, scales, codes);
-    return after_launch("k_encode<scales>");
+    return launch_encode(*st, kind, x, n, block, scales, codes, fused, stream);
 }
 
 int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, size_t block, float *out,
@@ -601,12 +769,29 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, block, *st);
+    Plan p = make_plan(n, block, st->cus, g_tune.dec_wpc, 1);
     if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
         return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
-    hipLaunchKernelGGL(k_decode, dim3(p.grid), dim3(kWg), 0, static_cast<hipStream_t>(hip_stream), tab, codes, scales, n,
-                       p.B, p.upb, p.n_units, p.n_waves, out);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+#define DQ8_DEC(Q, NT)                                                                                              \
+    hipLaunchKernelGGL((k_decode<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, tab, codes, scales, n, p.B, p.upb, p.n_units, \
+                       p.n_teams, out)
+#define DQ8_DEC_Q(NT)                    \
+    switch (g_tune.dec_q) {              \
+    case 1: DQ8_DEC(1, NT); break;       \
+    case 2: DQ8_DEC(2, NT); break;       \
+    case 8: DQ8_DEC(8, NT); break;       \
+    case 16: DQ8_DEC(16, NT); break;     \
+    default: DQ8_DEC(4, NT); break;      \
+    }
+    if (g_tune.nt) {
+        DQ8_DEC_Q(true)
+    } else {
+        DQ8_DEC_Q(false)
+    }
+#undef DQ8_DEC_Q
+#undef DQ8_DEC
     return after_launch("k_decode");
 }
 
@@ -622,7 +807,7 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, block, *st);
+    Plan p = make_plan(n, block, st->cus, g_tune.avg_wpc, 1);
     WorkerPtrs wp;
     std::memset(&wp, 0, sizeof(wp));
     for (int k = 0; k < K; ++k) {
@@ -634,16 +819,36 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     }
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-#define DQ8_LAUNCH_AVG(KT)                                                                                             \
-    hipLaunchKernelGGL(k_decode_avg<KT>, dim3(p.grid), dim3(kWg), 0, stream, tab, wp, K, n, p.B, p.upb, p.n_units,   \
-                       p.n_waves, out)
-    switch (K) {
-    case 2: DQ8_LAUNCH_AVG(2); break;
-    case 4: DQ8_LAUNCH_AVG(4); break;
-    case 8: DQ8_LAUNCH_AVG(8); break;
-    default: DQ8_LAUNCH_AVG(0); break;
+#define DQ8_AVG(KT, Q, NT)                                                                                        \
+    hipLaunchKernelGGL((k_decode_avg<KT, Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, tab, wp, K, n, p.B, p.upb,  \
+                       p.n_units, p.n_teams, out)
+#define DQ8_AVG_Q(KT, NT)                \
+    switch (g_tune.avg_q) {              \
+    case 1: DQ8_AVG(KT, 1, NT); break;   \
+    case 4: DQ8_AVG(KT, 4, NT); break;   \
+    default: DQ8_AVG(KT, 2, NT); break;  \
     }
-#undef DQ8_LAUNCH_AVG
+#define DQ8_AVG_NT(KT)                   \
+    if (g_tune.nt) {                     \
+        DQ8_AVG_Q(KT, true)              \
+    } else {                             \
+        DQ8_AVG_Q(KT, false)             \
+    }
+    switch (K) {
+    case 2: DQ8_AVG_NT(2) break;
+    case 4: DQ8_AVG_NT(4) break;
+    case 8: DQ8_AVG_NT(8) break;
+    default:
+        if (g_tune.nt) {
+            DQ8_AVG(0, 1, true);
+        } else {
+            DQ8_AVG(0, 1, false);
+        }
+        break;
+    }
+#undef DQ8_AVG_NT
+#undef DQ8_AVG_Q
+#undef DQ8_AVG
     return after_launch("k_decode_avg");
 }
 
@@ -667,18 +872,35 @@ int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key,
     return DQ8_OK;
 }
 
-int dq8_internal_plan(size_t n, size_t block, int cus, size_t *out6)
+int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t *out6)
 {
-    DeviceState st;
-    st.cus = cus;
-    Plan p = make_plan(n, block, st);
+    if (!out6 || cus < 1 || waves_per_cu < 1 || (wpb != 1 && wpb != 4)) return fail(DQ8_ERR_ARG, "dq8_internal_plan: bad argument");
+    Plan p = make_plan(n, block, cus, waves_per_cu, wpb);
     out6[0] = p.B;
     out6[1] = p.nb;
     out6[2] = p.upb;
     out6[3] = p.n_units;
-    out6[4] = p.n_waves;
+    out6[4] = p.n_teams;
     out6[5] = p.grid;
     return DQ8_OK;
+}
+
+int dq8_internal_tune(const char *key, int value)
+{
+    if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
+    struct { const char *name; int *slot; int lo, hi; } keys[] = {
+        {"nt", &g_tune.nt, 0, 1},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
+        {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+    };
+    for (auto &k : keys)
+        if (!std::strcmp(k.name, key)) {
+            if (value < k.lo || value > k.hi) return fail(DQ8_ERR_ARG, "dq8_internal_tune: %s = %d outside %d..%d", key, value, k.lo, k.hi);
+            *k.slot = value;
+            return DQ8_OK;
+        }
+    return fail(DQ8_ERR_ARG, "dq8_internal_tune: unknown key %s", key);
 }
 
 int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
@@ -688,55 +910,86 @@ int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
     DeviceState *st;
     int rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, 0, *st);
-    hipLaunchKernelGGL(k_copy, dim3(p.grid), dim3(kWg), 0, static_cast<hipStream_t>(hip_stream), src, dst, n, p.n_units,
-                       p.n_waves);
+    Plan p = make_plan(n, 0, st->cus, g_tune.copy_wpc, 1);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+#define DQ8_COPY(Q, NT) \
+    hipLaunchKernelGGL((k_copy<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, src, dst, n, p.n_units, p.n_teams)
+#define DQ8_COPY_Q(NT)                   \
+    switch (g_tune.copy_q) {             \
+    case 1: DQ8_COPY(1, NT); break;      \
+    case 2: DQ8_COPY(2, NT); break;      \
+    case 8: DQ8_COPY(8, NT); break;      \
+    case 16: DQ8_COPY(16, NT); break;    \
+    default: DQ8_COPY(4, NT); break;     \
+    }
+    if (g_tune.nt) {
+        DQ8_COPY_Q(true)
+    } else {
+        DQ8_COPY_Q(false)
+    }
+#undef DQ8_COPY_Q
+#undef DQ8_COPY
     return after_launch("k_copy");
 }
 
-static int host_search(int kind, Search *sr, const dq8::Tables **tp)
+static int host_search(int kind, Search *sr)
 {
     int rc = check_kind(kind);
     if (rc) return rc;
     static thread_local dq8::Tables t;
     if (dq8::build_tables(kind, &t)) return fail(DQ8_ERR_KIND, "table construction failed for kind %d", kind);
-    sr->bucket = t.bucket;
-    sr->lo_key = t.lo_key;
-    sr->hi_key = t.lo_key + t.n_bucket - 1;
-    *tp = &t;
+    *sr = make_search(t.bucket, t.lo_key, t.n_bucket);
     return DQ8_OK;
 }
 
-int dq8_internal_check_search(int kind, uint64_t *mismatches)
+int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_near)
 {
     Search sr;
-    const dq8::Tables *t;
-    int rc = host_search(kind, &sr, &t);
+    int rc = host_search(kind, &sr);
     if (rc) return rc;
+    static thread_local dq8::Tables t;
+    dq8::build_tables(kind, &t);
     uint32_t thr_bits[127];
-    std::memcpy(thr_bits, t->thr, sizeof(thr_bits));
-    uint64_t bad = 0;
+    std::memcpy(thr_bits, t.thr, sizeof(thr_bits));
+    uint64_t bad = 0, missed = 0;
     uint32_t j = 0;  // thresholds <= the current value
     for (uint32_t bits = 0; bits <= 0x7F800000u; ++bits) {
         while (j < 127 && thr_bits[j] <= bits) ++j;
-        float pos, neg;
-        uint32_t nb = bits | 0x80000000u;
-        std::memcpy(&pos, &bits, 4);
-        std::memcpy(&neg, &nb, 4);
-        bad += code_of(sr, pos) != j;
-        bad += code_of(sr, neg) != (j | 0x80u);
+        const float pos = u2f(bits), neg = u2f(bits | 0x80000000u);
+        const uint32_t sp = search_sum(sr, pos), sn = search_sum(sr, neg);
+        bad += code_from(sp, pos) != j;
+        bad += code_from(sn, neg) != (j | 0x80u);
+        // every value within kNearWindow steps of a threshold must raise the proximity flag
+        bool close = (j < 127 && thr_bits[j] - bits <= kNearWindow) || (j > 0 && bits - thr_bits[j - 1] <= kNearWindow);
+        if (close && near_key(sp) > 2 * kNearWindow) ++missed;
     }
-    *mismatches = bad;
+    if (mismatches) *mismatches = bad;
+    if (missed_near) *missed_near = missed;
     return DQ8_OK;
 }
 
-int dq8_internal_search(int kind, const float *xn, size_t n, uint8_t *codes)
+int dq8_internal_encode_host(int kind, const float *x, size_t n, float scale, int use_reciprocal, uint8_t *codes,
+                             uint64_t *n_exact)
 {
     Search sr;
-    const dq8::Tables *t;
-    int rc = host_search(kind, &sr, &t);
+    int rc = host_search(kind, &sr);
     if (rc) return rc;
-    for (size_t i = 0; i < n; ++i) codes[i] = (uint8_t)code_of(sr, xn[i]);
+    const float d = scale == 0.0f ? 1.0f : scale;
+    const float r = 1.0f / d;
+    const bool recip = use_reciprocal && reciprocal_ok(d);
+    uint64_t exact = 0;
+    for (size_t i = 0; i < n; ++i) {
+        if (recip) {
+            uint32_t s0 = search_sum(sr, x[i] * r);
+            if (near_key(s0) > 2 * kNearWindow) {
+                codes[i] = (uint8_t)code_from(s0, x[i]);
+                continue;
+            }
+        }
+        ++exact;
+        codes[i] = (uint8_t)code_exact(sr, x[i], d);
+    }
+    if (n_exact) *n_exact = exact;
     return DQ8_OK;
 }
 

@@ -13,17 +13,25 @@ extern "C" {
 int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key, uint32_t *n_bucket, uint32_t *bucket,
                         uint32_t bucket_capacity);
 
-// Launch plan for n elements with the given block on a device with `cus` compute units:
-// out6 = {B, nb, units per block, units, wavefronts, workgroups}.
-int dq8_internal_plan(size_t n, size_t block, int cus, size_t *out6);
+// Launch plan for n elements with the given block on a device with `cus` compute units,
+// `waves_per_cu` resident wavefronts per unit and teams of `wpb` wavefronts:
+// out6 = {B, nb, units per block, units, teams, workgroups}.
+int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t *out6);
 
-// Runs the kernels' code search (the same inline function, compiled for the host) over every
+// Runs the kernels' code search (the same inline functions, compiled for the host) over every
 // non-negative finite binary32 bit pattern and +inf, and compares it with a count of the
-// thresholds that are <= the value.  *mismatches receives the number of disagreements.
-int dq8_internal_check_search(int kind, uint64_t *mismatches);
+// thresholds that are <= the value.  *mismatches = number of disagreements; *missed_near =
+// number of values within the proximity window of a threshold that did not raise the flag.
+int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_near);
 
-// The kernels' code search on the host for an array of already normalised values.
-int dq8_internal_search(int kind, const float *xn, size_t n, uint8_t *codes);
+// The encoder's per-element arithmetic on the host (same inline functions): codes of x[0..n)
+// for one given scale, through the reciprocal path with its exact fallback (use_reciprocal
+// != 0) or through true divisions only.  *n_exact = elements that took a true division.
+int dq8_internal_encode_host(int kind, const float *x, size_t n, float scale, int use_reciprocal, uint8_t *codes,
+                             uint64_t *n_exact);
+
+// Changes a launch-shape parameter (experiments only; results never depend on them).
+int dq8_internal_tune(const char *key, int value);
 
 // Copies n floats device to device with the codec kernels' access pattern (bandwidth and
 // counter calibration: exactly 4 bytes read and 4 written per element).

@@ -100,11 +100,16 @@ int build_tables(int kind, Tables *t)
         t->thr[j] = f;  // smallest binary32 strictly above the midpoint
         if (j > 0 && !(t->thr[j - 1] < f)) return 5;
     }
-    const uint32_t hi_key = f2u(1.0f) >> 16;  // every threshold is below 1
     if (!(t->thr[126] < 1.0f)) return 5;
+    // Neighbouring thresholds must be more than a bucket apart (plus the width of the
+    // encoder's proximity window on both sides): then a bucket holds at most one threshold
+    // and a threshold close to a bucket edge has a threshold-free neighbour bucket.
+    for (int j = 1; j < 127; ++j)
+        if (f2u(t->thr[j]) - f2u(t->thr[j - 1]) <= 0x10000u + 2 * kNearWindow) return 5;
     uint32_t lo_key = (f2u(t->thr[0]) >> 16);
     if (lo_key == 0) return 5;
     lo_key -= 1;  // one bucket that lies entirely below the first threshold
+    const uint32_t hi_key = (f2u(t->thr[126]) >> 16) + 1;  // one bucket entirely above the last threshold
     uint32_t nb = hi_key - lo_key + 1;
     if (nb > (uint32_t)(kTableWords - kBucketOff)) return 5;
     t->lo_key = lo_key;

@@ -11,19 +11,32 @@
 // binary search; the bucket table replaces the seven dependent steps of that search by
 // one lookup keyed on the top bits of |xn| plus one integer add.
 //
-// Bucket table.  key = bits(|xn|) >> 16 (8 exponent bits + 7 mantissa bits), clamped to
-// [lo_key, lo_key + n_bucket - 1].  Every key range [key << 16, (key << 16) + 0xFFFF]
-// contains at most one threshold (checked when the table is built).  The entry is
+// Bucket table.  a = bits(|xn|) clamped to [lo_bits, hi_bits] with
+//   lo_bits = (lo_key << 16) + 0x8000,  hi_bits = (hi_key << 16) + 0x8000,
+// the middles of two buckets that hold no threshold and lie below the first / above the
+// last threshold (so clamping never changes the answer, and covers |xn| > 1, inf, NaN).
+// key = a >> 16 (8 exponent bits + 7 mantissa bits).  Every key range
+// [key << 16, (key << 16) + 0xFFFF] contains at most one threshold (checked when the table
+// is built).  The entry is
 //   S = (base << 16) + (0x10000 - t)
 // where base = number of thresholds below the range and t = low 16 bits of the threshold
 // inside the range (t = 0x10000 when there is none).  Then
-//   magnitude index = (S + (bits(|xn|) & 0xFFFF)) >> 16
+//   sum = S + (a & 0xFFFF),   magnitude index = sum >> 16
 // because the add carries into bit 16 exactly when the low bits reach t.
+//
+// Proximity.  The low 16 bits of sum are (a - threshold) mod 2^16 in a bucket with a
+// threshold and (a & 0xFFFF) in one without.  ((sum + W) & 0xFFFF) <= 2 W therefore holds
+// whenever a is within W binary32 steps of a threshold (also of one just across a bucket
+// edge, because thresholds are more than a bucket + 2 W apart, see build_tables) and
+// otherwise only for values within W steps of a bucket edge.  The encoder uses this to
+// decide when a quotient computed as x * (1/s) may differ from the correctly rounded x / s
+// in a way that matters, and redoes those with a true division.
 #pragma once
 #include <cstdint>
 
 namespace dq8 {
 
+constexpr uint32_t kNearWindow = 4;  // proximity window W in binary32 steps
 constexpr int kTableWords = 4096;   // device words reserved per data type
 constexpr int kCbOff = 0;           // 256 words: cb as raw binary32
 constexpr int kLoKeyOff = 256;      // 1 word

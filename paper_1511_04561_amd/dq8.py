@@ -42,6 +42,8 @@ def lib():
         L.dq8_last_error.restype = ctypes.c_char_p
         L.dq8_internal_copy.argtypes = [vp, vp, sz, vp]
         L.dq8_internal_copy.restype = ci
+        L.dq8_internal_tune.argtypes = [ctypes.c_char_p, ci]
+        L.dq8_internal_tune.restype = ci
         _lib = L
     return _lib
 
@@ -167,3 +169,9 @@ def calibration_copy(dst, src):
     with torch.cuda.device(src.device):
         _check(lib().dq8_internal_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream()), "dq8_internal_copy")
     return dst
+
+
+def tune(**kw):
+    """Changes launch-shape parameters of the kernels (experiments only; results never depend on them)."""
+    for k, v in kw.items():
+        _check(lib().dq8_internal_tune(k.encode(), int(v)), "dq8_internal_tune(%s)" % k)

@@ -82,14 +82,28 @@ def test_thresholds_are_the_first_binary32_above_each_midpoint(L, kind):
     t = thr.astype(np.float64)
     below = np.nextafter(thr, np.float32(0)).astype(np.float64)
     assert np.all(t > mid) and np.all(below <= mid)
-    assert nbk <= 4096 - 260 and (0x3F80 - lo + 1) == nbk
+    hi = lo + nbk - 1  # first and last bucket hold no threshold
+    tb = thr.view(np.uint32)
+    assert nbk <= 4096 - 260 and (int(tb[0]) >> 16) == lo + 1 and (int(tb[126]) >> 16) == hi - 1 and hi <= 0x3F80
 
 
 @pytest.mark.parametrize("kind", KINDS)
 def test_code_search_equals_threshold_count_for_every_binary32_value(L, kind):
-    bad = ctypes.c_uint64(123)
-    assert L.dq8_internal_check_search(kind, ctypes.byref(bad)) == 0
-    assert bad.value == 0
+    bad, missed = ctypes.c_uint64(123), ctypes.c_uint64(123)
+    assert L.dq8_internal_check_search(kind, ctypes.byref(bad), ctypes.byref(missed)) == 0
+    assert bad.value == 0      # the flattened search is the threshold count, for every bit pattern
+    assert missed.value == 0   # and every value next to a threshold raises the proximity flag
+
+
+def _encode_host(L, kind, x, scale, use_reciprocal):
+    L.dq8_internal_encode_host.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float, ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_void_p]
+    x = np.ascontiguousarray(x, np.float32)
+    got = np.empty(x.size, np.uint8)
+    n_exact = ctypes.c_uint64()
+    assert L.dq8_internal_encode_host(kind, x.ctypes.data_as(ctypes.c_void_p), x.size, float(scale), int(use_reciprocal),
+                                      got.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n_exact)) == 0
+    return got, n_exact.value
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -101,27 +115,75 @@ def test_code_search_equals_the_oracle_on_normalised_values(L, kind):
     pos = np.concatenate([near, rng.random(300000).astype(np.float32),
                           np.exp(rng.uniform(-25, 0, 300000)).astype(np.float32), np.array([0, 1, 2.5], np.float32)])
     x = np.concatenate([pos, -pos])
-    got = np.empty(x.size, np.uint8)
-    L.dq8_internal_search.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
-    assert L.dq8_internal_search(kind, x.ctypes.data_as(ctypes.c_void_p), x.size, got.ctypes.data_as(ctypes.c_void_p)) == 0
     want, _ = oracle.encode(kind, x, 0, scales=np.ones(1, np.float32))
-    assert np.array_equal(got, want)
+    for recip in (0, 1):
+        got, _ = _encode_host(L, kind, x, 1.0, recip)
+        assert np.array_equal(got, want)
+
+
+def test_reciprocal_product_is_within_three_steps_of_the_quotient():
+    """The encoder's shortcut rests on |bits(x * fl(1/s)) - bits(fl(x / s))| <= 3 for normal results."""
+    rng = np.random.Generator(np.random.PCG64(78))
+    worst = 0
+    for rep in range(8):
+        n = 1 << 21
+        s = np.exp(rng.uniform(-60, 60, n)).astype(np.float32)
+        x = (s * rng.uniform(2.0 ** -27, 1.0, n)).astype(np.float32)
+        if rep % 2:  # mantissas at the edges of a binade are the worst case
+            s = (s.view(np.uint32) | np.uint32(0x7FFFF0)).view(np.float32) if rep % 4 == 1 else \
+                (s.view(np.uint32) & np.uint32(0xFF80000F)).view(np.float32)
+        r = (np.float32(1.0) / s).astype(np.float32)
+        q0 = (x * r).astype(np.float32)
+        q = (x / s).astype(np.float32)
+        d = np.abs(q0.view(np.int32).astype(np.int64) - q.view(np.int32).astype(np.int64))
+        worst = max(worst, int(d.max()))
+    assert worst <= 3, worst
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_reciprocal_path_matches_the_oracle_around_every_threshold(L, kind):
+    """Inputs built so that x / s lands on, and next to, every decision point, for awkward scales."""
+    cb = oracle.codebook(kind)[:128]
+    mid = ((cb[:-1].astype(np.float64) + cb[1:]) / 2)
+    rng = np.random.Generator(np.random.PCG64(79 + kind))
+    total_exact = 0
+    for s in [1.0, 3.0, 0.7310585975646973, 1e-3, 1.9999998807907104, 1.0000001192092896, 5e-20, 7e19, 2.0 ** -100,
+              2.0 ** 100, 1e-38, 3e38, 1.1e-30]:
+        s32 = np.float32(s)
+        base = (mid * float(s32)).astype(np.float32).view(np.int32).astype(np.int64)
+        x = (base[:, None] + np.arange(-12, 13)[None, :]).reshape(-1)
+        x = x[(x > 0) & (x < 0x7F800000)].astype(np.int32).view(np.float32)
+        x = x[np.abs(x) <= s32]
+        extra = (rng.random(20000) * float(s32)).astype(np.float32)
+        x = np.concatenate([x, -x, extra, -extra, np.array([s32, -s32, 0.0, -0.0], np.float32)])
+        want, _ = oracle.encode(kind, x, 0, scales=np.array([s32], np.float32))
+        got, n_exact = _encode_host(L, kind, x, s32, 1)
+        assert np.array_equal(got, want), s
+        got0, n_all = _encode_host(L, kind, x, s32, 0)
+        assert np.array_equal(got0, want) and n_all == x.size
+        total_exact += n_exact
+    assert total_exact > 0  # the fallback was exercised
 
 
 def test_launch_plan_covers_every_element_once(L):
-    L.dq8_internal_plan.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    L.dq8_internal_plan.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     out = (ctypes.c_size_t * 6)()
     for n, block in [(61100840, 4096), (61100840, 0), (1, 0), (4097, 4096), (100, 7), (10 ** 6, 6000), (5000, 10 ** 9),
                      (4096 * 5000, 8192), (12345, 1)]:
-        assert L.dq8_internal_plan(n, block, 256, out) == 0
-        B, nb, upb, units, waves, grid = list(out)
-        Bw = n if (block == 0 or block > n) else block
-        assert B == Bw and nb == (n + Bw - 1) // Bw and upb == (Bw + 4095) // 4096
-        covered = 0
-        full, last = divmod(n, Bw)
-        want_units = full * upb + (last + 4095) // 4096
-        assert units == want_units
-        assert waves == grid * 4 and 1 <= grid and waves <= 256 * 16 + 3
-        per_wave = -(-units // waves)
-        assert per_wave * waves < units + waves + per_wave * 4  # balanced: nobody walks more than one extra unit
-        del covered
+        for wpc, wpb in [(8, 1), (16, 1), (8, 4), (3, 4)]:
+            assert L.dq8_internal_plan(n, block, 256, wpc, wpb, out) == 0
+            B, nb, upb, units, teams, grid = list(out)
+            Bw = n if (block == 0 or block > n) else block
+            assert B == Bw and nb == (n + Bw - 1) // Bw and upb == (Bw + 4095) // 4096
+            full, last = divmod(n, Bw)
+            assert units == full * upb + (last + 4095) // 4096
+            assert teams == grid * (4 // wpb) and grid >= 1 and teams <= max(1, 256 * wpc // wpb) + 3
+            per_team = -(-units // teams)
+            assert (per_team - 1) * teams < units  # balanced: no team walks more than one unit more than another
+    assert L.dq8_internal_plan(10, 0, 256, 8, 3, out) == 3
+
+
+def test_tuning_keys(L):
+    assert L.dq8_internal_tune(b"enc_wpc", 8) == 0
+    assert L.dq8_internal_tune(b"enc_wpc", 99) == 3
+    assert L.dq8_internal_tune(b"nonsense", 1) == 3
