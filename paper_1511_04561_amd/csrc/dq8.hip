@@ -1,20 +1,24 @@
 // dq8 kernels and C ABI for gfx950 (MI355X).  See include/dq8.h for the contract.
 //
-// Work decomposition shared by every kernel: the array is cut into UNITS.  A unit is
-// a run of at most kUnit consecutive elements that lies inside one scale block, so
-// one scale applies to the whole unit: unit u = (block b, chunk c) covers elements
-// [b*B + c*kUnit, min(b*B + (c+1)*kUnit, (b+1)*B, n)).  One 64-lane wavefront owns a
-// unit at a time and walks units with a grid-wide stride; the host sizes the grid so
-// that every wavefront gets the same number of units and all of them are resident.
+// Work decomposition shared by every kernel: the array is cut into UNITS.  A unit is a run of
+// at most U consecutive elements that lies inside one scale block, so one scale applies to the
+// whole unit: unit u = (block b, chunk c) covers elements
+// [b*B + c*U, min(b*B + (c+1)*U, (b+1)*B, n)).  A 64-lane wavefront (or, in the fused encoder,
+// a team of four) owns a unit at a time and walks units with a grid-wide stride, so at any
+// moment the whole chip streams through one narrow window of each array; the host sizes the
+// grid so that every wavefront gets the same number of units and all of them are resident.
+// U is 4096 where a whole block has to be held (fused encoder) and Q * 256 elsewhere, Q being
+// the number of 128-bit accesses a lane keeps in flight.
 //
-// Inside a unit lane L owns elements 4*(64*it + L) .. +3 for it = 0..15: fp32 data
-// moves as one 128-bit access per lane (1 KiB contiguous per wave instruction) and
-// the matching four codes as one 32-bit access (256 B contiguous per instruction).
-// Units that are short, or whose addresses are not aligned for that, take a plain
-// strided element loop with identical arithmetic.
+// Inside a unit lane L owns elements 4*(64*it + L) .. +3: fp32 data moves as one 128-bit
+// access per lane (1 KiB contiguous per wave instruction) and the matching four codes as one
+// 32-bit access (256 B contiguous per instruction).  Units that are short, or whose addresses
+// are not aligned for that, take a plain strided element loop with identical arithmetic.
+// Every loop is software-pipelined: the loads of a wavefront's next unit are issued before
+// the current one is processed.
 //
-// Built with -ffp-contract=off: the decode-and-average sum must round the product
-// and the sum separately.  Divisions are the compiler's correctly rounded ones.
+// Built with -ffp-contract=off: the decode-and-average sum must round the product and the sum
+// separately.  Divisions are the compiler's correctly rounded ones.
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
@@ -41,7 +45,7 @@ constexpr int kWg = kWave * kWavesPerWg;
 constexpr int kUnit = 4096;                      // elements per unit
 constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
 constexpr int kKinds = 3;
-constexpr int kLutCopies = 32;                   // one copy of the decode table per LDS bank
+constexpr int kLutCopies = 64;                   // one copy of the decode table per lane
 constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -102,13 +106,12 @@ __host__ __device__ __forceinline__ float u2f(uint32_t u)
 
 __device__ __forceinline__ uint32_t abs_bits(float f) { return f2u(f) & 0x7FFFFFFFu; }
 
-__device__ __forceinline__ uint32_t max4_abs(v4f v, uint32_t m)
+// Running maximum of |v|.  Exact for finite inputs, subnormals included.
+__device__ __forceinline__ float max4_abs(v4f v, float m)
 {
-    uint32_t a = abs_bits(v.x), b = abs_bits(v.y), c = abs_bits(v.z), d = abs_bits(v.w);
-    a = a > b ? a : b;
-    c = c > d ? c : d;
-    a = a > c ? a : c;
-    return m > a ? m : a;
+    float a = __builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y));
+    float b = __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w));
+    return __builtin_fmaxf(m, __builtin_fmaxf(a, b));
 }
 
 // Geometry of unit u.  All values are wave-uniform.
@@ -118,53 +121,71 @@ struct Unit {
     uint32_t len;   // 1..kUnit
 };
 
-__device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t upb)
+// min(v, U) of a 64-bit count as 32 bits, U a power of two.  Written with a shift and a compare
+// against zero so that it stays on the scalar unit: a 64-bit ordered compare of uniform values
+// is done on the vector unit, and the compiler has been seen to drop the copy of such a result
+// into the scalar condition bit when a branch on the same result follows, leaving a select
+// that reads a stale condition (wrong unit lengths, accesses past the end of the arrays).
+template <int U>
+__device__ __forceinline__ uint32_t cap_to_unit(size_t v)
+{
+    static_assert(U > 0 && (U & (U - 1)) == 0, "unit sizes are powers of two");
+    return (v >> __builtin_ctz(U)) != 0 ? (uint32_t)U : (uint32_t)v;
+}
+
+template <int U>
+__device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb, size_t upb)
 {
     Unit r;
     size_t c;
     if (upb == 1) {
         r.block = u;
         c = 0;
-    } else if (B >= n) {
+    } else if (nb == 1) {
         r.block = 0;
         c = u;
     } else {
         r.block = u / upb;
         c = u - r.block * upb;
     }
-    size_t off = c * (size_t)kUnit;
+    const size_t off = c * (size_t)U;
     r.start = r.block * B + off;
-    size_t len = B - off;
-    if (len > (size_t)kUnit) len = kUnit;
-    if (len > n - r.start) len = n - r.start;
-    r.len = (uint32_t)len;
+    const uint32_t in_block = cap_to_unit<U>(B - off), in_array = cap_to_unit<U>(n - r.start);
+    r.len = in_block < in_array ? in_block : in_array;
     return r;
 }
 
 // Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range.
 struct Search {
     const uint32_t *bucket;  // LDS on the device
-    uint32_t lo_key, lo_bits, hi_bits;
+    uint32_t lo_base;        // lo_key << 16
+    float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
 };
 
 __host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket)
 {
     Search s;
     s.bucket = bucket;
-    s.lo_key = lo_key;
-    s.lo_bits = (lo_key << 16) + 0x8000u;
-    s.hi_bits = ((lo_key + n_bucket - 1) << 16) + 0x8000u;
+    s.lo_base = lo_key << 16;
+    s.lo_f = u2f((lo_key << 16) + 0x8000u);
+    s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
     return s;
 }
 
 // sum >> 16 = number of thresholds <= |xn|; the low half of sum measures the distance to
-// the threshold of the bucket.
+// the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
+// so the clamp is done on the value.
 __host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
 {
-    uint32_t a = f2u(xn) & 0x7FFFFFFFu;
-    a = a < s.lo_bits ? s.lo_bits : a;
-    a = a > s.hi_bits ? s.hi_bits : a;
-    return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float c = __builtin_amdgcn_fmed3f(__builtin_fabsf(xn), s.lo_f, s.hi_f);
+#else
+    float c = __builtin_fabsf(xn);
+    c = c >= s.lo_f ? c : s.lo_f;  // also takes NaN to the low end; inputs are finite anyway
+    c = c <= s.hi_f ? c : s.hi_f;
+#endif
+    const uint32_t a = f2u(c) - s.lo_base;
+    return s.bucket[a >> 16] + (a & 0xFFFFu);
 }
 
 // (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
@@ -174,6 +195,18 @@ __host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (su
 __host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
 
 __host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_from(search_sum(s, x / d), x); }
+
+// Four codes in one word: byte i = magnitude index of sum i (its byte 2) with the sign bit of
+// x i (top bit of its byte 3).  v_perm_b32 gathers the bytes: selector byte 0..3 picks a byte
+// of the second operand, 4..7 of the first, 0x0C gives zero.
+__device__ __forceinline__ uint32_t pack_codes(uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
+{
+    const uint32_t m01 = __builtin_amdgcn_perm(s1, s0, 0x0C0C0602u);
+    const uint32_t m23 = __builtin_amdgcn_perm(s3, s2, 0x06020C0Cu);
+    const uint32_t g01 = __builtin_amdgcn_perm(f2u(v.y), f2u(v.x), 0x0C0C0703u);
+    const uint32_t g23 = __builtin_amdgcn_perm(f2u(v.w), f2u(v.z), 0x07030C0Cu);
+    return ((g01 | g23) & 0x80808080u) | m01 | m23;
+}
 
 // A scale qualifies for the reciprocal path when 1/d and every product x * (1/d) that can
 // reach a threshold are normal numbers: 2^-100 <= d <= 2^100.
@@ -191,17 +224,15 @@ template <bool FASTDIV>
 __device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d, float r, bool recip)
 {
     if (FASTDIV && recip) {
-        uint32_t s0 = search_sum(sr, v.x * r), s1 = search_sum(sr, v.y * r);
-        uint32_t s2 = search_sum(sr, v.z * r), s3 = search_sum(sr, v.w * r);
+        const uint32_t s0 = search_sum(sr, v.x * r), s1 = search_sum(sr, v.y * r);
+        const uint32_t s2 = search_sum(sr, v.z * r), s3 = search_sum(sr, v.w * r);
         uint32_t k0 = near_key(s0), k1 = near_key(s1), k2 = near_key(s2), k3 = near_key(s3);
         k0 = k0 < k1 ? k0 : k1;
         k2 = k2 < k3 ? k2 : k3;
         k0 = k0 < k2 ? k0 : k2;
-        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0)
-            return code_from(s0, v.x) | (code_from(s1, v.y) << 8) | (code_from(s2, v.z) << 16) | (code_from(s3, v.w) << 24);
+        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(s0, s1, s2, s3, v);
     }
-    return code_exact(sr, v.x, d) | (code_exact(sr, v.y, d) << 8) | (code_exact(sr, v.z, d) << 16) |
-           (code_exact(sr, v.w, d) << 24);
+    return pack_codes(search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
 }
 
 template <bool FASTDIV>
@@ -214,25 +245,49 @@ __device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float 
     return code_exact(sr, x, d);
 }
 
+// Copies the bucket table to LDS; the caller synchronises the workgroup before using it.
 __device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds)
 {
     uint32_t nbk = tab[kNBucketOff];
     for (uint32_t i = threadIdx.x; i < nbk; i += kWg) lds[i] = tab[kBucketOff + i];
-    __syncthreads();
     return make_search(lds, tab[kLoKeyOff], nbk);
 }
 
-// Decode table replicated once per LDS bank: entry (code, copy) at code * 32 + copy.
+// Decode table in LDS, one copy per lane: entry (code, lane) at byte address code * 256 +
+// lane * 4.  Lanes L and L + 32 share a bank but are served in different halves of the access,
+// so a lookup never conflicts, and the address is two byte fields - code in byte 1, lane * 4 in
+// byte 0 - which one v_perm_b32 assembles straight from a packed word of four codes.
+// Thread t < 256 owns code t (workgroups have at least 256 threads).  The caller synchronises before the
+// first lookup.
 __device__ __forceinline__ void load_lut(const uint32_t *tab, float *lds)
 {
-    for (uint32_t i = threadIdx.x; i < 256 * kLutCopies; i += kWg) lds[i] = u2f(tab[kCbOff + (i / kLutCopies)]);
-    __syncthreads();
+    if (threadIdx.x < 256) {
+        const float val = u2f(tab[kCbOff + threadIdx.x]);
+        const v4f four = {val, val, val, val};
+        v4f *row = reinterpret_cast<v4f *>(lds + threadIdx.x * kLutCopies);
+#pragma unroll
+        for (int c = 0; c < kLutCopies / 4; ++c) row[c] = four;
+    }
+}
+
+// Table value of code number J (0..3) of the packed word w, for the lane whose byte offset
+// into a table row is lane4 = lane * 4.
+template <int J>
+__device__ __forceinline__ float lut_at(const float *lut, uint32_t w, uint32_t lane4)
+{
+    const uint32_t addr = __builtin_amdgcn_perm(w, lane4, 0x0C0C0400u + (J << 8));
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + addr);
+}
+
+__device__ __forceinline__ float lut_code(const float *lut, uint32_t code, uint32_t lane4)
+{
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + ((code << 8) | lane4));
 }
 
 __device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
-__device__ __forceinline__ size_t first_unit() { return (size_t)blockIdx.x * kWavesPerWg + wave_in_wg(); }
+__device__ __forceinline__ size_t first_unit(int waves_per_wg = kWavesPerWg) { return (size_t)blockIdx.x * waves_per_wg + wave_in_wg(); }
 
 // ---------------------------------------------------------------- kernels
 
@@ -242,69 +297,80 @@ __global__ void k_fill_zero(float *p, size_t n)
     if (i < n) p[i] = 0.0f;
 }
 
-// Plain fp32 copy with the access pattern of the codec kernels (one unit per wavefront step,
+// Plain fp32 copy with the access pattern of the codec kernels (units of Q * 256 elements,
 // 128-bit accesses).  Exists to calibrate bandwidth and hardware-counter readings against a
 // kernel whose traffic is known exactly: 4 bytes read and 4 bytes written per element.
 template <int Q, bool NT>
 __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, float *__restrict__ dst, size_t n,
                                              size_t n_units, size_t n_waves)
 {
+    constexpr int U = Q * 4 * kWave;
     const uint32_t lane = threadIdx.x & 63;
     for (size_t u = first_unit(); u < n_units; u += n_waves) {
-        Unit un = unit_of(u, n, n, 0);
+        Unit un = unit_of<U>(u, n, n, 1, 0);
         const float *ps = src + un.start;
         float *pd = dst + un.start;
-        if (un.len == kUnit && (((uintptr_t)ps | (uintptr_t)pd) & 15) == 0) {
+        if (un.len == U && (((uintptr_t)ps | (uintptr_t)pd) & 15) == 0) {
             const v4f *s4 = reinterpret_cast<const v4f *>(ps);
             v4f *d4 = reinterpret_cast<v4f *>(pd);
-#pragma clang loop unroll(disable)
-            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
-                v4f v[Q];
+            v4f v[Q];
 #pragma unroll
-                for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(s4 + (sub * Q + j) * kWave + lane);
+            for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(s4 + j * kWave + lane);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) stg<NT>(d4 + (sub * Q + j) * kWave + lane, v[j]);
-            }
+            for (int j = 0; j < Q; ++j) stg<NT>(d4 + j * kWave + lane, v[j]);
         } else {
             for (uint32_t i = lane; i < un.len; i += kWave) pd[i] = ps[i];
         }
     }
 }
 
-// Block maxima.  One wavefront per unit, Q quads per lane in flight.  upb == 1: each unit is
-// a whole block and stores its maximum.  upb > 1: scales[] was zeroed and the units of a block
-// merge with an integer atomic max (non-negative binary32 numbers order like their bits).
+// Block maxima.  One wavefront per unit of Q * 256 elements.  upb == 1: each unit is a whole
+// block and stores its maximum.  upb > 1: scales[] was zeroed and the units of a block merge
+// with an integer atomic max (non-negative binary32 numbers order like their bit patterns).
 template <int Q, bool NT>
-__global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t upb,
+__global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t nb, size_t upb,
                                                size_t n_units, size_t n_waves, float *__restrict__ scales)
 {
+    constexpr int U = Q * 4 * kWave;
     const uint32_t lane = threadIdx.x & 63;
-    for (size_t u = first_unit(); u < n_units; u += n_waves) {
-        Unit un = unit_of(u, n, B, upb);
-        const float *px = x + un.start;
-        uint32_t m = 0;
-        if (un.len == kUnit && ((uintptr_t)px & 15) == 0) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(px);
-#pragma clang loop unroll(disable)
-            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
-                v4f v[Q];
+    size_t u = first_unit();
+    Unit un;
+    bool fast = false;
+    v4f v[Q];
+    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
+        q = unit_of<U>(uu, n, B, nb, upb);
+        f = q.len == U && ((uintptr_t)(x + q.start) & 15) == 0;
+        if (f) {
+            const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(p4 + (sub * Q + j) * kWave + lane);
+            for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(p4 + j * kWave + lane);
+        }
+    };
+    if (u < n_units) open_unit(u, un, fast);
+    while (u < n_units) {
+        uint32_t m;
+        if (fast) {
+            float fm = 0.0f;
 #pragma unroll
-                for (int j = 0; j < Q; ++j) m = max4_abs(v[j], m);
-            }
+            for (int j = 0; j < Q; ++j) fm = max4_abs(v[j], fm);
+            m = f2u(fm);
         } else {
+            const float *px = x + un.start;
+            m = 0;
             for (uint32_t i = lane; i < un.len; i += kWave) {
                 uint32_t a = abs_bits(px[i]);
                 m = m > a ? m : a;
             }
         }
+        const size_t blk = un.block;
+        u += n_waves;
+        if (u < n_units) open_unit(u, un, fast);  // next unit's loads fly during the reduction
         m = wave_max_u32(m);
         if (lane == 0) {
             if (upb == 1)
-                scales[un.block] = u2f(m);
+                scales[blk] = u2f(m);
             else
-                atomicMax(reinterpret_cast<unsigned int *>(scales) + un.block, m);
+                atomicMax(reinterpret_cast<unsigned int *>(scales) + blk, m);
         }
     }
 }
@@ -315,50 +381,65 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
 // FUSED: a unit is a whole block (upb == 1); the team reduces the block's maximum from
 // registers, stores it and quantises the same registers.  Otherwise the scale of the unit's
 // block is read from scales[].
+// The loop is software-pipelined: the loads of a team's next unit are issued before the
+// current unit is reduced and quantised, so each wavefront always has loads in flight.
 template <int WPB, bool NT, bool FUSED, bool FASTDIV>
-__global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
-                                               size_t B, size_t upb, size_t n_units, size_t n_teams,
-                                               float *__restrict__ scales, uint8_t *__restrict__ codes)
-{
-    static_assert(WPB == 1 || WPB == kWavesPerWg, "a team is one wavefront or the whole workgroup");
-    constexpr int Q = kUnitQuads / WPB;
-    constexpr uint32_t TEAM = kWave * WPB;
-    extern __shared__ uint32_t lds[];
-    uint32_t *slots = lds;  // kTeamSlots words
-    const Search sr = load_bucket_table(tab, lds + kTeamSlots);
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t wave = wave_in_wg();
-    const uint32_t tl = WPB == 1 ? lane : threadIdx.x;  // index inside the team
-    uint32_t phase = 0;
-    for (size_t u = (WPB == 1 ? first_unit() : (size_t)blockIdx.x); u < n_units; u += n_teams) {
-        Unit un = unit_of(u, n, B, upb);
-        const float *px = x + un.start;
-        uint8_t *pc = codes + un.start;
-        const bool fast = un.len == kUnit && ((uintptr_t)px & 15) == 0 && ((uintptr_t)pc & 3) == 0;
+struct Encoder {
+    static constexpr int Q = kUnitQuads / WPB;
+    static constexpr uint32_t TEAM = kWave * WPB;
+
+    const float *x;
+    uint8_t *codes;
+    float *scales;
+    size_t n, B, nb, upb;
+    uint32_t *slots;
+    Search sr;
+    uint32_t lane, wave, tl, phase;
+
+    struct Slot {
+        Unit un;
+        bool fast;
         v4f v[Q];
-        uint32_t m = 0;
-        if (fast) {
+    };
+
+    __device__ __forceinline__ void fetch(size_t u, Slot &sl) const
+    {
+        sl.un = unit_of<kUnit>(u, n, B, nb, upb);
+        const float *px = x + sl.un.start;
+        sl.fast = sl.un.len == kUnit && ((uintptr_t)px & 15) == 0 && ((uintptr_t)(codes + sl.un.start) & 3) == 0;
+        if (sl.fast) {
             const v4f *p4 = reinterpret_cast<const v4f *>(px);
 #pragma unroll
-            for (int it = 0; it < Q; ++it) v[it] = ldg<NT>(p4 + it * TEAM + tl);
-            if (FUSED) {
-#pragma unroll
-                for (int it = 0; it < Q; ++it) m = max4_abs(v[it], m);
-            }
-        } else if (FUSED) {
-            for (uint32_t i = tl; i < un.len; i += TEAM) {
-                uint32_t a = abs_bits(px[i]);
-                m = m > a ? m : a;
-            }
+            for (int it = 0; it < Q; ++it) sl.v[it] = ldg<NT>(p4 + it * TEAM + tl);
         }
+    }
+
+    __device__ __forceinline__ void process(Slot &sl)
+    {
+        const Unit &un = sl.un;
+        const float *px = x + un.start;
+        uint8_t *pc = codes + un.start;
         float s;
         if (FUSED) {
+            uint32_t m;
+            if (sl.fast) {
+                float fm = 0.0f;
+#pragma unroll
+                for (int it = 0; it < Q; ++it) fm = max4_abs(sl.v[it], fm);
+                m = f2u(fm);
+            } else {
+                m = 0;
+                for (uint32_t i = tl; i < un.len; i += TEAM) {
+                    uint32_t a = abs_bits(px[i]);
+                    m = m > a ? m : a;
+                }
+            }
             m = wave_max_u32(m);
             if (WPB > 1) {
                 if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
                 __syncthreads();  // every wavefront of the workgroup walks the same units
-                const uint32_t *sl = slots + phase * kWavesPerWg;
-                uint32_t a = sl[0] > sl[1] ? sl[0] : sl[1], b = sl[2] > sl[3] ? sl[2] : sl[3];
+                const uint32_t *sp = slots + phase * kWavesPerWg;
+                uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
                 m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
                 phase ^= 1;  // the other half of slots next time: one barrier per unit is enough
             }
@@ -370,132 +451,205 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
         const float d = s == 0.0f ? 1.0f : s;  // a zero scale leaves the value as it is
         const float r = 1.0f / d;
         const bool recip = reciprocal_ok(d);
-        if (fast) {
+        if (sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
 #pragma unroll
-            for (int it = 0; it < Q; ++it) stg<NT>(c4 + it * TEAM + tl, encode_quad<FASTDIV>(sr, v[it], d, r, recip));
+            for (int it = 0; it < Q; ++it) stg<NT>(c4 + it * TEAM + tl, encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip));
         } else {
             for (uint32_t i = tl; i < un.len; i += TEAM) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
         }
     }
+};
+
+template <int WPB, bool NT, bool FUSED, bool FASTDIV>
+__global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
+                                               size_t B, size_t nb, size_t upb, size_t n_units, size_t n_teams,
+                                               float *__restrict__ scales, uint8_t *__restrict__ codes)
+{
+    static_assert(WPB == 1 || WPB == kWavesPerWg, "a team is one wavefront or the whole workgroup");
+    using Enc = Encoder<WPB, NT, FUSED, FASTDIV>;
+    extern __shared__ uint32_t lds[];
+    Enc e;
+    e.x = x;
+    e.codes = codes;
+    e.scales = scales;
+    e.n = n;
+    e.B = B;
+    e.nb = nb;
+    e.upb = upb;
+    e.slots = lds;  // kTeamSlots words, then the bucket table
+    e.lane = threadIdx.x & 63;
+    e.wave = wave_in_wg();
+    e.tl = WPB == 1 ? e.lane : threadIdx.x;
+    e.phase = 0;
+    size_t u = WPB == 1 ? first_unit() : (size_t)blockIdx.x;
+    typename Enc::Slot a, b;
+    if (u < n_units) e.fetch(u, a);  // the first loads are in flight while the table is copied
+    e.sr = load_bucket_table(tab, lds + kTeamSlots);
+    __syncthreads();
+    while (u < n_units) {
+        size_t nx = u + n_teams;
+        if (nx < n_units) e.fetch(nx, b);
+        e.process(a);
+        u = nx;
+        if (!(u < n_units)) break;
+        nx = u + n_teams;
+        if (nx < n_units) e.fetch(nx, a);
+        e.process(b);
+        u = nx;
+    }
 }
 
-// Decompression of one buffer: out = table[code] * scale.  Q code words (4 codes each) per
-// lane in flight.
-template <int Q, bool NT>
-__global__ __launch_bounds__(kWg) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
-                                               const float *__restrict__ scales, size_t n, size_t B, size_t upb,
-                                               size_t n_units, size_t n_waves, float *__restrict__ out)
+// Decompression of one buffer: out = table[code] * scale.  One wavefront per unit of Q * 256
+// elements: Q code words (4 codes each) per lane; the next unit's words are loaded before the
+// current ones are expanded.
+template <int Q, bool NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
+                                                       const float *__restrict__ scales, size_t n, size_t B, size_t nb,
+                                                       size_t upb, size_t n_units, size_t n_waves, float *__restrict__ out)
 {
-    __shared__ float lut[256 * kLutCopies];
-    load_lut(tab, lut);
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int U = Q * 4 * kWave;
     const uint32_t lane = threadIdx.x & 63;
-    const float *my = lut + (lane & (kLutCopies - 1));
-    for (size_t u = first_unit(); u < n_units; u += n_waves) {
-        Unit un = unit_of(u, n, B, upb);
-        const uint8_t *pc = codes + un.start;
-        float *po = out + un.start;
+    const uint32_t lane4 = lane * 4;
+    size_t u = first_unit(WPW);
+    Unit un;
+    bool fast = false;
+    uint32_t w[Q];
+    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
+        q = unit_of<U>(uu, n, B, nb, upb);
+        f = q.len == U && ((uintptr_t)(out + q.start) & 15) == 0 && ((uintptr_t)(codes + q.start) & 3) == 0;
+        if (f) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes + q.start);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + j * kWave + lane);
+        }
+    };
+    if (u < n_units) open_unit(u, un, fast);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    while (u < n_units) {
         const float s = scales[un.block];
-        if (un.len == kUnit && ((uintptr_t)po & 15) == 0 && ((uintptr_t)pc & 3) == 0) {
-            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(pc);
+        float *po = out + un.start;
+        if (fast) {
+            uint32_t cur[Q];
+#pragma unroll
+            for (int j = 0; j < Q; ++j) cur[j] = w[j];
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast);
             v4f *o4 = reinterpret_cast<v4f *>(po);
-#pragma clang loop unroll(disable)
-            for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
-                uint32_t w[Q];
 #pragma unroll
-                for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + (sub * Q + j) * kWave + lane);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    v4f r;
-                    r.x = my[(w[j] & 0xFFu) * kLutCopies] * s;
-                    r.y = my[((w[j] >> 8) & 0xFFu) * kLutCopies] * s;
-                    r.z = my[((w[j] >> 16) & 0xFFu) * kLutCopies] * s;
-                    r.w = my[(w[j] >> 24) * kLutCopies] * s;
-                    stg<NT>(o4 + (sub * Q + j) * kWave + lane, r);
-                }
+            for (int j = 0; j < Q; ++j) {
+                v4f r;
+                r.x = lut_at<0>(lut, cur[j], lane4) * s;
+                r.y = lut_at<1>(lut, cur[j], lane4) * s;
+                r.z = lut_at<2>(lut, cur[j], lane4) * s;
+                r.w = lut_at<3>(lut, cur[j], lane4) * s;
+                stg<NT>(o4 + j * kWave + lane, r);
             }
         } else {
-            for (uint32_t i = lane; i < un.len; i += kWave) po[i] = my[(uint32_t)pc[i] * kLutCopies] * s;
+            const uint8_t *pc = codes + un.start;
+            for (uint32_t i = lane; i < un.len; i += kWave) po[i] = lut_code(lut, pc[i], lane4) * s;
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast);
         }
     }
 }
 
 // Decompress K buffers and average: acc = +0; acc += table[code_k] * scale_k for k = 0..K-1
 // in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled, Q code words per
-// lane and worker in flight), KT == 0 reads K from the argument.
-template <int KT, int Q, bool NT>
-__global__ __launch_bounds__(kWg) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt, size_t n,
-                                                   size_t B, size_t upb, size_t n_units, size_t n_waves,
-                                                   float *__restrict__ out)
+// lane and worker per unit, next unit's words requested before the current ones are used);
+// KT == 0 reads K from the argument.
+template <int KT, int Q, bool NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt,
+                                                           size_t n, size_t B, size_t nb, size_t upb, size_t n_units,
+                                                           size_t n_waves, float *__restrict__ out)
 {
-    __shared__ float lut[256 * kLutCopies];
-    load_lut(tab, lut);
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int KA = KT > 0 ? KT : 1;
+    constexpr int U = Q * 4 * kWave;
     const int K = KT > 0 ? KT : K_rt;
     const float fk = (float)K;
     const uint32_t lane = threadIdx.x & 63;
-    const float *my = lut + (lane & (kLutCopies - 1));
-    constexpr int KA = KT > 0 ? KT : 1;
-    for (size_t u = first_unit(); u < n_units; u += n_waves) {
-        Unit un = unit_of(u, n, B, upb);
+    const uint32_t lane4 = lane * 4;
+    size_t u = first_unit(WPW);
+    Unit un;
+    bool fast = false;
+    uint32_t w[KA][Q];
+    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
+        q = unit_of<U>(uu, n, B, nb, upb);
+        f = q.len == U && ((uintptr_t)(out + q.start) & 15) == 0;
+        for (int k = 0; k < K; ++k) f = f && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
+        if (KT > 0 && f) {
+#pragma unroll
+            for (int k = 0; k < KA; ++k) {
+                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + q.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + j * kWave + lane);
+            }
+        }
+    };
+    if (u < n_units) open_unit(u, un, fast);
+    load_lut(tab, lut);
+    __syncthreads();
+    while (u < n_units) {
         float *po = out + un.start;
-        bool fast = un.len == kUnit && ((uintptr_t)po & 15) == 0;
-        for (int k = 0; k < K; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
-        if (fast) {
+        if (fast && KT > 0) {
+            float sc[KA];
+#pragma unroll
+            for (int k = 0; k < KA; ++k) sc[k] = p.scales[k][un.block];
+            uint32_t cur[KA][Q];
+#pragma unroll
+            for (int k = 0; k < KA; ++k)
+#pragma unroll
+                for (int j = 0; j < Q; ++j) cur[k][j] = w[k][j];
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast);
             v4f *o4 = reinterpret_cast<v4f *>(po);
-            if (KT > 0) {
-                float sc[KA];
 #pragma unroll
-                for (int k = 0; k < KA; ++k) sc[k] = p.scales[k][un.block];
-#pragma clang loop unroll(disable)
-                for (int sub = 0; sub < kUnitQuads / Q; ++sub) {
-                    uint32_t w[KA][Q];
+            for (int j = 0; j < Q; ++j) {
+                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                    for (int k = 0; k < KA; ++k) {
-                        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
-#pragma unroll
-                        for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + (sub * Q + j) * kWave + lane);
-                    }
-#pragma unroll
-                    for (int j = 0; j < Q; ++j) {
-                        v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                        for (int k = 0; k < KA; ++k) {
-                            a.x = a.x + my[(w[k][j] & 0xFFu) * kLutCopies] * sc[k];
-                            a.y = a.y + my[((w[k][j] >> 8) & 0xFFu) * kLutCopies] * sc[k];
-                            a.z = a.z + my[((w[k][j] >> 16) & 0xFFu) * kLutCopies] * sc[k];
-                            a.w = a.w + my[(w[k][j] >> 24) * kLutCopies] * sc[k];
-                        }
-                        a.x = a.x / fk;
-                        a.y = a.y / fk;
-                        a.z = a.z / fk;
-                        a.w = a.w / fk;
-                        stg<NT>(o4 + (sub * Q + j) * kWave + lane, a);
-                    }
+                for (int k = 0; k < KA; ++k) {
+                    a.x = a.x + lut_at<0>(lut, cur[k][j], lane4) * sc[k];
+                    a.y = a.y + lut_at<1>(lut, cur[k][j], lane4) * sc[k];
+                    a.z = a.z + lut_at<2>(lut, cur[k][j], lane4) * sc[k];
+                    a.w = a.w + lut_at<3>(lut, cur[k][j], lane4) * sc[k];
                 }
-            } else {
-                for (int it = 0; it < kUnitQuads; ++it) {
+                a.x = a.x / fk;
+                a.y = a.y / fk;
+                a.z = a.z / fk;
+                a.w = a.w / fk;
+                stg<NT>(o4 + j * kWave + lane, a);
+            }
+        } else {
+            if (fast) {
+                v4f *o4 = reinterpret_cast<v4f *>(po);
+                for (int j = 0; j < Q; ++j) {
                     v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
                     for (int k = 0; k < K; ++k) {
-                        const uint32_t w = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + it * kWave + lane);
+                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + j * kWave + lane);
                         const float s = p.scales[k][un.block];
-                        a.x = a.x + my[(w & 0xFFu) * kLutCopies] * s;
-                        a.y = a.y + my[((w >> 8) & 0xFFu) * kLutCopies] * s;
-                        a.z = a.z + my[((w >> 16) & 0xFFu) * kLutCopies] * s;
-                        a.w = a.w + my[(w >> 24) * kLutCopies] * s;
+                        a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
+                        a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
+                        a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
+                        a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
                     }
                     a.x = a.x / fk;
                     a.y = a.y / fk;
                     a.z = a.z / fk;
                     a.w = a.w / fk;
-                    stg<NT>(o4 + it * kWave + lane, a);
+                    stg<NT>(o4 + j * kWave + lane, a);
+                }
+            } else {
+                for (uint32_t i = lane; i < un.len; i += kWave) {
+                    float a = 0.0f;
+                    for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+                    po[i] = a / fk;
                 }
             }
-        } else {
-            for (uint32_t i = lane; i < un.len; i += kWave) {
-                float a = 0.0f;
-                for (int k = 0; k < K; ++k) a = a + my[(uint32_t)p.codes[k][un.start + i] * kLutCopies] * p.scales[k][un.block];
-                po[i] = a / fk;
-            }
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast);
         }
     }
 }
@@ -572,8 +726,10 @@ struct Tuning {
     int amax_wpc = 8;
     int dec_q = 4;       // decode: code words per lane in flight
     int dec_wpc = 8;
+    int dec_wpw = 4;     // decode: wavefronts per workgroup (they share one table in LDS)
     int avg_q = 2;       // decode-and-average: code words per lane and worker in flight
     int avg_wpc = 8;
+    int avg_wpw = 4;
     int copy_q = 4;
     int copy_wpc = 8;
 };
@@ -585,23 +741,24 @@ struct Plan {
 };
 
 // Units, and a grid in which every team (wpb wavefronts) walks the same number of them.
-Plan make_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb)
+Plan make_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, int waves_per_wg = kWavesPerWg,
+               size_t unit = kUnit)
 {
     Plan p;
     p.B = (block == 0 || block > n) ? n : block;
     p.nb = (n + p.B - 1) / p.B;
-    p.upb = (p.B + kUnit - 1) / kUnit;
+    p.upb = (p.B + unit - 1) / unit;
     if (p.nb == 1) {
-        p.n_units = (n + kUnit - 1) / kUnit;
+        p.n_units = (n + unit - 1) / unit;
     } else {
         size_t last = n - (p.nb - 1) * p.B;  // the last block may be short
-        p.n_units = (p.nb - 1) * p.upb + (last + kUnit - 1) / kUnit;
+        p.n_units = (p.nb - 1) * p.upb + (last + unit - 1) / unit;
     }
     size_t max_teams = (size_t)cus * (size_t)waves_per_cu / (size_t)wpb;
     if (max_teams < 1) max_teams = 1;
     size_t per_team = (p.n_units + max_teams - 1) / max_teams;
     size_t teams = (p.n_units + per_team - 1) / per_team;
-    size_t teams_per_wg = kWavesPerWg / wpb;
+    size_t teams_per_wg = (size_t)waves_per_wg / wpb;
     size_t grid = (teams + teams_per_wg - 1) / teams_per_wg;
     p.grid = (unsigned)grid;
     p.n_teams = grid * teams_per_wg;
@@ -629,7 +786,8 @@ int after_launch(const char *what)
 
 int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block, float *scales, hipStream_t stream)
 {
-    Plan p = make_plan(n, block, st.cus, g_tune.amax_wpc, 1);
+    const int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
+    Plan p = make_plan(n, block, st.cus, g_tune.amax_wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
     if (p.upb > 1) {
         unsigned g = (unsigned)((p.nb + 255) / 256);
         hipLaunchKernelGGL(k_fill_zero, dim3(g), dim3(256), 0, stream, scales, p.nb);
@@ -637,10 +795,10 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
         if (rc) return rc;
     }
 #define DQ8_AMAX(Q, NT)                                                                                          \
-    hipLaunchKernelGGL((k_absmax<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, x, n, p.B, p.upb, p.n_units, p.n_teams, \
-                       scales)
+    hipLaunchKernelGGL((k_absmax<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, x, n, p.B, p.nb, p.upb, p.n_units, \
+                       p.n_teams, scales)
 #define DQ8_AMAX_Q(NT)                      \
-    switch (g_tune.amax_q) {                \
+    switch (q) {                            \
     case 1: DQ8_AMAX(1, NT); break;         \
     case 2: DQ8_AMAX(2, NT); break;         \
     case 8: DQ8_AMAX(8, NT); break;         \
@@ -665,8 +823,8 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.n_bucket[kind] + kTeamSlots) * sizeof(uint32_t);
 #define DQ8_ENC(WPB, NT, FUSED, FD)                                                                              \
-    hipLaunchKernelGGL((k_encode<WPB, NT, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.upb, \
-                       p.n_units, p.n_teams, scales, codes)
+    hipLaunchKernelGGL((k_encode<WPB, NT, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
+                       p.upb, p.n_units, p.n_teams, scales, codes)
 #define DQ8_ENC_FD(WPB, NT, FUSED)       \
     if (g_tune.fastdiv) {                \
         DQ8_ENC(WPB, NT, FUSED, true);   \
@@ -769,21 +927,28 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, block, st->cus, g_tune.dec_wpc, 1);
+    const int wpw = g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4);
+    const int q = (g_tune.dec_q == 2 || g_tune.dec_q == 8 || g_tune.dec_q == 16) ? g_tune.dec_q : 4;
+    Plan p = make_plan(n, block, st->cus, g_tune.dec_wpc, 1, wpw, (size_t)q * 4 * kWave);
     if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
         return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-#define DQ8_DEC(Q, NT)                                                                                              \
-    hipLaunchKernelGGL((k_decode<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, tab, codes, scales, n, p.B, p.upb, p.n_units, \
-                       p.n_teams, out)
-#define DQ8_DEC_Q(NT)                    \
-    switch (g_tune.dec_q) {              \
-    case 1: DQ8_DEC(1, NT); break;       \
-    case 2: DQ8_DEC(2, NT); break;       \
-    case 8: DQ8_DEC(8, NT); break;       \
-    case 16: DQ8_DEC(16, NT); break;     \
-    default: DQ8_DEC(4, NT); break;      \
+#define DQ8_DEC(Q, NT, WPW)                                                                                       \
+    hipLaunchKernelGGL((k_decode<Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
+                       p.nb, p.upb, p.n_units, p.n_teams, out)
+#define DQ8_DEC_W(Q, NT)                     \
+    switch (wpw) {                           \
+    case 16: DQ8_DEC(Q, NT, 16); break;      \
+    case 8: DQ8_DEC(Q, NT, 8); break;        \
+    default: DQ8_DEC(Q, NT, 4); break;       \
+    }
+#define DQ8_DEC_Q(NT)                        \
+    switch (q) {                             \
+    case 2: DQ8_DEC_W(2, NT) break;          \
+    case 8: DQ8_DEC_W(8, NT) break;          \
+    case 16: DQ8_DEC_W(16, NT) break;        \
+    default: DQ8_DEC_W(4, NT) break;         \
     }
     if (g_tune.nt) {
         DQ8_DEC_Q(true)
@@ -791,6 +956,7 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
         DQ8_DEC_Q(false)
     }
 #undef DQ8_DEC_Q
+#undef DQ8_DEC_W
 #undef DQ8_DEC
     return after_launch("k_decode");
 }
@@ -807,7 +973,10 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, block, st->cus, g_tune.avg_wpc, 1);
+    const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
+    const bool fixed_k = K == 2 || K == 4 || K == 8;
+    const int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
+    Plan p = make_plan(n, block, st->cus, g_tune.avg_wpc, 1, wpw, (size_t)q * 4 * kWave);
     WorkerPtrs wp;
     std::memset(&wp, 0, sizeof(wp));
     for (int k = 0; k < K; ++k) {
@@ -819,20 +988,26 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     }
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-#define DQ8_AVG(KT, Q, NT)                                                                                        \
-    hipLaunchKernelGGL((k_decode_avg<KT, Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, tab, wp, K, n, p.B, p.upb,  \
-                       p.n_units, p.n_teams, out)
-#define DQ8_AVG_Q(KT, NT)                \
-    switch (g_tune.avg_q) {              \
-    case 1: DQ8_AVG(KT, 1, NT); break;   \
-    case 4: DQ8_AVG(KT, 4, NT); break;   \
-    default: DQ8_AVG(KT, 2, NT); break;  \
+#define DQ8_AVG(KT, Q, NT, WPW)                                                                                   \
+    hipLaunchKernelGGL((k_decode_avg<KT, Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
+                       p.nb, p.upb, p.n_units, p.n_teams, out)
+#define DQ8_AVG_W(KT, Q, NT)                 \
+    switch (wpw) {                           \
+    case 16: DQ8_AVG(KT, Q, NT, 16); break;  \
+    case 8: DQ8_AVG(KT, Q, NT, 8); break;    \
+    default: DQ8_AVG(KT, Q, NT, 4); break;   \
     }
-#define DQ8_AVG_NT(KT)                   \
-    if (g_tune.nt) {                     \
-        DQ8_AVG_Q(KT, true)              \
-    } else {                             \
-        DQ8_AVG_Q(KT, false)             \
+#define DQ8_AVG_Q(KT, NT)                    \
+    switch (q) {                             \
+    case 1: DQ8_AVG_W(KT, 1, NT) break;      \
+    case 4: DQ8_AVG_W(KT, 4, NT) break;      \
+    default: DQ8_AVG_W(KT, 2, NT) break;     \
+    }
+#define DQ8_AVG_NT(KT)                       \
+    if (g_tune.nt) {                         \
+        DQ8_AVG_Q(KT, true)                  \
+    } else {                                 \
+        DQ8_AVG_Q(KT, false)                 \
     }
     switch (K) {
     case 2: DQ8_AVG_NT(2) break;
@@ -840,14 +1015,15 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     case 8: DQ8_AVG_NT(8) break;
     default:
         if (g_tune.nt) {
-            DQ8_AVG(0, 1, true);
+            DQ8_AVG_W(0, 1, true)
         } else {
-            DQ8_AVG(0, 1, false);
+            DQ8_AVG_W(0, 1, false)
         }
         break;
     }
 #undef DQ8_AVG_NT
 #undef DQ8_AVG_Q
+#undef DQ8_AVG_W
 #undef DQ8_AVG
     return after_launch("k_decode_avg");
 }
@@ -872,10 +1048,11 @@ int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key,
     return DQ8_OK;
 }
 
-int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t *out6)
+int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t unit, size_t *out6)
 {
-    if (!out6 || cus < 1 || waves_per_cu < 1 || (wpb != 1 && wpb != 4)) return fail(DQ8_ERR_ARG, "dq8_internal_plan: bad argument");
-    Plan p = make_plan(n, block, cus, waves_per_cu, wpb);
+    if (!out6 || cus < 1 || waves_per_cu < 1 || (wpb != 1 && wpb != 4) || unit < 256 || (unit & (unit - 1)))
+        return fail(DQ8_ERR_ARG, "dq8_internal_plan: bad argument");
+    Plan p = make_plan(n, block, cus, waves_per_cu, wpb, kWavesPerWg, unit);
     out6[0] = p.B;
     out6[1] = p.nb;
     out6[2] = p.upb;
@@ -892,7 +1069,7 @@ int dq8_internal_tune(const char *key, int value)
         {"nt", &g_tune.nt, 0, 1},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
-        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)
         if (!std::strcmp(k.name, key)) {
@@ -910,12 +1087,13 @@ int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
     DeviceState *st;
     int rc = device_state(&st);
     if (rc) return rc;
-    Plan p = make_plan(n, 0, st->cus, g_tune.copy_wpc, 1);
+    const int q = (g_tune.copy_q == 1 || g_tune.copy_q == 2 || g_tune.copy_q == 8 || g_tune.copy_q == 16) ? g_tune.copy_q : 4;
+    Plan p = make_plan(n, 0, st->cus, g_tune.copy_wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 #define DQ8_COPY(Q, NT) \
     hipLaunchKernelGGL((k_copy<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, src, dst, n, p.n_units, p.n_teams)
 #define DQ8_COPY_Q(NT)                   \
-    switch (g_tune.copy_q) {             \
+    switch (q) {                         \
     case 1: DQ8_COPY(1, NT); break;      \
     case 2: DQ8_COPY(2, NT); break;      \
     case 8: DQ8_COPY(8, NT); break;      \

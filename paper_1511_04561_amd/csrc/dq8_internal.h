@@ -14,9 +14,9 @@ int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key,
                         uint32_t bucket_capacity);
 
 // Launch plan for n elements with the given block on a device with `cus` compute units,
-// `waves_per_cu` resident wavefronts per unit and teams of `wpb` wavefronts:
-// out6 = {B, nb, units per block, units, teams, workgroups}.
-int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t *out6);
+// `waves_per_cu` resident wavefronts per compute unit, teams of `wpb` wavefronts and units of
+// `unit` elements: out6 = {B, nb, units per block, units, teams, workgroups}.
+int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t unit, size_t *out6);
 
 // Runs the kernels' code search (the same inline functions, compiled for the host) over every
 // non-negative finite binary32 bit pattern and +inf, and compares it with a count of the

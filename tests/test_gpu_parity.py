@@ -28,16 +28,37 @@ def dq8():
     return mod
 
 
+PAD = 8192  # guard elements on both sides of every device array: two whole units
+
+POISON = {np.dtype(np.float32): 3.0e38, np.dtype(np.uint8): 0xA5}
+
+
+class Guarded:
+    """A device array placed inside a larger buffer whose margins hold a known pattern.
+
+    Inputs: a read past either end picks up the pattern (3e38 as a value, 0xA5 as a code), which
+    changes scales or outputs.  Outputs: check() fails if a margin was written.
+    `offset` shifts the first element by that many elements from an aligned address.
+    """
+
+    def __init__(self, n, dtype, offset=0, data=None):
+        self.fill = POISON[np.dtype(dtype)]
+        tdt = torch.float32 if np.dtype(dtype) == np.float32 else torch.uint8
+        self.buf = torch.full((PAD + offset + n + PAD,), self.fill, dtype=tdt, device="cuda")
+        self.lo, self.hi = PAD + offset, PAD + offset + n
+        self.t = self.buf[self.lo:self.hi]
+        if data is not None:
+            self.t.copy_(torch.from_numpy(np.ascontiguousarray(data)))
+        assert self.t.data_ptr() == self.buf.data_ptr() + self.lo * self.buf.element_size()
+
+    def check(self, what):
+        ok = bool((self.buf[:self.lo] == self.fill).all().item()) and bool((self.buf[self.hi:] == self.fill).all().item())
+        assert ok, "%s: the kernel wrote outside its output array" % what
+
+
 def dev(a, offset=0):
-    """Device copy of a numpy array whose first element sits `offset` elements past an aligned address."""
-    t = torch.from_numpy(np.ascontiguousarray(a))
-    if offset == 0:
-        return t.cuda()
-    buf = torch.empty(t.numel() + offset, dtype=t.dtype, device="cuda")
-    view = buf[offset:]
-    view.copy_(t)
-    assert view.data_ptr() == buf.data_ptr() + offset * t.element_size()
-    return view
+    """Guarded device copy of a numpy array (see Guarded)."""
+    return Guarded(a.size, a.dtype, offset, a).t
 
 
 def same_bits(got, want, what):
@@ -55,19 +76,27 @@ def check_encode_decode(dq8, kind, x, block, x_off=0, c_off=0, tag=""):
     print("case %s kind=%d n=%d block=%d x_off=%d c_off=%d" % (tag, kind, x.size, block, x_off, c_off), flush=True)
     want_codes, want_scales = oracle.encode(kind, x, block)
     want_out = oracle.decode(kind, want_codes, want_scales, block)
+    nb = want_scales.size
     xd = dev(x, x_off)
-    codes_buf = torch.empty(x.size + c_off, dtype=torch.uint8, device="cuda")
-    codes, scales = dq8.encode(kind, xd, block, codes=codes_buf[c_off:])
+    gc, gs = Guarded(x.size, np.uint8, c_off), Guarded(nb, np.float32)
+    codes, scales = dq8.encode(kind, xd, block, scales=gs.t, codes=gc.t)
     same_bits(scales, want_scales, "scales " + tag)
     same_bits(codes, want_codes, "codes " + tag)
-    same_bits(dq8.absmax(xd, block), want_scales, "absmax " + tag)
+    gc.check("encode codes " + tag)
+    gs.check("encode scales " + tag)
+    ga = Guarded(nb, np.float32)
+    same_bits(dq8.absmax(xd, block, scales=ga.t), want_scales, "absmax " + tag)
+    ga.check("absmax " + tag)
     # encode with the scales handed in goes through the non-fused kernel
-    codes2, _ = dq8.encode(kind, xd, block, scales=dev(want_scales), scales_given=True)
+    gc2 = Guarded(x.size, np.uint8, c_off)
+    codes2, _ = dq8.encode(kind, xd, block, scales=dev(want_scales), codes=gc2.t, scales_given=True)
     same_bits(codes2, want_codes, "codes(scales given) " + tag)
+    gc2.check("encode(scales given) " + tag)
     # decode takes the oracle's codes as input
-    out_buf = torch.empty(x.size + x_off, dtype=torch.float32, device="cuda")
-    out = dq8.decode(kind, dev(want_codes, c_off), dev(want_scales), block, out=out_buf[x_off:])
+    go = Guarded(x.size, np.float32, x_off)
+    out = dq8.decode(kind, dev(want_codes, c_off), dev(want_scales), block, out=go.t)
     same_bits(out, want_out, "decode " + tag)
+    go.check("decode " + tag)
 
 
 SHAPES = [  # (n, block)
@@ -77,7 +106,7 @@ SHAPES = [  # (n, block)
     (50 * 1000, 1000),        # rows shorter than a unit
     (7 * 6000 + 17, 6000),    # blocks of one full unit plus a partial one
     (5 * 8192 + 100, 8192),   # two units per block
-    (1000, 7), (257, 1),      # tiny blocks
+    (1000, 7), (257, 1), (4096 * 3 + 1, 1),  # tiny blocks; the last wavefront's first unit is the ragged one
     (20000, 10 ** 9),         # block larger than the array
 ]
 
@@ -144,9 +173,10 @@ def test_decode_accumulate_avg(dq8, kind, K):
         cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
         sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
         want = oracle.decode_accumulate_avg(kind, cl, sl, block)
-        out_buf = torch.empty(n + off, dtype=torch.float32, device="cuda")
-        got = dq8.decode_accumulate_avg(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block, out=out_buf[off:])
+        go = Guarded(n, np.float32, off)
+        got = dq8.decode_accumulate_avg(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block, out=go.t)
         same_bits(got, want, "avg")
+        go.check("avg")
 
 
 def test_average_order_is_worker_zero_first(dq8):

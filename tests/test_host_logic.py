@@ -166,21 +166,23 @@ def test_reciprocal_path_matches_the_oracle_around_every_threshold(L, kind):
 
 
 def test_launch_plan_covers_every_element_once(L):
-    L.dq8_internal_plan.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    L.dq8_internal_plan.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                                    ctypes.c_void_p]
     out = (ctypes.c_size_t * 6)()
     for n, block in [(61100840, 4096), (61100840, 0), (1, 0), (4097, 4096), (100, 7), (10 ** 6, 6000), (5000, 10 ** 9),
                      (4096 * 5000, 8192), (12345, 1)]:
-        for wpc, wpb in [(8, 1), (16, 1), (8, 4), (3, 4)]:
-            assert L.dq8_internal_plan(n, block, 256, wpc, wpb, out) == 0
+        for wpc, wpb, unit in [(8, 1, 4096), (16, 1, 1024), (8, 4, 4096), (3, 4, 4096), (8, 1, 256)]:
+            assert L.dq8_internal_plan(n, block, 256, wpc, wpb, unit, out) == 0
             B, nb, upb, units, teams, grid = list(out)
             Bw = n if (block == 0 or block > n) else block
-            assert B == Bw and nb == (n + Bw - 1) // Bw and upb == (Bw + 4095) // 4096
+            assert B == Bw and nb == (n + Bw - 1) // Bw and upb == (Bw + unit - 1) // unit
             full, last = divmod(n, Bw)
-            assert units == full * upb + (last + 4095) // 4096
+            assert units == full * upb + (last + unit - 1) // unit
             assert teams == grid * (4 // wpb) and grid >= 1 and teams <= max(1, 256 * wpc // wpb) + 3
             per_team = -(-units // teams)
             assert (per_team - 1) * teams < units  # balanced: no team walks more than one unit more than another
-    assert L.dq8_internal_plan(10, 0, 256, 8, 3, out) == 3
+    assert L.dq8_internal_plan(10, 0, 256, 8, 3, 4096, out) == 3
+    assert L.dq8_internal_plan(10, 0, 256, 8, 1, 1000, out) == 3
 
 
 def test_tuning_keys(L):
