@@ -16,7 +16,7 @@ last-level cache cannot serve a step from an earlier one.
 value = fp32 bytes the five calls consume or produce (4 bytes x n each) per second over the
 whole timed region.  The roofline object is for the kernel that takes the largest share of a
 step (the K-way decode-and-average); `kernels` lists all of them, each timed with HIP events
-on the launch stream in a second pass over the same steps.
+on the launch stream around K consecutive launches of that call over the same rotating buffers.
 """
 import argparse
 import json
@@ -35,9 +35,9 @@ K_WORKERS = 8
 N_SETS = 4
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by the same counters on the calibration copy kernel); the runs and the
-# scale factor are recorded in profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": None}
+# WRITE_SIZE runs on this script, each scaled by what the same counter reads for the calibration
+# copy kernel: 1.99980 and 1.00000); the runs are recorded in profiles/hbm_traffic_bench_c5.md.
+MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481180 + 238675) * 1024)}
 
 
 def algorithmic_bytes(n, nb):
@@ -158,24 +158,25 @@ def main():
     fp32_bytes_per_step = 5 * 4 * n
     value = fp32_bytes_per_step / (elapsed / args.steps) / 1e9
 
-    # ---- per-kernel durations: the same steps again, HIP events on the launch stream around each call
+    # ---- per-kernel durations: the same calls again, one kernel at a time: HIP events on the launch
+    # stream bracket `steps` consecutive launches of that call, rotating through the buffer sets exactly
+    # as the steps above do, so launch gaps are amortised and the cache still cannot help.
     names = [nm for nm, _ in calls(0)]
     if args.only:
         names = [nm for nm in names if nm == args.only]
-    tot = {nm: 0.0 for nm in names}
-    evs = []
-    for i in range(args.steps):
-        for nm, f in calls(args.warmup + args.steps + i):
-            if nm not in tot:
-                continue
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            f()
-            b.record()
-            evs.append((nm, a, b))
-    torch.cuda.synchronize()
-    for nm, a, b in evs:
-        tot[nm] += a.elapsed_time(b)
+    tot = {}
+    for idx, nm in enumerate([nm for nm, _ in calls(0)]):
+        if nm not in names:
+            continue
+        for i in range(3):
+            calls(i)[idx][1]()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(args.steps):
+            calls(3 + i)[idx][1]()
+        b.record()
+        torch.cuda.synchronize()
+        tot[nm] = a.elapsed_time(b)
     alg = algorithmic_bytes(n, nb)
     kernels = {}
     for nm in names:

@@ -720,17 +720,17 @@ int device_state(DeviceState **out)
 struct Tuning {
     int nt = 1;          // non-temporal loads and stores
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
-    int enc_wpb = 1;     // wavefronts per unit in the encoder: 1 or 4
-    int enc_wpc = 8;     // encoder wavefronts per compute unit
-    int amax_q = 4;      // absmax: quads per lane in flight
-    int amax_wpc = 8;
-    int dec_q = 4;       // decode: code words per lane in flight
-    int dec_wpc = 8;
+    int enc_wpb = 4;     // wavefronts per unit in the encoder: 1 or 4
+    int enc_wpc = 24;    // encoder wavefronts per compute unit
+    int amax_q = 16;     // absmax: quads per lane in flight (unit = 256 q elements)
+    int amax_wpc = 4;
+    int dec_q = 16;      // decode: code words per lane in flight
+    int dec_wpc = 4;
     int dec_wpw = 4;     // decode: wavefronts per workgroup (they share one table in LDS)
     int avg_q = 2;       // decode-and-average: code words per lane and worker in flight
-    int avg_wpc = 8;
-    int avg_wpw = 4;
-    int copy_q = 4;
+    int avg_wpc = 16;
+    int avg_wpw = 8;
+    int copy_q = 2;
     int copy_wpc = 8;
 };
 Tuning g_tune;
