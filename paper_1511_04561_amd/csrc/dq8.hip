@@ -60,34 +60,60 @@ struct WorkerPtrs {
 
 // ---------------------------------------------------------------- device helpers
 
-// Streaming accesses: every byte is touched once, so loads and stores carry the
-// non-temporal hint (NT) and do not displace each other in the caches.
-template <bool NT, typename T>
+// Streaming accesses: every byte is touched once, so loads and stores carry cache-policy
+// bits that keep them from displacing each other in the caches.  NT is the policy:
+//   0  plain loads and stores;
+//   1  non-temporal loads and stores (the nt bit);
+//   2  non-temporal loads; 128-bit stores with nt plus system scope (sc0 sc1), i.e. streamed
+//      through every cache level; 32-bit stores as in policy 1.
+// The scope bits only strengthen coherence, so every policy gives the same memory contents.
+//
+// The compiler has no way to ask for "sc0 sc1 nt" on an ordinary store (a volatile store gets
+// sc0 sc1 but is also made to wait for completion), so policy 2 writes the instruction out.
+// A 128-bit store keeps reading its data registers for two cycles after issue; the compiler
+// cannot see that this statement is such a store, so the two wait states it would otherwise
+// insert before the next vector write to those registers are part of the statement.
+template <int NT, typename T>
 __device__ __forceinline__ T ldg(const T *p)
 {
-    if constexpr (NT)
+    if constexpr (NT != 0)
         return __builtin_nontemporal_load(p);
     else
         return *p;
 }
 
-template <bool NT, typename T>
+template <int NT, typename T>
 __device__ __forceinline__ void stg(T *p, T v)
 {
-    if constexpr (NT)
-        __builtin_nontemporal_store(v, p);
-    else
+    if constexpr (NT == 0)
         *p = v;
+    else if constexpr (NT == 2 && sizeof(T) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+    else
+        __builtin_nontemporal_store(v, p);
+}
+
+// Maximum over the 64 lanes, returned in a scalar register.  Six data-parallel-primitive steps
+// on the vector unit (no LDS traffic): exchange inside quads, mirror inside half rows and rows
+// of 16 lanes, then carry lane 15 of a row into the next row and lane 31 into the upper half;
+// lane 63 ends up with the maximum of all lanes.  A step leaves lanes it does not write at
+// their own value, which is the identity of max.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t max_dpp(uint32_t v)
+{
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
+    return o > v ? o : v;
 }
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)v, m, kWave);
-        v = o > v ? o : v;
-    }
-    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+    v = max_dpp<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
+    v = max_dpp<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
+    v = max_dpp<0x141, 0xF>(v);  // row_half_mirror
+    v = max_dpp<0x140, 0xF>(v);  // row_mirror
+    v = max_dpp<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+    v = max_dpp<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 __host__ __device__ __forceinline__ uint32_t f2u(float f)
@@ -300,7 +326,7 @@ __global__ void k_fill_zero(float *p, size_t n)
 // Plain fp32 copy with the access pattern of the codec kernels (units of Q * 256 elements,
 // 128-bit accesses).  Exists to calibrate bandwidth and hardware-counter readings against a
 // kernel whose traffic is known exactly: 4 bytes read and 4 bytes written per element.
-template <int Q, bool NT>
+template <int Q, int NT>
 __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, float *__restrict__ dst, size_t n,
                                              size_t n_units, size_t n_waves)
 {
@@ -327,7 +353,7 @@ __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, flo
 // Block maxima.  One wavefront per unit of Q * 256 elements.  upb == 1: each unit is a whole
 // block and stores its maximum.  upb > 1: scales[] was zeroed and the units of a block merge
 // with an integer atomic max (non-negative binary32 numbers order like their bit patterns).
-template <int Q, bool NT>
+template <int Q, int NT>
 __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t nb, size_t upb,
                                                size_t n_units, size_t n_waves, float *__restrict__ scales)
 {
@@ -383,7 +409,7 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
 // block is read from scales[].
 // The loop is software-pipelined: the loads of a team's next unit are issued before the
 // current unit is reduced and quantised, so each wavefront always has loads in flight.
-template <int WPB, bool NT, bool FUSED, bool FASTDIV>
+template <int WPB, int NT, bool FUSED, bool FASTDIV>
 struct Encoder {
     static constexpr int Q = kUnitQuads / WPB;
     static constexpr uint32_t TEAM = kWave * WPB;
@@ -461,7 +487,7 @@ struct Encoder {
     }
 };
 
-template <int WPB, bool NT, bool FUSED, bool FASTDIV>
+template <int WPB, int NT, bool FUSED, bool FASTDIV>
 __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
                                                size_t B, size_t nb, size_t upb, size_t n_units, size_t n_teams,
                                                float *__restrict__ scales, uint8_t *__restrict__ codes)
@@ -503,7 +529,7 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
 // Decompression of one buffer: out = table[code] * scale.  One wavefront per unit of Q * 256
 // elements: Q code words (4 codes each) per lane; the next unit's words are loaded before the
 // current ones are expanded.
-template <int Q, bool NT, int WPW>
+template <int Q, int NT, int WPW>
 __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
                                                        const float *__restrict__ scales, size_t n, size_t B, size_t nb,
                                                        size_t upb, size_t n_units, size_t n_waves, float *__restrict__ out)
@@ -560,7 +586,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restri
 // in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled, Q code words per
 // lane and worker per unit, next unit's words requested before the current ones are used);
 // KT == 0 reads K from the argument.
-template <int KT, int Q, bool NT, int WPW>
+template <int KT, int Q, int NT, int WPW>
 __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt,
                                                            size_t n, size_t B, size_t nb, size_t upb, size_t n_units,
                                                            size_t n_waves, float *__restrict__ out)
@@ -570,6 +596,12 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     constexpr int U = Q * 4 * kWave;
     const int K = KT > 0 ? KT : K_rt;
     const float fk = (float)K;
+    // For K a power of two, 1/K is exact and acc * (1/K) is the correctly rounded value of the
+    // same real number as acc / K (subnormal results and signed zeros included), at the cost
+    // of one multiplication instead of a division sequence.
+    const bool pow2 = (K & (K - 1)) == 0;
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t lane4 = lane * 4;
     size_t u = first_unit(WPW);
@@ -616,10 +648,10 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                     a.z = a.z + lut_at<2>(lut, cur[k][j], lane4) * sc[k];
                     a.w = a.w + lut_at<3>(lut, cur[k][j], lane4) * sc[k];
                 }
-                a.x = a.x / fk;
-                a.y = a.y / fk;
-                a.z = a.z / fk;
-                a.w = a.w / fk;
+                a.x = mean_of(a.x);
+                a.y = mean_of(a.y);
+                a.z = mean_of(a.z);
+                a.w = mean_of(a.w);
                 stg<NT>(o4 + j * kWave + lane, a);
             }
         } else {
@@ -635,17 +667,17 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                         a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
                         a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
                     }
-                    a.x = a.x / fk;
-                    a.y = a.y / fk;
-                    a.z = a.z / fk;
-                    a.w = a.w / fk;
+                    a.x = mean_of(a.x);
+                    a.y = mean_of(a.y);
+                    a.z = mean_of(a.z);
+                    a.w = mean_of(a.w);
                     stg<NT>(o4 + j * kWave + lane, a);
                 }
             } else {
                 for (uint32_t i = lane; i < un.len; i += kWave) {
                     float a = 0.0f;
                     for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
-                    po[i] = a / fk;
+                    po[i] = mean_of(a);
                 }
             }
             u += n_waves;
@@ -718,7 +750,11 @@ int device_state(DeviceState **out)
 // at roughly 16-32 KiB of loads in flight per compute unit); dq8_internal_tune() changes them
 // for experiments.  None of them affects results.
 struct Tuning {
-    int nt = 1;          // non-temporal loads and stores
+    int amax_nt = 1;     // cache policy of each kernel's streaming accesses, see ldg / stg
+    int enc_nt = 1;      //   4-byte code stores: plain non-temporal is best
+    int dec_nt = 2;      //   16-byte fp32 stores: write-through non-temporal is best
+    int avg_nt = 2;
+    int copy_nt = 1;
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
     int enc_wpb = 4;     // wavefronts per unit in the encoder: 1 or 4
     int enc_wpc = 24;    // encoder wavefronts per compute unit
@@ -728,8 +764,8 @@ struct Tuning {
     int dec_wpc = 4;
     int dec_wpw = 4;     // decode: wavefronts per workgroup (they share one table in LDS)
     int avg_q = 2;       // decode-and-average: code words per lane and worker in flight
-    int avg_wpc = 16;
-    int avg_wpw = 8;
+    int avg_wpc = 32;
+    int avg_wpw = 16;
     int copy_q = 2;
     int copy_wpc = 8;
 };
@@ -805,10 +841,10 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
     case 16: DQ8_AMAX(16, NT); break;       \
     default: DQ8_AMAX(4, NT); break;        \
     }
-    if (g_tune.nt) {
-        DQ8_AMAX_Q(true)
+    if (g_tune.amax_nt) {
+        DQ8_AMAX_Q(1)
     } else {
-        DQ8_AMAX_Q(false)
+        DQ8_AMAX_Q(0)
     }
 #undef DQ8_AMAX_Q
 #undef DQ8_AMAX
@@ -831,11 +867,11 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     } else {                             \
         DQ8_ENC(WPB, NT, FUSED, false);  \
     }
-#define DQ8_ENC_NT(WPB, FUSED)           \
-    if (g_tune.nt) {                     \
-        DQ8_ENC_FD(WPB, true, FUSED)     \
-    } else {                             \
-        DQ8_ENC_FD(WPB, false, FUSED)    \
+#define DQ8_ENC_NT(WPB, FUSED)                    \
+    switch (g_tune.enc_nt) {                      \
+    case 0: DQ8_ENC_FD(WPB, 0, FUSED) break;      \
+    case 2: DQ8_ENC_FD(WPB, 2, FUSED) break;      \
+    default: DQ8_ENC_FD(WPB, 1, FUSED) break;     \
     }
     if (wpb == 4) {
         if (fused) {
@@ -950,10 +986,10 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     case 16: DQ8_DEC_W(16, NT) break;        \
     default: DQ8_DEC_W(4, NT) break;         \
     }
-    if (g_tune.nt) {
-        DQ8_DEC_Q(true)
-    } else {
-        DQ8_DEC_Q(false)
+    switch (g_tune.dec_nt) {
+    case 0: DQ8_DEC_Q(0) break;
+    case 2: DQ8_DEC_Q(2) break;
+    default: DQ8_DEC_Q(1) break;
     }
 #undef DQ8_DEC_Q
 #undef DQ8_DEC_W
@@ -1004,20 +1040,20 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     default: DQ8_AVG_W(KT, 2, NT) break;     \
     }
 #define DQ8_AVG_NT(KT)                       \
-    if (g_tune.nt) {                         \
-        DQ8_AVG_Q(KT, true)                  \
-    } else {                                 \
-        DQ8_AVG_Q(KT, false)                 \
+    switch (g_tune.avg_nt) {                 \
+    case 0: DQ8_AVG_Q(KT, 0) break;          \
+    case 2: DQ8_AVG_Q(KT, 2) break;          \
+    default: DQ8_AVG_Q(KT, 1) break;         \
     }
     switch (K) {
     case 2: DQ8_AVG_NT(2) break;
     case 4: DQ8_AVG_NT(4) break;
     case 8: DQ8_AVG_NT(8) break;
     default:
-        if (g_tune.nt) {
-            DQ8_AVG_W(0, 1, true)
-        } else {
-            DQ8_AVG_W(0, 1, false)
+        switch (g_tune.avg_nt) {
+        case 0: DQ8_AVG_W(0, 1, 0) break;
+        case 2: DQ8_AVG_W(0, 1, 2) break;
+        default: DQ8_AVG_W(0, 1, 1) break;
         }
         break;
     }
@@ -1066,7 +1102,8 @@ int dq8_internal_tune(const char *key, int value)
 {
     if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
-        {"nt", &g_tune.nt, 0, 1},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, {"dec_nt", &g_tune.dec_nt, 0, 2},
+        {"avg_nt", &g_tune.avg_nt, 0, 2}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
@@ -1100,10 +1137,10 @@ int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
     case 16: DQ8_COPY(16, NT); break;    \
     default: DQ8_COPY(4, NT); break;     \
     }
-    if (g_tune.nt) {
-        DQ8_COPY_Q(true)
-    } else {
-        DQ8_COPY_Q(false)
+    switch (g_tune.copy_nt) {
+    case 0: DQ8_COPY_Q(0) break;
+    case 2: DQ8_COPY_Q(2) break;
+    default: DQ8_COPY_Q(1) break;
     }
 #undef DQ8_COPY_Q
 #undef DQ8_COPY

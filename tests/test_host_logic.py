@@ -140,6 +140,23 @@ def test_reciprocal_product_is_within_three_steps_of_the_quotient():
     assert worst <= 3, worst
 
 
+def test_division_by_a_power_of_two_equals_the_product_with_its_reciprocal():
+    """The K-way average multiplies by 1/K when K is a power of two: bit-identical to the division,
+    also where the result is subnormal, zero (either sign) or the sum is huge."""
+    rng = np.random.Generator(np.random.PCG64(79))
+    bits = rng.integers(0, 1 << 32, 1 << 22, dtype=np.uint64).astype(np.uint32)
+    a = bits.view(np.float32)
+    a = a[np.isfinite(a)]
+    edge = np.array([0.0, -0.0, 2.0 ** -149, -2.0 ** -149, 3 * 2.0 ** -149, 2.0 ** -126, 1.5 * 2.0 ** -126,
+                     np.finfo(np.float32).max, -np.finfo(np.float32).max], dtype=np.float32)
+    small = (rng.integers(-(1 << 24), 1 << 24, 1 << 16).astype(np.float64) * 2.0 ** -149).astype(np.float32)
+    a = np.concatenate([a, edge, small])
+    for K in (1, 2, 4, 8, 16, 32):
+        q = (a / np.float32(K)).astype(np.float32)
+        m = (a * (np.float32(1.0) / np.float32(K))).astype(np.float32)
+        assert np.array_equal(q.view(np.uint32), m.view(np.uint32)), K
+
+
 @pytest.mark.parametrize("kind", KINDS)
 def test_reciprocal_path_matches_the_oracle_around_every_threshold(L, kind):
     """Inputs built so that x / s lands on, and next to, every decision point, for awkward scales."""
