@@ -12,6 +12,7 @@ from .dq8_oracle import (  # noqa: F401
     codebook,
     decode,
     decode_accumulate_avg,
+    decode_avg_encode,
     encode,
     set_threads,
 )

@@ -26,6 +26,10 @@
  * its formula (bit-by-bit tree walk in exact rationals, sorted-table search,
  * exact rational rounding, numpy primitives, brute force on tiny inputs,
  * error bounds, and the relative-error ordering of the paper's Table 2).
+ * The average with a local 32-bit term and the average-then-compress round
+ * are pinned the same way (numpy and exact-rational re-computation, special
+ * cases with closed-form results); where the local term sits in the sum and
+ * that the divisor is K + 1 is a reading of one sentence of Sec. 3.4.
  * What is NOT pinned, because the paper prints no table values and its
  * figure of the bit layouts is missing: agreement with the bit patterns of
  * the authors' own implementation ("parity unpinned" for wire compatibility
@@ -35,6 +39,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -286,3 +291,77 @@ int dq8o_decode_accumulate_avg(int kind, const uint8_t *const *codes,
     }
     return 0;
 }
+
+/*
+ * Averaging with the worker's own 32-bit gradient (Sec. 3.4, MNIST paragraph: the
+ * incoming buffers of the other GPUs are 8-bit approximations, the local GPU's own
+ * gradient stays in 32 bits).  Reading taken here: the local value is the first
+ * term of the same running sum, the K decompressed buffers follow in worker order,
+ * and the divisor is the number of terms, K + 1:
+ *     acc = +0;  acc = acc + local[i];  acc = acc + cb[code_k] * scale_k (k = 0..K-1);
+ *     out = acc / (K + 1)
+ * with every operation rounded to binary32 on its own.  K = 0 is allowed (the
+ * local gradient alone).
+ */
+int dq8o_decode_accumulate_avg_local(int kind, const uint8_t *const *codes,
+                                     const float *const *scales, int K, const float *local,
+                                     size_t n, size_t block, float *out)
+{
+    float cb[256];
+    size_t B, nb;
+    long long b;
+    int k, rc = dq8o_codebook(kind, cb);
+    if (rc) return rc;
+    if (K < 0) return 3;
+    if (n == 0) return 0;
+    if (!local || !out || (K > 0 && (!codes || !scales))) return 1;
+    for (k = 0; k < K; ++k)
+        if (!codes[k] || !scales[k]) return 1;
+    B = block_len(n, block);
+    nb = (n + B - 1) / B;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (b = 0; b < (long long)nb; ++b) {
+        size_t lo = (size_t)b * B, hi = lo + B < n ? lo + B : n, i;
+        for (i = lo; i < hi; ++i) {
+            float acc = 0.0f;
+            int kk;
+            acc = acc + local[i];
+            for (kk = 0; kk < K; ++kk) {
+                float v = cb[codes[kk][i]] * scales[kk][b];
+                acc = acc + v;
+            }
+            out[i] = acc / (float)(K + 1);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Second round of the gradient exchange (Appendix, cluster model: the gradients
+ * are distributed once raw and once accumulated): the owner of a slice averages
+ * the K received buffers (with its own 32-bit gradient when local != NULL) and
+ * compresses the average again for redistribution.  By definition this is the
+ * averaging above followed by the compression above, applied to the binary32
+ * averages; nothing is fused or reordered here.
+ */
+int dq8o_decode_avg_encode(int kind, const uint8_t *const *codes, const float *const *scales,
+                           int K, const float *local, size_t n, size_t block,
+                           float *out_scales, uint8_t *out_codes)
+{
+    float cb[256];
+    float *mean;
+    int rc = dq8o_codebook(kind, cb); /* only to reject an unknown kind when n == 0 */
+    if (rc) return rc;
+    if (n == 0) return 0;
+    if (!out_scales || !out_codes) return 1;
+    mean = (float *)malloc(n * sizeof(float));
+    if (!mean) return 4;
+    if (local)
+        rc = dq8o_decode_accumulate_avg_local(kind, codes, scales, K, local, n, block, mean);
+    else
+        rc = dq8o_decode_accumulate_avg(kind, codes, scales, K, n, block, mean);
+    if (!rc) rc = dq8o_encode(kind, mean, n, block, out_scales, out_codes, 0);
+    free(mean);
+    return rc;
+}
+

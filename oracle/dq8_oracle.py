@@ -42,9 +42,14 @@ def _load():
         lib.dq8o_decode.argtypes = [ctypes.c_int, c_u8, c_f, c_sz, c_sz, c_f]
         lib.dq8o_decode_accumulate_avg.argtypes = [ctypes.c_int, ctypes.POINTER(c_u8), ctypes.POINTER(c_f),
                                                    ctypes.c_int, c_sz, c_sz, c_f]
+        lib.dq8o_decode_accumulate_avg_local.argtypes = [ctypes.c_int, ctypes.POINTER(c_u8), ctypes.POINTER(c_f),
+                                                         ctypes.c_int, c_f, c_sz, c_sz, c_f]
+        lib.dq8o_decode_avg_encode.argtypes = [ctypes.c_int, ctypes.POINTER(c_u8), ctypes.POINTER(c_f), ctypes.c_int,
+                                               c_f, c_sz, c_sz, c_f, c_u8]
         lib.dq8o_set_threads.argtypes = [ctypes.c_int]
         for f in (lib.dq8o_codebook, lib.dq8o_absmax, lib.dq8o_encode, lib.dq8o_decode,
-                  lib.dq8o_decode_accumulate_avg, lib.dq8o_set_threads, lib.dq8o_get_threads):
+                  lib.dq8o_decode_accumulate_avg, lib.dq8o_decode_accumulate_avg_local, lib.dq8o_decode_avg_encode,
+                  lib.dq8o_set_threads, lib.dq8o_get_threads):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -127,19 +132,46 @@ def decode(kind, codes, scales, block=0):
     return out
 
 
-def decode_accumulate_avg(kind, codes_list, scales_list, block=0):
+def _workers(codes_list, scales_list, block, n=None):
     K = len(codes_list)
     if K != len(scales_list):
         raise ValueError("codes_list and scales_list differ in length")
     codes_list = [_u8(c) for c in codes_list]
     scales_list = [_f32(s) for s in scales_list]
-    n = codes_list[0].size if K else 0
+    if n is None:
+        n = codes_list[0].size if K else 0
     for c, s in zip(codes_list, scales_list):
         if c.size != n or s.size != n_blocks(n, block):
             raise ValueError("worker buffers differ in size")
     cp = (ctypes.POINTER(ctypes.c_uint8) * max(K, 1))(*[_bp(c) for c in codes_list])
     sp = (ctypes.POINTER(ctypes.c_float) * max(K, 1))(*[_fp(s) for s in scales_list])
+    return K, n, cp, sp, (codes_list, scales_list)  # the last item keeps the arrays alive
+
+
+def decode_accumulate_avg(kind, codes_list, scales_list, block=0, local=None):
+    """Mean of the K decoded buffers; with ``local`` the fp32 array is the first of K + 1 terms."""
+    if local is None:
+        K, n, cp, sp, _keep = _workers(codes_list, scales_list, block)
+        out = np.empty(n, dtype=np.float32)
+        _check(_load().dq8o_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), _fp(out)),
+               "decode_accumulate_avg")
+        return out
+    local = _f32(local)
+    K, n, cp, sp, _keep = _workers(codes_list, scales_list, block, local.size)
     out = np.empty(n, dtype=np.float32)
-    _check(_load().dq8o_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), _fp(out)),
-           "decode_accumulate_avg")
+    _check(_load().dq8o_decode_accumulate_avg_local(int(kind), cp, sp, K, _fp(local), n, int(block), _fp(out)),
+           "decode_accumulate_avg_local")
     return out
+
+
+def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None):
+    """Average (optionally with the fp32 ``local`` term) and compress the average: (codes, scales)."""
+    if local is not None:
+        local = _f32(local)
+    K, n, cp, sp, _keep = _workers(codes_list, scales_list, block, None if local is None else local.size)
+    out_codes = np.empty(n, dtype=np.uint8)
+    out_scales = np.empty(n_blocks(n, block), dtype=np.float32)
+    lp = _fp(local) if local is not None else ctypes.POINTER(ctypes.c_float)()
+    _check(_load().dq8o_decode_avg_encode(int(kind), cp, sp, K, lp, n, int(block), _fp(out_scales), _bp(out_codes)),
+           "decode_avg_encode")
+    return out_codes, out_scales

@@ -184,7 +184,7 @@ __device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb,
 // Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range.
 struct Search {
     const uint32_t *bucket;  // LDS on the device
-    uint32_t lo_base;        // lo_key << 16
+    uint32_t lo_key;         // key of the first bucket
     float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
 };
 
@@ -192,7 +192,7 @@ __host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, u
 {
     Search s;
     s.bucket = bucket;
-    s.lo_base = lo_key << 16;
+    s.lo_key = lo_key;
     s.lo_f = u2f((lo_key << 16) + 0x8000u);
     s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
     return s;
@@ -210,8 +210,8 @@ __host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float x
     c = c >= s.lo_f ? c : s.lo_f;  // also takes NaN to the low end; inputs are finite anyway
     c = c <= s.hi_f ? c : s.hi_f;
 #endif
-    const uint32_t a = f2u(c) - s.lo_base;
-    return s.bucket[a >> 16] + (a & 0xFFFFu);
+    const uint32_t a = f2u(c);  // the low 16 bits of lo_base are zero: subtracting it only moves the key
+    return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
 }
 
 // (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.

@@ -277,6 +277,132 @@ def test_averaging_order_is_worker_0_first():
     assert out[0] == 0.0  # 1e8 + 1 rounds back to 1e8 in binary32
 
 
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("K", [0, 1, 3, 7])
+def test_local_average_is_sequential_binary32_arithmetic(kind, K):
+    """Sec. 3.4: the local gradient stays in 32 bits; here it is the first of K + 1 terms of the running sum."""
+    rng = np.random.Generator(np.random.PCG64(300 + K))
+    n, B = 3001, 128
+    nb = (n + B - 1) // B
+    cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+    sl = [np.exp(rng.uniform(-6, 6, nb)).astype(np.float32) for _ in range(K)]
+    local = (rng.standard_normal(n) * np.exp(rng.uniform(-6, 6, n))).astype(np.float32)
+    got = oracle.decode_accumulate_avg(kind, cl, sl, B, local=local)
+    cb = oracle.codebook(kind)
+    acc = np.zeros(n, np.float32) + local
+    for k in range(K):
+        acc = acc + cb[cl[k]] * np.repeat(sl[k], B)[:n]
+    want = acc / np.float32(K + 1)
+    assert want.dtype == np.float32 and got.tobytes() == want.tobytes()
+    for i in range(0, n, 499):
+        a = Fraction(float(local[i]))
+        for k in range(K):
+            p = Fraction(float(round_to_f32(Fraction(float(cb[cl[k][i]])) * Fraction(float(sl[k][i // B])))))
+            a = Fraction(float(round_to_f32(a + p)))
+        assert np.float32(round_to_f32(a / (K + 1))) == got[i]
+
+
+def test_local_average_special_cases():
+    kind = oracle.LINEAR  # cb[0] = 0, cb[127] = 1: decoded values are 0 and the scale itself
+    n = 9
+    local = np.array([3, -5, 0.0, -0.0, 7, 1e-40, -1e30, 2.5, 11], np.float32)
+    zeros = np.zeros(n, np.uint8)
+    s1 = np.array([4.0], np.float32)
+    # workers that decode to zero leave local / (K + 1)
+    out = oracle.decode_accumulate_avg(kind, [zeros] * 3, [s1] * 3, 0, local=local)
+    assert out.tobytes() == ((np.zeros(n, np.float32) + local) / np.float32(4)).tobytes()
+    # no workers: the local gradient alone; -0 becomes +0 because the sum starts from +0
+    out = oracle.decode_accumulate_avg(kind, [], [], 0, local=local)
+    assert out.tobytes() == (np.zeros(n, np.float32) + local).tobytes() and not np.signbit(out[3])
+    # integers: (local + 4 + 4 + 4) / 4 is exact
+    ones = np.full(n, 127, np.uint8)
+    ints = np.arange(n, dtype=np.float32) * 4 - 8
+    out = oracle.decode_accumulate_avg(kind, [ones] * 3, [s1] * 3, 0, local=ints)
+    assert np.array_equal(out, ints / 4 + 3)
+    # the local term cancels the single worker exactly
+    out = oracle.decode_accumulate_avg(kind, [ones], [s1], 0, local=np.full(n, -4.0, np.float32))
+    assert out.tobytes() == np.zeros(n, np.float32).tobytes()
+    # order: local first.  (1e8 + -1e8) + 1 keeps the 1; a worker-first order would lose it
+    out = oracle.decode_accumulate_avg(kind, [np.array([255], np.uint8), np.array([127], np.uint8)],
+                                       [np.array([1e8], np.float32), np.array([1.0], np.float32)], 0,
+                                       local=np.array([1e8], np.float32))
+    assert out[0] == np.float32(1.0) / np.float32(3.0)
+    out = oracle.decode_accumulate_avg(kind, [np.array([127], np.uint8), np.array([255], np.uint8)],
+                                       [np.array([1.0], np.float32), np.array([1e8], np.float32)], 0,
+                                       local=np.array([1e8], np.float32))
+    assert out[0] == 0.0
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("with_local", [False, True])
+def test_average_then_compress_against_exact_rationals(kind, with_local):
+    """Appendix (gradients are distributed raw, then accumulated): the accumulated value is compressed again.
+    Every step recomputed with Fractions and explicit binary32 roundings on small blocks."""
+    rng = np.random.Generator(np.random.PCG64(400 + kind + 10 * with_local))
+    cb = oracle.codebook(kind)
+    cbf = [Fraction(float(v)) for v in cb]
+    cbs = [bool(np.signbit(v)) for v in cb]
+    for trial in range(12):
+        K = int(rng.integers(1, 5))
+        B = int(rng.integers(1, 6))
+        n = int(rng.integers(1, 14))
+        nb = (n + B - 1) // B
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-3, 3, nb)).astype(np.float32) for _ in range(K)]
+        local = (rng.standard_normal(n)).astype(np.float32) if with_local else None
+        if trial == 0:  # a block whose mean is exactly zero everywhere
+            cl = [cl[0], cl[0] ^ np.uint8(0x80)]
+            sl = [sl[0], sl[0]]
+            K, local = 2, (np.zeros(n, np.float32) if with_local else None)
+        got_codes, got_scales = oracle.decode_avg_encode(kind, cl, sl, B, local=local)
+        terms = K + (1 if with_local else 0)
+        mean = []
+        for i in range(n):
+            a = Fraction(0)
+            if with_local:
+                a = Fraction(float(round_to_f32(a + Fraction(float(local[i])))))
+            for k in range(K):
+                p = Fraction(float(round_to_f32(cbf[cl[k][i]] * Fraction(float(sl[k][i // B])))))
+                a = Fraction(float(round_to_f32(a + p)))
+            mean.append(round_to_f32(a / terms))
+        for b in range(nb):
+            blk = mean[b * B:(b + 1) * B]
+            s = max(abs(Fraction(float(v))) for v in blk)
+            assert Fraction(float(got_scales[b])) == s
+            for j, v in enumerate(blk):
+                xn = Fraction(float(v)) if s == 0 else Fraction(float(round_to_f32(Fraction(float(v)) / s)))
+                sign = bool(np.signbit(v)) if xn == 0 else xn < 0
+                assert got_codes[b * B + j] == nearest_code_exact(cbf, cbs, xn, sign), (trial, b, j)
+
+
+def test_average_then_compress_invariants():
+    """The re-compressed average decodes to within half a code gap (times the block's scale) of the average."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    kind, K, B = oracle.DYNAMIC_TREE, 8, 4096
+    xs = [workloads.tensor(5, 2, worker=w, limit=3 * B + 100) for w in range(K)]
+    enc = [oracle.encode(kind, x, B) for x in xs]
+    cl, sl = [e[0] for e in enc], [e[1] for e in enc]
+    codes, scales = oracle.decode_avg_encode(kind, cl, sl, B)
+    cb = oracle.codebook(kind)
+    acc = np.zeros(xs[0].size, np.float32)
+    for k in range(K):
+        acc = acc + cb[cl[k]] * np.repeat(sl[k], B)[:acc.size]
+    mean = acc / np.float32(K)
+    nb = scales.size
+    want_scales = np.array([np.abs(mean[b * B:(b + 1) * B]).max() for b in range(nb)], np.float32)
+    assert scales.tobytes() == want_scales.tobytes()
+    mags = cb[:128].astype(np.float64)
+    gaps = np.diff(mags)
+    back = oracle.decode(kind, codes, scales, B).astype(np.float64)
+    s_el = np.repeat(scales, B)[:mean.size].astype(np.float64)
+    err = np.abs(back - mean.astype(np.float64))
+    j = (codes & 127).astype(int)
+    half_gap = 0.5 * np.maximum(gaps[np.minimum(j, 126)], gaps[np.maximum(j - 1, 0)])
+    top = (j == 127) * (1.0 - mags[127])  # values above the largest magnitude
+    assert np.all(err <= (np.maximum(half_gap, top) + 2.0 ** -22) * s_el)
+    assert np.array_equal((codes >> 7).astype(bool), np.signbit(mean))
+
+
 def test_relative_error_ordering_matches_table_2(golden_dir):
     """Table 2: dynamic tree < linear < static tree in mean relative error; values in the paper's ballpark.
 
