@@ -17,6 +17,8 @@ value = fp32 bytes the five calls consume or produce (4 bytes x n each) per seco
 whole timed region.  The roofline object is for the kernel that takes the largest share of a
 step (the K-way decode-and-average); `kernels` lists all of them, each timed with HIP events
 on the launch stream around K consecutive launches of that call over the same rotating buffers.
+`kernels` also times two calls that are not part of a step: dq8_decode_avg_encode (the average and
+the re-compression in one call) and dq8_decode_accumulate_avg_local (a local fp32 term in the average).
 """
 import argparse
 import json
@@ -48,6 +50,9 @@ def algorithmic_bytes(n, nb):
         "decode": n + 4 * nb + 4 * n,
         "decode_accumulate_avg": K_WORKERS * (n + 4 * nb) + 4 * n,
         "re_encode": 4 * n + n + 4 * nb,
+        # not part of a step: the second exchange round as one call, and the average with a local fp32 term
+        "decode_avg_encode": K_WORKERS * (n + 4 * nb) + n + 4 * nb,
+        "decode_accumulate_avg_local": K_WORKERS * (n + 4 * nb) + 4 * n + 4 * n,
     }
 
 
@@ -141,6 +146,16 @@ def main():
             ("re_encode", lambda: dq8.encode(KIND, nxt["mean"], BLOCK, scales=st["rs"], codes=st["rc"])),
         ]
 
+    def extra_calls(i):
+        """Calls beside the step: timed per kernel only."""
+        st, nxt = sets[i % N_SETS], sets[(i + 1) % N_SETS]
+        return [
+            ("decode_avg_encode", lambda: dq8.decode_avg_encode(KIND, st["codes"], st["scales"], BLOCK,
+                                                                scales=st["rs"], codes=st["rc"])),
+            ("decode_accumulate_avg_local", lambda: dq8.decode_accumulate_avg(KIND, st["codes"], st["scales"], BLOCK,
+                                                                              out=st["dec"], local=nxt["x"])),
+        ]
+
     def step(i):
         for _, f in calls(i):
             f()
@@ -161,19 +176,22 @@ def main():
     # ---- per-kernel durations: the same calls again, one kernel at a time: HIP events on the launch
     # stream bracket `steps` consecutive launches of that call, rotating through the buffer sets exactly
     # as the steps above do, so launch gaps are amortised and the cache still cannot help.
-    names = [nm for nm, _ in calls(0)]
+    def all_calls(i):
+        return calls(i) + extra_calls(i)
+
+    names = [nm for nm, _ in all_calls(0)]
     if args.only:
         names = [nm for nm in names if nm == args.only]
     tot = {}
-    for idx, nm in enumerate([nm for nm, _ in calls(0)]):
+    for idx, nm in enumerate([nm for nm, _ in all_calls(0)]):
         if nm not in names:
             continue
         for i in range(3):
-            calls(i)[idx][1]()
+            all_calls(i)[idx][1]()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for i in range(args.steps):
-            calls(3 + i)[idx][1]()
+            all_calls(3 + i)[idx][1]()
         b.record()
         torch.cuda.synchronize()
         tot[nm] = a.elapsed_time(b)

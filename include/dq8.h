@@ -122,6 +122,33 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
 int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float *const *scales,
                               int K, size_t n, size_t block, float *out, void *hip_stream);
 
+/*
+ * The same average with the caller's own 32-bit gradient as one more term (Sec. 3.4, MNIST
+ * paragraph: incoming buffers are 8-bit, the local GPU's gradient stays in 32 bits):
+ *   acc = +0;  acc = acc + local[i];  then the K workers in index order as above;
+ *   out[i] = acc / (K + 1)
+ * every operation rounded to binary32 on its own.  local: n floats (read, device).
+ * 0 <= K <= DQ8_MAX_K (K == 0: the local values alone; `codes` / `scales` may then be NULL).
+ * out: n floats (written), must not overlap any input.
+ */
+int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const float *const *scales,
+                                    int K, const float *local, size_t n, size_t block, float *out,
+                                    void *hip_stream);
+
+/*
+ * Second round of the gradient exchange (Appendix, cluster model: the gradients are sent once
+ * raw and once accumulated): average the K received buffers -- with `local` as the first term
+ * when it is not NULL, divisor K + 1 -- and compress the averages again, without an fp32 array
+ * in between.  Results are identical to dq8_decode_accumulate_avg[_local] followed by
+ * dq8_encode of its output with the same kind and block.
+ * out_scales: nb floats (written), out_codes: n bytes (written); neither may overlap an input.
+ * A scale block must fit the registers of one wavefront: block (or n when block == 0) <= 4096,
+ * otherwise DQ8_ERR_ARG (use the two separate calls).  1 <= K <= DQ8_MAX_K, or 0 <= K with local.
+ */
+int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *const *scales, int K,
+                          const float *local, size_t n, size_t block, float *out_scales,
+                          uint8_t *out_codes, void *hip_stream);
+
 /* Text of the calling thread's most recent error ("" if none).  Static storage, never NULL. */
 const char *dq8_last_error(void);
 

@@ -310,6 +310,17 @@ __device__ __forceinline__ float lut_code(const float *lut, uint32_t code, uint3
     return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + ((code << 8) | lane4));
 }
 
+// A wave-uniform pointer pinned to scalar registers, so that indexing it with a 32-bit lane
+// offset becomes "scalar base + vector offset" addressing instead of a 64-bit address per lane.
+template <typename T>
+__device__ __forceinline__ T *uniform_ptr(T *p)
+{
+    const uintptr_t v = (uintptr_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (T *)(((uintptr_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
@@ -686,6 +697,358 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     }
 }
 
+// Average of K workers' buffers (plus, optionally, a local fp32 array as the first term) with a
+// whole unit of 4096 elements held in one wavefront's registers: 16 quads of running sums per
+// lane, the workers added one after the other while the next worker's code words are in flight.
+// The means can be stored as fp32 (mean_out) and / or compressed again from the registers
+// (codes_out, scales_out; needs a unit to be a whole scale block, upb == 1): the second round of
+// the gradient exchange then reads K bytes and writes one byte per element instead of going
+// through an fp32 array in memory.  Arithmetic and order are those of k_decode_avg followed by
+// k_encode, so the results are identical to the two calls.
+// Two workgroups of WPW wavefronts share a compute unit (each holds the 64 KiB decode table),
+// so the register budget per lane is 512 / (WPW / 2): 170 for six wavefronts, 128 for eight.
+template <int NT, bool FASTDIV, int WPW>
+__global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+                                                          const float *__restrict__ local, size_t n, size_t B,
+                                                          size_t nb, size_t upb, size_t n_units, size_t n_waves,
+                                                          float *__restrict__ mean_out, float *__restrict__ scales_out,
+                                                          uint8_t *__restrict__ codes_out)
+{
+    static_assert(WPW >= 4, "the decode table is filled by 256 threads");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint32_t bucket_lds[];
+    constexpr int Q = kUnitQuads;
+    const int terms = K + (local ? 1 : 0);
+    const float fk = (float)terms;
+    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    load_lut(tab, lut);
+    Search sr = make_search(bucket_lds, tab[kLoKeyOff], tab[kNBucketOff]);
+    if (codes_out) {
+        const uint32_t nbk = tab[kNBucketOff];
+        for (uint32_t i = threadIdx.x; i < nbk; i += kWave * WPW) bucket_lds[i] = tab[kBucketOff + i];
+    }
+    __syncthreads();
+    for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
+        const Unit un = unit_of<kUnit>(u, n, B, nb, upb);
+        bool fast = un.len == kUnit;
+        for (int k = 0; k < K; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
+        if (local) fast = fast && (((uintptr_t)(local + un.start) & 15) == 0);
+        if (mean_out) fast = fast && (((uintptr_t)(mean_out + un.start) & 15) == 0);
+        if (codes_out) fast = fast && (((uintptr_t)(codes_out + un.start) & 3) == 0);
+        if (fast) {
+            v4f acc[Q];
+            uint32_t wa[Q], wb[Q];
+            auto load_w = [&](uint32_t(&w)[Q], int k) {
+                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + j * kWave + lane);
+            };
+            auto add_w = [&](const uint32_t(&w)[Q], int k) {
+                const float s = p.scales[k][un.block];
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lut_at<0>(lut, w[j], lane4) * s;
+                    acc[j].y = acc[j].y + lut_at<1>(lut, w[j], lane4) * s;
+                    acc[j].z = acc[j].z + lut_at<2>(lut, w[j], lane4) * s;
+                    acc[j].w = acc[j].w + lut_at<3>(lut, w[j], lane4) * s;
+                }
+                // pin the sums here, or the compiler defers them and holds the products of several workers
+#pragma unroll
+                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+            };
+            if (K > 0) load_w(wa, 0);
+            if (local) {
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = ldg<NT>(l4 + j * kWave + lane);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                    acc[j].x = 0.0f + acc[j].x;
+                    acc[j].y = 0.0f + acc[j].y;
+                    acc[j].z = 0.0f + acc[j].z;
+                    acc[j].w = 0.0f + acc[j].w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            for (int k = 0; k < K; k += 2) {
+                const bool more = k + 1 < K;
+                if (more) load_w(wb, k + 1);
+                add_w(wa, k);
+                if (more) {
+                    if (k + 2 < K) load_w(wa, k + 2);
+                    add_w(wb, k + 1);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
+            }
+            if (mean_out) {
+                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) stg<NT>(o4 + j * kWave + lane, acc[j]);
+            }
+            if (codes_out) {
+                float fm = 0.0f;
+#pragma unroll
+                for (int j = 0; j < Q; ++j) fm = max4_abs(acc[j], fm);
+                const float s = u2f(wave_max_u32(f2u(fm)));
+                if (lane == 0) scales_out[un.block] = s;
+                const float d = s == 0.0f ? 1.0f : s;
+                const float r = 1.0f / d;
+                const bool recip = reciprocal_ok(d);
+                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWave + lane, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
+            }
+        } else {
+            auto mean_at = [&](uint32_t i) {
+                float a = 0.0f;
+                if (local) a = a + local[un.start + i];
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+                return mean_of(a);
+            };
+            if (mean_out)
+                for (uint32_t i = lane; i < un.len; i += kWave) mean_out[un.start + i] = mean_at(i);
+            if (codes_out) {  // the means are formed twice rather than kept: first for the maximum
+                uint32_t m = 0;
+                for (uint32_t i = lane; i < un.len; i += kWave) {
+                    const uint32_t a = abs_bits(mean_at(i));
+                    m = m > a ? m : a;
+                }
+                const float s = u2f(wave_max_u32(m));
+                if (lane == 0) scales_out[un.block] = s;
+                const float d = s == 0.0f ? 1.0f : s;
+                const float r = 1.0f / d;
+                const bool recip = reciprocal_ok(d);
+                for (uint32_t i = lane; i < un.len; i += kWave)
+                    codes_out[un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(i), d, r, recip);
+            }
+        }
+    }
+}
+
+// The same average-then-compress round for K = 2, 4 or 8 workers at full speed.  A team of four
+// wavefronts owns a unit of 4096 elements (one scale block): every lane holds four quads of
+// running sums and K x 4 code words.  The code words are one register set that is refilled
+// in place: as soon as worker k's words of the current unit have been decoded and added, the
+// loads of worker k's words of the team's next unit are issued into the same registers, so
+// loads are in flight all through the reduction to the block maximum (wave reduction, then one
+// LDS exchange between the team's wavefronts) and the compression from the registers.
+// TEAMS teams share a workgroup and its tables; the workgroup barrier that separates the
+// exchange of the maxima from their use is executed by every wavefront the same number of
+// times (`iters`), whether or not its team still has a unit.
+template <int KT, int NT, bool FASTDIV, int TEAMS>
+struct AvgTeam {
+    static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
+
+    WorkerPtrs p;
+    const float *local;
+    float *scales_out;
+    uint8_t *codes_out;
+    size_t n, B, nb, n_units;
+    const float *lut;
+    uint32_t *slots;
+    Search sr;
+    uint32_t lane4, lane, team, wv, tl, phase;
+    float fk, rk;
+    bool pow2;
+    uint32_t w[KT][Q];  // code words: of the current unit until used, then of the next one
+
+    struct Slot {
+        Unit un;
+        bool active, fast;
+    };
+
+    __device__ __forceinline__ float mean_of(float acc) const { return pow2 ? acc * rk : acc / fk; }
+
+    // Element i of the unit, the slow way.
+    __device__ __forceinline__ float mean_at(const Unit &un, uint32_t i) const
+    {
+        float a = 0.0f;
+        if (local) a = a + local[un.start + i];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+        return mean_of(a);
+    }
+
+    // Geometry of unit u and whether it can take the register path.
+    __device__ __forceinline__ void open(size_t u, Slot &sl) const
+    {
+        sl.active = u < n_units;
+        sl.fast = false;
+        if (!sl.active) return;
+        sl.un = unit_of<kUnit>(u, n, B, nb, 1);
+        bool f = sl.un.len == kUnit && (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
+#pragma unroll
+        for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
+        if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
+        sl.fast = f;
+    }
+
+    __device__ __forceinline__ void load_worker(const Slot &sl, int k)
+    {
+        const uint32_t *c4 = uniform_ptr(reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start));
+#pragma unroll
+        for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + j * kWg + tl);
+    }
+
+    __device__ __forceinline__ void load_all(const Slot &sl)
+    {
+        if (sl.fast) {
+#pragma unroll
+            for (int k = 0; k < KT; ++k) load_worker(sl, k);
+        }
+    }
+
+    // Processes unit `sl`, whose code words are in w if it is fast, and leaves the words of `nx` there.
+    __device__ __forceinline__ void process(const Slot &sl, const Slot &nx)
+    {
+        v4f acc[Q];
+        uint32_t m = 0;
+        if (sl.active && sl.fast) {
+            if (local) {  // not prefetched: the code words take the registers
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                    const v4f l = ldg<NT>(l4 + j * kWg + tl);
+                    acc[j].x = 0.0f + l.x;
+                    acc[j].y = 0.0f + l.y;
+                    acc[j].z = 0.0f + l.z;
+                    acc[j].w = 0.0f + l.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            float sc[KT];  // the K scales of this block, moved to scalar registers
+#pragma unroll
+            for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(p.scales[k][sl.un.block])));
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lut_at<0>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].y = acc[j].y + lut_at<1>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].z = acc[j].z + lut_at<2>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].w = acc[j].w + lut_at<3>(lut, w[k][j], lane4) * sc[k];
+                }
+                // Pin the sums here.  Otherwise the compiler starts the lookups of every worker
+                // at once and holds all K x 16 products in registers until the ordered sums get
+                // to them, which costs a wavefront per SIMD.
+#pragma unroll
+                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+                if (nx.fast) load_worker(nx, k);  // refill in place
+            }
+            float fm = 0.0f;
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
+                fm = max4_abs(acc[j], fm);
+            }
+            m = f2u(fm);
+        } else {
+            if (sl.active) {
+                for (uint32_t i = tl; i < sl.un.len; i += kWg) {
+                    const uint32_t a = abs_bits(mean_at(sl.un, i));
+                    m = m > a ? m : a;
+                }
+            }
+            load_all(nx);
+        }
+        m = wave_max_u32(m);
+        uint32_t *sp = slots + (phase * TEAMS + team) * kWavesPerWg;
+        if (lane == 0) sp[wv] = m;
+        __syncthreads();
+        {
+            const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
+            m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+        }
+        phase ^= 1;  // the other half of the slots next time: one barrier per unit is enough
+        if (!sl.active) return;
+        const float s = u2f(m);
+        if (tl == 0) scales_out[sl.un.block] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        if (sl.fast) {
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWg + tl, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
+        } else {
+            for (uint32_t i = tl; i < sl.un.len; i += kWg)
+                codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);
+        }
+    }
+};
+
+template <int KT, int NT, bool FASTDIV, int TEAMS>
+__global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
+                                                            const float *__restrict__ local, size_t n, size_t B, size_t nb,
+                                                            size_t n_units, size_t n_teams, uint32_t iters,
+                                                            float *__restrict__ scales_out, uint8_t *__restrict__ codes_out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
+    constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
+    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS>;
+    Avg e;
+    e.p = p;
+    e.local = local;
+    e.scales_out = scales_out;
+    e.codes_out = codes_out;
+    e.n = n;
+    e.B = B;
+    e.nb = nb;
+    e.n_units = n_units;
+    e.lut = lut;
+    e.slots = dyn_lds;
+    e.lane = threadIdx.x & 63;
+    e.lane4 = e.lane * 4;
+    const uint32_t wave = wave_in_wg();
+    e.team = wave / kWavesPerWg;
+    e.wv = wave % kWavesPerWg;
+    e.tl = threadIdx.x & (kWg - 1);  // lane within the team
+    e.phase = 0;
+    const int terms = KT + (local ? 1 : 0);
+    e.fk = (float)terms;
+    e.rk = 1.0f / e.fk;
+    e.pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    size_t u = (size_t)blockIdx.x * TEAMS + e.team;
+    typename Avg::Slot a, b;
+    e.open(u, a);
+    e.load_all(a);  // the first loads are in flight while the tables are copied
+    load_lut(tab, lut);
+    {
+        uint32_t *bucket = dyn_lds + kSlots;
+        const uint32_t nbk = tab[kNBucketOff];
+        for (uint32_t i = threadIdx.x; i < nbk; i += kWg * TEAMS) bucket[i] = tab[kBucketOff + i];
+        e.sr = make_search(bucket, tab[kLoKeyOff], nbk);
+    }
+    __syncthreads();
+    for (uint32_t it = 0; it < iters; it += 2) {
+        e.open(u + n_teams, b);
+        e.process(a, b);
+        u += n_teams;
+        if (it + 1 >= iters) break;
+        e.open(u + n_teams, a);
+        e.process(b, a);
+        u += n_teams;
+    }
+}
+
 // ---------------------------------------------------------------- host side
 
 thread_local char t_err[512] = "";
@@ -766,6 +1129,11 @@ struct Tuning {
     int avg_q = 2;       // decode-and-average: code words per lane and worker in flight
     int avg_wpc = 32;
     int avg_wpw = 16;
+    int blk_wpw = 8;     // register-resident average: wavefronts per workgroup (two workgroups per compute unit)
+    int blk_nt = 2;
+    int avg_team = 1;    // average-then-compress with K = 2, 4, 8: the team kernel (0: the wave-per-block kernel)
+    int avg_teams = 3;   //   teams per workgroup: 2, 3 or 4
+    int avg_wgpc = 1;    //   workgroups per compute unit (2 only with 2 teams)
     int copy_q = 2;
     int copy_wpc = 8;
 };
@@ -890,6 +1258,98 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
 #undef DQ8_ENC_FD
 #undef DQ8_ENC
     return after_launch("k_encode");
+}
+
+// Copies and checks the K (codes, scales) pairs of a call; `out` / `out_bytes` is a buffer the
+// call writes that must not overlap any of them (may be NULL).
+int gather_workers(const char *who, const uint8_t *const *codes, const float *const *scales, int K, size_t n, size_t nb,
+                   const void *out, size_t out_bytes, WorkerPtrs *wp)
+{
+    std::memset(wp, 0, sizeof(*wp));
+    if (K > 0 && (!codes || !scales)) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    for (int k = 0; k < K; ++k) {
+        if (!codes[k] || !scales[k]) return fail(DQ8_ERR_NULL, "%s: worker %d has a NULL buffer", who, k);
+        if (out && (overlaps(out, out_bytes, codes[k], n) || overlaps(out, out_bytes, scales[k], nb * 4)))
+            return fail(DQ8_ERR_ARG, "%s: an output overlaps worker %d", who, k);
+        wp->codes[k] = codes[k];
+        wp->scales[k] = scales[k];
+    }
+    return DQ8_OK;
+}
+
+// Average-then-compress for K = 2, 4, 8: teams of four wavefronts; two teams per workgroup and two
+// workgroups per compute unit (128 registers per lane), or three teams in one workgroup per compute
+// unit (170 registers per lane).
+int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                    size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
+{
+    const int teams = (g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2;
+    const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
+    Plan p = make_plan(n, block, st.cus, 4 * teams * wgs_per_cu, 4, 4 * teams, kUnit);
+    const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = ((size_t)st.n_bucket[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
+#define DQ8_TEAM(KT, NT, FD, T)                                                                               \
+    hipLaunchKernelGGL((k_avg_team<KT, NT, FD, T>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
+                       p.B, p.nb, p.n_units, p.n_teams, iters, scales_out, codes_out)
+#define DQ8_TEAM_T(KT, NT, FD)   \
+    if (teams == 3) {            \
+        DQ8_TEAM(KT, NT, FD, 3); \
+    } else if (teams == 4) {     \
+        DQ8_TEAM(KT, NT, FD, 4); \
+    } else {                     \
+        DQ8_TEAM(KT, NT, FD, 2); \
+    }
+#define DQ8_TEAM_FD(KT, NT)      \
+    if (g_tune.fastdiv) {        \
+        DQ8_TEAM_T(KT, NT, true) \
+    } else {                     \
+        DQ8_TEAM_T(KT, NT, false)\
+    }
+    switch (K) {
+    case 2: DQ8_TEAM_FD(2, 1) break;
+    case 4: DQ8_TEAM_FD(4, 1) break;
+    default: DQ8_TEAM_FD(8, 1) break;
+    }
+#undef DQ8_TEAM_FD
+#undef DQ8_TEAM_T
+#undef DQ8_TEAM
+    return after_launch("k_avg_team");
+}
+
+int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                     size_t block, float *mean_out, float *scales_out, uint8_t *codes_out, hipStream_t stream)
+{
+    if (codes_out && !mean_out && (K == 2 || K == 4 || K == 8) && g_tune.avg_team)
+        return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
+    const int wpw = g_tune.blk_wpw == 8 ? 8 : 6;
+    Plan p = make_plan(n, block, st.cus, 2 * wpw, 1, wpw, kUnit);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = codes_out ? (size_t)st.n_bucket[kind] * sizeof(uint32_t) : 0;
+#define DQ8_BLK(NT, FD, WPW)                                                                                     \
+    hipLaunchKernelGGL((k_avg_block<NT, FD, WPW>), dim3(p.grid), dim3(kWave * WPW), lds, stream, tab, wp, K, local, n, \
+                       p.B, p.nb, p.upb, p.n_units, p.n_teams, mean_out, scales_out, codes_out)
+#define DQ8_BLK_W(NT, FD)      \
+    if (wpw == 8) {            \
+        DQ8_BLK(NT, FD, 8);    \
+    } else {                   \
+        DQ8_BLK(NT, FD, 6);    \
+    }
+#define DQ8_BLK_FD(NT)         \
+    if (g_tune.fastdiv) {      \
+        DQ8_BLK_W(NT, true)    \
+    } else {                   \
+        DQ8_BLK_W(NT, false)   \
+    }
+    switch (g_tune.blk_nt) {
+    case 0: DQ8_BLK_FD(0) break;
+    case 2: DQ8_BLK_FD(2) break;
+    default: DQ8_BLK_FD(1) break;
+    }
+#undef DQ8_BLK_FD
+#undef DQ8_BLK_W
+#undef DQ8_BLK
+    return after_launch("k_avg_block");
 }
 
 }  // namespace
@@ -1064,6 +1524,59 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     return after_launch("k_decode_avg");
 }
 
+int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const float *const *scales, int K,
+                                    const float *local, size_t n, size_t block, float *out, void *hip_stream)
+{
+    static const char who[] = "dq8_decode_accumulate_avg_local";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (K < 0 || K > DQ8_MAX_K) return fail(DQ8_ERR_ARG, "%s: K = %d outside 0..%d", who, K, DQ8_MAX_K);
+    if (n == 0) return DQ8_OK;
+    if (!local || !out) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t nbq = (n + Bq - 1) / Bq;
+    if (overlaps(out, n * 4, local, n * 4)) return fail(DQ8_ERR_ARG, "%s: out overlaps local", who);
+    WorkerPtrs wp;
+    rc = gather_workers(who, codes, scales, K, n, nbq, out, n * 4, &wp);
+    if (rc) return rc;
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    return launch_avg_block(*st, kind, wp, K, local, n, block, out, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *const *scales, int K, const float *local,
+                          size_t n, size_t block, float *out_scales, uint8_t *out_codes, void *hip_stream)
+{
+    static const char who[] = "dq8_decode_avg_encode";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (K < (local ? 0 : 1) || K > DQ8_MAX_K)
+        return fail(DQ8_ERR_ARG, "%s: K = %d outside %d..%d", who, K, local ? 0 : 1, DQ8_MAX_K);
+    if (n == 0) return DQ8_OK;
+    if (!out_scales || !out_codes) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t nbq = (n + Bq - 1) / Bq;
+    if (Bq > (size_t)kUnit)
+        return fail(DQ8_ERR_ARG, "%s: a scale block of %zu elements does not fit the registers of a wavefront (at most %d); "
+                    "use dq8_decode_accumulate_avg and dq8_encode", who, Bq, kUnit);
+    if (overlaps(out_codes, n, out_scales, nbq * 4)) return fail(DQ8_ERR_ARG, "%s: outputs overlap", who);
+    if (local && (overlaps(out_codes, n, local, n * 4) || overlaps(out_scales, nbq * 4, local, n * 4)))
+        return fail(DQ8_ERR_ARG, "%s: an output overlaps local", who);
+    WorkerPtrs wp;
+    rc = gather_workers(who, codes, scales, K, n, nbq, out_codes, n, &wp);
+    if (rc) return rc;
+    rc = gather_workers(who, codes, scales, K, n, nbq, out_scales, nbq * 4, &wp);
+    if (rc) return rc;
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    return launch_avg_block(*st, kind, wp, K, local, n, block, nullptr, out_scales, out_codes,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
 // ---- internal entry points used by the CPU tests of the host logic (dq8_internal.h)
 
 int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key, uint32_t *n_bucket, uint32_t *bucket,
@@ -1106,7 +1619,7 @@ int dq8_internal_tune(const char *key, int value)
         {"avg_nt", &g_tune.avg_nt, 0, 2}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
-        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"blk_nt", &g_tune.blk_nt, 0, 2}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)
         if (!std::strcmp(k.name, key)) {

@@ -37,7 +37,10 @@ def lib():
         L.dq8_encode.argtypes = [ci, vp, sz, sz, vp, vp, ctypes.c_uint, vp]
         L.dq8_decode.argtypes = [ci, vp, vp, sz, sz, vp, vp]
         L.dq8_decode_accumulate_avg.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, sz, sz, vp, vp]
-        for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg):
+        L.dq8_decode_accumulate_avg_local.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp]
+        L.dq8_decode_avg_encode.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp, vp]
+        for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg,
+                  L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode):
             f.restype = ci
         L.dq8_last_error.restype = ctypes.c_char_p
         L.dq8_internal_copy.argtypes = [vp, vp, sz, vp]
@@ -135,29 +138,64 @@ def decode(kind, codes, scales, block=0, out=None):
     return out
 
 
-def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None):
+def _workers(codes_list, scales_list, block, n=None):
     K = len(codes_list)
     if K != len(scales_list):
         raise ValueError("codes_list and scales_list differ in length")
-    if K == 0:
-        raise ValueError("need at least one worker buffer")
-    n = codes_list[0].numel()
+    if n is None:
+        if K == 0:
+            raise ValueError("need at least one worker buffer")
+        n = codes_list[0].numel()
     for c, s in zip(codes_list, scales_list):
         _dev(c, torch.uint8, "codes")
         _dev(s, torch.float32, "scales")
         if c.numel() != n or s.numel() < n_blocks(n, block):
             raise ValueError("worker buffers differ in size")
+    cp = (ctypes.c_void_p * max(K, 1))(*[c.data_ptr() for c in codes_list])
+    sp = (ctypes.c_void_p * max(K, 1))(*[s.data_ptr() for s in scales_list])
+    return K, n, cp, sp
+
+
+def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None, local=None):
+    """Mean of the K decoded buffers; with ``local`` (fp32) that array is the first of K + 1 terms."""
+    if local is not None:
+        _dev(local, torch.float32, "local")
+    K, n, cp, sp = _workers(codes_list, scales_list, block, None if local is None else local.numel())
+    dev = local.device if local is not None else codes_list[0].device
     if out is None:
-        out = torch.empty(n, dtype=torch.float32, device=codes_list[0].device)
+        out = torch.empty(n, dtype=torch.float32, device=dev)
     _dev(out, torch.float32, "out")
     if out.numel() < n:
         raise ValueError("out too small")
-    cp = (ctypes.c_void_p * K)(*[c.data_ptr() for c in codes_list])
-    sp = (ctypes.c_void_p * K)(*[s.data_ptr() for s in scales_list])
     with torch.cuda.device(out.device):
-        _check(lib().dq8_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), out.data_ptr(), _stream()),
-               "dq8_decode_accumulate_avg")
+        if local is None:
+            _check(lib().dq8_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), out.data_ptr(), _stream()),
+                   "dq8_decode_accumulate_avg")
+        else:
+            _check(lib().dq8_decode_accumulate_avg_local(int(kind), cp, sp, K, local.data_ptr(), n, int(block),
+                                                         out.data_ptr(), _stream()), "dq8_decode_accumulate_avg_local")
     return out
+
+
+def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None, scales=None, codes=None):
+    """Average the K buffers (with ``local`` as first term if given) and compress the average: (codes, scales)."""
+    if local is not None:
+        _dev(local, torch.float32, "local")
+    K, n, cp, sp = _workers(codes_list, scales_list, block, None if local is None else local.numel())
+    dev = local.device if local is not None else codes_list[0].device
+    if scales is None:
+        scales = torch.empty(n_blocks(n, block), dtype=torch.float32, device=dev)
+    if codes is None:
+        codes = torch.empty(n, dtype=torch.uint8, device=dev)
+    _dev(scales, torch.float32, "scales")
+    _dev(codes, torch.uint8, "codes")
+    if scales.numel() < n_blocks(n, block) or codes.numel() < n:
+        raise ValueError("output buffers too small")
+    with torch.cuda.device(codes.device):
+        _check(lib().dq8_decode_avg_encode(int(kind), cp, sp, K, None if local is None else local.data_ptr(), n,
+                                           int(block), scales.data_ptr(), codes.data_ptr(), _stream()),
+               "dq8_decode_avg_encode")
+    return codes, scales
 
 
 def calibration_copy(dst, src):

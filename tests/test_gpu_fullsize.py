@@ -85,7 +85,12 @@ def test_config5_aggregation_pipeline(dq8):
     print("C5: gpu decode_accumulate_avg + re-encode", flush=True)
     mean = dq8.decode_accumulate_avg(KIND, codes_d, scales_d, B)
     rcodes, rscales = dq8.encode(KIND, mean, B)
+    print("C5: gpu decode_avg_encode in one call", flush=True)
+    fcodes, fscales = dq8.decode_avg_encode(KIND, codes_d, scales_d, B)
     torch.cuda.synchronize()
+    # the single call must reproduce the two calls everywhere (and those are checked against the oracle below)
+    assert torch.equal(fcodes, rcodes) and fscales.cpu().numpy().tobytes() == rscales.cpu().numpy().tobytes()
+    del fcodes, fscales
     print("C5: oracle on %d sampled blocks" % sample.size, flush=True)
     mean_h, rcodes_h, rscales_h = mean.cpu().numpy(), rcodes.cpu().numpy(), rscales.cpu().numpy()
     codes_h = [c.cpu().numpy() for c in codes_d]

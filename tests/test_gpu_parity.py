@@ -179,6 +179,79 @@ def test_decode_accumulate_avg(dq8, kind, K):
         go.check("avg")
 
 
+AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1),
+             (100, 7, 0), (4096, 0, 0), (4095, 0, 0)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("K", [0, 1, 2, 3, 7, 8, 32])
+def test_decode_accumulate_avg_with_local_term(dq8, kind, K):
+    """The caller's own fp32 gradient is the first of K + 1 terms."""
+    rng = np.random.Generator(np.random.PCG64(1900 + 10 * K + kind))
+    for n, block, off in AVG_CASES:
+        print("avg+local kind=%d K=%d n=%d block=%d off=%d" % (kind, K, n, block, off), flush=True)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
+        local = (rng.standard_normal(n) * np.exp(rng.uniform(-8, 8, n))).astype(np.float32)
+        local[::17] = 0.0
+        local[5::23] = -0.0
+        want = oracle.decode_accumulate_avg(kind, cl, sl, block, local=local)
+        go = Guarded(n, np.float32, off)
+        got = dq8.decode_accumulate_avg(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block, out=go.t,
+                                        local=dev(local, off))
+        same_bits(got, want, "avg+local")
+        go.check("avg+local")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("K,with_local", [(1, False), (2, False), (3, False), (8, False), (32, False), (0, True),
+                                          (3, True), (7, True)])
+def test_decode_avg_encode(dq8, kind, K, with_local):
+    """One call: average, then compress the average.  Inputs are codes of seeded gradients (so that the means
+    spread over the whole table) and, for the ragged shapes, random codes."""
+    rng = np.random.Generator(np.random.PCG64(2900 + 10 * K + kind + 1000 * with_local))
+    for n, block, off in AVG_CASES:
+        Bq = n if block == 0 else block
+        if Bq > 4096:
+            continue
+        print("avg->encode kind=%d K=%d local=%d n=%d block=%d off=%d" % (kind, K, with_local, n, block, off), flush=True)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        if n >= 4096:
+            enc = [oracle.encode(kind, workloads.tensor(5, 2, worker=w, limit=n), block) for w in range(K)]
+            cl, sl = [e[0] for e in enc], [e[1] for e in enc]
+        else:
+            cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+            sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
+        local = (workloads.tensor(5, 4, worker=9, limit=n) if n >= 4096 else rng.standard_normal(n).astype(np.float32)) \
+            if with_local else None
+        if n == 3 * 4096:  # one block whose average is zero everywhere, one with a denormal maximum
+            if K >= 2 and not with_local:
+                cl[1][:4096] = cl[0][:4096] ^ np.uint8(0x80)
+                sl[1][0] = sl[0][0]
+                for k in range(2, K):  # the other workers contribute +-0 to that block
+                    sl[k][0] = 0.0
+            for k in range(K):
+                sl[k][1] = np.float32(1e-42)
+            if with_local:
+                local[4096:8192] = np.float32(3e-43)
+        want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)
+        gc, gs = Guarded(n, np.uint8, off), Guarded(nb, np.float32)
+        codes, scales = dq8.decode_avg_encode(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block,
+                                              local=None if local is None else dev(local, off), scales=gs.t, codes=gc.t)
+        same_bits(scales, want_scales, "avg->encode scales")
+        same_bits(codes, want_codes, "avg->encode codes")
+        gc.check("avg->encode codes")
+        gs.check("avg->encode scales")
+
+
+def test_decode_avg_encode_rejects_blocks_that_do_not_fit(dq8):
+    c = torch.zeros(10000, dtype=torch.uint8, device="cuda")
+    s = torch.ones(1, device="cuda")
+    with pytest.raises(dq8.Dq8Error, match="4096"):
+        dq8.decode_avg_encode(0, [c, c], [s, s], 0)
+
+
 def test_average_order_is_worker_zero_first(dq8):
     c_pos, c_neg = np.full(5000, 127, np.uint8), np.full(5000, 255, np.uint8)
     big, small = np.array([1e8], np.float32), np.array([1.0], np.float32)

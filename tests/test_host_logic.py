@@ -26,8 +26,9 @@ def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "dq8.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(dq8_[a-z0-9_]+)\s*\(", header)))
-    assert names == ["dq8_absmax", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg", "dq8_encode",
-                     "dq8_init", "dq8_last_error"]
+    assert names == ["dq8_absmax", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
+                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_encode", "dq8_init",
+                     "dq8_last_error"]
     for n in names:
         assert hasattr(L, n), n
 
@@ -61,6 +62,22 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode_accumulate_avg(0, None, arr, 2, n, z, p, None) == 1
     assert L.dq8_decode_accumulate_avg(5, arr, arr, 2, n, z, p, None) == 2
     assert L.dq8_decode_accumulate_avg(0, arr, arr, 2, z, z, None, None) == 0
+    # the average with a local term and the average-then-compress round
+    assert L.dq8_decode_accumulate_avg_local(0, arr, arr, -1, p, n, z, p, None) == 3
+    assert L.dq8_decode_accumulate_avg_local(0, arr, arr, 33, p, n, z, p, None) == 3
+    assert L.dq8_decode_accumulate_avg_local(0, arr, arr, 2, None, n, z, p, None) == 1
+    assert L.dq8_decode_accumulate_avg_local(4, arr, arr, 2, p, n, z, p, None) == 2
+    assert L.dq8_decode_accumulate_avg_local(0, arr, arr, 2, p, n, z, p, None) == 3  # out overlaps local
+    assert L.dq8_decode_accumulate_avg_local(0, None, None, 0, None, z, z, None, None) == 0
+    assert L.dq8_decode_avg_encode(0, arr, arr, 0, None, n, z, p, p, None) == 3  # no worker and no local term
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, None, p, None) == 1
+    assert L.dq8_decode_avg_encode(3, arr, arr, 2, None, n, z, p, p, None) == 2
+    big = ctypes.c_size_t(10000)
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, z, p, p, None) == 3  # one block of 10000 > 4096
+    assert b"4096" in L.dq8_last_error()
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, ctypes.c_size_t(5000), p, p, None) == 3
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, p, p, None) == 3  # outputs overlap each other
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, z, z, None, None, None) == 0
     assert isinstance(L.dq8_last_error(), bytes)
 
 
