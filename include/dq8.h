@@ -149,6 +149,27 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
                           const float *local, size_t n, size_t block, float *out_scales,
                           uint8_t *out_codes, void *hip_stream);
 
+/*
+ * Single-node speed-up model (Appendix, "A theoretical single node model for 4 GPUs"): the
+ * convolutional part runs data-parallel at one GPU's speed, the fully connected part runs
+ * model-parallel over `sub_batches` passes of `parallel_fc_ms` each, and communication that
+ * cannot be hidden under computation is added as penalties:
+ *   *speedup = n_gpus * total_ms /
+ *              ((total_ms - fc_ms) + conv_penalty_ms + sub_batches * parallel_fc_ms + fc_penalty_ms)
+ * Pure host arithmetic in double precision; all pointers are HOST pointers.  DQ8_ERR_ARG when
+ * n_gpus < 1, sub_batches < 0, a time is negative or not finite, fc_ms > total_ms or the
+ * denominator is not positive.
+ */
+int dq8_model_speedup(int n_gpus, double total_ms, double fc_ms, double conv_penalty_ms, int sub_batches,
+                      double parallel_fc_ms, double fc_penalty_ms, double *speedup);
+
+/*
+ * The penalty term of that model: *penalty_ms = sum over i of max(transfer_ms[i] - compute_ms[i], 0),
+ * the part of each transfer that the computation it overlaps with does not cover (compute 0 for a
+ * transfer that overlaps with nothing).  HOST arrays of `count` doubles; count == 0 gives 0.
+ */
+int dq8_model_penalty(const double *transfer_ms, const double *compute_ms, size_t count, double *penalty_ms);
+
 /* Text of the calling thread's most recent error ("" if none).  Static storage, never NULL. */
 const char *dq8_last_error(void);
 

@@ -1577,6 +1577,35 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
                             static_cast<hipStream_t>(hip_stream));
 }
 
+int dq8_model_penalty(const double *transfer_ms, const double *compute_ms, size_t count, double *penalty_ms)
+{
+    if (!penalty_ms || (count > 0 && (!transfer_ms || !compute_ms))) return fail(DQ8_ERR_NULL, "dq8_model_penalty: NULL pointer");
+    double total = 0.0;
+    for (size_t i = 0; i < count; ++i) {
+        if (!(transfer_ms[i] >= 0.0) || !(compute_ms[i] >= 0.0) || transfer_ms[i] > 1e300 || compute_ms[i] > 1e300)
+            return fail(DQ8_ERR_ARG, "dq8_model_penalty: entry %zu is negative or not finite", i);
+        const double open_part = transfer_ms[i] - compute_ms[i];
+        total = total + (open_part > 0.0 ? open_part : 0.0);
+    }
+    *penalty_ms = total;
+    return DQ8_OK;
+}
+
+int dq8_model_speedup(int n_gpus, double total_ms, double fc_ms, double conv_penalty_ms, int sub_batches,
+                      double parallel_fc_ms, double fc_penalty_ms, double *speedup)
+{
+    if (!speedup) return fail(DQ8_ERR_NULL, "dq8_model_speedup: speedup is NULL");
+    const double t[5] = {total_ms, fc_ms, conv_penalty_ms, parallel_fc_ms, fc_penalty_ms};
+    for (double v : t)
+        if (!(v >= 0.0) || v > 1e300) return fail(DQ8_ERR_ARG, "dq8_model_speedup: a time is negative or not finite");
+    if (n_gpus < 1 || sub_batches < 0) return fail(DQ8_ERR_ARG, "dq8_model_speedup: n_gpus = %d, sub_batches = %d", n_gpus, sub_batches);
+    if (fc_ms > total_ms) return fail(DQ8_ERR_ARG, "dq8_model_speedup: the fully connected part is longer than the whole pass");
+    const double denominator = (total_ms - fc_ms) + conv_penalty_ms + sub_batches * parallel_fc_ms + fc_penalty_ms;
+    if (!(denominator > 0.0)) return fail(DQ8_ERR_ARG, "dq8_model_speedup: the parallel pass takes no time");
+    *speedup = n_gpus * total_ms / denominator;
+    return DQ8_OK;
+}
+
 // ---- internal entry points used by the CPU tests of the host logic (dq8_internal.h)
 
 int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key, uint32_t *n_bucket, uint32_t *bucket,

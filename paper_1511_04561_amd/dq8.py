@@ -42,6 +42,11 @@ def lib():
         for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg,
                   L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode):
             f.restype = ci
+        dbl = ctypes.c_double
+        L.dq8_model_speedup.argtypes = [ci, dbl, dbl, dbl, ci, dbl, dbl, ctypes.POINTER(dbl)]
+        L.dq8_model_penalty.argtypes = [ctypes.POINTER(dbl), ctypes.POINTER(dbl), sz, ctypes.POINTER(dbl)]
+        L.dq8_model_speedup.restype = ci
+        L.dq8_model_penalty.restype = ci
         L.dq8_last_error.restype = ctypes.c_char_p
         L.dq8_internal_copy.argtypes = [vp, vp, sz, vp]
         L.dq8_internal_copy.restype = ci
@@ -196,6 +201,25 @@ def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None, scales
                                            int(block), scales.data_ptr(), codes.data_ptr(), _stream()),
                "dq8_decode_avg_encode")
     return codes, scales
+
+
+def model_speedup(n_gpus, total_ms, fc_ms, conv_penalty_ms, sub_batches, parallel_fc_ms, fc_penalty_ms):
+    """Predicted speed-up of the single-node model (host arithmetic in the library)."""
+    out = ctypes.c_double()
+    _check(lib().dq8_model_speedup(int(n_gpus), total_ms, fc_ms, conv_penalty_ms, int(sub_batches), parallel_fc_ms,
+                                   fc_penalty_ms, ctypes.byref(out)), "dq8_model_speedup")
+    return out.value
+
+
+def model_penalty(transfer_ms, compute_ms):
+    """Sum of the parts of the transfers that their overlapping computations do not cover."""
+    n = len(transfer_ms)
+    if n != len(compute_ms):
+        raise ValueError("transfer_ms and compute_ms differ in length")
+    arr = ctypes.c_double * max(n, 1)
+    out = ctypes.c_double()
+    _check(lib().dq8_model_penalty(arr(*transfer_ms), arr(*compute_ms), n, ctypes.byref(out)), "dq8_model_penalty")
+    return out.value
 
 
 def calibration_copy(dst, src):

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(L):
     names = sorted(set(re.findall(r"\b(dq8_[a-z0-9_]+)\s*\(", header)))
     assert names == ["dq8_absmax", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
                      "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_encode", "dq8_init",
-                     "dq8_last_error"]
+                     "dq8_last_error", "dq8_model_penalty", "dq8_model_speedup"]
     for n in names:
         assert hasattr(L, n), n
 
