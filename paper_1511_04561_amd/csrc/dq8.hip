@@ -310,15 +310,41 @@ __device__ __forceinline__ float lut_code(const float *lut, uint32_t code, uint3
     return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + ((code << 8) | lane4));
 }
 
-// A wave-uniform pointer pinned to scalar registers, so that indexing it with a 32-bit lane
-// offset becomes "scalar base + vector offset" addressing instead of a 64-bit address per lane.
+// Element idx of an array whose base pointer is wave-uniform, addressed as "scalar base +
+// 32-bit vector offset": the base is pinned to scalar registers, so that the compiler neither
+// keeps a 64-bit address per lane nor hoists one out of the loop for every array it walks.
+// The pointer goes through an integer on the way, which would make it a generic pointer; the
+// cast names the global address space again (address space 1), so the access stays a global one.
+#define DQ8_GLOBAL __attribute__((address_space(1)))
+
 template <typename T>
-__device__ __forceinline__ T *uniform_ptr(T *p)
+__device__ __forceinline__ DQ8_GLOBAL T *uniform_global(T *p)
 {
     const uintptr_t v = (uintptr_t)p;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return (T *)(((uintptr_t)hi << 32) | lo);
+    return (DQ8_GLOBAL T *)(((uintptr_t)hi << 32) | lo);
+}
+
+template <int NT, typename T>
+__device__ __forceinline__ T ldg_at(const T *uniform_base, uint32_t idx)
+{
+    const DQ8_GLOBAL T *g = uniform_global(uniform_base);
+    if constexpr (NT != 0)
+        return __builtin_nontemporal_load(g + idx);
+    else
+        return g[idx];
+}
+
+// Store with the plain or non-temporal policy (the write-through policy of stg keeps its own form).
+template <int NT, typename T>
+__device__ __forceinline__ void stg_at(T *uniform_base, uint32_t idx, T v)
+{
+    DQ8_GLOBAL T *g = uniform_global(uniform_base);
+    if constexpr (NT != 0)
+        __builtin_nontemporal_store(v, g + idx);
+    else
+        g[idx] = v;
 }
 
 __device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
@@ -534,6 +560,97 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
         if (nx < n_units) e.fetch(nx, a);
         e.process(b);
         u = nx;
+    }
+}
+
+// Compression of whole, aligned blocks of 4096 elements: the common case of k_encode<4, NT, true,
+// FASTDIV> (a team of four wavefronts per block, maximum and quantisation from registers) with
+// nothing else in the loop.  Block b starts at element 4096 b, x is 16-byte and codes 4-byte
+// aligned, so unit geometry is a multiplication and there is no slow path to branch around.
+// A ragged last block of tail_len elements is done by the last workgroup after its loop.
+template <int NT, bool FASTDIV>
+__global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict__ tab, const float *__restrict__ x,
+                                                    uint32_t n_full, uint32_t n_teams, uint32_t tail_len,
+                                                    float *__restrict__ scales, uint8_t *__restrict__ codes)
+{
+    constexpr int Q = kUnitQuads / kWavesPerWg;
+    extern __shared__ uint32_t lds[];
+    uint32_t *slots = lds;  // kTeamSlots words, then the bucket table
+    const uint32_t lane = threadIdx.x & 63, wave = wave_in_wg(), tl = threadIdx.x;
+    uint32_t phase = 0;
+    Search sr;
+    auto fetch = [&](uint32_t u, v4f(&v)[Q]) {
+        const v4f *p4 = reinterpret_cast<const v4f *>(x) + (size_t)u * (kUnit / 4);
+#pragma unroll
+        for (int it = 0; it < Q; ++it) v[it] = ldg_at<NT>(p4, it * kWg + tl);
+    };
+    // Maximum over the team of the wave maxima m, through LDS; one barrier per call.
+    auto team_max = [&](uint32_t m) {
+        if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
+        __syncthreads();
+        const uint32_t *sp = slots + phase * kWavesPerWg;
+        const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
+        phase ^= 1;  // the other half of slots next time
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+    };
+    auto process = [&](uint32_t u, v4f(&v)[Q]) {
+        float fm = 0.0f;
+#pragma unroll
+        for (int it = 0; it < Q; ++it) fm = max4_abs(v[it], fm);
+        const float s = u2f(team_max(wave_max_u32(f2u(fm))));
+        if (tl == 0) scales[u] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        uint32_t *c4 = reinterpret_cast<uint32_t *>(codes) + (size_t)u * (kUnit / 4);
+#pragma unroll
+        for (int it = 0; it < Q; ++it) stg_at<NT>(c4, it * kWg + tl, encode_quad<FASTDIV>(sr, v[it], d, r, recip));
+    };
+    uint32_t u = blockIdx.x;
+    v4f a[Q], b[Q];
+    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is copied
+    sr = load_bucket_table(tab, lds + kTeamSlots);
+    __syncthreads();
+    // Steady state: the fetch of the next block is unconditional and comes before the work on the
+    // current one, so at the point where the current block's registers are first read the compiler
+    // knows exactly how many younger loads are outstanding and waits for the older ones only.  (A
+    // fetch under "if there is a next block" merges with the path that has none, and the merged
+    // state makes it wait for the loads it has just issued.)  The last block of a team is done
+    // outside the steady state.
+    if (u < n_full) {
+        for (;;) {
+            uint32_t nx = u + n_teams;
+            if (!(nx < n_full)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_teams;
+            if (!(nx < n_full)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
+    }
+    if (tail_len != 0 && blockIdx.x == gridDim.x - 1) {
+        const float *px = x + (size_t)n_full * kUnit;
+        uint8_t *pc = codes + (size_t)n_full * kUnit;
+        uint32_t m = 0;
+        for (uint32_t i = tl; i < tail_len; i += kWg) {
+            const uint32_t v = abs_bits(px[i]);
+            m = m > v ? m : v;
+        }
+        const float s = u2f(team_max(wave_max_u32(m)));
+        if (tl == 0) scales[n_full] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        for (uint32_t i = tl; i < tail_len; i += kWg) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
     }
 }
 
@@ -897,9 +1014,9 @@ struct AvgTeam {
 
     __device__ __forceinline__ void load_worker(const Slot &sl, int k)
     {
-        const uint32_t *c4 = uniform_ptr(reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start));
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start);
 #pragma unroll
-        for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + j * kWg + tl);
+        for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, j * kWg + tl);
     }
 
     __device__ __forceinline__ void load_all(const Slot &sl)
@@ -1120,7 +1237,10 @@ struct Tuning {
     int copy_nt = 1;
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
     int enc_wpb = 4;     // wavefronts per unit in the encoder: 1 or 4
-    int enc_wpc = 24;    // encoder wavefronts per compute unit
+    int enc_wpc = 24;    // encoder wavefronts per compute unit (general kernel)
+    int enc_lean = 1;    // whole aligned 4096-element blocks go to the kernel without slow paths in its loop,
+    int enc_lean_wpc = 8;  //   which keeps its loads in flight with this many wavefronts per compute unit
+    int enc_fill = 1;    //   and puts a team on every resident slot, even if some then get one block fewer
     int amax_q = 16;     // absmax: quads per lane in flight (unit = 256 q elements)
     int amax_wpc = 4;
     int dec_q = 16;      // decode: code words per lane in flight
@@ -1226,6 +1346,24 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     Plan p = make_plan(n, block, st.cus, g_tune.enc_wpc, wpb);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.n_bucket[kind] + kTeamSlots) * sizeof(uint32_t);
+    // Whole aligned blocks of exactly one unit: the kernel without slow paths in its loop.
+    if (fused && g_tune.enc_lean && p.B == (size_t)kUnit && n / kUnit >= 1 && n / kUnit < 0xFFFFFFFFull &&
+        ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
+        const uint32_t n_full = (uint32_t)(n / kUnit), tail = (uint32_t)(n % kUnit);
+        size_t teams = (size_t)st.cus * (size_t)g_tune.enc_lean_wpc / 4;  // a team on every resident slot
+        if (!g_tune.enc_fill) {  // or the smaller grid in which no team gets a block fewer than another
+            const size_t per = (n_full + teams - 1) / teams;
+            teams = (n_full + per - 1) / per;
+        }
+        if (teams > n_full) teams = n_full;
+        if (g_tune.fastdiv)
+            hipLaunchKernelGGL((k_encode_full<1, true>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x, n_full,
+                               (uint32_t)teams, tail, scales, codes);
+        else
+            hipLaunchKernelGGL((k_encode_full<1, false>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x, n_full,
+                               (uint32_t)teams, tail, scales, codes);
+        return after_launch("k_encode_full");
+    }
 #define DQ8_ENC(WPB, NT, FUSED, FD)                                                                              \
     hipLaunchKernelGGL((k_encode<WPB, NT, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
                        p.upb, p.n_units, p.n_teams, scales, codes)
@@ -1646,7 +1784,7 @@ int dq8_internal_tune(const char *key, int value)
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, {"dec_nt", &g_tune.dec_nt, 0, 2},
         {"avg_nt", &g_tune.avg_nt, 0, 2}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
-        {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
+        {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"blk_nt", &g_tune.blk_nt, 0, 2}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
