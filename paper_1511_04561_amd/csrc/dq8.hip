@@ -814,6 +814,98 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     }
 }
 
+// K-way decode-and-average of whole, aligned units, K = 2, 4 or 8: the common case of
+// k_decode_avg with nothing else in the loop.  Unit u covers elements [U u, U (u + 1)), U divides
+// the block size and block / U is a power of two, so a unit's block is u >> block_shift; out is
+// 16-byte and every code buffer 4-byte aligned.  The K scales of a unit travel with its code
+// words (read at the start of the unit's work they would cost a memory round trip per unit),
+// and the fetch of the next unit is unconditional in the steady state, so the compiler waits
+// for exactly the loads it needs.  A ragged last unit of tail_len elements is done by one
+// wavefront of the last workgroup after its loop.
+template <int KT, int Q, int NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t *__restrict__ tab, WorkerPtrs p,
+                                                                uint32_t n_full, uint32_t n_waves, uint32_t block_shift,
+                                                                uint32_t tail_len, float *__restrict__ out)
+{
+    static_assert(KT == 2 || KT == 4 || KT == 8, "1 / K must be exact");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int U = Q * 4 * kWave;
+    constexpr float rk = 1.0f / (float)KT;  // acc * (1 / K) equals acc / K exactly for a power of two
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    struct Slot {
+        uint32_t w[KT][Q];
+        float sw[KT];
+    };
+    auto fetch = [&](uint32_t u, Slot &sl) {
+#pragma unroll
+        for (int k = 0; k < KT; ++k) sl.sw[k] = p.scales[k][u >> block_shift];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.w[k][j] = ldg_at<NT>(c4, j * kWave + lane);
+        }
+    };
+    auto process = [&](uint32_t u, Slot &sl) {
+        float sc[KT];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[k])));
+        v4f *o4 = reinterpret_cast<v4f *>(out) + (size_t)u * (U / 4);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                a.x = a.x + lut_at<0>(lut, sl.w[k][j], lane4) * sc[k];
+                a.y = a.y + lut_at<1>(lut, sl.w[k][j], lane4) * sc[k];
+                a.z = a.z + lut_at<2>(lut, sl.w[k][j], lane4) * sc[k];
+                a.w = a.w + lut_at<3>(lut, sl.w[k][j], lane4) * sc[k];
+            }
+            a.x = a.x * rk;
+            a.y = a.y * rk;
+            a.z = a.z * rk;
+            a.w = a.w * rk;
+            stg<NT>(o4 + j * kWave + lane, a);
+        }
+    };
+    uint32_t u = (uint32_t)first_unit(WPW);
+    Slot a, b;
+    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    if (u < n_full) {
+        for (;;) {
+            uint32_t nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
+    }
+    if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
+        const size_t start = (size_t)n_full * U;
+        const size_t blk = n_full >> block_shift;
+        for (uint32_t i = lane; i < tail_len; i += kWave) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+            out[start + i] = acc * rk;
+        }
+    }
+}
+
 // Average of K workers' buffers (plus, optionally, a local fp32 array as the first term) with a
 // whole unit of 4096 elements held in one wavefront's registers: 16 quads of running sums per
 // lane, the workers added one after the other while the next worker's code words are in flight.
@@ -1028,11 +1120,15 @@ struct AvgTeam {
     }
 
     // Processes unit `sl`, whose code words are in w if it is fast, and leaves the words of `nx` there.
+    // STEADY: the caller knows that both units exist and are whole and aligned (true for all but a
+    // team's last two units when the host found the buffers aligned), so nothing here is
+    // conditional and the compiler waits for exactly the loads each step needs.
+    template <bool STEADY>
     __device__ __forceinline__ void process(const Slot &sl, const Slot &nx)
     {
         v4f acc[Q];
         uint32_t m = 0;
-        if (sl.active && sl.fast) {
+        if (STEADY || (sl.active && sl.fast)) {
             if (local) {  // not prefetched: the code words take the registers
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
 #pragma unroll
@@ -1064,7 +1160,7 @@ struct AvgTeam {
                 // to them, which costs a wavefront per SIMD.
 #pragma unroll
                 for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-                if (nx.fast) load_worker(nx, k);  // refill in place
+                if (STEADY || nx.fast) load_worker(nx, k);  // refill in place
             }
             float fm = 0.0f;
 #pragma unroll
@@ -1094,13 +1190,13 @@ struct AvgTeam {
             m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
         }
         phase ^= 1;  // the other half of the slots next time: one barrier per unit is enough
-        if (!sl.active) return;
+        if (!STEADY && !sl.active) return;
         const float s = u2f(m);
         if (tl == 0) scales_out[sl.un.block] = s;
         const float d = s == 0.0f ? 1.0f : s;
         const float r = 1.0f / d;
         const bool recip = reciprocal_ok(d);
-        if (sl.fast) {
+        if (STEADY || sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
 #pragma unroll
             for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWg + tl, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
@@ -1114,7 +1210,7 @@ struct AvgTeam {
 template <int KT, int NT, bool FASTDIV, int TEAMS>
 __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
                                                             const float *__restrict__ local, size_t n, size_t B, size_t nb,
-                                                            size_t n_units, size_t n_teams, uint32_t iters,
+                                                            size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
                                                             float *__restrict__ scales_out, uint8_t *__restrict__ codes_out)
 {
     __shared__ __align__(256) float lut[256 * kLutCopies];
@@ -1155,13 +1251,24 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
         e.sr = make_search(bucket, tab[kLoKeyOff], nbk);
     }
     __syncthreads();
-    for (uint32_t it = 0; it < iters; it += 2) {
+    // `steady` (even) leading iterations in which this and the next unit of every team are whole
+    // aligned units, then the general ones.
+    uint32_t it = 0;
+    for (; it < steady; it += 2) {
         e.open(u + n_teams, b);
-        e.process(a, b);
+        e.template process<true>(a, b);
+        u += n_teams;
+        e.open(u + n_teams, a);
+        e.template process<true>(b, a);
+        u += n_teams;
+    }
+    for (; it < iters; it += 2) {
+        e.open(u + n_teams, b);
+        e.template process<false>(a, b);
         u += n_teams;
         if (it + 1 >= iters) break;
         e.open(u + n_teams, a);
-        e.process(b, a);
+        e.template process<false>(b, a);
         u += n_teams;
     }
 }
@@ -1234,6 +1341,10 @@ struct Tuning {
     int enc_nt = 1;      //   4-byte code stores: plain non-temporal is best
     int dec_nt = 2;      //   16-byte fp32 stores: write-through non-temporal is best
     int avg_nt = 2;
+    int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
+    int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
+    int avg_lean_wpc = 4;
+    int avg_lean_wpw = 4;
     int copy_nt = 1;
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
     int enc_wpb = 4;     // wavefronts per unit in the encoder: 1 or 4
@@ -1252,6 +1363,7 @@ struct Tuning {
     int blk_wpw = 8;     // register-resident average: wavefronts per workgroup (two workgroups per compute unit)
     int blk_nt = 2;
     int avg_team = 1;    // average-then-compress with K = 2, 4, 8: the team kernel (0: the wave-per-block kernel)
+    int avg_steady = 1;  //   unconditional steady-state iterations when the buffers are aligned
     int avg_teams = 3;   //   teams per workgroup: 2, 3 or 4
     int avg_wgpc = 1;    //   workgroups per compute unit (2 only with 2 teams)
     int copy_q = 2;
@@ -1425,11 +1537,19 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
     Plan p = make_plan(n, block, st.cus, 4 * teams * wgs_per_cu, 4, 4 * teams, kUnit);
     const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
+    // Iterations in which every team's current and next unit are whole aligned blocks.
+    uint32_t steady = 0;
+    bool aligned = g_tune.avg_steady && p.B == (size_t)kUnit && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
+    if (aligned) {
+        const size_t all_valid = (n / kUnit) / p.n_teams;  // iterations in which every team has a whole unit
+        if (all_valid >= 2) steady = (uint32_t)((all_valid - 1) & ~(size_t)1);
+    }
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.n_bucket[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
 #define DQ8_TEAM(KT, NT, FD, T)                                                                               \
     hipLaunchKernelGGL((k_avg_team<KT, NT, FD, T>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
-                       p.B, p.nb, p.n_units, p.n_teams, iters, scales_out, codes_out)
+                       p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
 #define DQ8_TEAM_T(KT, NT, FD)   \
     if (teams == 3) {            \
         DQ8_TEAM(KT, NT, FD, 3); \
@@ -1622,6 +1742,53 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     }
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // Whole aligned units with a power-of-two number of them per block (or a single block): the
+    // kernel without slow paths in its loop.
+    if (fixed_k && g_tune.avg_lean) {
+        const int lq = g_tune.avg_lean_q == 4 ? 4 : 2;
+        const int lw = g_tune.avg_lean_wpw == 16 ? 16 : (g_tune.avg_lean_wpw == 8 ? 8 : 4);
+        const size_t U = (size_t)lq * 4 * kWave;
+        const size_t upb_l = p.B / U;
+        bool ok = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);
+        ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0;
+        for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)codes[k] & 3) == 0;
+        if (ok) {
+            uint32_t shift = 31;  // a single block: every unit belongs to block 0
+            if (p.nb > 1) {
+                shift = 0;
+                while (((size_t)1 << shift) < upb_l) ++shift;
+            }
+            const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
+            size_t waves = (size_t)st->cus * (size_t)g_tune.avg_lean_wpc;
+            if (waves > n_full) waves = n_full;
+            const unsigned grid = (unsigned)((waves + lw - 1) / lw);
+            const uint32_t n_waves = grid * (uint32_t)lw;
+#define DQ8_AVGL(KT, Q, WPW)                                                                                      \
+    hipLaunchKernelGGL((k_decode_avg_full<KT, Q, 2, WPW>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, n_full, \
+                       n_waves, shift, tail, out)
+#define DQ8_AVGL_W(KT, Q)                  \
+    switch (lw) {                          \
+    case 16: DQ8_AVGL(KT, Q, 16); break;   \
+    case 8: DQ8_AVGL(KT, Q, 8); break;     \
+    default: DQ8_AVGL(KT, Q, 4); break;    \
+    }
+#define DQ8_AVGL_Q(KT)                     \
+    if (lq == 4) {                         \
+        DQ8_AVGL_W(KT, 4)                  \
+    } else {                               \
+        DQ8_AVGL_W(KT, 2)                  \
+    }
+            switch (K) {
+            case 2: DQ8_AVGL_Q(2) break;
+            case 4: DQ8_AVGL_Q(4) break;
+            default: DQ8_AVGL_Q(8) break;
+            }
+#undef DQ8_AVGL_Q
+#undef DQ8_AVGL_W
+#undef DQ8_AVGL
+            return after_launch("k_decode_avg_full");
+        }
+    }
 #define DQ8_AVG(KT, Q, NT, WPW)                                                                                   \
     hipLaunchKernelGGL((k_decode_avg<KT, Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
                        p.nb, p.upb, p.n_units, p.n_teams, out)
@@ -1783,10 +1950,11 @@ int dq8_internal_tune(const char *key, int value)
     if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, {"dec_nt", &g_tune.dec_nt, 0, 2},
-        {"avg_nt", &g_tune.avg_nt, 0, 2}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"avg_nt", &g_tune.avg_nt, 0, 2}, {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
+        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
-        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"blk_nt", &g_tune.blk_nt, 0, 2}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"blk_nt", &g_tune.blk_nt, 0, 2}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)
         if (!std::strcmp(k.name, key)) {
