@@ -822,22 +822,32 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
 // and the fetch of the next unit is unconditional in the steady state, so the compiler waits
 // for exactly the loads it needs.  A ragged last unit of tail_len elements is done by one
 // wavefront of the last workgroup after its loop.
-template <int KT, int Q, int NT, int WPW>
+// LOCAL: an fp32 array (16-byte aligned) is the first term of every sum and the divisor is K + 1.
+template <int KT, int Q, int NT, int WPW, bool LOCAL>
 __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t *__restrict__ tab, WorkerPtrs p,
-                                                                uint32_t n_full, uint32_t n_waves, uint32_t block_shift,
-                                                                uint32_t tail_len, float *__restrict__ out)
+                                                                const float *__restrict__ local, uint32_t n_full,
+                                                                uint32_t n_waves, uint32_t block_shift, uint32_t tail_len,
+                                                                float *__restrict__ out)
 {
-    static_assert(KT == 2 || KT == 4 || KT == 8, "1 / K must be exact");
+    static_assert(KT == 2 || KT == 4 || KT == 8, "unrolled for these K");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     constexpr int U = Q * 4 * kWave;
+    constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
     constexpr float rk = 1.0f / (float)KT;  // acc * (1 / K) equals acc / K exactly for a power of two
+    auto mean_of = [&](float acc) { return LOCAL ? acc / fk : acc * rk; };
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t lane4 = lane * 4;
     struct Slot {
         uint32_t w[KT][Q];
         float sw[KT];
+        v4f loc[LOCAL ? Q : 1];
     };
     auto fetch = [&](uint32_t u, Slot &sl) {
+        if (LOCAL) {
+            const v4f *l4 = reinterpret_cast<const v4f *>(local) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.loc[j] = ldg_at<NT>(l4, j * kWave + lane);
+        }
 #pragma unroll
         for (int k = 0; k < KT; ++k) sl.sw[k] = p.scales[k][u >> block_shift];
 #pragma unroll
@@ -855,6 +865,12 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
 #pragma unroll
         for (int j = 0; j < Q; ++j) {
             v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (LOCAL) {  // the sum starts at +0: a local -0 becomes +0
+                a.x = a.x + sl.loc[j].x;
+                a.y = a.y + sl.loc[j].y;
+                a.z = a.z + sl.loc[j].z;
+                a.w = a.w + sl.loc[j].w;
+            }
 #pragma unroll
             for (int k = 0; k < KT; ++k) {
                 a.x = a.x + lut_at<0>(lut, sl.w[k][j], lane4) * sc[k];
@@ -862,10 +878,10 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
                 a.z = a.z + lut_at<2>(lut, sl.w[k][j], lane4) * sc[k];
                 a.w = a.w + lut_at<3>(lut, sl.w[k][j], lane4) * sc[k];
             }
-            a.x = a.x * rk;
-            a.y = a.y * rk;
-            a.z = a.z * rk;
-            a.w = a.w * rk;
+            a.x = mean_of(a.x);
+            a.y = mean_of(a.y);
+            a.z = mean_of(a.z);
+            a.w = mean_of(a.w);
             stg<NT>(o4 + j * kWave + lane, a);
         }
     };
@@ -899,9 +915,10 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
         const size_t blk = n_full >> block_shift;
         for (uint32_t i = lane; i < tail_len; i += kWave) {
             float acc = 0.0f;
+            if (LOCAL) acc = acc + local[start + i];
 #pragma unroll
             for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
-            out[start + i] = acc * rk;
+            out[start + i] = mean_of(acc);
         }
     }
 }
@@ -1610,6 +1627,66 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     return after_launch("k_avg_block");
 }
 
+// K-way decode-and-average (K = 2, 4, 8; optional local term) of whole aligned units with a power-of-two
+// number of them per block (or a single block): the kernel without slow paths in its loop.
+// *launched = false (and nothing done) when the buffers do not qualify.
+int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                    const Plan &p, float *out, hipStream_t stream, bool *launched)
+{
+    *launched = false;
+    const int lq = g_tune.avg_lean_q == 4 ? 4 : 2;
+    const int lw = g_tune.avg_lean_wpw == 16 ? 16 : (g_tune.avg_lean_wpw == 8 ? 8 : 4);
+    const size_t U = (size_t)lq * 4 * kWave;
+    const size_t upb_l = p.B / U;
+    bool ok = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);
+    ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
+    if (!ok) return DQ8_OK;
+    uint32_t shift = 31;  // a single block: every unit belongs to block 0
+    if (p.nb > 1) {
+        shift = 0;
+        while (((size_t)1 << shift) < upb_l) ++shift;
+    }
+    const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
+    size_t waves = (size_t)st.cus * (size_t)g_tune.avg_lean_wpc;
+    if (waves > n_full) waves = n_full;
+    const unsigned grid = (unsigned)((waves + lw - 1) / lw);
+    const uint32_t n_waves = grid * (uint32_t)lw;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+#define DQ8_AVGL(KT, Q, WPW, LOC)                                                                                     \
+    hipLaunchKernelGGL((k_decode_avg_full<KT, Q, 2, WPW, LOC>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, local, \
+                       n_full, n_waves, shift, tail, out)
+#define DQ8_AVGL_L(KT, Q, WPW)         \
+    if (local) {                       \
+        DQ8_AVGL(KT, Q, WPW, true);    \
+    } else {                           \
+        DQ8_AVGL(KT, Q, WPW, false);   \
+    }
+#define DQ8_AVGL_W(KT, Q)                  \
+    switch (lw) {                          \
+    case 16: DQ8_AVGL_L(KT, Q, 16) break;  \
+    case 8: DQ8_AVGL_L(KT, Q, 8) break;    \
+    default: DQ8_AVGL_L(KT, Q, 4) break;   \
+    }
+#define DQ8_AVGL_Q(KT)                     \
+    if (lq == 4) {                         \
+        DQ8_AVGL_W(KT, 4)                  \
+    } else {                               \
+        DQ8_AVGL_W(KT, 2)                  \
+    }
+    switch (K) {
+    case 2: DQ8_AVGL_Q(2) break;
+    case 4: DQ8_AVGL_Q(4) break;
+    default: DQ8_AVGL_Q(8) break;
+    }
+#undef DQ8_AVGL_Q
+#undef DQ8_AVGL_W
+#undef DQ8_AVGL_L
+#undef DQ8_AVGL
+    *launched = true;
+    return after_launch("k_decode_avg_full");
+}
+
 }  // namespace
 
 extern "C" {
@@ -1742,52 +1819,10 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     }
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // Whole aligned units with a power-of-two number of them per block (or a single block): the
-    // kernel without slow paths in its loop.
     if (fixed_k && g_tune.avg_lean) {
-        const int lq = g_tune.avg_lean_q == 4 ? 4 : 2;
-        const int lw = g_tune.avg_lean_wpw == 16 ? 16 : (g_tune.avg_lean_wpw == 8 ? 8 : 4);
-        const size_t U = (size_t)lq * 4 * kWave;
-        const size_t upb_l = p.B / U;
-        bool ok = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);
-        ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0;
-        for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)codes[k] & 3) == 0;
-        if (ok) {
-            uint32_t shift = 31;  // a single block: every unit belongs to block 0
-            if (p.nb > 1) {
-                shift = 0;
-                while (((size_t)1 << shift) < upb_l) ++shift;
-            }
-            const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
-            size_t waves = (size_t)st->cus * (size_t)g_tune.avg_lean_wpc;
-            if (waves > n_full) waves = n_full;
-            const unsigned grid = (unsigned)((waves + lw - 1) / lw);
-            const uint32_t n_waves = grid * (uint32_t)lw;
-#define DQ8_AVGL(KT, Q, WPW)                                                                                      \
-    hipLaunchKernelGGL((k_decode_avg_full<KT, Q, 2, WPW>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, n_full, \
-                       n_waves, shift, tail, out)
-#define DQ8_AVGL_W(KT, Q)                  \
-    switch (lw) {                          \
-    case 16: DQ8_AVGL(KT, Q, 16); break;   \
-    case 8: DQ8_AVGL(KT, Q, 8); break;     \
-    default: DQ8_AVGL(KT, Q, 4); break;    \
-    }
-#define DQ8_AVGL_Q(KT)                     \
-    if (lq == 4) {                         \
-        DQ8_AVGL_W(KT, 4)                  \
-    } else {                               \
-        DQ8_AVGL_W(KT, 2)                  \
-    }
-            switch (K) {
-            case 2: DQ8_AVGL_Q(2) break;
-            case 4: DQ8_AVGL_Q(4) break;
-            default: DQ8_AVGL_Q(8) break;
-            }
-#undef DQ8_AVGL_Q
-#undef DQ8_AVGL_W
-#undef DQ8_AVGL
-            return after_launch("k_decode_avg_full");
-        }
+        bool launched = false;
+        rc = launch_avg_full(*st, kind, wp, K, nullptr, n, p, out, stream, &launched);
+        if (rc || launched) return rc;
     }
 #define DQ8_AVG(KT, Q, NT, WPW)                                                                                   \
     hipLaunchKernelGGL((k_decode_avg<KT, Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
@@ -1848,6 +1883,12 @@ int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
+    if ((K == 2 || K == 4 || K == 8) && g_tune.avg_lean) {
+        const Plan p = make_plan(n, block, st->cus, 1, 1);
+        bool launched = false;
+        rc = launch_avg_full(*st, kind, wp, K, local, n, p, out, static_cast<hipStream_t>(hip_stream), &launched);
+        if (rc || launched) return rc;
+    }
     return launch_avg_block(*st, kind, wp, K, local, n, block, out, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
