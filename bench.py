@@ -39,7 +39,7 @@ N_SETS = 4
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs on this script, each scaled by what the same counter reads for the calibration
 # copy kernel: 1.99980 and 1.00000); the runs are recorded in profiles/hbm_traffic_bench_c5.md.
-MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481300 + 238675) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481263 + 238675) * 1024)}
 
 
 def algorithmic_bytes(n, nb):
