@@ -163,11 +163,18 @@ def test_all_codes_decode_and_reencode(dq8):
             same_bits(back, codes, "encode(decode(c)) == c")
 
 
+AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1),
+             (100, 7, 0), (4096, 0, 0), (4095, 0, 0),
+             (5 * 1024 + 100, 1024, 0),   # two whole units per block, ragged last unit
+             (3 * 1536, 1536, 0),         # three units per block: not a power of two
+             (3 * 2048 + 7, 2048, 0), (40 * 512, 512, 0), (511, 0, 0), (512, 0, 0), (513, 0, 0)]
+
+
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 32])
 def test_decode_accumulate_avg(dq8, kind, K):
     rng = np.random.Generator(np.random.PCG64(900 + 10 * K + kind))
-    for n, block, off in [(2 * 4096 + 333, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1), (100, 7, 0)]:
+    for n, block, off in AVG_CASES:
         print("avg kind=%d K=%d n=%d block=%d off=%d" % (kind, K, n, block, off), flush=True)
         nb = oracle.dq8_oracle.n_blocks(n, block)
         cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
@@ -179,8 +186,6 @@ def test_decode_accumulate_avg(dq8, kind, K):
         go.check("avg")
 
 
-AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1),
-             (100, 7, 0), (4096, 0, 0), (4095, 0, 0)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
