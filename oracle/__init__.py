@@ -6,6 +6,7 @@ package.  It shares nothing with the HIP library.
 from .dq8_oracle import (  # noqa: F401
     DYNAMIC_TREE,
     LINEAR,
+    MANTISSA,
     STATIC_TREE,
     absmax,
     build,

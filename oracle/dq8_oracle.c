@@ -51,7 +51,7 @@
 #error "build the oracle without fast-math and without FMA contraction"
 #endif
 
-enum { DQ8O_DYNAMIC_TREE = 0, DQ8O_LINEAR = 1, DQ8O_STATIC_TREE = 2 };
+enum { DQ8O_DYNAMIC_TREE = 0, DQ8O_LINEAR = 1, DQ8O_STATIC_TREE = 2, DQ8O_MANTISSA = 3 };
 
 static int g_threads = 1; /* used only to time the oracle; results do not depend on it */
 
@@ -88,6 +88,12 @@ int dq8o_get_threads(void) { return g_threads; }
  * a larger value: decade 10^(E-7), value (0.1 + 0.9 (k + 1/2) / 16) 10^(E-7)
  *     = (32 + 9 (2k+1)) / (32 10^(8-E)).
  * This type has no zero.
+ *
+ * Mantissa type (Sec. 3.1, first paragraph: with a 3-bit exponent the mantissa
+ * holds the values 0 to 15): 3-bit exponent field E, 4-bit mantissa m, value
+ * m 10^(E-8) = m / 10^(8-E), the same decades as the static tree (whose tree
+ * covers 0.1 .. 1 of 10^(E-7)).  Several fields stand for the same value: m = 0
+ * is zero for every E, and m = 10 of one decade equals m = 1 of the next.
  */
 int dq8o_codebook(int kind, float *cb)
 {
@@ -117,6 +123,11 @@ int dq8o_codebook(int kind, float *cb)
             num = (double)(32 + 9 * (2 * k + 1));
             den = 32.0;
             for (e = 0; e < 8 - E; ++e) den *= 10.0; /* exact: at most 32e8 */
+        } else if (kind == DQ8O_MANTISSA) {
+            int E = j >> 4, m = j & 15, e;
+            num = (double)m;
+            den = 1.0;
+            for (e = 0; e < 8 - E; ++e) den *= 10.0; /* exact: at most 1e8 */
         } else {
             return 2;
         }
@@ -165,7 +176,8 @@ int dq8o_absmax(const float *x, size_t n, size_t block, float *scales)
  * comparison of the real distances.
  * Tie rules: equal distance -> the code of smaller magnitude; equal magnitude as
  * well (+v / -v when xn is a zero or rounds to a tie, or the two zeros) -> the
- * code whose sign bit equals the sign bit of xn.
+ * code whose sign bit equals the sign bit of xn; and among codes of one sign that
+ * stand for the same value (the mantissa type has such) -> the smallest code.
  */
 static uint8_t nearest_code(const float *cb, float xn)
 {

@@ -12,7 +12,7 @@ import subprocess
 
 import numpy as np
 
-DYNAMIC_TREE, LINEAR, STATIC_TREE = 0, 1, 2
+DYNAMIC_TREE, LINEAR, STATIC_TREE, MANTISSA = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dq8_oracle.c")

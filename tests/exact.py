@@ -37,11 +37,17 @@ def tree_walk_value(kind, field):
     kind 1 linear: the field counts equal steps from 0 to 1.
     kind 2 static tree: 3 exponent bits (larger = bigger decade, top decade 10^0),
     4 bits bisect (0.1, 1).
+    kind 3 mantissa: 3 exponent bits as in the static tree, 4 bits are the integer mantissa 0..15,
+    which counts tenths of the decade: m * 10^(E-7) / 10.
     The value of a tree path is the middle of the interval the path ends in.
     """
     bits = [(field >> (6 - i)) & 1 for i in range(7)]
     if kind == 1:
         return Fraction(field, 127)
+    if kind == 3:
+        e = bits[0] * 4 + bits[1] * 2 + bits[2]
+        m = bits[3] * 8 + bits[4] * 4 + bits[5] * 2 + bits[6]
+        return Fraction(m, 10) * Fraction(1, 10 ** (7 - e))
     if kind == 0:
         n = 0
         while n < 7 and bits[n] == 0:

@@ -17,7 +17,7 @@ from tests.exact import codebook_exact, round_to_f32
 KINDS = [oracle.DYNAMIC_TREE, oracle.LINEAR, oracle.STATIC_TREE]
 
 
-@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("kind", KINDS + [oracle.MANTISSA])
 def test_tree_walk_in_exact_rationals_gives_the_same_table(kind):
     cb = oracle.codebook(kind)
     exact = codebook_exact(kind)
@@ -71,6 +71,25 @@ def test_static_tree_structure():
         assert np.allclose(np.diff(dec), 0.9 / 16 * 10.0 ** (e - 7), rtol=1e-5, atol=0)
     assert np.all(cb[:128] > 0)  # this type has no zero
     assert abs(cb[127] - 0.971875) < 1e-7
+
+
+def test_mantissa_structure():
+    """Sec. 3.1: a 3-bit exponent and a mantissa that holds 0..15.  The type repeats values: zero once per
+    exponent, and ten tenths of a decade are one tenth of the next."""
+    cb = oracle.codebook(oracle.MANTISSA)
+    bits = cb.view(np.uint32)
+    assert np.all(bits[128:] == (bits[:128] | np.uint32(0x80000000)))
+    mags = cb[:128]
+    for E in range(8):
+        dec = mags[16 * E:16 * E + 16].astype(np.float64)
+        assert dec[0] == 0
+        assert np.allclose(dec[1:] / dec[1], np.arange(1, 16), rtol=1e-6)  # equal steps: a linear mantissa
+        if E < 7:
+            assert mags[16 * E + 10] == mags[16 * (E + 1) + 1]  # 10 tenths = 1 tenth of the next decade
+            assert mags[16 * E + 15] < mags[16 * (E + 1) + 2]
+    assert mags[16 * 7 + 10] == 1.0 and mags.max() == np.float32(1.5)
+    assert float(mags[1]) == float(np.float32(1e-8))
+    assert len(set(mags.tolist())) == 1 + 8 * 15 - 7  # 114 distinct magnitudes
 
 
 def test_paper_worked_examples_fall_in_the_oracle_leaf(golden_dir):

@@ -168,7 +168,7 @@ def _exhaustive_values(kind):
     return [np.float32(v) for v in vals]
 
 
-@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("kind", KINDS + [oracle.MANTISSA])
 def test_exhaustive_tiny_inputs_against_exact_rationals(kind):
     vals = _exhaustive_values(kind)
     cbf = oracle.codebook(kind)
@@ -224,6 +224,61 @@ def test_zero_blocks_and_degenerate_scales(kind):
     # n == 0
     c0, s0 = oracle.encode(kind, np.zeros(0, np.float32), 16)
     assert c0.size == 0 and s0.size == 0
+
+
+def _canonical(cb):
+    """Smallest code of each (value, sign) class."""
+    first = {}
+    canon = np.zeros(256, np.uint8)
+    for c in range(256):
+        key = (float(abs(cb[c])), c >> 7)
+        first.setdefault(key, c)
+        canon[c] = first[key]
+    return canon
+
+
+def test_mantissa_type_repeated_values_encode_to_the_smallest_code():
+    """The mantissa type has several codes per value; compression picks the smallest one, so
+    encode(decode(c)) is the canonical code of c's value, for every code and several scales."""
+    kind = oracle.MANTISSA
+    cb = oracle.codebook(kind)
+    canon = _canonical(cb)
+    assert np.sum(canon != np.arange(256)) == 2 * (7 + 7)  # 7 spare zeros and 7 repeated tenths per sign
+    codes = np.arange(256, dtype=np.uint8)
+    for s in (1.0, 3.0, 1e-3, 1e30, 1e-30):
+        sc = np.array([s], np.float32)
+        dec = oracle.decode(kind, codes, sc, 0)
+        back, _ = oracle.encode(kind, dec, 0, scales=sc)
+        assert np.array_equal(back, canon), s
+
+
+def test_mantissa_type_is_nearest_over_its_distinct_values():
+    """Sorted-table search over the distinct magnitudes (Sec. 3.2) against the 256-way scan."""
+    kind = oracle.MANTISSA
+    cb = oracle.codebook(kind)
+    canon = _canonical(cb)
+    mags = np.unique(cb[:128]).astype(np.float64)
+    code_of = {float(v): int(canon[np.nonzero(cb[:128] == np.float32(v))[0][0]]) for v in mags}
+    mid = (mags[:-1] + mags[1:]) / 2
+    rng = np.random.Generator(np.random.PCG64(5))
+    near = ulp_neighbourhood(mid.astype(np.float32), 3)
+    rnd = rng.integers(0, 0x3FC00000, 200000).astype(np.int32).view(np.float32)  # [0, 1.5)
+    xn = np.concatenate([near, -near, rnd, -rnd, np.array([0.0, -0.0, 1.5, 1.75, -2.0], np.float32)])
+    idx = np.searchsorted(mid, np.abs(xn).astype(np.float64), side="left")  # ties to the lower magnitude
+    want = np.array([code_of[float(mags[i])] for i in idx], np.int64) | (np.signbit(xn).astype(np.int64) << 7)
+    got, _ = oracle.encode(kind, xn, 0, scales=ONE)
+    assert np.array_equal(got, want.astype(np.uint8))
+
+
+def test_mantissa_type_round_trip_error_is_at_most_half_a_step():
+    kind = oracle.MANTISSA
+    rng = np.random.Generator(np.random.PCG64(6))
+    x = (rng.standard_normal(200000) * np.exp(rng.uniform(-12, 0, 200000))).astype(np.float32)
+    codes, scales = oracle.encode(kind, x, 0)
+    out = oracle.decode(kind, codes, scales, 0).astype(np.float64)
+    xn = np.abs(x.astype(np.float64)) / float(scales[0])
+    step = 10.0 ** np.clip(np.floor(np.log10(np.maximum(xn, 1e-300))), -8, -1)  # one unit of the mantissa in xn's decade
+    assert np.all(np.abs(out - x) <= (0.5 * step * 1.0000001 + 2.0 ** -24) * float(scales[0]))
 
 
 def test_averaging_special_cases():
