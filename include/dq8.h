@@ -53,7 +53,8 @@ enum {
 enum {
     DQ8_DYNAMIC_TREE = 0, /* dynamic exponent + bisection tree over (0.1, 1) */
     DQ8_LINEAR = 1,       /* linear quantisation, magnitudes j / 127 */
-    DQ8_STATIC_TREE = 2   /* 3-bit static exponent + 4-bit bisection tree */
+    DQ8_STATIC_TREE = 2,  /* 3-bit static exponent + 4-bit bisection tree */
+    DQ8_MANTISSA = 3      /* 3-bit static exponent + 4-bit integer mantissa 0..15 */
 };
 
 /* dq8_encode flag: `scales` is an input computed elsewhere (e.g. by dq8_absmax). */
@@ -65,12 +66,18 @@ enum {
 /*
  * The table of a data type (Sec. 3.1): cb256_host[c] is the value code c stands for when the
  * scale is 1.  HOST pointer to 256 floats, written by the call.  Entries 0..127 are the
- * magnitudes in ascending order, entry c + 128 is the negation of entry c (so entry 128 is
- * -0.0f where entry 0 is 0).  Pure host computation, needs no device.
+ * magnitudes (ascending for the tree and linear types), entry c + 128 is the negation of
+ * entry c (so entry 128 is -0.0f where entry 0 is 0).  Pure host computation, needs no device.
  *   dynamic tree: entry 0 is 0; an entry whose 7-bit index has n leading zeros, then a one,
  *     then t = 6 - n bits read as k, is (0.1 + 0.9 (k + 1/2) / 2^t) * 10^-n;
  *   linear: j / 127;
- *   static tree: index = 16 E + k, value (0.1 + 0.9 (k + 1/2) / 16) * 10^(E - 7).
+ *   static tree: index = 16 E + k, value (0.1 + 0.9 (k + 1/2) / 16) * 10^(E - 7);
+ *   mantissa: index = 16 E + m, value m * 10^(E - 8): the decades of the static tree, counted
+ *     in tenths.  Its entries are not ascending and several stand for one value (m = 0 of every
+ *     decade is zero, m = 10 of a decade is m = 1 of the next, and entries above 1 exist:
+ *     1.1 .. 1.5); the encoder emits the smallest index among those of the nearest value, so
+ *     encode(decode(c)) is that smallest index, not always c.  A decade offset as in
+ *     Sec. 3.1 is a scale: pass scales 10^offset with DQ8_SCALES_GIVEN instead of the absmax.
  * Each entry is the exact ratio rounded once to binary32.
  */
 int dq8_codebook(int kind, float *cb256_host);

@@ -33,6 +33,9 @@
 namespace {
 
 using dq8::kBucketOff;
+using dq8::kHasRemapOff;
+using dq8::kRemapOff;
+using dq8::kRemapWords;
 using dq8::kCbOff;
 using dq8::kLoKeyOff;
 using dq8::kNBucketOff;
@@ -44,7 +47,7 @@ constexpr int kWavesPerWg = 4;
 constexpr int kWg = kWave * kWavesPerWg;
 constexpr int kUnit = 4096;                      // elements per unit
 constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
-constexpr int kKinds = 3;
+constexpr int kKinds = 4;
 constexpr int kLutCopies = 64;                   // one copy of the decode table per lane
 constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
 
@@ -181,25 +184,30 @@ __device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb,
     return r;
 }
 
-// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range.
+// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and
+// for a data type with repeated values the table that turns a rank into its code.
 struct Search {
     const uint32_t *bucket;  // LDS on the device
+    const uint32_t *remap;   // NULL when every rank is its own code
     uint32_t lo_key;         // key of the first bucket
     float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
 };
 
-__host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket)
+__host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket,
+                                                       const uint32_t *remap = nullptr)
 {
     Search s;
     s.bucket = bucket;
+    s.remap = remap;
     s.lo_key = lo_key;
     s.lo_f = u2f((lo_key << 16) + 0x8000u);
     s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
     return s;
 }
 
-// sum >> 16 = number of thresholds <= |xn|; the low half of sum measures the distance to
-// the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
+// sum >> 16 = rank of the nearest table value (the number of thresholds <= |xn|), which is its
+// magnitude field except for a type with a rank-to-code table (see finish_sum); the low half of
+// sum measures the distance to the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
 // so the clamp is done on the value.
 __host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
 {
@@ -214,19 +222,35 @@ __host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float x
     return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
 }
 
+// Rank to magnitude field in bits 16..22, for the types where the two differ.  Kept out of
+// search_sum so that an encoder takes this (wavefront-uniform) branch once per group of sums.
+__host__ __device__ __forceinline__ uint32_t finish_sum(const Search &s, uint32_t sum) { return s.remap[sum >> 16] << 16; }
+
 // (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
 __host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (sum + kNearWindow) & 0xFFFFu; }
 
 // Code = magnitude index, bit 7 = sign bit of the input (the divisor is positive).
 __host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
 
-__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_from(search_sum(s, x / d), x); }
+__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, uint32_t sum, float x)
+{
+    if (s.remap) sum = finish_sum(s, sum);
+    return code_from(sum, x);
+}
+
+__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_of(s, search_sum(s, x / d), x); }
 
 // Four codes in one word: byte i = magnitude index of sum i (its byte 2) with the sign bit of
 // x i (top bit of its byte 3).  v_perm_b32 gathers the bytes: selector byte 0..3 picks a byte
 // of the second operand, 4..7 of the first, 0x0C gives zero.
-__device__ __forceinline__ uint32_t pack_codes(uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
+__device__ __forceinline__ uint32_t pack_codes(const Search &sr, uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
 {
+    if (sr.remap) {
+        s0 = finish_sum(sr, s0);
+        s1 = finish_sum(sr, s1);
+        s2 = finish_sum(sr, s2);
+        s3 = finish_sum(sr, s3);
+    }
     const uint32_t m01 = __builtin_amdgcn_perm(s1, s0, 0x0C0C0602u);
     const uint32_t m23 = __builtin_amdgcn_perm(s3, s2, 0x06020C0Cu);
     const uint32_t g01 = __builtin_amdgcn_perm(f2u(v.y), f2u(v.x), 0x0C0C0703u);
@@ -256,9 +280,9 @@ __device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d
         k0 = k0 < k1 ? k0 : k1;
         k2 = k2 < k3 ? k2 : k3;
         k0 = k0 < k2 ? k0 : k2;
-        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(s0, s1, s2, s3, v);
+        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(sr, s0, s1, s2, s3, v);
     }
-    return pack_codes(search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
+    return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
 }
 
 template <bool FASTDIV>
@@ -266,17 +290,24 @@ __device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float 
 {
     if (FASTDIV && recip) {
         uint32_t s0 = search_sum(sr, x * r);
-        if (near_key(s0) > 2 * kNearWindow) return code_from(s0, x);
+        if (near_key(s0) > 2 * kNearWindow) return code_of(sr, s0, x);
     }
     return code_exact(sr, x, d);
 }
 
-// Copies the bucket table to LDS; the caller synchronises the workgroup before using it.
-__device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds)
+// Copies the bucket table (and the rank-to-code table of a type that has one, right behind it)
+// to LDS with all `n_threads` threads of the workgroup; the caller synchronises the workgroup
+// before using it.
+__device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds, uint32_t n_threads = kWg)
 {
-    uint32_t nbk = tab[kNBucketOff];
-    for (uint32_t i = threadIdx.x; i < nbk; i += kWg) lds[i] = tab[kBucketOff + i];
-    return make_search(lds, tab[kLoKeyOff], nbk);
+    const uint32_t nbk = tab[kNBucketOff];
+    for (uint32_t i = threadIdx.x; i < nbk; i += n_threads) lds[i] = tab[kBucketOff + i];
+    const uint32_t *remap = nullptr;
+    if (tab[kHasRemapOff]) {
+        for (uint32_t i = threadIdx.x; i < (uint32_t)kRemapWords; i += n_threads) lds[nbk + i] = tab[kRemapOff + i];
+        remap = lds + nbk;
+    }
+    return make_search(lds, tab[kLoKeyOff], nbk, remap);
 }
 
 // Decode table in LDS, one copy per lane: entry (code, lane) at byte address code * 256 +
@@ -568,7 +599,8 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
 // nothing else in the loop.  Block b starts at element 4096 b, x is 16-byte and codes 4-byte
 // aligned, so unit geometry is a multiplication and there is no slow path to branch around.
 // A ragged last block of tail_len elements is done by the last workgroup after its loop.
-template <int NT, bool FASTDIV>
+// REMAP = false promises a type without a rank-to-code table: the test for one drops out of the loop.
+template <int NT, bool FASTDIV, bool REMAP>
 __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict__ tab, const float *__restrict__ x,
                                                     uint32_t n_full, uint32_t n_teams, uint32_t tail_len,
                                                     float *__restrict__ scales, uint8_t *__restrict__ codes)
@@ -610,6 +642,7 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
     v4f a[Q], b[Q];
     if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is copied
     sr = load_bucket_table(tab, lds + kTeamSlots);
+    if (!REMAP) sr.remap = nullptr;
     __syncthreads();
     // Steady state: the fetch of the next block is unconditional and comes before the work on the
     // current one, so at the point where the current block's registers are first read the compiler
@@ -953,10 +986,7 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
     const uint32_t lane4 = lane * 4;
     load_lut(tab, lut);
     Search sr = make_search(bucket_lds, tab[kLoKeyOff], tab[kNBucketOff]);
-    if (codes_out) {
-        const uint32_t nbk = tab[kNBucketOff];
-        for (uint32_t i = threadIdx.x; i < nbk; i += kWave * WPW) bucket_lds[i] = tab[kBucketOff + i];
-    }
+    if (codes_out) sr = load_bucket_table(tab, bucket_lds, kWave * WPW);
     __syncthreads();
     for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
         const Unit un = unit_of<kUnit>(u, n, B, nb, upb);
@@ -1224,7 +1254,7 @@ struct AvgTeam {
     }
 };
 
-template <int KT, int NT, bool FASTDIV, int TEAMS>
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP>
 __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
                                                             const float *__restrict__ local, size_t n, size_t B, size_t nb,
                                                             size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
@@ -1262,10 +1292,8 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     e.load_all(a);  // the first loads are in flight while the tables are copied
     load_lut(tab, lut);
     {
-        uint32_t *bucket = dyn_lds + kSlots;
-        const uint32_t nbk = tab[kNBucketOff];
-        for (uint32_t i = threadIdx.x; i < nbk; i += kWg * TEAMS) bucket[i] = tab[kBucketOff + i];
-        e.sr = make_search(bucket, tab[kLoKeyOff], nbk);
+        e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWg * TEAMS);
+        if (!REMAP) e.sr.remap = nullptr;  // a type without a rank-to-code table: no test for one in the loop
     }
     __syncthreads();
     // `steady` (even) leading iterations in which this and the next unit of every team are whole
@@ -1315,7 +1343,8 @@ struct DeviceState {
     bool ready = false;
     uint32_t *tables = nullptr;  // device address of g_tables on this device
     int cus = 0;
-    uint32_t n_bucket[kKinds] = {0, 0, 0};
+    bool has_remap[kKinds] = {false, false, false, false};  // the type needs the rank-to-code table
+    uint32_t search_words[kKinds] = {0, 0, 0, 0};  // LDS words of a type's search tables (buckets + rank-to-code)
 };
 
 std::mutex g_mu;
@@ -1335,7 +1364,8 @@ int device_state(DeviceState **out)
             int rc = dq8::build_tables(k, &t);
             if (rc) return fail(DQ8_ERR_KIND, "table construction failed for kind %d (status %d)", k, rc);
             dq8::pack_tables(t, image[k]);
-            st.n_bucket[k] = t.n_bucket;
+            st.has_remap[k] = t.has_remap;
+            st.search_words[k] = t.n_bucket + (t.has_remap ? (uint32_t)kRemapWords : 0u);
         }
         void *sym = nullptr;
         DQ8_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(g_tables)));
@@ -1474,7 +1504,7 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     const int wpb = g_tune.enc_wpb == 4 ? 4 : 1;
     Plan p = make_plan(n, block, st.cus, g_tune.enc_wpc, wpb);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = ((size_t)st.n_bucket[kind] + kTeamSlots) * sizeof(uint32_t);
+    const size_t lds = ((size_t)st.search_words[kind] + kTeamSlots) * sizeof(uint32_t);
     // Whole aligned blocks of exactly one unit: the kernel without slow paths in its loop.
     if (fused && g_tune.enc_lean && p.B == (size_t)kUnit && n / kUnit >= 1 && n / kUnit < 0xFFFFFFFFull &&
         ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
@@ -1485,12 +1515,17 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
             teams = (n_full + per - 1) / per;
         }
         if (teams > n_full) teams = n_full;
-        if (g_tune.fastdiv)
-            hipLaunchKernelGGL((k_encode_full<1, true>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x, n_full,
-                               (uint32_t)teams, tail, scales, codes);
-        else
-            hipLaunchKernelGGL((k_encode_full<1, false>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x, n_full,
-                               (uint32_t)teams, tail, scales, codes);
+#define DQ8_ENC_FULL(FD, RM)                                                                                        \
+    hipLaunchKernelGGL((k_encode_full<1, FD, RM>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x, n_full, \
+                       (uint32_t)teams, tail, scales, codes)
+        if (st.has_remap[kind]) {
+            DQ8_ENC_FULL(true, true);
+        } else if (g_tune.fastdiv) {
+            DQ8_ENC_FULL(true, false);
+        } else {
+            DQ8_ENC_FULL(false, false);
+        }
+#undef DQ8_ENC_FULL
         return after_launch("k_encode_full");
     }
 #define DQ8_ENC(WPB, NT, FUSED, FD)                                                                              \
@@ -1563,20 +1598,20 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         if (all_valid >= 2) steady = (uint32_t)((all_valid - 1) & ~(size_t)1);
     }
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = ((size_t)st.n_bucket[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
-#define DQ8_TEAM(KT, NT, FD, T)                                                                               \
-    hipLaunchKernelGGL((k_avg_team<KT, NT, FD, T>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
+    const size_t lds = ((size_t)st.search_words[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
+#define DQ8_TEAM(KT, NT, RM, T)                                                                                      \
+    hipLaunchKernelGGL((k_avg_team<KT, NT, true, T, RM>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
                        p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
-#define DQ8_TEAM_T(KT, NT, FD)   \
+#define DQ8_TEAM_T(KT, NT, RM)   \
     if (teams == 3) {            \
-        DQ8_TEAM(KT, NT, FD, 3); \
+        DQ8_TEAM(KT, NT, RM, 3); \
     } else if (teams == 4) {     \
-        DQ8_TEAM(KT, NT, FD, 4); \
+        DQ8_TEAM(KT, NT, RM, 4); \
     } else {                     \
-        DQ8_TEAM(KT, NT, FD, 2); \
+        DQ8_TEAM(KT, NT, RM, 2); \
     }
 #define DQ8_TEAM_FD(KT, NT)      \
-    if (g_tune.fastdiv) {        \
+    if (st.has_remap[kind]) {    \
         DQ8_TEAM_T(KT, NT, true) \
     } else {                     \
         DQ8_TEAM_T(KT, NT, false)\
@@ -1600,7 +1635,7 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     const int wpw = g_tune.blk_wpw == 8 ? 8 : 6;
     Plan p = make_plan(n, block, st.cus, 2 * wpw, 1, wpw, kUnit);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = codes_out ? (size_t)st.n_bucket[kind] * sizeof(uint32_t) : 0;
+    const size_t lds = codes_out ? (size_t)st.search_words[kind] * sizeof(uint32_t) : 0;
 #define DQ8_BLK(NT, FD, WPW)                                                                                     \
     hipLaunchKernelGGL((k_avg_block<NT, FD, WPW>), dim3(p.grid), dim3(kWave * WPW), lds, stream, tab, wp, K, local, n, \
                        p.B, p.nb, p.upb, p.n_units, p.n_teams, mean_out, scales_out, codes_out)
@@ -1972,6 +2007,17 @@ int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key,
     return DQ8_OK;
 }
 
+int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128)
+{
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    static thread_local dq8::Tables t;
+    if (dq8::build_tables(kind, &t)) return fail(DQ8_ERR_KIND, "table construction failed for kind %d", kind);
+    if (n_mag) *n_mag = t.n_mag;
+    if (canon128) std::memcpy(canon128, t.canon, sizeof(t.canon));
+    return DQ8_OK;
+}
+
 int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t unit, size_t *out6)
 {
     if (!out6 || cus < 1 || waves_per_cu < 1 || (wpb != 1 && wpb != 4) || unit < 256 || (unit & (unit - 1)))
@@ -2041,8 +2087,10 @@ static int host_search(int kind, Search *sr)
     int rc = check_kind(kind);
     if (rc) return rc;
     static thread_local dq8::Tables t;
+    static thread_local uint32_t remap[kRemapWords];
     if (dq8::build_tables(kind, &t)) return fail(DQ8_ERR_KIND, "table construction failed for kind %d", kind);
-    *sr = make_search(t.bucket, t.lo_key, t.n_bucket);
+    for (int r = 0; r < kRemapWords; ++r) remap[r] = t.canon[r];
+    *sr = make_search(t.bucket, t.lo_key, t.n_bucket, t.has_remap ? remap : nullptr);
     return DQ8_OK;
 }
 
@@ -2053,18 +2101,20 @@ int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_n
     if (rc) return rc;
     static thread_local dq8::Tables t;
     dq8::build_tables(kind, &t);
+    const uint32_t n_thr = t.n_mag - 1;
     uint32_t thr_bits[127];
     std::memcpy(thr_bits, t.thr, sizeof(thr_bits));
     uint64_t bad = 0, missed = 0;
-    uint32_t j = 0;  // thresholds <= the current value
+    uint32_t j = 0;  // thresholds <= the current value = rank of the nearest magnitude
     for (uint32_t bits = 0; bits <= 0x7F800000u; ++bits) {
-        while (j < 127 && thr_bits[j] <= bits) ++j;
+        while (j < n_thr && thr_bits[j] <= bits) ++j;
         const float pos = u2f(bits), neg = u2f(bits | 0x80000000u);
         const uint32_t sp = search_sum(sr, pos), sn = search_sum(sr, neg);
-        bad += code_from(sp, pos) != j;
-        bad += code_from(sn, neg) != (j | 0x80u);
+        const uint32_t want = t.canon[j];
+        bad += code_of(sr, sp, pos) != want;
+        bad += code_of(sr, sn, neg) != (want | 0x80u);
         // every value within kNearWindow steps of a threshold must raise the proximity flag
-        bool close = (j < 127 && thr_bits[j] - bits <= kNearWindow) || (j > 0 && bits - thr_bits[j - 1] <= kNearWindow);
+        bool close = (j < n_thr && thr_bits[j] - bits <= kNearWindow) || (j > 0 && bits - thr_bits[j - 1] <= kNearWindow);
         if (close && near_key(sp) > 2 * kNearWindow) ++missed;
     }
     if (mismatches) *mismatches = bad;
@@ -2086,7 +2136,7 @@ int dq8_internal_encode_host(int kind, const float *x, size_t n, float scale, in
         if (recip) {
             uint32_t s0 = search_sum(sr, x[i] * r);
             if (near_key(s0) > 2 * kNearWindow) {
-                codes[i] = (uint8_t)code_from(s0, x[i]);
+                codes[i] = (uint8_t)code_of(sr, s0, x[i]);
                 continue;
             }
         }

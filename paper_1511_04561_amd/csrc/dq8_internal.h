@@ -13,6 +13,11 @@ extern "C" {
 int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key, uint32_t *n_bucket, uint32_t *bucket,
                         uint32_t bucket_capacity);
 
+// Ranks of a data type: *n_mag = number of distinct magnitudes; canon128[r] = the 7-bit field the
+// encoder emits for the magnitude of rank r (ascending), entries from n_mag on repeat the last one.
+// thr127 of dq8_internal_tables has n_mag - 1 thresholds followed by +inf.
+int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128);
+
 // Launch plan for n elements with the given block on a device with `cus` compute units,
 // `waves_per_cu` resident wavefronts per compute unit, teams of `wpb` wavefronts and units of
 // `unit` elements: out6 = {B, nb, units per block, units, teams, workgroups}.

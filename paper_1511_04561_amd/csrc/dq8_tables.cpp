@@ -22,7 +22,7 @@ float u2f(uint32_t u)
 }
 
 // num / den rounded once to binary32 (nearest, ties to even), in integer arithmetic.
-// Requires 0 <= num / den <= 1 and a result that is zero or a normal number.
+// Requires 0 <= num / den < 2 and a result that is zero or a normal number.
 float ratio_to_f32(uint64_t num, uint64_t den)
 {
     if (num == 0) return 0.0f;
@@ -78,6 +78,12 @@ bool magnitude_ratio(int kind, int j, uint64_t *num, uint64_t *den)
         *den = 32ull * 10 * pow10u(7 - E);
         return true;
     }
+    if (kind == 3) {  // mantissa: 3 exponent bits, 4-bit integer mantissa counting tenths of the decade 10^(E-7)
+        int E = j >> 4;
+        *num = (uint64_t)(j & 15);
+        *den = 10 * pow10u(7 - E);
+        return true;
+    }
     return false;
 }
 
@@ -91,27 +97,48 @@ int build_tables(int kind, Tables *t)
         t->cb[j] = ratio_to_f32(num, den);
         t->cb[j + 128] = u2f(f2u(t->cb[j]) | 0x80000000u);
     }
-    for (int j = 0; j < 127; ++j) {
-        if (!(t->cb[j] < t->cb[j + 1])) return 5;
+    // Rank the distinct magnitudes (binary32 values of non-negative numbers order like their bit
+    // patterns); of several fields with one value the smallest is the code.
+    float mag[128];
+    uint32_t n_mag = 0;
+    t->has_remap = false;
+    for (;;) {
+        int best = -1;
+        for (int j = 0; j < 128; ++j) {
+            if (n_mag > 0 && !(f2u(t->cb[j]) > f2u(mag[n_mag - 1]))) continue;  // ranked already, or a repeat of it
+            if (best < 0 || f2u(t->cb[j]) < f2u(t->cb[best])) best = j;         // strict: the smallest field wins
+        }
+        if (best < 0) break;
+        mag[n_mag] = t->cb[best];
+        t->canon[n_mag] = (uint8_t)best;
+        if ((uint32_t)best != n_mag) t->has_remap = true;
+        ++n_mag;
+    }
+    for (uint32_t r = n_mag; r < 128; ++r) t->canon[r] = t->canon[n_mag - 1];
+    t->n_mag = n_mag;
+    if (n_mag < 2) return 5;
+    const int n_thr = (int)n_mag - 1;
+    for (int j = 0; j < 127; ++j) t->thr[j] = u2f(0x7F800000u);  // unused entries: never reached
+    for (int j = 0; j < n_thr; ++j) {
         // the midpoint of two nearby binary32 numbers is exact in binary64
-        double mid = ((double)t->cb[j] + (double)t->cb[j + 1]) * 0.5;
+        double mid = ((double)mag[j] + (double)mag[j + 1]) * 0.5;
         float f = (float)mid;
-        if ((double)f <= mid) f = std::nextafterf(f, 2.0f);
+        if ((double)f <= mid) f = std::nextafterf(f, 4.0f);
         t->thr[j] = f;  // smallest binary32 strictly above the midpoint
         if (j > 0 && !(t->thr[j - 1] < f)) return 5;
     }
-    if (!(t->thr[126] < 1.0f)) return 5;
+    if (!(t->thr[n_thr - 1] < 2.0f)) return 5;
     // Neighbouring thresholds must be more than a bucket apart (plus the width of the
     // encoder's proximity window on both sides): then a bucket holds at most one threshold
     // and a threshold close to a bucket edge has a threshold-free neighbour bucket.
-    for (int j = 1; j < 127; ++j)
+    for (int j = 1; j < n_thr; ++j)
         if (f2u(t->thr[j]) - f2u(t->thr[j - 1]) <= 0x10000u + 2 * kNearWindow) return 5;
     uint32_t lo_key = (f2u(t->thr[0]) >> 16);
     if (lo_key == 0) return 5;
     lo_key -= 1;  // one bucket that lies entirely below the first threshold
-    const uint32_t hi_key = (f2u(t->thr[126]) >> 16) + 1;  // one bucket entirely above the last threshold
+    const uint32_t hi_key = (f2u(t->thr[n_thr - 1]) >> 16) + 1;  // one bucket entirely above the last threshold
     uint32_t nb = hi_key - lo_key + 1;
-    if (nb > (uint32_t)(kTableWords - kBucketOff)) return 5;
+    if (nb > (uint32_t)(kRemapOff - kBucketOff)) return 5;
     t->lo_key = lo_key;
     t->n_bucket = nb;
     int j = 0;  // next threshold not yet passed
@@ -119,7 +146,7 @@ int build_tables(int kind, Tables *t)
         uint32_t first = key << 16, last = first | 0xFFFFu;
         uint32_t base = (uint32_t)j, tlow = 0x10000u;
         int inside = 0;
-        while (j < 127 && f2u(t->thr[j]) <= last) {
+        while (j < n_thr && f2u(t->thr[j]) <= last) {
             if (f2u(t->thr[j]) < first) return 5;  // cannot happen: thresholds ascend
             tlow = f2u(t->thr[j]) & 0xFFFFu;
             ++inside;
@@ -128,7 +155,7 @@ int build_tables(int kind, Tables *t)
         if (inside > 1) return 5;  // two thresholds in one bucket: scheme not applicable
         t->bucket[key - lo_key] = (base << 16) + (0x10000u - tlow);
     }
-    if (j != 127) return 5;
+    if (j != n_thr) return 5;
     return 0;
 }
 
@@ -138,7 +165,9 @@ void pack_tables(const Tables &t, uint32_t *words)
     for (int c = 0; c < 256; ++c) words[kCbOff + c] = f2u(t.cb[c]);
     words[kLoKeyOff] = t.lo_key;
     words[kNBucketOff] = t.n_bucket;
+    words[kHasRemapOff] = t.has_remap ? 1u : 0u;
     for (uint32_t i = 0; i < t.n_bucket; ++i) words[kBucketOff + i] = t.bucket[i];
+    for (int r = 0; r < kRemapWords; ++r) words[kRemapOff + r] = t.canon[r];
 }
 
 }  // namespace dq8

@@ -2,9 +2,9 @@
 //
 // For each 8-bit data type of Sec. 3.1 of arXiv 1511.04561 the library keeps
 //   cb[256]      the value of every code (bit 7 = sign, bits 6..0 = magnitude index),
-//   thr[127]     thr[j] = smallest binary32 number strictly above the real midpoint of
-//                magnitudes j and j+1, so that the nearest magnitude to |xn| with ties to
-//                the smaller one is  #{ j : thr[j] <= |xn| },
+//   thr[]        thr[j] = smallest binary32 number strictly above the real midpoint of the
+//                distinct magnitudes of rank j and j+1, so that the rank of the nearest
+//                magnitude to |xn|, with ties to the smaller one, is  #{ j : thr[j] <= |xn| },
 //   bucket[]     the same search flattened into one lookup, see below.
 //
 // Sec. 3.2 of the paper searches a sorted table of the 128 positive values with a
@@ -37,18 +37,28 @@
 namespace dq8 {
 
 constexpr uint32_t kNearWindow = 4;  // proximity window W in binary32 steps
-constexpr int kTableWords = 4096;   // device words reserved per data type
+constexpr int kTableWords = 4352;   // device words reserved per data type
 constexpr int kCbOff = 0;           // 256 words: cb as raw binary32
 constexpr int kLoKeyOff = 256;      // 1 word
 constexpr int kNBucketOff = 257;    // 1 word
+constexpr int kHasRemapOff = 258;   // 1 word: non-zero when ranks have to be mapped to codes (see Tables::canon)
 constexpr int kBucketOff = 260;     // bucket entries, 16-byte aligned
+constexpr int kRemapOff = 4224;     // 128 words: canon[] widened to words
+constexpr int kRemapWords = 128;
 
 struct Tables {
     float cb[256];
-    float thr[127];
+    // Distinct magnitudes in ascending order are ranked 0 .. n_mag - 1; thr[r] separates rank r
+    // from rank r + 1 and canon[r] is the 7-bit magnitude field the encoder emits for rank r.
+    // For the tree and linear types every field is its own rank (n_mag == 128, canon[r] == r).
+    // The mantissa type has fields of equal value; the smallest field of a value is its code.
+    uint32_t n_mag;
+    uint8_t canon[128];
+    bool has_remap;
+    float thr[127];  // n_mag - 1 entries used
     uint32_t lo_key;
     uint32_t n_bucket;
-    uint32_t bucket[kTableWords - kBucketOff];
+    uint32_t bucket[kRemapOff - kBucketOff];
 };
 
 // Returns 0 on success, 2 for an unknown kind, 5 if the type does not fit the bucket scheme.

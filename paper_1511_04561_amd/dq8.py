@@ -9,7 +9,7 @@ import os
 
 import torch
 
-DYNAMIC_TREE, LINEAR, STATIC_TREE = 0, 1, 2
+DYNAMIC_TREE, LINEAR, STATIC_TREE, MANTISSA = 0, 1, 2, 3
 SCALES_GIVEN = 1
 MAX_K = 32
 

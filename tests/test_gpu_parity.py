@@ -13,8 +13,8 @@ from paper_1511_04561_amd import workloads
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
-KINDS = [0, 1, 2]
-NAMES = {0: "dynamic_tree", 1: "linear", 2: "static_tree"}
+KINDS = [0, 1, 2, 3]
+NAMES = {0: "dynamic_tree", 1: "linear", 2: "static_tree", 3: "mantissa"}
 
 
 @pytest.fixture(scope="module")
@@ -141,7 +141,7 @@ def test_degenerate_blocks(dq8, kind):
 
 @pytest.mark.parametrize("kind", KINDS)
 def test_values_on_and_next_to_every_decision_point(dq8, kind):
-    cb = oracle.codebook(kind)[:128]
+    cb = np.unique(oracle.codebook(kind)[:128])  # ascending distinct magnitudes (the mantissa type repeats some)
     mid = ((cb[:-1].astype(np.float64) + cb[1:]) / 2).astype(np.float32).view(np.int32).astype(np.int64)
     near = (mid[:, None] + np.arange(-3, 4)[None, :]).reshape(-1).astype(np.int32).view(np.float32)
     pos = np.concatenate([near, cb, np.array([1.0], np.float32)])
@@ -160,7 +160,31 @@ def test_all_codes_decode_and_reencode(dq8):
             got = dq8.decode(kind, dev(codes), dev(sc), 0)
             same_bits(got, want, "decode all codes")
             back, _ = dq8.encode(kind, dev(want), 0, scales=dev(sc), scales_given=True)
-            same_bits(back, codes, "encode(decode(c)) == c")
+            canon, _ = oracle.encode(kind, want, 0, scales=sc)
+            same_bits(back, canon, "encode(decode(c))")
+            if kind != oracle.MANTISSA:  # every code is the only one of its value
+                same_bits(back, codes, "encode(decode(c)) == c")
+            else:  # the smallest code of the same sign and value
+                cbk = oracle.codebook(kind)
+                first = np.array([min(d for d in range(c & 0x80, (c & 0x80) + 128) if cbk[d] == cbk[c]) for c in range(256)])
+                same_bits(back, first.astype(np.uint8), "encode(decode(c)) == smallest code of that value")
+
+
+@pytest.mark.parametrize("kind", [2, 3])
+def test_static_exponent_with_a_decade_offset(dq8, kind):
+    """Sec. 3.1 shifts the static-exponent types by a fixed decade offset instead of normalising:
+    that is the codec with the scale 10^offset handed in.  Values beyond the scale go to the
+    nearest (largest) table value, which for the mantissa type lies above 1."""
+    rng = np.random.Generator(np.random.PCG64(4100 + kind))
+    n, block = 3 * 4096 + 500, 4096
+    for offset in (-3, 0, 2):
+        print("offset kind=%d 10^%d" % (kind, offset), flush=True)
+        s = np.full(4, 10.0 ** offset, np.float32)
+        x = (rng.standard_normal(n) * np.exp(rng.uniform(-12, 1, n)) * float(s[0])).astype(np.float32)
+        want, _ = oracle.encode(kind, x, block, scales=s)
+        got, _ = dq8.encode(kind, dev(x), block, scales=dev(s), scales_given=True)
+        same_bits(got, want, "codes, decade offset %d" % offset)
+        same_bits(dq8.decode(kind, got, dev(s), block), oracle.decode(kind, want, s, block), "decode, decade offset")
 
 
 AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1),

@@ -11,7 +11,7 @@ import oracle
 from paper_1511_04561_amd import build as dq8_build
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-KINDS = [0, 1, 2]
+KINDS = [0, 1, 2, 3]
 
 
 @pytest.fixture(scope="module")
@@ -45,7 +45,7 @@ def test_argument_errors_need_no_device(L):
     p = buf.ctypes.data_as(ctypes.c_void_p)
     n = ctypes.c_size_t(16)
     z = ctypes.c_size_t(0)
-    assert L.dq8_codebook(3, p) == 2 and b"3" in L.dq8_last_error()
+    assert L.dq8_codebook(7, p) == 2 and b"7" in L.dq8_last_error()
     assert L.dq8_codebook(0, None) == 1
     assert L.dq8_absmax(None, n, z, p, None) == 1
     assert L.dq8_absmax(None, z, z, None, None) == 0  # n == 0 is a no-op
@@ -71,7 +71,7 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode_accumulate_avg_local(0, None, None, 0, None, z, z, None, None) == 0
     assert L.dq8_decode_avg_encode(0, arr, arr, 0, None, n, z, p, p, None) == 3  # no worker and no local term
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, None, p, None) == 1
-    assert L.dq8_decode_avg_encode(3, arr, arr, 2, None, n, z, p, p, None) == 2
+    assert L.dq8_decode_avg_encode(4, arr, arr, 2, None, n, z, p, p, None) == 2
     big = ctypes.c_size_t(10000)
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, z, p, p, None) == 3  # one block of 10000 > 4096
     assert b"4096" in L.dq8_last_error()
@@ -91,17 +91,47 @@ def _tables(L, kind):
     return cb, thr, lo.value, nbk.value, bucket[:nbk.value]
 
 
+def _ranks(L, kind):
+    n_mag, canon = ctypes.c_uint32(), np.empty(128, np.uint8)
+    assert L.dq8_internal_ranks(kind, ctypes.byref(n_mag), canon.ctypes.data_as(ctypes.c_void_p)) == 0
+    return n_mag.value, canon
+
+
+def _distinct_magnitudes(kind):
+    """Ascending distinct magnitudes of the oracle's table and the smallest field of each."""
+    o = oracle.codebook(kind)[:128]
+    vals, first = np.unique(o, return_index=True)  # first occurrence = smallest field
+    return vals, first
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_ranks_are_the_distinct_magnitudes_with_their_smallest_field(L, kind):
+    n_mag, canon = _ranks(L, kind)
+    vals, first = _distinct_magnitudes(kind)
+    assert n_mag == vals.size
+    assert np.array_equal(canon[:n_mag], first.astype(np.uint8))
+    assert np.all(canon[n_mag:] == canon[n_mag - 1])
+    if kind != 3:
+        assert n_mag == 128 and np.array_equal(canon, np.arange(128, dtype=np.uint8))
+    else:  # the 8 zeros count once, and m = 10 of decades 0..6 repeats m = 1 of the next
+        assert n_mag == 128 - 7 - 7
+
+
 @pytest.mark.parametrize("kind", KINDS)
 def test_thresholds_are_the_first_binary32_above_each_midpoint(L, kind):
     cb, thr, lo, nbk, bucket = _tables(L, kind)
-    o = oracle.codebook(kind)[:128].astype(np.float64)
+    vals, _ = _distinct_magnitudes(kind)
+    o = vals.astype(np.float64)
+    n_thr = o.size - 1
     mid = (o[:-1] + o[1:]) / 2
+    assert np.all(np.isinf(thr[n_thr:]))
+    thr = thr[:n_thr]
     t = thr.astype(np.float64)
     below = np.nextafter(thr, np.float32(0)).astype(np.float64)
     assert np.all(t > mid) and np.all(below <= mid)
     hi = lo + nbk - 1  # first and last bucket hold no threshold
     tb = thr.view(np.uint32)
-    assert nbk <= 4096 - 260 and (int(tb[0]) >> 16) == lo + 1 and (int(tb[126]) >> 16) == hi - 1 and hi <= 0x3F80
+    assert nbk <= 4224 - 260 and (int(tb[0]) >> 16) == lo + 1 and (int(tb[-1]) >> 16) == hi - 1 and hi <= 0x3FC0
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -126,7 +156,7 @@ def _encode_host(L, kind, x, scale, use_reciprocal):
 @pytest.mark.parametrize("kind", KINDS)
 def test_code_search_equals_the_oracle_on_normalised_values(L, kind):
     rng = np.random.Generator(np.random.PCG64(77))
-    cb = oracle.codebook(kind)[:128]
+    cb = _distinct_magnitudes(kind)[0]
     mid = ((cb[:-1].astype(np.float64) + cb[1:]) / 2).astype(np.float32).view(np.int32).astype(np.int64)
     near = (mid[:, None] + np.arange(-40, 41)[None, :]).reshape(-1).astype(np.int32).view(np.float32)
     pos = np.concatenate([near, rng.random(300000).astype(np.float32),
@@ -177,14 +207,15 @@ def test_division_by_a_power_of_two_equals_the_product_with_its_reciprocal():
 @pytest.mark.parametrize("kind", KINDS)
 def test_reciprocal_path_matches_the_oracle_around_every_threshold(L, kind):
     """Inputs built so that x / s lands on, and next to, every decision point, for awkward scales."""
-    cb = oracle.codebook(kind)[:128]
+    cb = _distinct_magnitudes(kind)[0]
     mid = ((cb[:-1].astype(np.float64) + cb[1:]) / 2)
     rng = np.random.Generator(np.random.PCG64(79 + kind))
     total_exact = 0
     for s in [1.0, 3.0, 0.7310585975646973, 1e-3, 1.9999998807907104, 1.0000001192092896, 5e-20, 7e19, 2.0 ** -100,
               2.0 ** 100, 1e-38, 3e38, 1.1e-30]:
         s32 = np.float32(s)
-        base = (mid * float(s32)).astype(np.float32).view(np.int32).astype(np.int64)
+        with np.errstate(over="ignore"):  # products beyond binary32 become inf and are dropped below
+            base = (mid * float(s32)).astype(np.float32).view(np.int32).astype(np.int64)
         x = (base[:, None] + np.arange(-12, 13)[None, :]).reshape(-1)
         x = x[(x > 0) & (x < 0x7F800000)].astype(np.int32).view(np.float32)
         x = x[np.abs(x) <= s32]
