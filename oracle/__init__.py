@@ -15,5 +15,6 @@ from .dq8_oracle import (  # noqa: F401
     decode_accumulate_avg,
     decode_avg_encode,
     encode,
+    error_stats,
     set_threads,
 )

@@ -30,6 +30,11 @@
  * are pinned the same way (numpy and exact-rational re-computation, special
  * cases with closed-form results); where the local term sits in the sum and
  * that the divisor is K + 1 is a reading of one sentence of Sec. 3.4.
+ * The error statistics (Sec. 3.4, Table 2) are pinned by exact rational sums,
+ * the quarter-step closed form of uniform quantisation, special cases,
+ * additivity over blocks and a band around the 16 relative errors the paper
+ * prints for synthetic samples; that zeros are left out of the relative mean is
+ * a reading (the paper does not say).
  * What is NOT pinned, because the paper prints no table values and its
  * figure of the bit layouts is missing: agreement with the bit patterns of
  * the authors' own implementation ("parity unpinned" for wire compatibility
@@ -377,3 +382,86 @@ int dq8o_decode_avg_encode(int kind, const uint8_t *const *codes, const float *c
     return rc;
 }
 
+
+/*
+ * Approximation error of a data type on a sample (Sec. 3.4, first paragraph and
+ * Table 2: mean absolute and mean relative error of compress-then-decompress;
+ * the tree and linear types normalise by the absolute maximum, the static types
+ * may instead be given a fixed decade as the scale).  For every block b:
+ *     q_i      = cb[code_i] * s_b              (binary32, as dq8o_decode)
+ *     e_i      = | (double) q_i - (double) x_i |
+ *     stats[4b+0] = sum of e_i over the block
+ *     stats[4b+1] = sum of e_i / |x_i| over the elements with x_i != 0
+ *     stats[4b+2] = number of elements with x_i != 0
+ *     stats[4b+3] = largest e_i
+ * The paper does not say what the relative error of a zero is; here zeros are
+ * left out of that sum and counted, so that the caller divides by the number of
+ * terms.  Sums run over the block in index order in long double (64-bit
+ * significand on this target), so they are far closer to the real sums than any
+ * binary64 summation; only the last step rounds to binary64.
+ * means (may be NULL): means[0] = (sum of all e_i) / n, means[1] = (sum of all
+ * relative errors) / (number of non-zero x_i), or 0 when there is none; block
+ * sums are added in block order in long double.
+ */
+int dq8o_error_stats(int kind, const float *x, size_t n, size_t block, float *scales,
+                     int scales_given, double *stats, double *means)
+{
+    float cb[256];
+    size_t B, nb;
+    long long b;
+    long double *part;
+    int rc = dq8o_codebook(kind, cb);
+    if (rc) return rc;
+    if (n == 0) {
+        if (means) means[0] = means[1] = 0.0;
+        return 0;
+    }
+    if (!x || !scales || !stats) return 1;
+    B = block_len(n, block);
+    nb = (n + B - 1) / B;
+    part = (long double *)malloc(nb * 2 * sizeof(long double));
+    if (!part) return 4;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (b = 0; b < (long long)nb; ++b) {
+        size_t lo = (size_t)b * B, hi = lo + B < n ? lo + B : n, i;
+        float s = scales_given ? scales[b] : block_absmax(x, lo, hi);
+        long double sum_abs = 0.0L, sum_rel = 0.0L;
+        double count = 0.0, worst = 0.0;
+        if (!scales_given) scales[b] = s;
+        for (i = lo; i < hi; ++i) {
+            float xn, q;
+            double e;
+            if (s == 0.0f)
+                xn = x[i];
+            else
+                xn = x[i] / s;
+            q = cb[nearest_code(cb, xn)] * s;
+            e = fabs((double)q - (double)x[i]);
+            sum_abs += (long double)e;
+            if (x[i] != 0.0f) {
+                sum_rel += (long double)e / (long double)fabs((double)x[i]);
+                count += 1.0;
+            }
+            if (e > worst) worst = e;
+        }
+        part[2 * b] = sum_abs;
+        part[2 * b + 1] = sum_rel;
+        stats[4 * b] = (double)sum_abs;
+        stats[4 * b + 1] = (double)sum_rel;
+        stats[4 * b + 2] = count;
+        stats[4 * b + 3] = worst;
+    }
+    if (means) {
+        long double ta = 0.0L, tr = 0.0L;
+        double tc = 0.0;
+        for (b = 0; b < (long long)nb; ++b) {
+            ta += part[2 * b];
+            tr += part[2 * b + 1];
+            tc += stats[4 * b + 2];
+        }
+        means[0] = (double)(ta / (long double)n);
+        means[1] = tc > 0.0 ? (double)(tr / (long double)tc) : 0.0;
+    }
+    free(part);
+    return 0;
+}

@@ -46,8 +46,10 @@ def _load():
                                                          ctypes.c_int, c_f, c_sz, c_sz, c_f]
         lib.dq8o_decode_avg_encode.argtypes = [ctypes.c_int, ctypes.POINTER(c_u8), ctypes.POINTER(c_f), ctypes.c_int,
                                                c_f, c_sz, c_sz, c_f, c_u8]
+        c_d = ctypes.POINTER(ctypes.c_double)
+        lib.dq8o_error_stats.argtypes = [ctypes.c_int, c_f, c_sz, c_sz, c_f, ctypes.c_int, c_d, c_d]
         lib.dq8o_set_threads.argtypes = [ctypes.c_int]
-        for f in (lib.dq8o_codebook, lib.dq8o_absmax, lib.dq8o_encode, lib.dq8o_decode,
+        for f in (lib.dq8o_error_stats, lib.dq8o_codebook, lib.dq8o_absmax, lib.dq8o_encode, lib.dq8o_decode,
                   lib.dq8o_decode_accumulate_avg, lib.dq8o_decode_accumulate_avg_local, lib.dq8o_decode_avg_encode,
                   lib.dq8o_set_threads, lib.dq8o_get_threads):
             f.restype = ctypes.c_int
@@ -175,3 +177,27 @@ def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None):
     _check(_load().dq8o_decode_avg_encode(int(kind), cp, sp, K, lp, n, int(block), _fp(out_scales), _bp(out_codes)),
            "decode_avg_encode")
     return out_codes, out_scales
+
+
+def error_stats(kind, x, block=0, scales=None):
+    """Approximation error of compress-then-decompress (Sec. 3.4, Table 2).
+
+    Returns (stats float64[nb, 4], means float64[2]): per block the sum of absolute errors, the
+    sum of relative errors over non-zero inputs, the number of non-zero inputs and the largest
+    absolute error; means = (mean absolute error, mean relative error over non-zero inputs).
+    scales given -> used instead of the absolute maxima."""
+    x = _f32(x)
+    given = scales is not None
+    nb = n_blocks(x.size, block)
+    if given:
+        scales = _f32(scales).copy()
+        if scales.size != nb:
+            raise ValueError("scales has %d entries, want %d" % (scales.size, nb))
+    else:
+        scales = np.empty(nb, dtype=np.float32)
+    stats = np.zeros((nb, 4), dtype=np.float64)
+    means = np.zeros(2, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    _check(_load().dq8o_error_stats(int(kind), _fp(x), x.size, int(block), _fp(scales), int(given),
+                                    stats.ctypes.data_as(dp), means.ctypes.data_as(dp)), "error_stats")
+    return stats, means

@@ -1,0 +1,154 @@
+"""Pins for the oracle's approximation-error statistics (Sec. 3.4, Table 2).
+
+Expected values come from exact rational arithmetic, a closed form for uniform quantisation,
+special cases with known results, additivity over blocks and the paper's printed Table 2.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from tests.exact import codebook_exact, nearest_code_exact, round_to_f32
+
+KINDS = [oracle.DYNAMIC_TREE, oracle.LINEAR, oracle.STATIC_TREE, oracle.MANTISSA]
+NAMES = {oracle.DYNAMIC_TREE: "dynamic_tree", oracle.LINEAR: "linear", oracle.STATIC_TREE: "static_tree",
+         oracle.MANTISSA: "mantissa"}
+
+
+def exact_stats(kind, x, s):
+    """Sums of |q - x| and |q - x| / |x| as exact rationals; q and xn rounded to binary32 exactly."""
+    cbf = [Fraction(float(round_to_f32(v))) for v in codebook_exact(kind)]
+    signs = [c >> 7 for c in range(256)]
+    sf = Fraction(float(s))
+    sum_abs, sum_rel, count, worst = Fraction(0), Fraction(0), 0, Fraction(0)
+    for v in x:
+        xf = Fraction(float(v))
+        xn = Fraction(float(round_to_f32(xf / sf))) if sf != 0 else xf
+        c = nearest_code_exact(cbf, signs, xn, int(np.signbit(v)))
+        q = Fraction(float(round_to_f32(cbf[c] * sf)))
+        e = abs(q - xf)
+        sum_abs += e
+        worst = max(worst, e)
+        if xf != 0:
+            sum_rel += e / abs(xf)
+            count += 1
+    return sum_abs, sum_rel, count, worst
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_small_samples_against_exact_rationals(kind):
+    rng = np.random.Generator(np.random.PCG64(500 + kind))
+    x = (rng.standard_normal(60) * np.exp(rng.uniform(-6, 2, 60))).astype(np.float32)
+    x[7] = 0.0
+    x[11] = -0.0
+    stats, means = oracle.error_stats(kind, x, 0)
+    s = np.abs(x).max()
+    sa, sr, cnt, worst = exact_stats(kind, x, s)
+    assert cnt == 58 and stats[0, 2] == 58.0
+    assert abs(Fraction(float(stats[0, 0])) - sa) <= sa * Fraction(1, 10 ** 14)
+    assert abs(Fraction(float(stats[0, 1])) - sr) <= sr * Fraction(1, 10 ** 14)
+    assert abs(Fraction(float(stats[0, 3])) - worst) <= worst * Fraction(1, 2 ** 52)
+    assert abs(Fraction(float(means[0])) - sa / 60) <= sa * Fraction(1, 10 ** 14)
+    assert abs(Fraction(float(means[1])) - sr / 58) <= sr * Fraction(1, 10 ** 14)
+    # with a given scale (a decade, as the static types are used in Sec. 3.4)
+    ten = np.array([10.0], np.float32)
+    stats, _ = oracle.error_stats(kind, x, 0, scales=ten)
+    sa, sr, cnt, worst = exact_stats(kind, x, ten[0])
+    assert abs(Fraction(float(stats[0, 0])) - sa) <= sa * Fraction(1, 10 ** 14)
+    assert abs(Fraction(float(stats[0, 1])) - sr) <= sr * Fraction(1, 10 ** 14)
+
+
+def test_uniform_quantisation_has_mean_error_of_a_quarter_step():
+    """Linear type, scale 1, inputs evenly spread over [0, 1]: the error is uniform on [0, h/2], h = 1/127."""
+    N = 127 * 4096
+    x = ((np.arange(N) + 0.5) / N).astype(np.float32)
+    stats, means = oracle.error_stats(oracle.LINEAR, x, 0, scales=np.ones(1, np.float32))
+    assert abs(means[0] * 4 * 127 - 1) < 1e-4
+    assert abs(stats[0, 3] * 2 * 127 - 1) < 1e-3     # largest error: half a step
+    assert stats[0, 2] == N
+    # relative error: (1/N) sum e/x; around level j >= 1 the mean of |x - j h| / x over a cell is close to
+    # (h/4) / (j h) for large j; the sum is dominated by small x -- compare with a float64 recomputation
+    # of the same definition on the rounded grid instead (independent of the oracle's search)
+    h = 1.0 / 127
+    xd = x.astype(np.float64)
+    q = (np.ceil(xd / h - 0.5) * h).astype(np.float32).astype(np.float64)  # nearest level, ties down
+    ref = np.mean(np.abs(q - xd) / xd)
+    assert abs(means[1] / ref - 1) < 1e-5
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_table_values_have_no_error_and_zeros_are_left_out_of_the_relative_mean(kind):
+    cb = oracle.codebook(kind)
+    x = (cb * np.float32(0.5)).astype(np.float32)  # decoded values for scale 0.5
+    stats, means = oracle.error_stats(kind, x, 0, scales=np.array([0.5], np.float32))
+    assert stats[0, 0] == 0 and stats[0, 1] == 0 and stats[0, 3] == 0 and means[0] == 0 and means[1] == 0
+    assert stats[0, 2] == np.count_nonzero(x)
+    z = np.zeros(100, np.float32)
+    z[50:] = -0.0
+    stats, means = oracle.error_stats(kind, z, 10)
+    assert stats.shape == (10, 4) and means[1] == 0 and np.all(stats[:, 2] == 0) and np.all(stats[:, 1] == 0)
+    if kind != oracle.STATIC_TREE:  # the static tree has no zero, but with scale 0 it still decodes to 0
+        assert means[0] == 0
+
+
+def test_a_single_outlier_sets_the_scale_and_the_largest_error():
+    x = np.full(1000, 1e-3, np.float32)
+    x[123] = 1.0
+    stats, means = oracle.error_stats(oracle.LINEAR, x, 0)
+    # 1e-3 is below half a step (1/254): it decodes to 0 and the error is the value itself
+    assert stats[0, 3] == float(np.float32(1e-3))
+    assert abs(means[0] - 999 * float(np.float32(1e-3)) / 1000) < 1e-12
+    assert abs(means[1] - 0.999) < 1e-12
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_block_statistics_add_up(kind):
+    rng = np.random.Generator(np.random.PCG64(600 + kind))
+    n, B = 10000, 768
+    x = rng.standard_normal(n).astype(np.float32)
+    x[::9] = 0
+    given = np.full(1, 8.0, np.float32)
+    whole, m0 = oracle.error_stats(kind, x, 0, scales=given)
+    parts, m1 = oracle.error_stats(kind, x, B, scales=np.full((n + B - 1) // B, 8.0, np.float32))
+    assert parts.shape == ((n + B - 1) // B, 4)
+    assert np.allclose(parts[:, :2].sum(0), whole[0, :2], rtol=1e-13, atol=0)
+    assert parts[:, 2].sum() == whole[0, 2] == np.count_nonzero(x)
+    assert parts[:, 3].max() == whole[0, 3]
+    assert np.allclose(m0, m1, rtol=1e-13, atol=0)
+    assert abs(m1[0] - parts[:, 0].sum() / n) <= 1e-13 * m1[0]
+    assert abs(m1[1] - parts[:, 1].sum() / parts[:, 2].sum()) <= 1e-13 * m1[1]
+    # per-block absmax scales: each block's statistics equal those of the block on its own
+    parts, _ = oracle.error_stats(kind, x, B)
+    for b in (0, 5, parts.shape[0] - 1):
+        alone, _ = oracle.error_stats(kind, x[b * B:(b + 1) * B], 0)
+        assert alone[0].tobytes() == parts[b].tobytes()
+
+
+def test_mean_relative_errors_are_in_the_band_of_table_2(golden_dir):
+    """All 16 synthetic rows of Table 2.  The paper's errors are about 1.4x the ones of an exactly nearest
+    search, for every type alike, so the pin is a band for the ratio, the best type of each distribution and
+    that the two static-exponent types are the worst on U(0,1)."""
+    rows = []
+    for l in open(os.path.join(golden_dir, "table2_mre_all_types.txt")):
+        if l.strip() and l[0] != "#":
+            dist, typ, v, off = l.split()
+            rows.append((dist, typ, float(v), off))
+    assert len(rows) == 16
+    rng = np.random.Generator(np.random.PCG64(3))
+    n = 1 << 19
+    data = {"U(0,1)": rng.random(n), "N(0,1)": rng.standard_normal(n), "N(0,10^2)": 10 * rng.standard_normal(n),
+            "N(0,0.2^2)": 0.2 * rng.standard_normal(n)}
+    kind_of = {v: k for k, v in NAMES.items()}
+    ours = {}
+    for dist, typ, paper, off in rows:
+        x = data[dist].astype(np.float32)
+        scales = None if off == "-" else np.array([10.0 ** int(off)], np.float32)
+        _, means = oracle.error_stats(kind_of[typ], x, 0, scales=scales)
+        ours[(dist, typ)] = 100 * means[1]
+        assert 0.6 < ours[(dist, typ)] / paper < 0.9, (dist, typ, ours[(dist, typ)], paper)
+    for dist in data:
+        best = min(NAMES.values(), key=lambda t: ours[(dist, t)])
+        assert best == "dynamic_tree", (dist, ours)  # the paper's bold entries
+    assert ours[("U(0,1)", "linear")] < ours[("U(0,1)", "static_tree")] < ours[("U(0,1)", "mantissa")]
