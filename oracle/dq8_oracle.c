@@ -391,7 +391,8 @@ int dq8o_decode_avg_encode(int kind, const uint8_t *const *codes, const float *c
  *     q_i      = cb[code_i] * s_b              (binary32, as dq8o_decode)
  *     e_i      = | (double) q_i - (double) x_i |
  *     stats[4b+0] = sum of e_i over the block
- *     stats[4b+1] = sum of e_i / |x_i| over the elements with x_i != 0
+ *     stats[4b+1] = sum of e_i / |x_i| (each quotient one binary64 division) over
+ *                   the elements with x_i != 0
  *     stats[4b+2] = number of elements with x_i != 0
  *     stats[4b+3] = largest e_i
  * The paper does not say what the relative error of a zero is; here zeros are
@@ -439,7 +440,8 @@ int dq8o_error_stats(int kind, const float *x, size_t n, size_t block, float *sc
             e = fabs((double)q - (double)x[i]);
             sum_abs += (long double)e;
             if (x[i] != 0.0f) {
-                sum_rel += (long double)e / (long double)fabs((double)x[i]);
+                double rel = e / fabs((double)x[i]); /* one binary64 division per term */
+                sum_rel += (long double)rel;
                 count += 1.0;
             }
             if (e > worst) worst = e;
