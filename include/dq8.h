@@ -157,6 +157,29 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
                           uint8_t *out_codes, void *hip_stream);
 
 /*
+ * Approximation error of a data type on a sample (Sec. 3.4, first paragraph, and Table 2: mean
+ * absolute and mean relative error of compress-then-decompress; the tree and linear types
+ * normalise by the absolute maximum, the static-exponent types may be given a decade as scale).
+ * x: DEVICE, n floats, finite.  scales: DEVICE, ceil(n / block) floats; written with the block
+ * maxima first (as dq8_encode does) unless flags has DQ8_SCALES_GIVEN, then read only.
+ * stats: DEVICE, 4 doubles per block, written: with q = fl32(cb[code] * s) and
+ * e = |(double) q - (double) x| (both roundings as written: one binary64 subtraction, one
+ * correctly rounded binary64 division),
+ *   stats[4 b + 0] = sum of e over block b
+ *   stats[4 b + 1] = sum of e / |x| over the elements of the block with x != 0
+ *   stats[4 b + 2] = number of elements with x != 0 (zeros have no relative error; divide by this)
+ *   stats[4 b + 3] = largest e of the block.
+ * means: DEVICE, 2 doubles, or NULL: means[0] = (sum of e over the array) / n, means[1] = (sum of
+ * relative errors) / (number of non-zero x), 0 when all x are zero.
+ * The count and the maximum are exact.  The sums are binary64 sums of non-negative terms whose
+ * order is not fixed: they are within (terms) * 2^-52 (relative) of the real sums and may differ
+ * in the last bits between calls.  stats and means 8-byte aligned; no buffer may overlap another.
+ * n == 0 writes nothing.  Asynchronous on the stream like the other calls.
+ */
+int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *scales, unsigned flags, double *stats,
+                    double *means, void *hip_stream);
+
+/*
  * Single-node speed-up model (Appendix, "A theoretical single node model for 4 GPUs"): the
  * convolutional part runs data-parallel at one GPU's speed, the fully connected part runs
  * model-parallel over `sub_batches` passes of `parallel_fc_ms` each, and communication that

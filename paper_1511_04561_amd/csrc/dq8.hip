@@ -1318,6 +1318,120 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     }
 }
 
+// Approximation-error statistics of compress-then-decompress (Sec. 3.4, Table 2).  Per block b,
+// stats[4 b + 0] = sum of e, [1] = sum of e / |x| over x != 0, [2] = number of x != 0,
+// [3] = largest e, with q = fl32(cb[code] * s) and e = |(double) q - (double) x| (one binary64
+// subtraction; the quotient one correctly rounded binary64 division).  stats[] was zeroed.
+// A wavefront walks a contiguous run of units of Q * 256 elements, keeps binary64 running sums per
+// lane while the block stays the same, and merges them into stats[] with atomics when the block
+// changes and at the end: the count and the maximum are exact in any order (integers below 2^53,
+// and non-negative binary64 numbers order like their bit patterns); the two sums depend on the
+// order only in their last bits.
+template <int Q>
+__global__ __launch_bounds__(kWg) void k_error_stats(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
+                                                    size_t B, size_t nb, size_t upb, size_t n_units, size_t per_wave,
+                                                    const float *__restrict__ scales, double *__restrict__ stats)
+{
+    constexpr int U = Q * 4 * kWave;
+    extern __shared__ uint32_t lds[];  // 256 table values, then the search tables
+    for (uint32_t i = threadIdx.x; i < 256; i += kWg) lds[i] = tab[kCbOff + i];
+    const Search sr = load_bucket_table(tab, lds + 256);
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const size_t u0 = first_unit() * per_wave;
+    const size_t u1 = u0 + per_wave < n_units ? u0 + per_wave : n_units;
+    double sum_abs = 0.0, sum_rel = 0.0, count = 0.0, worst = 0.0;
+    auto add = [&](float xv, uint32_t code, float s) {
+        const float q = u2f(lds[code & 0xFFu]) * s;
+        const double e = __builtin_fabs((double)q - (double)xv);
+        const double rel = e / __builtin_fabs((double)xv);  // not used when xv is a zero
+        sum_abs += e;
+        sum_rel += xv != 0.0f ? rel : 0.0;
+        count += xv != 0.0f ? 1.0 : 0.0;
+        worst = e > worst ? e : worst;
+    };
+    auto flush = [&](size_t blk) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {  // the same tree in every launch
+            sum_abs += __shfl_xor(sum_abs, m);
+            sum_rel += __shfl_xor(sum_rel, m);
+            count += __shfl_xor(count, m);
+            const double o = __shfl_xor(worst, m);
+            worst = o > worst ? o : worst;
+        }
+        if (lane == 0) {
+            double *p = stats + 4 * blk;
+            atomicAdd(p, sum_abs);
+            atomicAdd(p + 1, sum_rel);
+            atomicAdd(p + 2, count);
+            atomicMax(reinterpret_cast<unsigned long long *>(p + 3), (unsigned long long)__double_as_longlong(worst));
+        }
+        sum_abs = sum_rel = count = worst = 0.0;
+    };
+    bool open = false;
+    size_t cur = 0;
+    for (size_t u = u0; u < u1; ++u) {
+        const Unit un = unit_of<U>(u, n, B, nb, upb);
+        if (open && un.block != cur) flush(cur);
+        open = true;
+        cur = un.block;
+        const float s = scales[un.block];
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        const float *px = x + un.start;
+        if (un.len == U && ((uintptr_t)px & 15) == 0) {
+            const v4f *p4 = reinterpret_cast<const v4f *>(px);
+            v4f v[Q];
+#pragma unroll
+            for (int j = 0; j < Q; ++j) v[j] = ldg<1>(p4 + j * kWave + lane);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                const uint32_t c = encode_quad<true>(sr, v[j], d, r, recip);
+                add(v[j].x, c, s);
+                add(v[j].y, c >> 8, s);
+                add(v[j].z, c >> 16, s);
+                add(v[j].w, c >> 24, s);
+            }
+        } else {
+            for (uint32_t i = lane; i < un.len; i += kWave) add(px[i], encode_one<true>(sr, px[i], d, r, recip), s);
+        }
+    }
+    if (open) flush(cur);
+}
+
+// Means over all blocks from the per-block statistics: means[0] = (sum of absolute errors) / n,
+// means[1] = (sum of relative errors) / (number of non-zero inputs), 0 when there is none.
+// One workgroup; thread t adds blocks t, t + 256, ... in that order and the threads' sums are
+// combined by a fixed tree, so the result is the same in every launch.
+__global__ __launch_bounds__(kWg) void k_error_means(const double *__restrict__ stats, size_t nb, size_t n,
+                                                    double *__restrict__ means)
+{
+    __shared__ double part[3][kWg];
+    double a = 0.0, r = 0.0, c = 0.0;
+    for (size_t b = threadIdx.x; b < nb; b += kWg) {
+        a += stats[4 * b];
+        r += stats[4 * b + 1];
+        c += stats[4 * b + 2];
+    }
+    part[0][threadIdx.x] = a;
+    part[1][threadIdx.x] = r;
+    part[2][threadIdx.x] = c;
+    __syncthreads();
+    for (uint32_t w = kWg / 2; w >= 1; w >>= 1) {
+        if (threadIdx.x < w) {
+            part[0][threadIdx.x] += part[0][threadIdx.x + w];
+            part[1][threadIdx.x] += part[1][threadIdx.x + w];
+            part[2][threadIdx.x] += part[2][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        means[0] = part[0][0] / (double)n;
+        means[1] = part[2][0] > 0.0 ? part[1][0] / part[2][0] : 0.0;
+    }
+}
+
 // ---------------------------------------------------------------- host side
 
 thread_local char t_err[512] = "";
@@ -1560,6 +1674,28 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
 #undef DQ8_ENC_FD
 #undef DQ8_ENC
     return after_launch("k_encode");
+}
+
+// Error statistics of compress-then-decompress into stats[4 nb] (and means[2] when not NULL).
+int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n, size_t block, const float *scales,
+                       double *stats, double *means, hipStream_t stream)
+{
+    constexpr int Q = 4;
+    Plan p = make_plan(n, block, st.cus, 16, 1, kWavesPerWg, (size_t)Q * 4 * kWave);
+    const size_t zero_words = 8 * p.nb;  // 4 binary64 zeros per block
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, stream,
+                       reinterpret_cast<float *>(stats), zero_words);
+    int rc = after_launch("k_fill_zero");
+    if (rc) return rc;
+    const size_t per_wave = (p.n_units + p.n_teams - 1) / p.n_teams;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = (256 + (size_t)st.search_words[kind]) * sizeof(uint32_t);
+    hipLaunchKernelGGL((k_error_stats<Q>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, p.upb, p.n_units,
+                       per_wave, scales, stats);
+    rc = after_launch("k_error_stats");
+    if (rc || !means) return rc;
+    hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kWg), 0, stream, stats, p.nb, n, means);
+    return after_launch("k_error_means");
 }
 
 // Copies and checks the K (codes, scales) pairs of a call; `out` / `out_bytes` is a buffer the
@@ -1956,6 +2092,33 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     if (rc) return rc;
     return launch_avg_block(*st, kind, wp, K, local, n, block, nullptr, out_scales, out_codes,
                             static_cast<hipStream_t>(hip_stream));
+}
+
+int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *scales, unsigned flags, double *stats,
+                    double *means, void *hip_stream)
+{
+    static const char who[] = "dq8_error_stats";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (flags & ~DQ8_SCALES_GIVEN) return fail(DQ8_ERR_ARG, "%s: unknown flags 0x%x", who, flags);
+    if (n == 0) return DQ8_OK;
+    if (!x || !scales || !stats) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
+    if (((uintptr_t)stats & 7) || ((uintptr_t)means & 7)) return fail(DQ8_ERR_ARG, "%s: stats and means must be 8-byte aligned", who);
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t nbq = (n + Bq - 1) / Bq;
+    if (overlaps(stats, nbq * 32, x, n * 4) || overlaps(stats, nbq * 32, scales, nbq * 4) || overlaps(scales, nbq * 4, x, n * 4) ||
+        (means && (overlaps(means, 16, x, n * 4) || overlaps(means, 16, scales, nbq * 4) || overlaps(means, 16, stats, nbq * 32))))
+        return fail(DQ8_ERR_ARG, "%s: buffers overlap", who);
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!(flags & DQ8_SCALES_GIVEN)) {
+        rc = launch_absmax(*st, x, n, block, scales, stream);
+        if (rc) return rc;
+    }
+    return launch_error_stats(*st, kind, x, n, block, scales, stats, means, stream);
 }
 
 int dq8_model_penalty(const double *transfer_ms, const double *compute_ms, size_t count, double *penalty_ms)

@@ -39,6 +39,7 @@ def lib():
         L.dq8_decode_accumulate_avg.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, sz, sz, vp, vp]
         L.dq8_decode_accumulate_avg_local.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp]
         L.dq8_decode_avg_encode.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp, vp]
+        L.dq8_error_stats.argtypes = [ci, vp, sz, sz, vp, ctypes.c_uint, vp, vp, vp]
         for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg,
                   L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode):
             f.restype = ci
@@ -201,6 +202,35 @@ def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None, scales
                                            int(block), scales.data_ptr(), codes.data_ptr(), _stream()),
                "dq8_decode_avg_encode")
     return codes, scales
+
+
+def error_stats(kind, x, block=0, scales=None, scales_given=False, stats=None, means=None):
+    """Approximation error of compress-then-decompress (Sec. 3.4, Table 2).
+
+    Returns (stats float64[nb, 4], means float64[2]) on the device: per block the sum of absolute errors,
+    the sum of relative errors over non-zero inputs, the number of non-zero inputs and the largest absolute
+    error; means = (mean absolute error, mean relative error over non-zero inputs)."""
+    x = _dev(x, torch.float32, "x")
+    n = x.numel()
+    nb = n_blocks(n, block)
+    if scales is None:
+        if scales_given:
+            raise ValueError("scales_given needs scales")
+        scales = torch.empty(nb, dtype=torch.float32, device=x.device)
+    if stats is None:
+        stats = torch.zeros((nb, 4), dtype=torch.float64, device=x.device)
+    if means is None:
+        means = torch.zeros(2, dtype=torch.float64, device=x.device)
+    _dev(scales, torch.float32, "scales")
+    _dev(stats, torch.float64, "stats")
+    _dev(means, torch.float64, "means")
+    if scales.numel() < nb or stats.numel() < 4 * nb or means.numel() < 2:
+        raise ValueError("output buffers too small")
+    with torch.cuda.device(x.device):
+        _check(lib().dq8_error_stats(int(kind), x.data_ptr(), n, int(block), scales.data_ptr(),
+                                     SCALES_GIVEN if scales_given else 0, stats.data_ptr(), means.data_ptr(), _stream()),
+               "dq8_error_stats")
+    return stats, means
 
 
 def model_speedup(n_gpus, total_ms, fc_ms, conv_penalty_ms, sub_batches, parallel_fc_ms, fc_penalty_ms):

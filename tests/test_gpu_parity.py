@@ -65,8 +65,8 @@ def same_bits(got, want, what):
     got = got.cpu().numpy() if hasattr(got, "cpu") else got
     assert got.dtype == want.dtype and got.shape == want.shape, (what, got.dtype, got.shape, want.shape)
     if got.tobytes() != want.tobytes():
-        gi, wi = got.view(np.uint8 if got.dtype == np.uint8 else np.uint32), want.view(
-            np.uint8 if want.dtype == np.uint8 else np.uint32)
+        word = {1: np.uint8, 4: np.uint32, 8: np.uint64}[got.dtype.itemsize]
+        gi, wi = got.view(word), want.view(word)
         bad = np.nonzero(gi != wi)[0]
         raise AssertionError("%s: %d of %d differ, first at %d: got %r want %r" % (
             what, bad.size, got.size, bad[0], got[bad[0]], want[bad[0]]))
@@ -185,6 +185,88 @@ def test_static_exponent_with_a_decade_offset(dq8, kind):
         got, _ = dq8.encode(kind, dev(x), block, scales=dev(s), scales_given=True)
         same_bits(got, want, "codes, decade offset %d" % offset)
         same_bits(dq8.decode(kind, got, dev(s), block), oracle.decode(kind, want, s, block), "decode, decade offset")
+
+
+def check_error_stats(dq8, kind, x, block, given=None, tag=""):
+    """Counts and maxima bit-exact; the sums are binary64 sums of non-negative terms in an order that is not
+    fixed, so each side is within (terms) * 2^-53 (relative) of the real sum: tolerance 2 * terms * 2^-53."""
+    print("error stats %s kind=%d n=%d block=%d given=%s" % (tag, kind, x.size, block, given is not None), flush=True)
+    want, want_means = oracle.error_stats(kind, x, block, scales=given)
+    nb = want.shape[0]
+    gs = Guarded(nb, np.float32, data=given)
+    gstats = torch.full((nb + 2, 4), 7.0, dtype=torch.float64, device="cuda")
+    gmeans = torch.full((6,), 7.0, dtype=torch.float64, device="cuda")
+    stats, means = dq8.error_stats(kind, dev(x), block, scales=gs.t, scales_given=given is not None,
+                                   stats=gstats[1:nb + 1], means=gmeans[2:4])
+    gs.check("error stats scales")
+    got, got_means = stats.cpu().numpy(), means.cpu().numpy()
+    assert bool((gstats[0] == 7.0).all()) and bool((gstats[nb + 1] == 7.0).all()), "stats margins written"
+    assert bool((gmeans[:2] == 7.0).all()) and bool((gmeans[4:] == 7.0).all()), "means margins written"
+    if given is None:
+        same_bits(gs.t, oracle.absmax(x, block), "error stats scales " + tag)
+    B = x.size if block == 0 or block > x.size else block
+    terms = np.minimum(B, x.size - B * np.arange(nb)).astype(np.float64)
+    assert got[:, 2].tobytes() == want[:, 2].tobytes(), "non-zero counts " + tag
+    assert got[:, 3].tobytes() == want[:, 3].tobytes(), "largest errors " + tag
+    for col in (0, 1):
+        tol = 2 * terms * 2.0 ** -53 * want[:, col]
+        bad = np.nonzero(np.abs(got[:, col] - want[:, col]) > tol)[0]
+        assert bad.size == 0, (tag, col, bad[:5], got[bad[:5], col], want[bad[:5], col])
+    tol = 4 * x.size * 2.0 ** -53
+    assert np.all(np.abs(got_means - want_means) <= tol * want_means), (tag, got_means, want_means)
+    return got
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_error_stats_per_element_are_bit_exact(dq8, kind):
+    """Blocks of one element: every sum has a single term, so all four columns are exact."""
+    rng = np.random.Generator(np.random.PCG64(5100 + kind))
+    n = 5000
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-10, 3, n))).astype(np.float32)
+    x[::13] = 0.0
+    x[5::29] = -0.0
+    given = np.full(n, 16.0, np.float32)
+    want, _ = oracle.error_stats(kind, x, 1, scales=given)
+    stats, _ = dq8.error_stats(kind, dev(x), 1, scales=dev(given), scales_given=True)
+    same_bits(stats.reshape(-1), want.reshape(-1), "per-element error statistics")
+    want, _ = oracle.error_stats(kind, x, 1)  # own absmax: every element is its own scale
+    stats, _ = dq8.error_stats(kind, dev(x), 1)
+    same_bits(stats.reshape(-1), want.reshape(-1), "per-element error statistics, own scale")
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_error_stats_shapes(dq8, kind):
+    for i, (n, block) in enumerate(SHAPES):
+        x = workloads.edge_case_block("wide", n, seed=7000 + 10 * kind + i)
+        x[::11] = 0.0
+        check_error_stats(dq8, kind, x, block, tag="shape%d" % i)
+    n = 3 * 4096 + 77
+    x = workloads.edge_case_block("wide", n, seed=7100 + kind)
+    for off in (1, 3):  # misaligned input
+        want, _ = oracle.error_stats(kind, x, 4096)
+        got, _ = dq8.error_stats(kind, dev(x, off), 4096)
+        got = got.cpu().numpy()
+        assert got[:, 2:].tobytes() == want[:, 2:].tobytes()
+        assert np.allclose(got[:, :2], want[:, :2], rtol=1e-12, atol=0)
+    z = np.zeros(5000, np.float32)
+    z[100:200] = -0.0
+    got = check_error_stats(dq8, kind, z, 1024, tag="zeros")
+    assert np.all(got == 0)
+
+
+def test_error_stats_of_the_table_2_samples(dq8):
+    """Sec. 3.4: samples from U(0,1) and normal distributions; static-exponent types with a decade as scale."""
+    rng = np.random.Generator(np.random.PCG64(5200))
+    n = 300000
+    data = {"U(0,1)": (rng.random(n), 1), "N(0,1)": (rng.standard_normal(n), 1),
+            "N(0,10^2)": (10 * rng.standard_normal(n), 2), "N(0,0.2^2)": (0.2 * rng.standard_normal(n), 1)}
+    for name, (xs, offset) in data.items():
+        x = xs.astype(np.float32)
+        for kind in (oracle.DYNAMIC_TREE, oracle.LINEAR):
+            check_error_stats(dq8, kind, x, 0, tag=name)
+        for kind in (oracle.STATIC_TREE, oracle.MANTISSA):
+            check_error_stats(dq8, kind, x, 0, given=np.array([10.0 ** offset], np.float32), tag=name)
+            check_error_stats(dq8, kind, x, 4096, given=np.full((n + 4095) // 4096, 10.0 ** offset, np.float32), tag=name)
 
 
 AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (3000, 1000, 0), (4096 * 3, 4096, 1),

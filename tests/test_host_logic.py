@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(dq8_[a-z0-9_]+)\s*\(", header)))
     assert names == ["dq8_absmax", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
-                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_encode", "dq8_init",
+                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_encode", "dq8_error_stats",
+                     "dq8_init",
                      "dq8_last_error", "dq8_model_penalty", "dq8_model_speedup"]
     for n in names:
         assert hasattr(L, n), n
@@ -78,6 +79,13 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, ctypes.c_size_t(5000), p, p, None) == 3
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, p, p, None) == 3  # outputs overlap each other
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, z, z, None, None, None) == 0
+    # approximation-error statistics
+    assert L.dq8_error_stats(9, p, n, z, p, 0, p, None, None) == 2
+    assert L.dq8_error_stats(0, p, n, z, p, 2, p, None, None) == 3   # unknown flag
+    assert L.dq8_error_stats(0, None, n, z, p, 0, p, None, None) == 1
+    assert L.dq8_error_stats(0, p, n, z, p, 0, None, None, None) == 1
+    assert L.dq8_error_stats(0, p, n, z, p, 0, p, None, None) == 3   # x, scales and stats are one buffer
+    assert L.dq8_error_stats(0, None, z, z, None, 0, None, None, None) == 0
     assert isinstance(L.dq8_last_error(), bytes)
 
 
