@@ -53,6 +53,8 @@ def algorithmic_bytes(n, nb):
         # not part of a step: the second exchange round as one call, and the average with a local fp32 term
         "decode_avg_encode": K_WORKERS * (n + 4 * nb) + n + 4 * nb,
         "decode_accumulate_avg_local": K_WORKERS * (n + 4 * nb) + 4 * n + 4 * n,
+        # the approximation-error statistics with the scales handed in: one pass over the fp32 input
+        "error_stats": 4 * n + 4 * nb + 32 * nb,
     }
 
 
@@ -129,6 +131,8 @@ def main():
             "mean": torch.empty(n, dtype=torch.float32, device="cuda"),
             "rc": torch.empty(n, dtype=torch.uint8, device="cuda"),
             "rs": torch.empty(nb, dtype=torch.float32, device="cuda"),
+            "stats": torch.empty((nb, 4), dtype=torch.float64, device="cuda"),
+            "means": torch.empty(2, dtype=torch.float64, device="cuda"),
         }
         sets.append(st)
     for st in sets:  # every mean buffer holds a valid average before it is re-encoded
@@ -154,6 +158,8 @@ def main():
                                                                 scales=st["rs"], codes=st["rc"])),
             ("decode_accumulate_avg_local", lambda: dq8.decode_accumulate_avg(KIND, st["codes"], st["scales"], BLOCK,
                                                                               out=st["dec"], local=nxt["x"])),
+            ("error_stats", lambda: dq8.error_stats(KIND, st["x"], BLOCK, scales=st["s_out"], scales_given=True,
+                                                    stats=st["stats"], means=st["means"])),
         ]
 
     def step(i):

@@ -112,3 +112,36 @@ def test_config5_aggregation_pipeline(dq8):
     bound = np.repeat(np.mean(np.stack(scales_h).astype(np.float64), axis=0), B)[:n]
     assert np.all(np.abs(mean_h) <= bound * (1 + 1e-6))
     assert np.array_equal((rcodes_h >> 7).astype(bool), np.signbit(mean_h))
+
+
+def test_error_statistics_of_a_25_million_sample(dq8):
+    """Sec. 3.4: the errors of Table 2 are means over 25 million draws.  One such sample, one scale for the
+    whole sample on the GPU; the oracle takes it in blocks that all use that scale (the same terms, summed
+    per block), so that it can use every host core."""
+    import math
+    rng = np.random.Generator(np.random.PCG64(25))
+    n, B = 25_000_000, 1 << 16
+    x = rng.standard_normal(n).astype(np.float32)
+    nb = (n + B - 1) // B
+    for kind, scale in ((oracle.DYNAMIC_TREE, None), (oracle.MANTISSA, np.float32(10.0))):
+        print("25M sample kind=%d" % kind, flush=True)
+        xd = torch.from_numpy(x).cuda()
+        if scale is None:
+            stats, means = dq8.error_stats(kind, xd, 0)
+            s = np.abs(x).max()
+        else:
+            stats, means = dq8.error_stats(kind, xd, 0, scales=torch.full((1,), float(scale), device="cuda"),
+                                           scales_given=True)
+            s = scale
+        got, got_means = stats.cpu().numpy()[0], means.cpu().numpy()
+        want, _ = oracle.error_stats(kind, x, B, scales=np.full(nb, s, np.float32))
+        sum_abs, sum_rel = math.fsum(want[:, 0]), math.fsum(want[:, 1])
+        tol = 2 * n * 2.0 ** -53
+        assert abs(got[0] - sum_abs) <= tol * sum_abs and abs(got[1] - sum_rel) <= tol * sum_rel
+        assert got[2] == want[:, 2].sum() and got[3] == want[:, 3].max()
+        assert abs(got_means[0] - sum_abs / n) <= tol * sum_abs / n
+        assert abs(got_means[1] - sum_rel / got[2]) <= tol * sum_rel / got[2]
+        # and the figure itself: the paper prints 2.46 % and 6.89 % for these two rows; an exactly nearest
+        # search gives about 0.75 of the paper's errors on every row
+        paper = 2.46 if kind == oracle.DYNAMIC_TREE else 6.89
+        assert 0.6 < 100 * got_means[1] / paper < 0.9
