@@ -383,6 +383,30 @@ __device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_am
 // Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
 __device__ __forceinline__ size_t first_unit(int waves_per_wg = kWavesPerWg) { return (size_t)blockIdx.x * waves_per_wg + wave_in_wg(); }
 
+// Maximum of |x[0..len)| over the elements this lane takes, for a unit that is short or not
+// 16-byte aligned: whole quads with 128-bit loads when the start is aligned (the lanes take quads
+// lane, lane + 64, ...; a tail of fewer than four elements goes one by one), else element by element.
+template <int NT>
+__device__ __forceinline__ uint32_t slow_absmax(const float *px, uint32_t len, uint32_t lane)
+{
+    uint32_t m = 0;
+    uint32_t done = 0;
+    if (((uintptr_t)px & 15) == 0) {
+        const v4f *p4 = reinterpret_cast<const v4f *>(px);
+        const uint32_t nq = len >> 2;
+        float fm = 0.0f;
+#pragma unroll 4
+        for (uint32_t q = lane; q < nq; q += kWave) fm = max4_abs(ldg<NT>(p4 + q), fm);
+        m = f2u(fm);
+        done = nq << 2;
+    }
+    for (uint32_t i = done + lane; i < len; i += kWave) {
+        const uint32_t a = abs_bits(px[i]);
+        m = m > a ? m : a;
+    }
+    return m;
+}
+
 // ---------------------------------------------------------------- kernels
 
 __global__ void k_fill_zero(float *p, size_t n)
@@ -419,15 +443,22 @@ __global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, flo
 }
 
 // Block maxima.  One wavefront per unit of Q * 256 elements.  upb == 1: each unit is a whole
-// block and stores its maximum.  upb > 1: scales[] was zeroed and the units of a block merge
+// block and stores its maximum.  upb > 1: scales[] was zeroed and the pieces of a block merge
 // with an integer atomic max (non-negative binary32 numbers order like their bit patterns).
+// per_wave == 0: wavefront w takes units w, w + n_waves, ...  per_wave > 0 (used when blocks span
+// several units): it takes the per_wave consecutive units from w * per_wave on, keeps one
+// running maximum per lane while the block stays the same and issues one atomic per block it
+// touches -- thousands of atomics on one address cost more than reading the array.
 template <int Q, int NT>
 __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t nb, size_t upb,
-                                               size_t n_units, size_t n_waves, float *__restrict__ scales)
+                                               size_t n_units, size_t n_waves, size_t per_wave, float *__restrict__ scales)
 {
     constexpr int U = Q * 4 * kWave;
     const uint32_t lane = threadIdx.x & 63;
-    size_t u = first_unit();
+    const size_t w = first_unit();
+    size_t u = per_wave ? w * per_wave : w;
+    const size_t stride = per_wave ? 1 : n_waves;
+    const size_t end = per_wave ? (u + per_wave < n_units ? u + per_wave : n_units) : n_units;
     Unit un;
     bool fast = false;
     v4f v[Q];
@@ -440,8 +471,9 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
             for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(p4 + j * kWave + lane);
         }
     };
-    if (u < n_units) open_unit(u, un, fast);
-    while (u < n_units) {
+    if (u < end) open_unit(u, un, fast);
+    uint32_t run = 0;  // this lane's maximum over the units of the current block so far
+    while (u < end) {
         uint32_t m;
         if (fast) {
             float fm = 0.0f;
@@ -449,22 +481,22 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
             for (int j = 0; j < Q; ++j) fm = max4_abs(v[j], fm);
             m = f2u(fm);
         } else {
-            const float *px = x + un.start;
-            m = 0;
-            for (uint32_t i = lane; i < un.len; i += kWave) {
-                uint32_t a = abs_bits(px[i]);
-                m = m > a ? m : a;
-            }
+            m = slow_absmax<NT>(x + un.start, un.len, lane);
         }
         const size_t blk = un.block;
-        u += n_waves;
-        if (u < n_units) open_unit(u, un, fast);  // next unit's loads fly during the reduction
-        m = wave_max_u32(m);
-        if (lane == 0) {
-            if (upb == 1)
-                scales[blk] = u2f(m);
-            else
-                atomicMax(reinterpret_cast<unsigned int *>(scales) + blk, m);
+        u += stride;
+        const bool more = u < end;
+        if (more) open_unit(u, un, fast);  // next unit's loads fly during the reduction
+        run = run > m ? run : m;
+        if (!more || un.block != blk) {
+            const uint32_t r = wave_max_u32(run);
+            run = 0;
+            if (lane == 0) {
+                if (upb == 1)
+                    scales[blk] = u2f(r);
+                else
+                    atomicMax(reinterpret_cast<unsigned int *>(scales) + blk, r);
+            }
         }
     }
 }
@@ -1583,17 +1615,27 @@ int after_launch(const char *what)
 
 int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block, float *scales, hipStream_t stream)
 {
-    const int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
-    Plan p = make_plan(n, block, st.cus, g_tune.amax_wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
+    // Units no longer than a block (so that whole blocks are whole units when the block is a power of two),
+    // and the more wavefronts per compute unit the smaller the unit: the bytes in flight stay the same.
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
+    int wpc = g_tune.amax_wpc;
+    while (q > 1 && (size_t)q * 4 * kWave > Bq) {
+        q >>= 1;
+        wpc = wpc * 2 > 32 ? 32 : wpc * 2;
+    }
+    Plan p = make_plan(n, block, st.cus, wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
+    size_t per_wave = 0;
     if (p.upb > 1) {
         unsigned g = (unsigned)((p.nb + 255) / 256);
         hipLaunchKernelGGL(k_fill_zero, dim3(g), dim3(256), 0, stream, scales, p.nb);
         int rc = after_launch("k_fill_zero");
         if (rc) return rc;
+        per_wave = (p.n_units + p.n_teams - 1) / p.n_teams;
     }
 #define DQ8_AMAX(Q, NT)                                                                                          \
     hipLaunchKernelGGL((k_absmax<Q, NT>), dim3(p.grid), dim3(kWg), 0, stream, x, n, p.B, p.nb, p.upb, p.n_units, \
-                       p.n_teams, scales)
+                       p.n_teams, per_wave, scales)
 #define DQ8_AMAX_Q(NT)                      \
     switch (q) {                            \
     case 1: DQ8_AMAX(1, NT); break;         \
