@@ -384,9 +384,10 @@ __device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_am
 __device__ __forceinline__ size_t first_unit(int waves_per_wg = kWavesPerWg) { return (size_t)blockIdx.x * waves_per_wg + wave_in_wg(); }
 
 // Maximum of |x[0..len)| over the elements this lane takes, for a unit that is short or not
-// 16-byte aligned: whole quads with 128-bit loads when the start is aligned (the lanes take quads
-// lane, lane + 64, ...; a tail of fewer than four elements goes one by one), else element by element.
-template <int NT>
+// 16-byte aligned: whole quads with 128-bit loads when the start is aligned (the STRIDE lanes that
+// share the unit take quads lane, lane + STRIDE, ...; a tail of fewer than four elements goes one by
+// one), else element by element.
+template <int NT, uint32_t STRIDE = kWave>
 __device__ __forceinline__ uint32_t slow_absmax(const float *px, uint32_t len, uint32_t lane)
 {
     uint32_t m = 0;
@@ -396,11 +397,11 @@ __device__ __forceinline__ uint32_t slow_absmax(const float *px, uint32_t len, u
         const uint32_t nq = len >> 2;
         float fm = 0.0f;
 #pragma unroll 4
-        for (uint32_t q = lane; q < nq; q += kWave) fm = max4_abs(ldg<NT>(p4 + q), fm);
+        for (uint32_t q = lane; q < nq; q += STRIDE) fm = max4_abs(ldg<NT>(p4 + q), fm);
         m = f2u(fm);
         done = nq << 2;
     }
-    for (uint32_t i = done + lane; i < len; i += kWave) {
+    for (uint32_t i = done + lane; i < len; i += STRIDE) {
         const uint32_t a = abs_bits(px[i]);
         m = m > a ? m : a;
     }
@@ -554,11 +555,7 @@ struct Encoder {
                 for (int it = 0; it < Q; ++it) fm = max4_abs(sl.v[it], fm);
                 m = f2u(fm);
             } else {
-                m = 0;
-                for (uint32_t i = tl; i < un.len; i += TEAM) {
-                    uint32_t a = abs_bits(px[i]);
-                    m = m > a ? m : a;
-                }
+                m = slow_absmax<NT, TEAM>(px, un.len, tl);
             }
             m = wave_max_u32(m);
             if (WPB > 1) {
@@ -582,7 +579,17 @@ struct Encoder {
 #pragma unroll
             for (int it = 0; it < Q; ++it) stg<NT>(c4 + it * TEAM + tl, encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip));
         } else {
-            for (uint32_t i = tl; i < un.len; i += TEAM) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
+            // a short or misaligned unit: whole quads where the addresses allow (the lanes of the team take quads
+            // tl, tl + TEAM, ...), the rest element by element
+            uint32_t done = 0;
+            if ((((uintptr_t)px & 15) | ((uintptr_t)pc & 3)) == 0) {
+                const v4f *p4 = reinterpret_cast<const v4f *>(px);
+                uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
+                const uint32_t nq = un.len >> 2;
+                for (uint32_t q = tl; q < nq; q += TEAM) stg<NT>(c4 + q, encode_quad<FASTDIV>(sr, ldg<NT>(p4 + q), d, r, recip));
+                done = nq << 2;
+            }
+            for (uint32_t i = done + tl; i < un.len; i += TEAM) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
         }
     }
 };
@@ -767,8 +774,26 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restri
                 stg<NT>(o4 + j * kWave + lane, r);
             }
         } else {
+            // a short or misaligned unit: whole quads with 128-bit stores where the addresses allow, the rest
+            // element by element
             const uint8_t *pc = codes + un.start;
-            for (uint32_t i = lane; i < un.len; i += kWave) po[i] = lut_code(lut, pc[i], lane4) * s;
+            uint32_t done = 0;
+            if ((((uintptr_t)po & 15) | ((uintptr_t)pc & 3)) == 0) {
+                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(pc);
+                v4f *o4 = reinterpret_cast<v4f *>(po);
+                const uint32_t nq = un.len >> 2;
+                for (uint32_t q = lane; q < nq; q += kWave) {
+                    const uint32_t cw = ldg<NT>(c4 + q);
+                    v4f r;
+                    r.x = lut_at<0>(lut, cw, lane4) * s;
+                    r.y = lut_at<1>(lut, cw, lane4) * s;
+                    r.z = lut_at<2>(lut, cw, lane4) * s;
+                    r.w = lut_at<3>(lut, cw, lane4) * s;
+                    stg<NT>(o4 + q, r);
+                }
+                done = nq << 2;
+            }
+            for (uint32_t i = done + lane; i < un.len; i += kWave) po[i] = lut_code(lut, pc[i], lane4) * s;
             u += n_waves;
             if (u < n_units) open_unit(u, un, fast);
         }
@@ -799,12 +824,14 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     const uint32_t lane4 = lane * 4;
     size_t u = first_unit(WPW);
     Unit un;
-    bool fast = false;
+    bool fast = false;     // a whole unit at aligned addresses
+    bool aligned = false;  // 128-bit stores and 32-bit code loads are possible
     uint32_t w[KA][Q];
-    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
+    auto open_unit = [&](size_t uu, Unit &q, bool &f, bool &al) {
         q = unit_of<U>(uu, n, B, nb, upb);
-        f = q.len == U && ((uintptr_t)(out + q.start) & 15) == 0;
-        for (int k = 0; k < K; ++k) f = f && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
+        al = ((uintptr_t)(out + q.start) & 15) == 0;
+        for (int k = 0; k < K; ++k) al = al && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
+        f = al && q.len == U;
         if (KT > 0 && f) {
 #pragma unroll
             for (int k = 0; k < KA; ++k) {
@@ -814,7 +841,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
             }
         }
     };
-    if (u < n_units) open_unit(u, un, fast);
+    if (u < n_units) open_unit(u, un, fast, aligned);
     load_lut(tab, lut);
     __syncthreads();
     while (u < n_units) {
@@ -829,7 +856,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
 #pragma unroll
                 for (int j = 0; j < Q; ++j) cur[k][j] = w[k][j];
             u += n_waves;
-            if (u < n_units) open_unit(u, un, fast);
+            if (u < n_units) open_unit(u, un, fast, aligned);
             v4f *o4 = reinterpret_cast<v4f *>(po);
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
@@ -848,12 +875,16 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                 stg<NT>(o4 + j * kWave + lane, a);
             }
         } else {
-            if (fast) {
+            // any K, and short or misaligned units: whole quads where the addresses allow (lanes take quads
+            // lane, lane + 64, ...), the rest element by element
+            uint32_t done = 0;
+            if (aligned) {
                 v4f *o4 = reinterpret_cast<v4f *>(po);
-                for (int j = 0; j < Q; ++j) {
+                const uint32_t nq = un.len >> 2;
+                for (uint32_t q = lane; q < nq; q += kWave) {
                     v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
                     for (int k = 0; k < K; ++k) {
-                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + j * kWave + lane);
+                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
                         const float s = p.scales[k][un.block];
                         a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
                         a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
@@ -864,17 +895,17 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                     a.y = mean_of(a.y);
                     a.z = mean_of(a.z);
                     a.w = mean_of(a.w);
-                    stg<NT>(o4 + j * kWave + lane, a);
+                    stg<NT>(o4 + q, a);
                 }
-            } else {
-                for (uint32_t i = lane; i < un.len; i += kWave) {
-                    float a = 0.0f;
-                    for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
-                    po[i] = mean_of(a);
-                }
+                done = nq << 2;
+            }
+            for (uint32_t i = done + lane; i < un.len; i += kWave) {
+                float a = 0.0f;
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+                po[i] = mean_of(a);
             }
             u += n_waves;
-            if (u < n_units) open_unit(u, un, fast);
+            if (u < n_units) open_unit(u, un, fast, aligned);
         }
     }
 }
@@ -1022,11 +1053,12 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
     __syncthreads();
     for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
         const Unit un = unit_of<kUnit>(u, n, B, nb, upb);
-        bool fast = un.len == kUnit;
-        for (int k = 0; k < K; ++k) fast = fast && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
-        if (local) fast = fast && (((uintptr_t)(local + un.start) & 15) == 0);
-        if (mean_out) fast = fast && (((uintptr_t)(mean_out + un.start) & 15) == 0);
-        if (codes_out) fast = fast && (((uintptr_t)(codes_out + un.start) & 3) == 0);
+        bool aligned = true;  // 128-bit accesses to the fp32 arrays and 32-bit ones to the codes are possible
+        for (int k = 0; k < K; ++k) aligned = aligned && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
+        if (local) aligned = aligned && (((uintptr_t)(local + un.start) & 15) == 0);
+        if (mean_out) aligned = aligned && (((uintptr_t)(mean_out + un.start) & 15) == 0);
+        if (codes_out) aligned = aligned && (((uintptr_t)(codes_out + un.start) & 3) == 0);
+        const bool fast = aligned && un.len == kUnit;
         if (fast) {
             v4f acc[Q];
             uint32_t wa[Q], wb[Q];
@@ -1099,17 +1131,50 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                 for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWave + lane, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
             }
         } else {
+            // A short or misaligned unit.  Whole quads where the addresses allow (lanes take quads lane,
+            // lane + 64, ...), the remaining elements one by one.  The means are formed again for each use
+            // (store, maximum, compression) rather than kept.
+            const uint32_t nq = aligned ? un.len >> 2 : 0;
+            const uint32_t done = nq << 2;
             auto mean_at = [&](uint32_t i) {
                 float a = 0.0f;
                 if (local) a = a + local[un.start + i];
                 for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
                 return mean_of(a);
             };
-            if (mean_out)
-                for (uint32_t i = lane; i < un.len; i += kWave) mean_out[un.start + i] = mean_at(i);
-            if (codes_out) {  // the means are formed twice rather than kept: first for the maximum
-                uint32_t m = 0;
-                for (uint32_t i = lane; i < un.len; i += kWave) {
+            auto mean_quad = [&](uint32_t q) {
+                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (local) {
+                    const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + un.start) + q);
+                    a.x = a.x + l.x;
+                    a.y = a.y + l.y;
+                    a.z = a.z + l.z;
+                    a.w = a.w + l.w;
+                }
+                for (int k = 0; k < K; ++k) {
+                    const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
+                    const float s = p.scales[k][un.block];
+                    a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
+                    a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
+                    a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
+                    a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
+                }
+                a.x = mean_of(a.x);
+                a.y = mean_of(a.y);
+                a.z = mean_of(a.z);
+                a.w = mean_of(a.w);
+                return a;
+            };
+            if (mean_out) {
+                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
+                for (uint32_t q = lane; q < nq; q += kWave) stg<NT>(o4 + q, mean_quad(q));
+                for (uint32_t i = done + lane; i < un.len; i += kWave) mean_out[un.start + i] = mean_at(i);
+            }
+            if (codes_out) {
+                float fm = 0.0f;
+                for (uint32_t q = lane; q < nq; q += kWave) fm = max4_abs(mean_quad(q), fm);
+                uint32_t m = f2u(fm);
+                for (uint32_t i = done + lane; i < un.len; i += kWave) {
                     const uint32_t a = abs_bits(mean_at(i));
                     m = m > a ? m : a;
                 }
@@ -1118,7 +1183,9 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                 const float d = s == 0.0f ? 1.0f : s;
                 const float r = 1.0f / d;
                 const bool recip = reciprocal_ok(d);
-                for (uint32_t i = lane; i < un.len; i += kWave)
+                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
+                for (uint32_t q = lane; q < nq; q += kWave) stg<1>(c4 + q, encode_quad<FASTDIV>(sr, mean_quad(q), d, r, recip));
+                for (uint32_t i = done + lane; i < un.len; i += kWave)
                     codes_out[un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(i), d, r, recip);
             }
         }
@@ -1532,8 +1599,6 @@ int device_state(DeviceState **out)
 struct Tuning {
     int amax_nt = 1;     // cache policy of each kernel's streaming accesses, see ldg / stg
     int enc_nt = 1;      //   4-byte code stores: plain non-temporal is best
-    int dec_nt = 2;      //   16-byte fp32 stores: write-through non-temporal is best
-    int avg_nt = 2;
     int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
@@ -1657,8 +1722,12 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
 int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
                   bool fused, hipStream_t stream)
 {
-    const int wpb = g_tune.enc_wpb == 4 ? 4 : 1;
-    Plan p = make_plan(n, block, st.cus, g_tune.enc_wpc, wpb);
+    // Blocks of up to 1024 elements: one wavefront per unit (a block has at most four quads per lane) and every
+    // wavefront slot of the compute units in use; larger ones: a team of four wavefronts per unit.
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const bool small = Bq <= 1024;
+    const int wpb = small ? 1 : (g_tune.enc_wpb == 4 ? 4 : 1);
+    Plan p = make_plan(n, block, st.cus, small ? 32 : g_tune.enc_wpc, wpb);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + kTeamSlots) * sizeof(uint32_t);
     // Whole aligned blocks of exactly one unit: the kernel without slow paths in its loop.
@@ -1971,35 +2040,41 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    const int wpw = g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4);
-    const int q = (g_tune.dec_q == 2 || g_tune.dec_q == 8 || g_tune.dec_q == 16) ? g_tune.dec_q : 4;
-    Plan p = make_plan(n, block, st->cus, g_tune.dec_wpc, 1, wpw, (size_t)q * 4 * kWave);
+    // Units no longer than a block, and the smaller the unit the more wavefronts per compute unit (the bytes
+    // in flight stay the same); 16 wavefronts share a workgroup's 64 KiB table when there are that many.
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 8 || g_tune.dec_q == 16) ? g_tune.dec_q : 4;
+    int wpc = g_tune.dec_wpc;
+    int wpw = g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4);
+    while (q > 1 && (size_t)q * 4 * kWave > Bq) {
+        q >>= 1;
+        wpc = wpc * 2 > 32 ? 32 : wpc * 2;
+    }
+    if (wpc >= 16)
+        wpw = 16;
+    else if (wpc >= 8 && wpw < 8)
+        wpw = 8;
+    Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
         return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-#define DQ8_DEC(Q, NT, WPW)                                                                                       \
-    hipLaunchKernelGGL((k_decode<Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
+#define DQ8_DEC(Q, WPW)                                                                                          \
+    hipLaunchKernelGGL((k_decode<Q, 2, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
                        p.nb, p.upb, p.n_units, p.n_teams, out)
-#define DQ8_DEC_W(Q, NT)                     \
-    switch (wpw) {                           \
-    case 16: DQ8_DEC(Q, NT, 16); break;      \
-    case 8: DQ8_DEC(Q, NT, 8); break;        \
-    default: DQ8_DEC(Q, NT, 4); break;       \
+#define DQ8_DEC_W(Q)                     \
+    switch (wpw) {                       \
+    case 16: DQ8_DEC(Q, 16); break;      \
+    case 8: DQ8_DEC(Q, 8); break;        \
+    default: DQ8_DEC(Q, 4); break;       \
     }
-#define DQ8_DEC_Q(NT)                        \
-    switch (q) {                             \
-    case 2: DQ8_DEC_W(2, NT) break;          \
-    case 8: DQ8_DEC_W(8, NT) break;          \
-    case 16: DQ8_DEC_W(16, NT) break;        \
-    default: DQ8_DEC_W(4, NT) break;         \
+    switch (q) {
+    case 1: DQ8_DEC_W(1) break;
+    case 2: DQ8_DEC_W(2) break;
+    case 8: DQ8_DEC_W(8) break;
+    case 16: DQ8_DEC_W(16) break;
+    default: DQ8_DEC_W(4) break;
     }
-    switch (g_tune.dec_nt) {
-    case 0: DQ8_DEC_Q(0) break;
-    case 2: DQ8_DEC_Q(2) break;
-    default: DQ8_DEC_Q(1) break;
-    }
-#undef DQ8_DEC_Q
 #undef DQ8_DEC_W
 #undef DQ8_DEC
     return after_launch("k_decode");
@@ -2019,7 +2094,9 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     if (rc) return rc;
     const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
     const bool fixed_k = K == 2 || K == 4 || K == 8;
-    const int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
+    while (q > 1 && (size_t)q * 4 * kWave > Bq) q >>= 1;  // units no longer than a block
     Plan p = make_plan(n, block, st->cus, g_tune.avg_wpc, 1, wpw, (size_t)q * 4 * kWave);
     WorkerPtrs wp;
     std::memset(&wp, 0, sizeof(wp));
@@ -2037,40 +2114,27 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
         rc = launch_avg_full(*st, kind, wp, K, nullptr, n, p, out, stream, &launched);
         if (rc || launched) return rc;
     }
-#define DQ8_AVG(KT, Q, NT, WPW)                                                                                   \
-    hipLaunchKernelGGL((k_decode_avg<KT, Q, NT, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
+#define DQ8_AVG(KT, Q, WPW)                                                                                      \
+    hipLaunchKernelGGL((k_decode_avg<KT, Q, 2, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
                        p.nb, p.upb, p.n_units, p.n_teams, out)
-#define DQ8_AVG_W(KT, Q, NT)                 \
-    switch (wpw) {                           \
-    case 16: DQ8_AVG(KT, Q, NT, 16); break;  \
-    case 8: DQ8_AVG(KT, Q, NT, 8); break;    \
-    default: DQ8_AVG(KT, Q, NT, 4); break;   \
+#define DQ8_AVG_W(KT, Q)                 \
+    switch (wpw) {                       \
+    case 16: DQ8_AVG(KT, Q, 16); break;  \
+    case 8: DQ8_AVG(KT, Q, 8); break;    \
+    default: DQ8_AVG(KT, Q, 4); break;   \
     }
-#define DQ8_AVG_Q(KT, NT)                    \
-    switch (q) {                             \
-    case 1: DQ8_AVG_W(KT, 1, NT) break;      \
-    case 4: DQ8_AVG_W(KT, 4, NT) break;      \
-    default: DQ8_AVG_W(KT, 2, NT) break;     \
-    }
-#define DQ8_AVG_NT(KT)                       \
-    switch (g_tune.avg_nt) {                 \
-    case 0: DQ8_AVG_Q(KT, 0) break;          \
-    case 2: DQ8_AVG_Q(KT, 2) break;          \
-    default: DQ8_AVG_Q(KT, 1) break;         \
+#define DQ8_AVG_Q(KT)                    \
+    switch (q) {                         \
+    case 1: DQ8_AVG_W(KT, 1) break;      \
+    case 4: DQ8_AVG_W(KT, 4) break;      \
+    default: DQ8_AVG_W(KT, 2) break;     \
     }
     switch (K) {
-    case 2: DQ8_AVG_NT(2) break;
-    case 4: DQ8_AVG_NT(4) break;
-    case 8: DQ8_AVG_NT(8) break;
-    default:
-        switch (g_tune.avg_nt) {
-        case 0: DQ8_AVG_W(0, 1, 0) break;
-        case 2: DQ8_AVG_W(0, 1, 2) break;
-        default: DQ8_AVG_W(0, 1, 1) break;
-        }
-        break;
+    case 2: DQ8_AVG_Q(2) break;
+    case 4: DQ8_AVG_Q(4) break;
+    case 8: DQ8_AVG_Q(8) break;
+    default: DQ8_AVG_W(0, 1) break;
     }
-#undef DQ8_AVG_NT
 #undef DQ8_AVG_Q
 #undef DQ8_AVG_W
 #undef DQ8_AVG
@@ -2241,8 +2305,8 @@ int dq8_internal_tune(const char *key, int value)
 {
     if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
-        {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, {"dec_nt", &g_tune.dec_nt, 0, 2},
-        {"avg_nt", &g_tune.avg_nt, 0, 2}, {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
+        {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, 
+        {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},

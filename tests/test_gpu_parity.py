@@ -108,6 +108,8 @@ SHAPES = [  # (n, block)
     (5 * 8192 + 100, 8192),   # two units per block
     (1000, 7), (257, 1), (4096 * 3 + 1, 1),  # tiny blocks; the last wavefront's first unit is the ragged one
     (20000, 10 ** 9),         # block larger than the array
+    (100 * 64 + 20, 64), (50 * 256 + 8, 256), (7 * 1024 + 4, 1024), (9 * 516 + 2, 516),  # short aligned blocks:
+    (3 * 12000 + 40, 12000),  # whole quads, partly with a tail; a block of two whole units and a short aligned one
 ]
 
 
@@ -273,7 +275,9 @@ AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (300
              (100, 7, 0), (4096, 0, 0), (4095, 0, 0),
              (5 * 1024 + 100, 1024, 0),   # two whole units per block, ragged last unit
              (3 * 1536, 1536, 0),         # three units per block: not a power of two
-             (3 * 2048 + 7, 2048, 0), (40 * 512, 512, 0), (511, 0, 0), (512, 0, 0), (513, 0, 0)]
+             (3 * 2048 + 7, 2048, 0), (40 * 512, 512, 0), (511, 0, 0), (512, 0, 0), (513, 0, 0),
+             (20 * 256 + 12, 256, 0), (64 * 64, 64, 0), (7 * 1000 + 4, 1000, 0), (5 * 516 + 2, 516, 0),
+             (3 * 1000, 1000, 2)]     # short blocks: aligned (whole quads), with a tail, and misaligned
 
 
 @pytest.mark.parametrize("kind", KINDS)
