@@ -502,18 +502,23 @@ __global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, siz
     }
 }
 
-// Compression.  A team of WPB wavefronts owns a unit: WPB == 1, each wavefront of the
-// workgroup walks its own units with 16 quads per lane; WPB == 4, the workgroup's four
-// wavefronts share a unit, 4 quads per lane, and combine their maxima through LDS.
+// Compression.  A team of WPB wavefronts owns a unit of WPB * QL * 256 elements, QL quads per lane:
+// WPB == 1, each wavefront of the workgroup walks its own units; WPB == 4, the workgroup's four
+// wavefronts share a unit and combine their maxima through LDS.
 // FUSED: a unit is a whole block (upb == 1); the team reduces the block's maximum from
 // registers, stores it and quantises the same registers.  Otherwise the scale of the unit's
 // block is read from scales[].
 // The loop is software-pipelined: the loads of a team's next unit are issued before the
 // current unit is reduced and quantised, so each wavefront always has loads in flight.
-template <int WPB, int NT, bool FUSED, bool FASTDIV>
+// A unit shorter than that (a block that is not a power of two, the end of a block or of the
+// array) takes the same path when it consists of whole aligned quads: a lane whose quad lies
+// past the end loads the unit's last quad instead (an unconditional load of valid memory: the
+// maximum does not change and the lane stores nothing).
+template <int WPB, int QL, int NT, bool FUSED, bool FASTDIV>
 struct Encoder {
-    static constexpr int Q = kUnitQuads / WPB;
+    static constexpr int Q = QL;
     static constexpr uint32_t TEAM = kWave * WPB;
+    static constexpr int U = QL * 4 * (int)TEAM;
 
     const float *x;
     uint8_t *codes;
@@ -531,13 +536,18 @@ struct Encoder {
 
     __device__ __forceinline__ void fetch(size_t u, Slot &sl) const
     {
-        sl.un = unit_of<kUnit>(u, n, B, nb, upb);
+        sl.un = unit_of<U>(u, n, B, nb, upb);
         const float *px = x + sl.un.start;
-        sl.fast = sl.un.len == kUnit && ((uintptr_t)px & 15) == 0 && ((uintptr_t)(codes + sl.un.start) & 3) == 0;
+        sl.fast = sl.un.len >= 4 && (sl.un.len & 3) == 0 && ((uintptr_t)px & 15) == 0 &&
+                  ((uintptr_t)(codes + sl.un.start) & 3) == 0;
         if (sl.fast) {
             const v4f *p4 = reinterpret_cast<const v4f *>(px);
+            const uint32_t last = (sl.un.len >> 2) - 1;
 #pragma unroll
-            for (int it = 0; it < Q; ++it) sl.v[it] = ldg<NT>(p4 + it * TEAM + tl);
+            for (int it = 0; it < Q; ++it) {
+                const uint32_t q = it * TEAM + tl;
+                sl.v[it] = ldg<NT>(p4 + (q < last ? q : last));
+            }
         }
     }
 
@@ -576,10 +586,14 @@ struct Encoder {
         const bool recip = reciprocal_ok(d);
         if (sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
+            const uint32_t nq = un.len >> 2;
 #pragma unroll
-            for (int it = 0; it < Q; ++it) stg<NT>(c4 + it * TEAM + tl, encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip));
+            for (int it = 0; it < Q; ++it) {
+                const uint32_t cw = encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip);
+                if (it * TEAM + tl < nq) stg<NT>(c4 + it * TEAM + tl, cw);
+            }
         } else {
-            // a short or misaligned unit: whole quads where the addresses allow (the lanes of the team take quads
+            // a misaligned unit or one that does not consist of whole quads: whole quads where the addresses allow (the lanes of the team take quads
             // tl, tl + TEAM, ...), the rest element by element
             uint32_t done = 0;
             if ((((uintptr_t)px & 15) | ((uintptr_t)pc & 3)) == 0) {
@@ -594,13 +608,13 @@ struct Encoder {
     }
 };
 
-template <int WPB, int NT, bool FUSED, bool FASTDIV>
+template <int WPB, int QL, int NT, bool FUSED, bool FASTDIV>
 __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
                                                size_t B, size_t nb, size_t upb, size_t n_units, size_t n_teams,
                                                float *__restrict__ scales, uint8_t *__restrict__ codes)
 {
     static_assert(WPB == 1 || WPB == kWavesPerWg, "a team is one wavefront or the whole workgroup");
-    using Enc = Encoder<WPB, NT, FUSED, FASTDIV>;
+    using Enc = Encoder<WPB, QL, NT, FUSED, FASTDIV>;
     extern __shared__ uint32_t lds[];
     Enc e;
     e.x = x;
@@ -1598,7 +1612,6 @@ int device_state(DeviceState **out)
 // for experiments.  None of them affects results.
 struct Tuning {
     int amax_nt = 1;     // cache policy of each kernel's streaming accesses, see ldg / stg
-    int enc_nt = 1;      //   4-byte code stores: plain non-temporal is best
     int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
@@ -1722,12 +1735,16 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
 int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
                   bool fused, hipStream_t stream)
 {
-    // Blocks of up to 1024 elements: one wavefront per unit (a block has at most four quads per lane) and every
-    // wavefront slot of the compute units in use; larger ones: a team of four wavefronts per unit.
+    // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.  4096: a team of four
+    // wavefronts per unit, four quads per lane.  Smaller: one wavefront per unit (1, 2, 4 or 8 quads per lane) and
+    // every wavefront slot of the compute units in use.
     const size_t Bq = (block == 0 || block > n) ? n : block;
-    const bool small = Bq <= 1024;
+    size_t unit = 256;
+    while (unit < Bq && unit < (size_t)kUnit) unit <<= 1;
+    const bool small = unit < (size_t)kUnit;
     const int wpb = small ? 1 : (g_tune.enc_wpb == 4 ? 4 : 1);
-    Plan p = make_plan(n, block, st.cus, small ? 32 : g_tune.enc_wpc, wpb);
+    const int ql = (int)(unit / (size_t)(4 * kWave * wpb));
+    Plan p = make_plan(n, block, st.cus, small ? 32 : g_tune.enc_wpc, wpb, kWavesPerWg, unit);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + kTeamSlots) * sizeof(uint32_t);
     // Whole aligned blocks of exactly one unit: the kernel without slow paths in its loop.
@@ -1753,36 +1770,38 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
 #undef DQ8_ENC_FULL
         return after_launch("k_encode_full");
     }
-#define DQ8_ENC(WPB, NT, FUSED, FD)                                                                              \
-    hipLaunchKernelGGL((k_encode<WPB, NT, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
+#define DQ8_ENC(WPB, QL, FUSED, FD)                                                                               \
+    hipLaunchKernelGGL((k_encode<WPB, QL, 1, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
                        p.upb, p.n_units, p.n_teams, scales, codes)
-#define DQ8_ENC_FD(WPB, NT, FUSED)       \
-    if (g_tune.fastdiv) {                \
-        DQ8_ENC(WPB, NT, FUSED, true);   \
-    } else {                             \
-        DQ8_ENC(WPB, NT, FUSED, false);  \
+#define DQ8_ENC_F(WPB, QL, FD)       \
+    if (fused) {                     \
+        DQ8_ENC(WPB, QL, true, FD);  \
+    } else {                         \
+        DQ8_ENC(WPB, QL, false, FD); \
     }
-#define DQ8_ENC_NT(WPB, FUSED)                    \
-    switch (g_tune.enc_nt) {                      \
-    case 0: DQ8_ENC_FD(WPB, 0, FUSED) break;      \
-    case 2: DQ8_ENC_FD(WPB, 2, FUSED) break;      \
-    default: DQ8_ENC_FD(WPB, 1, FUSED) break;     \
-    }
+    const bool fd = g_tune.fastdiv != 0;
     if (wpb == 4) {
-        if (fused) {
-            DQ8_ENC_NT(4, true)
+        if (fd) {
+            DQ8_ENC_F(4, 4, true)
         } else {
-            DQ8_ENC_NT(4, false)
+            DQ8_ENC_F(4, 4, false)
         }
     } else {
-        if (fused) {
-            DQ8_ENC_NT(1, true)
-        } else {
-            DQ8_ENC_NT(1, false)
+        switch (ql) {
+        case 1: DQ8_ENC_F(1, 1, true) break;
+        case 2: DQ8_ENC_F(1, 2, true) break;
+        case 4: DQ8_ENC_F(1, 4, true) break;
+        case 8: DQ8_ENC_F(1, 8, true) break;
+        default:
+            if (fd) {
+                DQ8_ENC_F(1, 16, true)
+            } else {
+                DQ8_ENC_F(1, 16, false)
+            }
+            break;
         }
     }
-#undef DQ8_ENC_NT
-#undef DQ8_ENC_FD
+#undef DQ8_ENC_F
 #undef DQ8_ENC
     return after_launch("k_encode");
 }
@@ -2305,7 +2324,7 @@ int dq8_internal_tune(const char *key, int value)
 {
     if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
-        {"amax_nt", &g_tune.amax_nt, 0, 1}, {"enc_nt", &g_tune.enc_nt, 0, 2}, 
+        {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
