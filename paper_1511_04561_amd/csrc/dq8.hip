@@ -743,7 +743,10 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
 // Decompression of one buffer: out = table[code] * scale.  One wavefront per unit of Q * 256
 // elements: Q code words (4 codes each) per lane; the next unit's words are loaded before the
 // current ones are expanded.
-template <int Q, int NT, int WPW>
+// RAGGED = true (chosen by the host when blocks are not whole units): a unit of fewer whole aligned
+// quads stays on this path; a lane whose quad lies past the end loads the unit's last code word
+// instead (unconditional, valid memory) and stores nothing.
+template <int Q, int NT, int WPW, bool RAGGED>
 __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
                                                        const float *__restrict__ scales, size_t n, size_t B, size_t nb,
                                                        size_t upb, size_t n_units, size_t n_waves, float *__restrict__ out)
@@ -758,11 +761,16 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restri
     uint32_t w[Q];
     auto open_unit = [&](size_t uu, Unit &q, bool &f) {
         q = unit_of<U>(uu, n, B, nb, upb);
-        f = q.len == U && ((uintptr_t)(out + q.start) & 15) == 0 && ((uintptr_t)(codes + q.start) & 3) == 0;
+        f = ((uintptr_t)(out + q.start) & 15) == 0 && ((uintptr_t)(codes + q.start) & 3) == 0;
+        f = f && (RAGGED ? (q.len >= 4 && (q.len & 3) == 0) : q.len == U);
         if (f) {
             const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes + q.start);
+            const uint32_t last = (q.len >> 2) - 1;
 #pragma unroll
-            for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + j * kWave + lane);
+            for (int j = 0; j < Q; ++j) {
+                const uint32_t i = j * kWave + lane;
+                w[j] = ldg<NT>(c4 + (RAGGED ? (i < last ? i : last) : i));
+            }
         }
     };
     if (u < n_units) open_unit(u, un, fast);  // the first loads are in flight while the table is built
@@ -775,6 +783,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restri
             uint32_t cur[Q];
 #pragma unroll
             for (int j = 0; j < Q; ++j) cur[j] = w[j];
+            const uint32_t nq = un.len >> 2;
             u += n_waves;
             if (u < n_units) open_unit(u, un, fast);
             v4f *o4 = reinterpret_cast<v4f *>(po);
@@ -785,7 +794,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restri
                 r.y = lut_at<1>(lut, cur[j], lane4) * s;
                 r.z = lut_at<2>(lut, cur[j], lane4) * s;
                 r.w = lut_at<3>(lut, cur[j], lane4) * s;
-                stg<NT>(o4 + j * kWave + lane, r);
+                if (!RAGGED || j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, r);
             }
         } else {
             // a short or misaligned unit: whole quads with 128-bit stores where the addresses allow, the rest
@@ -838,20 +847,26 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     const uint32_t lane4 = lane * 4;
     size_t u = first_unit(WPW);
     Unit un;
-    bool fast = false;     // a whole unit at aligned addresses
+    bool fast = false;     // whole quads at aligned addresses
     bool aligned = false;  // 128-bit stores and 32-bit code loads are possible
     uint32_t w[KA][Q];
     auto open_unit = [&](size_t uu, Unit &q, bool &f, bool &al) {
         q = unit_of<U>(uu, n, B, nb, upb);
         al = ((uintptr_t)(out + q.start) & 15) == 0;
         for (int k = 0; k < K; ++k) al = al && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
-        f = al && q.len == U;
+        // a unit of fewer whole quads stays on the pipelined path: a lane whose quad lies past the end loads
+        // the unit's last code word instead (unconditional, valid memory) and stores nothing
+        f = al && q.len >= 4 && (q.len & 3) == 0;
         if (KT > 0 && f) {
+            const uint32_t last = (q.len >> 2) - 1;
 #pragma unroll
             for (int k = 0; k < KA; ++k) {
                 const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + q.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) w[k][j] = ldg<NT>(c4 + j * kWave + lane);
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t i = j * kWave + lane;
+                    w[k][j] = ldg<NT>(c4 + (i < last ? i : last));
+                }
             }
         }
     };
@@ -869,6 +884,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
             for (int k = 0; k < KA; ++k)
 #pragma unroll
                 for (int j = 0; j < Q; ++j) cur[k][j] = w[k][j];
+            const uint32_t nq = un.len >> 2;
             u += n_waves;
             if (u < n_units) open_unit(u, un, fast, aligned);
             v4f *o4 = reinterpret_cast<v4f *>(po);
@@ -886,10 +902,10 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                 a.y = mean_of(a.y);
                 a.z = mean_of(a.z);
                 a.w = mean_of(a.w);
-                stg<NT>(o4 + j * kWave + lane, a);
+                if (j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, a);
             }
         } else {
-            // any K, and short or misaligned units: whole quads where the addresses allow (lanes take quads
+            // any K, and misaligned units or units that are not whole quads: whole quads where the addresses allow (lanes take quads
             // lane, lane + 64, ...), the rest element by element
             uint32_t done = 0;
             if (aligned) {
@@ -1043,7 +1059,12 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
 // k_encode, so the results are identical to the two calls.
 // Two workgroups of WPW wavefronts share a compute unit (each holds the 64 KiB decode table),
 // so the register budget per lane is 512 / (WPW / 2): 170 for six wavefronts, 128 for eight.
-template <int NT, bool FASTDIV, int WPW>
+// The unit is QL * 256 elements (the host picks the smallest that holds a block, up to 4096).
+// RAGGED = true (chosen by the host when blocks are not whole units): a unit of fewer whole aligned
+// quads stays on the register path; a lane whose quad lies past the end loads the unit's last quad
+// instead (unconditional loads of valid memory; the maximum does not change) and stores nothing.
+// This costs a register per quad for the clamped offsets, which the kernel for whole units cannot spare.
+template <int QL, int NT, bool FASTDIV, int WPW, bool RAGGED>
 __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
                                                           const float *__restrict__ local, size_t n, size_t B,
                                                           size_t nb, size_t upb, size_t n_units, size_t n_waves,
@@ -1053,7 +1074,8 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
     static_assert(WPW >= 4, "the decode table is filled by 256 threads");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t bucket_lds[];
-    constexpr int Q = kUnitQuads;
+    constexpr int Q = QL;
+    constexpr int U = QL * 4 * kWave;
     const int terms = K + (local ? 1 : 0);
     const float fk = (float)terms;
     const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
@@ -1066,20 +1088,25 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
     if (codes_out) sr = load_bucket_table(tab, bucket_lds, kWave * WPW);
     __syncthreads();
     for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
-        const Unit un = unit_of<kUnit>(u, n, B, nb, upb);
+        const Unit un = unit_of<U>(u, n, B, nb, upb);
         bool aligned = true;  // 128-bit accesses to the fp32 arrays and 32-bit ones to the codes are possible
         for (int k = 0; k < K; ++k) aligned = aligned && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
         if (local) aligned = aligned && (((uintptr_t)(local + un.start) & 15) == 0);
         if (mean_out) aligned = aligned && (((uintptr_t)(mean_out + un.start) & 15) == 0);
         if (codes_out) aligned = aligned && (((uintptr_t)(codes_out + un.start) & 3) == 0);
-        const bool fast = aligned && un.len == kUnit;
+        const bool fast = aligned && (RAGGED ? (un.len >= 4 && (un.len & 3) == 0) : un.len == (uint32_t)U);
         if (fast) {
+            const uint32_t nq = un.len >> 2, last = nq - 1;
+            auto qi = [&](int j) {  // this lane's j-th quad, clamped to the unit
+                const uint32_t i = j * kWave + lane;
+                return RAGGED ? (i < last ? i : last) : i;
+            };
             v4f acc[Q];
             uint32_t wa[Q], wb[Q];
             auto load_w = [&](uint32_t(&w)[Q], int k) {
                 const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) w[j] = ldg<NT>(c4 + j * kWave + lane);
+                for (int j = 0; j < Q; ++j) w[j] = ldg_at<NT>(c4, qi(j));  // scalar base + 32-bit offset
             };
             auto add_w = [&](const uint32_t(&w)[Q], int k) {
                 const float s = p.scales[k][un.block];
@@ -1098,7 +1125,7 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
             if (local) {
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + un.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = ldg<NT>(l4 + j * kWave + lane);
+                for (int j = 0; j < Q; ++j) acc[j] = ldg_at<NT>(l4, qi(j));
 #pragma unroll
                 for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
                     acc[j].x = 0.0f + acc[j].x;
@@ -1129,7 +1156,8 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
             if (mean_out) {
                 v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) stg<NT>(o4 + j * kWave + lane, acc[j]);
+                for (int j = 0; j < Q; ++j)
+                    if (!RAGGED || j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, acc[j]);
             }
             if (codes_out) {
                 float fm = 0.0f;
@@ -1142,10 +1170,13 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                 const bool recip = reciprocal_ok(d);
                 uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
 #pragma unroll
-                for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWave + lane, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
+                    if (!RAGGED || j * kWave + lane < nq) stg<1>(c4 + j * kWave + lane, cw);
+                }
             }
         } else {
-            // A short or misaligned unit.  Whole quads where the addresses allow (lanes take quads lane,
+            // A misaligned unit or one that is not whole quads.  Whole quads where the addresses allow (lanes take quads lane,
             // lane + 64, ...), the remaining elements one by one.  The means are formed again for each use
             // (store, maximum, compression) rather than kept.
             const uint32_t nq = aligned ? un.len >> 2 : 0;
@@ -1257,25 +1288,39 @@ struct AvgTeam {
         sl.fast = false;
         if (!sl.active) return;
         sl.un = unit_of<kUnit>(u, n, B, nb, 1);
-        bool f = sl.un.len == kUnit && (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
+        // whole aligned quads: a short unit takes the register path too (see load_worker)
+        bool f = sl.un.len >= 4 && (sl.un.len & 3) == 0 && (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
 #pragma unroll
         for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
         if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
         sl.fast = f;
     }
 
+    // This lane's j-th quad of the unit; WHOLE promises a unit of 4096 elements, otherwise a quad past the
+    // end of a shorter unit becomes the unit's last one (an unconditional load of valid memory whose result
+    // is not stored and cannot change the maximum).
+    template <bool WHOLE>
+    __device__ __forceinline__ uint32_t quad_of(const Slot &sl, int j) const
+    {
+        const uint32_t i = j * kWg + tl;
+        if (WHOLE) return i;
+        const uint32_t last = (sl.un.len >> 2) - 1;
+        return i < last ? i : last;
+    }
+
+    template <bool WHOLE>
     __device__ __forceinline__ void load_worker(const Slot &sl, int k)
     {
         const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start);
 #pragma unroll
-        for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, j * kWg + tl);
+        for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, quad_of<WHOLE>(sl, j));
     }
 
     __device__ __forceinline__ void load_all(const Slot &sl)
     {
         if (sl.fast) {
 #pragma unroll
-            for (int k = 0; k < KT; ++k) load_worker(sl, k);
+            for (int k = 0; k < KT; ++k) load_worker<false>(sl, k);
         }
     }
 
@@ -1293,7 +1338,7 @@ struct AvgTeam {
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
 #pragma unroll
                 for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
-                    const v4f l = ldg<NT>(l4 + j * kWg + tl);
+                    const v4f l = ldg<NT>(l4 + quad_of<STEADY>(sl, j));
                     acc[j].x = 0.0f + l.x;
                     acc[j].y = 0.0f + l.y;
                     acc[j].z = 0.0f + l.z;
@@ -1320,7 +1365,7 @@ struct AvgTeam {
                 // to them, which costs a wavefront per SIMD.
 #pragma unroll
                 for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-                if (STEADY || nx.fast) load_worker(nx, k);  // refill in place
+                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place
             }
             float fm = 0.0f;
 #pragma unroll
@@ -1359,7 +1404,10 @@ struct AvgTeam {
         if (STEADY || sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
 #pragma unroll
-            for (int j = 0; j < Q; ++j) stg<1>(c4 + j * kWg + tl, encode_quad<FASTDIV>(sr, acc[j], d, r, recip));
+            for (int j = 0; j < Q; ++j) {
+                const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
+                if (STEADY || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
+            }
         } else {
             for (uint32_t i = tl; i < sl.un.len; i += kWg)
                 codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);
@@ -1632,7 +1680,6 @@ struct Tuning {
     int avg_wpc = 32;
     int avg_wpw = 16;
     int blk_wpw = 8;     // register-resident average: wavefronts per workgroup (two workgroups per compute unit)
-    int blk_nt = 2;
     int avg_team = 1;    // average-then-compress with K = 2, 4, 8: the team kernel (0: the wave-per-block kernel)
     int avg_steady = 1;  //   unconditional steady-state iterations when the buffers are aligned
     int avg_teams = 3;   //   teams per workgroup: 2, 3 or 4
@@ -1896,34 +1943,43 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                      size_t block, float *mean_out, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
-    if (codes_out && !mean_out && (K == 2 || K == 4 || K == 8) && g_tune.avg_team)
+    // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    size_t unit = 256;
+    while (unit < Bq && unit < (size_t)kUnit) unit <<= 1;
+    // K = 2, 4, 8 and blocks that need a 4096-element unit: the team kernel
+    if (codes_out && !mean_out && (K == 2 || K == 4 || K == 8) && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
-    const int wpw = g_tune.blk_wpw == 8 ? 8 : 6;
-    Plan p = make_plan(n, block, st.cus, 2 * wpw, 1, wpw, kUnit);
+    const int ql = (int)(unit / (size_t)(4 * kWave));
+    // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave
+    const bool ragged = Bq < n && Bq % unit != 0;  // blocks end inside units
+    const int wpw = (ql == 16 && (ragged || g_tune.blk_wpw != 8)) ? 6 : 8;
+    Plan p = make_plan(n, block, st.cus, 2 * wpw, 1, wpw, unit);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = codes_out ? (size_t)st.search_words[kind] * sizeof(uint32_t) : 0;
-#define DQ8_BLK(NT, FD, WPW)                                                                                     \
-    hipLaunchKernelGGL((k_avg_block<NT, FD, WPW>), dim3(p.grid), dim3(kWave * WPW), lds, stream, tab, wp, K, local, n, \
-                       p.B, p.nb, p.upb, p.n_units, p.n_teams, mean_out, scales_out, codes_out)
-#define DQ8_BLK_W(NT, FD)      \
-    if (wpw == 8) {            \
-        DQ8_BLK(NT, FD, 8);    \
-    } else {                   \
-        DQ8_BLK(NT, FD, 6);    \
+#define DQ8_BLK(QL, WPW, RG)                                                                                              \
+    hipLaunchKernelGGL((k_avg_block<QL, 2, true, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), lds, stream, tab, wp, K, local, \
+                       n, p.B, p.nb, p.upb, p.n_units, p.n_teams, mean_out, scales_out, codes_out)
+#define DQ8_BLK_R(QL, WPW)       \
+    if (ragged) {                \
+        DQ8_BLK(QL, WPW, true);  \
+    } else {                     \
+        DQ8_BLK(QL, WPW, false); \
     }
-#define DQ8_BLK_FD(NT)         \
-    if (g_tune.fastdiv) {      \
-        DQ8_BLK_W(NT, true)    \
-    } else {                   \
-        DQ8_BLK_W(NT, false)   \
+    switch (ql) {
+    case 1: DQ8_BLK_R(1, 8) break;
+    case 2: DQ8_BLK_R(2, 8) break;
+    case 4: DQ8_BLK_R(4, 8) break;
+    case 8: DQ8_BLK_R(8, 8) break;
+    default:
+        if (wpw == 8) {
+            DQ8_BLK_R(16, 8)
+        } else {
+            DQ8_BLK_R(16, 6)
+        }
+        break;
     }
-    switch (g_tune.blk_nt) {
-    case 0: DQ8_BLK_FD(0) break;
-    case 2: DQ8_BLK_FD(2) break;
-    default: DQ8_BLK_FD(1) break;
-    }
-#undef DQ8_BLK_FD
-#undef DQ8_BLK_W
+#undef DQ8_BLK_R
 #undef DQ8_BLK
     return after_launch("k_avg_block");
 }
@@ -2062,39 +2118,42 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     // Units no longer than a block, and the smaller the unit the more wavefronts per compute unit (the bytes
     // in flight stay the same); 16 wavefronts share a workgroup's 64 KiB table when there are that many.
     const size_t Bq = (block == 0 || block > n) ? n : block;
-    int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 8 || g_tune.dec_q == 16) ? g_tune.dec_q : 4;
+    int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 4 || g_tune.dec_q == 8) ? g_tune.dec_q : 16;
     int wpc = g_tune.dec_wpc;
-    int wpw = g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4);
     while (q > 1 && (size_t)q * 4 * kWave > Bq) {
         q >>= 1;
         wpc = wpc * 2 > 32 ? 32 : wpc * 2;
     }
-    if (wpc >= 16)
-        wpw = 16;
-    else if (wpc >= 8 && wpw < 8)
-        wpw = 8;
+    const int wpw = q == 16 ? (g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4)) : (q == 8 ? 8 : 16);
     Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
         return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-#define DQ8_DEC(Q, WPW)                                                                                          \
-    hipLaunchKernelGGL((k_decode<Q, 2, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
+    const bool ragged = p.nb > 1 && p.B % ((size_t)q * 4 * kWave) != 0;  // blocks end inside units
+#define DQ8_DEC(Q, WPW, RG)                                                                                          \
+    hipLaunchKernelGGL((k_decode<Q, 2, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
                        p.nb, p.upb, p.n_units, p.n_teams, out)
-#define DQ8_DEC_W(Q)                     \
-    switch (wpw) {                       \
-    case 16: DQ8_DEC(Q, 16); break;      \
-    case 8: DQ8_DEC(Q, 8); break;        \
-    default: DQ8_DEC(Q, 4); break;       \
+#define DQ8_DEC_R(Q, WPW)        \
+    if (ragged) {                \
+        DQ8_DEC(Q, WPW, true);   \
+    } else {                     \
+        DQ8_DEC(Q, WPW, false);  \
     }
     switch (q) {
-    case 1: DQ8_DEC_W(1) break;
-    case 2: DQ8_DEC_W(2) break;
-    case 8: DQ8_DEC_W(8) break;
-    case 16: DQ8_DEC_W(16) break;
-    default: DQ8_DEC_W(4) break;
+    case 1: DQ8_DEC_R(1, 16) break;
+    case 2: DQ8_DEC_R(2, 16) break;
+    case 4: DQ8_DEC_R(4, 16) break;
+    case 8: DQ8_DEC_R(8, 8) break;
+    default:
+        switch (wpw) {
+        case 16: DQ8_DEC_R(16, 16) break;
+        case 8: DQ8_DEC_R(16, 8) break;
+        default: DQ8_DEC_R(16, 4) break;
+        }
+        break;
     }
-#undef DQ8_DEC_W
+#undef DQ8_DEC_R
 #undef DQ8_DEC
     return after_launch("k_decode");
 }
@@ -2329,7 +2388,7 @@ int dq8_internal_tune(const char *key, int value)
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
-        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"blk_nt", &g_tune.blk_nt, 0, 2}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)
         if (!std::strcmp(k.name, key)) {
