@@ -1247,7 +1247,9 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
 // TEAMS teams share a workgroup and its tables; the workgroup barrier that separates the
 // exchange of the maxima from their use is executed by every wavefront the same number of
 // times (`iters`), whether or not its team still has a unit.
-template <int KT, int NT, bool FASTDIV, int TEAMS>
+// RAGGED = true (chosen by the host for blocks shorter than 4096): a unit of fewer whole aligned quads
+// takes the register path as well.
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED>
 struct AvgTeam {
     static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
 
@@ -1289,7 +1291,8 @@ struct AvgTeam {
         if (!sl.active) return;
         sl.un = unit_of<kUnit>(u, n, B, nb, 1);
         // whole aligned quads: a short unit takes the register path too (see load_worker)
-        bool f = sl.un.len >= 4 && (sl.un.len & 3) == 0 && (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
+        bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == kUnit) &&
+                 (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
 #pragma unroll
         for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
         if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
@@ -1303,7 +1306,7 @@ struct AvgTeam {
     __device__ __forceinline__ uint32_t quad_of(const Slot &sl, int j) const
     {
         const uint32_t i = j * kWg + tl;
-        if (WHOLE) return i;
+        if (WHOLE || !RAGGED) return i;
         const uint32_t last = (sl.un.len >> 2) - 1;
         return i < last ? i : last;
     }
@@ -1406,7 +1409,7 @@ struct AvgTeam {
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
                 const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
-                if (STEADY || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
+                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
             }
         } else {
             for (uint32_t i = tl; i < sl.un.len; i += kWg)
@@ -1415,7 +1418,7 @@ struct AvgTeam {
     }
 };
 
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP>
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED>
 __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
                                                             const float *__restrict__ local, size_t n, size_t B, size_t nb,
                                                             size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
@@ -1424,7 +1427,7 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
     constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
-    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS>;
+    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED>;
     Avg e;
     e.p = p;
     e.local = local;
@@ -1563,14 +1566,16 @@ __global__ __launch_bounds__(kWg) void k_error_stats(const uint32_t *__restrict_
 
 // Means over all blocks from the per-block statistics: means[0] = (sum of absolute errors) / n,
 // means[1] = (sum of relative errors) / (number of non-zero inputs), 0 when there is none.
-// One workgroup; thread t adds blocks t, t + 256, ... in that order and the threads' sums are
-// combined by a fixed tree, so the result is the same in every launch.
-__global__ __launch_bounds__(kWg) void k_error_means(const double *__restrict__ stats, size_t nb, size_t n,
-                                                    double *__restrict__ means)
+// One workgroup of 1024 threads; thread t adds blocks t, t + 1024, ... in that order and the threads'
+// sums are combined by a fixed tree, so the result is the same in every launch.
+constexpr uint32_t kMeansThreads = 1024;
+__global__ __launch_bounds__(kMeansThreads) void k_error_means(const double *__restrict__ stats, size_t nb, size_t n,
+                                                              double *__restrict__ means)
 {
-    __shared__ double part[3][kWg];
+    __shared__ double part[3][kMeansThreads];
     double a = 0.0, r = 0.0, c = 0.0;
-    for (size_t b = threadIdx.x; b < nb; b += kWg) {
+#pragma unroll 4
+    for (size_t b = threadIdx.x; b < nb; b += kMeansThreads) {
         a += stats[4 * b];
         r += stats[4 * b + 1];
         c += stats[4 * b + 2];
@@ -1579,7 +1584,7 @@ __global__ __launch_bounds__(kWg) void k_error_means(const double *__restrict__ 
     part[1][threadIdx.x] = r;
     part[2][threadIdx.x] = c;
     __syncthreads();
-    for (uint32_t w = kWg / 2; w >= 1; w >>= 1) {
+    for (uint32_t w = kMeansThreads / 2; w >= 1; w >>= 1) {
         if (threadIdx.x < w) {
             part[0][threadIdx.x] += part[0][threadIdx.x + w];
             part[1][threadIdx.x] += part[1][threadIdx.x + w];
@@ -1871,7 +1876,7 @@ int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n
                        per_wave, scales, stats);
     rc = after_launch("k_error_stats");
     if (rc || !means) return rc;
-    hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kWg), 0, stream, stats, p.nb, n, means);
+    hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kMeansThreads), 0, stream, stats, p.nb, n, means);
     return after_launch("k_error_means");
 }
 
@@ -1898,7 +1903,9 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
 int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                     size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
-    const int teams = (g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2;
+    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
+    const int teams = ragged ? 3 : ((g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2);
     const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
     Plan p = make_plan(n, block, st.cus, 4 * teams * wgs_per_cu, 4, 4 * teams, kUnit);
     const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
@@ -1912,29 +1919,31 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     }
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
-#define DQ8_TEAM(KT, NT, RM, T)                                                                                      \
-    hipLaunchKernelGGL((k_avg_team<KT, NT, true, T, RM>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
+#define DQ8_TEAM(KT, RM, T, RG)                                                                                          \
+    hipLaunchKernelGGL((k_avg_team<KT, 1, true, T, RM, RG>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
                        p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
-#define DQ8_TEAM_T(KT, NT, RM)   \
-    if (teams == 3) {            \
-        DQ8_TEAM(KT, NT, RM, 3); \
-    } else if (teams == 4) {     \
-        DQ8_TEAM(KT, NT, RM, 4); \
-    } else {                     \
-        DQ8_TEAM(KT, NT, RM, 2); \
+#define DQ8_TEAM_T(KT, RM)              \
+    if (ragged) {                       \
+        DQ8_TEAM(KT, RM, 3, true);      \
+    } else if (teams == 3) {            \
+        DQ8_TEAM(KT, RM, 3, false);     \
+    } else if (teams == 4) {            \
+        DQ8_TEAM(KT, RM, 4, false);     \
+    } else {                            \
+        DQ8_TEAM(KT, RM, 2, false);     \
     }
-#define DQ8_TEAM_FD(KT, NT)      \
+#define DQ8_TEAM_RM(KT)          \
     if (st.has_remap[kind]) {    \
-        DQ8_TEAM_T(KT, NT, true) \
+        DQ8_TEAM_T(KT, true)     \
     } else {                     \
-        DQ8_TEAM_T(KT, NT, false)\
+        DQ8_TEAM_T(KT, false)    \
     }
     switch (K) {
-    case 2: DQ8_TEAM_FD(2, 1) break;
-    case 4: DQ8_TEAM_FD(4, 1) break;
-    default: DQ8_TEAM_FD(8, 1) break;
+    case 2: DQ8_TEAM_RM(2) break;
+    case 4: DQ8_TEAM_RM(4) break;
+    default: DQ8_TEAM_RM(8) break;
     }
-#undef DQ8_TEAM_FD
+#undef DQ8_TEAM_RM
 #undef DQ8_TEAM_T
 #undef DQ8_TEAM
     return after_launch("k_avg_team");
