@@ -7,15 +7,23 @@
 // a team of four) owns a unit at a time and walks units with a grid-wide stride, so at any
 // moment the whole chip streams through one narrow window of each array; the host sizes the
 // grid so that every wavefront gets the same number of units and all of them are resident.
-// U is 4096 where a whole block has to be held (fused encoder) and Q * 256 elsewhere, Q being
-// the number of 128-bit accesses a lane keeps in flight.
+// U is Q * 256 (times four for a team), Q being the number of 128-bit accesses a lane keeps in
+// flight; the host picks it per call: no longer than a block where units may be pieces of a block,
+// the smallest power of two that holds a block (at most 4096) where a whole block has to be held.
 //
 // Inside a unit lane L owns elements 4*(64*it + L) .. +3: fp32 data moves as one 128-bit
 // access per lane (1 KiB contiguous per wave instruction) and the matching four codes as one
-// 32-bit access (256 B contiguous per instruction).  Units that are short, or whose addresses
-// are not aligned for that, take a plain strided element loop with identical arithmetic.
+// 32-bit access (256 B contiguous per instruction).  A unit of fewer whole aligned quads stays on
+// that path (lanes past its end load its last quad and store nothing); units whose addresses are
+// not aligned for it take quad or element loops with identical arithmetic.
 // Every loop is software-pipelined: the loads of a wavefront's next unit are issued before
 // the current one is processed.
+//
+// Files: dq8_device.hpp (access policies, reductions, unit geometry, code search, decode table),
+// dq8_kernels_codec.hpp (absmax, encode, decode), dq8_kernels_avg.hpp (decode-and-average),
+// dq8_kernels_avg_encode.hpp (average in registers, store and / or compress), dq8_kernels_stats.hpp
+// (error statistics), dq8_tables.cpp (host-side table construction); this file holds the launch
+// logic and the C ABI.
 //
 // Built with -ffp-contract=off: the decode-and-average sum must round the product and the sum
 // separately.  Divisions are the compiler's correctly rounded ones.
@@ -30,1573 +38,13 @@
 #include "dq8_internal.h"
 #include "dq8_tables.hpp"
 
+#include "dq8_device.hpp"
+#include "dq8_kernels_avg.hpp"
+#include "dq8_kernels_avg_encode.hpp"
+#include "dq8_kernels_codec.hpp"
+#include "dq8_kernels_stats.hpp"
+
 namespace {
-
-using dq8::kBucketOff;
-using dq8::kHasRemapOff;
-using dq8::kRemapOff;
-using dq8::kRemapWords;
-using dq8::kCbOff;
-using dq8::kLoKeyOff;
-using dq8::kNBucketOff;
-using dq8::kNearWindow;
-using dq8::kTableWords;
-
-constexpr int kWave = 64;
-constexpr int kWavesPerWg = 4;
-constexpr int kWg = kWave * kWavesPerWg;
-constexpr int kUnit = 4096;                      // elements per unit
-constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
-constexpr int kKinds = 4;
-constexpr int kLutCopies = 64;                   // one copy of the decode table per lane
-constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-// Tables of the three data types, one image per device (each GPU holds its own copy).
-__device__ __align__(256) uint32_t g_tables[kKinds][kTableWords];
-
-struct WorkerPtrs {
-    const uint8_t *codes[DQ8_MAX_K];
-    const float *scales[DQ8_MAX_K];
-};
-
-// ---------------------------------------------------------------- device helpers
-
-// Streaming accesses: every byte is touched once, so loads and stores carry cache-policy
-// bits that keep them from displacing each other in the caches.  NT is the policy:
-//   0  plain loads and stores;
-//   1  non-temporal loads and stores (the nt bit);
-//   2  non-temporal loads; 128-bit stores with nt plus system scope (sc0 sc1), i.e. streamed
-//      through every cache level; 32-bit stores as in policy 1.
-// The scope bits only strengthen coherence, so every policy gives the same memory contents.
-//
-// The compiler has no way to ask for "sc0 sc1 nt" on an ordinary store (a volatile store gets
-// sc0 sc1 but is also made to wait for completion), so policy 2 writes the instruction out.
-// A 128-bit store keeps reading its data registers for two cycles after issue; the compiler
-// cannot see that this statement is such a store, so the two wait states it would otherwise
-// insert before the next vector write to those registers are part of the statement.
-template <int NT, typename T>
-__device__ __forceinline__ T ldg(const T *p)
-{
-    if constexpr (NT != 0)
-        return __builtin_nontemporal_load(p);
-    else
-        return *p;
-}
-
-template <int NT, typename T>
-__device__ __forceinline__ void stg(T *p, T v)
-{
-    if constexpr (NT == 0)
-        *p = v;
-    else if constexpr (NT == 2 && sizeof(T) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
-    else
-        __builtin_nontemporal_store(v, p);
-}
-
-// Maximum over the 64 lanes, returned in a scalar register.  Six data-parallel-primitive steps
-// on the vector unit (no LDS traffic): exchange inside quads, mirror inside half rows and rows
-// of 16 lanes, then carry lane 15 of a row into the next row and lane 31 into the upper half;
-// lane 63 ends up with the maximum of all lanes.  A step leaves lanes it does not write at
-// their own value, which is the identity of max.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t max_dpp(uint32_t v)
-{
-    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
-    return o > v ? o : v;
-}
-
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
-{
-    v = max_dpp<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
-    v = max_dpp<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
-    v = max_dpp<0x141, 0xF>(v);  // row_half_mirror
-    v = max_dpp<0x140, 0xF>(v);  // row_mirror
-    v = max_dpp<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
-    v = max_dpp<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-}
-
-__host__ __device__ __forceinline__ uint32_t f2u(float f)
-{
-    uint32_t u;
-    __builtin_memcpy(&u, &f, 4);
-    return u;
-}
-
-__host__ __device__ __forceinline__ float u2f(uint32_t u)
-{
-    float f;
-    __builtin_memcpy(&f, &u, 4);
-    return f;
-}
-
-__device__ __forceinline__ uint32_t abs_bits(float f) { return f2u(f) & 0x7FFFFFFFu; }
-
-// Running maximum of |v|.  Exact for finite inputs, subnormals included.
-__device__ __forceinline__ float max4_abs(v4f v, float m)
-{
-    float a = __builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y));
-    float b = __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w));
-    return __builtin_fmaxf(m, __builtin_fmaxf(a, b));
-}
-
-// Geometry of unit u.  All values are wave-uniform.
-struct Unit {
-    size_t block;   // scale index
-    size_t start;   // first element
-    uint32_t len;   // 1..kUnit
-};
-
-// min(v, U) of a 64-bit count as 32 bits, U a power of two.  Written with a shift and a compare
-// against zero so that it stays on the scalar unit: a 64-bit ordered compare of uniform values
-// is done on the vector unit, and the compiler has been seen to drop the copy of such a result
-// into the scalar condition bit when a branch on the same result follows, leaving a select
-// that reads a stale condition (wrong unit lengths, accesses past the end of the arrays).
-template <int U>
-__device__ __forceinline__ uint32_t cap_to_unit(size_t v)
-{
-    static_assert(U > 0 && (U & (U - 1)) == 0, "unit sizes are powers of two");
-    return (v >> __builtin_ctz(U)) != 0 ? (uint32_t)U : (uint32_t)v;
-}
-
-template <int U>
-__device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb, size_t upb)
-{
-    Unit r;
-    size_t c;
-    if (upb == 1) {
-        r.block = u;
-        c = 0;
-    } else if (nb == 1) {
-        r.block = 0;
-        c = u;
-    } else {
-        r.block = u / upb;
-        c = u - r.block * upb;
-    }
-    const size_t off = c * (size_t)U;
-    r.start = r.block * B + off;
-    const uint32_t in_block = cap_to_unit<U>(B - off), in_array = cap_to_unit<U>(n - r.start);
-    r.len = in_block < in_array ? in_block : in_array;
-    return r;
-}
-
-// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and
-// for a data type with repeated values the table that turns a rank into its code.
-struct Search {
-    const uint32_t *bucket;  // LDS on the device
-    const uint32_t *remap;   // NULL when every rank is its own code
-    uint32_t lo_key;         // key of the first bucket
-    float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
-};
-
-__host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket,
-                                                       const uint32_t *remap = nullptr)
-{
-    Search s;
-    s.bucket = bucket;
-    s.remap = remap;
-    s.lo_key = lo_key;
-    s.lo_f = u2f((lo_key << 16) + 0x8000u);
-    s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
-    return s;
-}
-
-// sum >> 16 = rank of the nearest table value (the number of thresholds <= |xn|), which is its
-// magnitude field except for a type with a rank-to-code table (see finish_sum); the low half of
-// sum measures the distance to the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
-// so the clamp is done on the value.
-__host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    const float c = __builtin_amdgcn_fmed3f(__builtin_fabsf(xn), s.lo_f, s.hi_f);
-#else
-    float c = __builtin_fabsf(xn);
-    c = c >= s.lo_f ? c : s.lo_f;  // also takes NaN to the low end; inputs are finite anyway
-    c = c <= s.hi_f ? c : s.hi_f;
-#endif
-    const uint32_t a = f2u(c);  // the low 16 bits of lo_base are zero: subtracting it only moves the key
-    return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
-}
-
-// Rank to magnitude field in bits 16..22, for the types where the two differ.  Kept out of
-// search_sum so that an encoder takes this (wavefront-uniform) branch once per group of sums.
-__host__ __device__ __forceinline__ uint32_t finish_sum(const Search &s, uint32_t sum) { return s.remap[sum >> 16] << 16; }
-
-// (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
-__host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (sum + kNearWindow) & 0xFFFFu; }
-
-// Code = magnitude index, bit 7 = sign bit of the input (the divisor is positive).
-__host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
-
-__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, uint32_t sum, float x)
-{
-    if (s.remap) sum = finish_sum(s, sum);
-    return code_from(sum, x);
-}
-
-__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_of(s, search_sum(s, x / d), x); }
-
-// Four codes in one word: byte i = magnitude index of sum i (its byte 2) with the sign bit of
-// x i (top bit of its byte 3).  v_perm_b32 gathers the bytes: selector byte 0..3 picks a byte
-// of the second operand, 4..7 of the first, 0x0C gives zero.
-__device__ __forceinline__ uint32_t pack_codes(const Search &sr, uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
-{
-    if (sr.remap) {
-        s0 = finish_sum(sr, s0);
-        s1 = finish_sum(sr, s1);
-        s2 = finish_sum(sr, s2);
-        s3 = finish_sum(sr, s3);
-    }
-    const uint32_t m01 = __builtin_amdgcn_perm(s1, s0, 0x0C0C0602u);
-    const uint32_t m23 = __builtin_amdgcn_perm(s3, s2, 0x06020C0Cu);
-    const uint32_t g01 = __builtin_amdgcn_perm(f2u(v.y), f2u(v.x), 0x0C0C0703u);
-    const uint32_t g23 = __builtin_amdgcn_perm(f2u(v.w), f2u(v.z), 0x07030C0Cu);
-    return ((g01 | g23) & 0x80808080u) | m01 | m23;
-}
-
-// A scale qualifies for the reciprocal path when 1/d and every product x * (1/d) that can
-// reach a threshold are normal numbers: 2^-100 <= d <= 2^100.
-__host__ __device__ __forceinline__ bool reciprocal_ok(float d)
-{
-    uint32_t b = f2u(d);
-    return b >= 0x0D800000u && b <= 0x71800000u;
-}
-
-// Four codes packed into one word.  With `recip` the quotients are first taken as x * r with
-// r = fl(1/d): that differs from the correctly rounded x / d by at most 3 binary32 steps, so
-// the code is already right unless the product lies within kNearWindow steps of a threshold;
-// if any lane of the wavefront sees such a value the quad is redone with true divisions.
-template <bool FASTDIV>
-__device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d, float r, bool recip)
-{
-    if (FASTDIV && recip) {
-        const uint32_t s0 = search_sum(sr, v.x * r), s1 = search_sum(sr, v.y * r);
-        const uint32_t s2 = search_sum(sr, v.z * r), s3 = search_sum(sr, v.w * r);
-        uint32_t k0 = near_key(s0), k1 = near_key(s1), k2 = near_key(s2), k3 = near_key(s3);
-        k0 = k0 < k1 ? k0 : k1;
-        k2 = k2 < k3 ? k2 : k3;
-        k0 = k0 < k2 ? k0 : k2;
-        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(sr, s0, s1, s2, s3, v);
-    }
-    return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
-}
-
-template <bool FASTDIV>
-__device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float d, float r, bool recip)
-{
-    if (FASTDIV && recip) {
-        uint32_t s0 = search_sum(sr, x * r);
-        if (near_key(s0) > 2 * kNearWindow) return code_of(sr, s0, x);
-    }
-    return code_exact(sr, x, d);
-}
-
-// Copies the bucket table (and the rank-to-code table of a type that has one, right behind it)
-// to LDS with all `n_threads` threads of the workgroup; the caller synchronises the workgroup
-// before using it.
-__device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds, uint32_t n_threads = kWg)
-{
-    const uint32_t nbk = tab[kNBucketOff];
-    for (uint32_t i = threadIdx.x; i < nbk; i += n_threads) lds[i] = tab[kBucketOff + i];
-    const uint32_t *remap = nullptr;
-    if (tab[kHasRemapOff]) {
-        for (uint32_t i = threadIdx.x; i < (uint32_t)kRemapWords; i += n_threads) lds[nbk + i] = tab[kRemapOff + i];
-        remap = lds + nbk;
-    }
-    return make_search(lds, tab[kLoKeyOff], nbk, remap);
-}
-
-// Decode table in LDS, one copy per lane: entry (code, lane) at byte address code * 256 +
-// lane * 4.  Lanes L and L + 32 share a bank but are served in different halves of the access,
-// so a lookup never conflicts, and the address is two byte fields - code in byte 1, lane * 4 in
-// byte 0 - which one v_perm_b32 assembles straight from a packed word of four codes.
-// Thread t < 256 owns code t (workgroups have at least 256 threads).  The caller synchronises before the
-// first lookup.
-__device__ __forceinline__ void load_lut(const uint32_t *tab, float *lds)
-{
-    if (threadIdx.x < 256) {
-        const float val = u2f(tab[kCbOff + threadIdx.x]);
-        const v4f four = {val, val, val, val};
-        v4f *row = reinterpret_cast<v4f *>(lds + threadIdx.x * kLutCopies);
-#pragma unroll
-        for (int c = 0; c < kLutCopies / 4; ++c) row[c] = four;
-    }
-}
-
-// Table value of code number J (0..3) of the packed word w, for the lane whose byte offset
-// into a table row is lane4 = lane * 4.
-template <int J>
-__device__ __forceinline__ float lut_at(const float *lut, uint32_t w, uint32_t lane4)
-{
-    const uint32_t addr = __builtin_amdgcn_perm(w, lane4, 0x0C0C0400u + (J << 8));
-    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + addr);
-}
-
-__device__ __forceinline__ float lut_code(const float *lut, uint32_t code, uint32_t lane4)
-{
-    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + ((code << 8) | lane4));
-}
-
-// Element idx of an array whose base pointer is wave-uniform, addressed as "scalar base +
-// 32-bit vector offset": the base is pinned to scalar registers, so that the compiler neither
-// keeps a 64-bit address per lane nor hoists one out of the loop for every array it walks.
-// The pointer goes through an integer on the way, which would make it a generic pointer; the
-// cast names the global address space again (address space 1), so the access stays a global one.
-#define DQ8_GLOBAL __attribute__((address_space(1)))
-
-template <typename T>
-__device__ __forceinline__ DQ8_GLOBAL T *uniform_global(T *p)
-{
-    const uintptr_t v = (uintptr_t)p;
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
-    return (DQ8_GLOBAL T *)(((uintptr_t)hi << 32) | lo);
-}
-
-template <int NT, typename T>
-__device__ __forceinline__ T ldg_at(const T *uniform_base, uint32_t idx)
-{
-    const DQ8_GLOBAL T *g = uniform_global(uniform_base);
-    if constexpr (NT != 0)
-        return __builtin_nontemporal_load(g + idx);
-    else
-        return g[idx];
-}
-
-// Store with the plain or non-temporal policy (the write-through policy of stg keeps its own form).
-template <int NT, typename T>
-__device__ __forceinline__ void stg_at(T *uniform_base, uint32_t idx, T v)
-{
-    DQ8_GLOBAL T *g = uniform_global(uniform_base);
-    if constexpr (NT != 0)
-        __builtin_nontemporal_store(v, g + idx);
-    else
-        g[idx] = v;
-}
-
-__device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
-
-// Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
-__device__ __forceinline__ size_t first_unit(int waves_per_wg = kWavesPerWg) { return (size_t)blockIdx.x * waves_per_wg + wave_in_wg(); }
-
-// Maximum of |x[0..len)| over the elements this lane takes, for a unit that is short or not
-// 16-byte aligned: whole quads with 128-bit loads when the start is aligned (the STRIDE lanes that
-// share the unit take quads lane, lane + STRIDE, ...; a tail of fewer than four elements goes one by
-// one), else element by element.
-template <int NT, uint32_t STRIDE = kWave>
-__device__ __forceinline__ uint32_t slow_absmax(const float *px, uint32_t len, uint32_t lane)
-{
-    uint32_t m = 0;
-    uint32_t done = 0;
-    if (((uintptr_t)px & 15) == 0) {
-        const v4f *p4 = reinterpret_cast<const v4f *>(px);
-        const uint32_t nq = len >> 2;
-        float fm = 0.0f;
-#pragma unroll 4
-        for (uint32_t q = lane; q < nq; q += STRIDE) fm = max4_abs(ldg<NT>(p4 + q), fm);
-        m = f2u(fm);
-        done = nq << 2;
-    }
-    for (uint32_t i = done + lane; i < len; i += STRIDE) {
-        const uint32_t a = abs_bits(px[i]);
-        m = m > a ? m : a;
-    }
-    return m;
-}
-
-// ---------------------------------------------------------------- kernels
-
-__global__ void k_fill_zero(float *p, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.0f;
-}
-
-// Plain fp32 copy with the access pattern of the codec kernels (units of Q * 256 elements,
-// 128-bit accesses).  Exists to calibrate bandwidth and hardware-counter readings against a
-// kernel whose traffic is known exactly: 4 bytes read and 4 bytes written per element.
-template <int Q, int NT>
-__global__ __launch_bounds__(kWg) void k_copy(const float *__restrict__ src, float *__restrict__ dst, size_t n,
-                                             size_t n_units, size_t n_waves)
-{
-    constexpr int U = Q * 4 * kWave;
-    const uint32_t lane = threadIdx.x & 63;
-    for (size_t u = first_unit(); u < n_units; u += n_waves) {
-        Unit un = unit_of<U>(u, n, n, 1, 0);
-        const float *ps = src + un.start;
-        float *pd = dst + un.start;
-        if (un.len == U && (((uintptr_t)ps | (uintptr_t)pd) & 15) == 0) {
-            const v4f *s4 = reinterpret_cast<const v4f *>(ps);
-            v4f *d4 = reinterpret_cast<v4f *>(pd);
-            v4f v[Q];
-#pragma unroll
-            for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(s4 + j * kWave + lane);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) stg<NT>(d4 + j * kWave + lane, v[j]);
-        } else {
-            for (uint32_t i = lane; i < un.len; i += kWave) pd[i] = ps[i];
-        }
-    }
-}
-
-// Block maxima.  One wavefront per unit of Q * 256 elements.  upb == 1: each unit is a whole
-// block and stores its maximum.  upb > 1: scales[] was zeroed and the pieces of a block merge
-// with an integer atomic max (non-negative binary32 numbers order like their bit patterns).
-// per_wave == 0: wavefront w takes units w, w + n_waves, ...  per_wave > 0 (used when blocks span
-// several units): it takes the per_wave consecutive units from w * per_wave on, keeps one
-// running maximum per lane while the block stays the same and issues one atomic per block it
-// touches -- thousands of atomics on one address cost more than reading the array.
-template <int Q, int NT>
-__global__ __launch_bounds__(kWg) void k_absmax(const float *__restrict__ x, size_t n, size_t B, size_t nb, size_t upb,
-                                               size_t n_units, size_t n_waves, size_t per_wave, float *__restrict__ scales)
-{
-    constexpr int U = Q * 4 * kWave;
-    const uint32_t lane = threadIdx.x & 63;
-    const size_t w = first_unit();
-    size_t u = per_wave ? w * per_wave : w;
-    const size_t stride = per_wave ? 1 : n_waves;
-    const size_t end = per_wave ? (u + per_wave < n_units ? u + per_wave : n_units) : n_units;
-    Unit un;
-    bool fast = false;
-    v4f v[Q];
-    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
-        q = unit_of<U>(uu, n, B, nb, upb);
-        f = q.len == U && ((uintptr_t)(x + q.start) & 15) == 0;
-        if (f) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) v[j] = ldg<NT>(p4 + j * kWave + lane);
-        }
-    };
-    if (u < end) open_unit(u, un, fast);
-    uint32_t run = 0;  // this lane's maximum over the units of the current block so far
-    while (u < end) {
-        uint32_t m;
-        if (fast) {
-            float fm = 0.0f;
-#pragma unroll
-            for (int j = 0; j < Q; ++j) fm = max4_abs(v[j], fm);
-            m = f2u(fm);
-        } else {
-            m = slow_absmax<NT>(x + un.start, un.len, lane);
-        }
-        const size_t blk = un.block;
-        u += stride;
-        const bool more = u < end;
-        if (more) open_unit(u, un, fast);  // next unit's loads fly during the reduction
-        run = run > m ? run : m;
-        if (!more || un.block != blk) {
-            const uint32_t r = wave_max_u32(run);
-            run = 0;
-            if (lane == 0) {
-                if (upb == 1)
-                    scales[blk] = u2f(r);
-                else
-                    atomicMax(reinterpret_cast<unsigned int *>(scales) + blk, r);
-            }
-        }
-    }
-}
-
-// Compression.  A team of WPB wavefronts owns a unit of WPB * QL * 256 elements, QL quads per lane:
-// WPB == 1, each wavefront of the workgroup walks its own units; WPB == 4, the workgroup's four
-// wavefronts share a unit and combine their maxima through LDS.
-// FUSED: a unit is a whole block (upb == 1); the team reduces the block's maximum from
-// registers, stores it and quantises the same registers.  Otherwise the scale of the unit's
-// block is read from scales[].
-// The loop is software-pipelined: the loads of a team's next unit are issued before the
-// current unit is reduced and quantised, so each wavefront always has loads in flight.
-// A unit shorter than that (a block that is not a power of two, the end of a block or of the
-// array) takes the same path when it consists of whole aligned quads: a lane whose quad lies
-// past the end loads the unit's last quad instead (an unconditional load of valid memory: the
-// maximum does not change and the lane stores nothing).
-template <int WPB, int QL, int NT, bool FUSED, bool FASTDIV>
-struct Encoder {
-    static constexpr int Q = QL;
-    static constexpr uint32_t TEAM = kWave * WPB;
-    static constexpr int U = QL * 4 * (int)TEAM;
-
-    const float *x;
-    uint8_t *codes;
-    float *scales;
-    size_t n, B, nb, upb;
-    uint32_t *slots;
-    Search sr;
-    uint32_t lane, wave, tl, phase;
-
-    struct Slot {
-        Unit un;
-        bool fast;
-        v4f v[Q];
-    };
-
-    __device__ __forceinline__ void fetch(size_t u, Slot &sl) const
-    {
-        sl.un = unit_of<U>(u, n, B, nb, upb);
-        const float *px = x + sl.un.start;
-        sl.fast = sl.un.len >= 4 && (sl.un.len & 3) == 0 && ((uintptr_t)px & 15) == 0 &&
-                  ((uintptr_t)(codes + sl.un.start) & 3) == 0;
-        if (sl.fast) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(px);
-            const uint32_t last = (sl.un.len >> 2) - 1;
-#pragma unroll
-            for (int it = 0; it < Q; ++it) {
-                const uint32_t q = it * TEAM + tl;
-                sl.v[it] = ldg<NT>(p4 + (q < last ? q : last));
-            }
-        }
-    }
-
-    __device__ __forceinline__ void process(Slot &sl)
-    {
-        const Unit &un = sl.un;
-        const float *px = x + un.start;
-        uint8_t *pc = codes + un.start;
-        float s;
-        if (FUSED) {
-            uint32_t m;
-            if (sl.fast) {
-                float fm = 0.0f;
-#pragma unroll
-                for (int it = 0; it < Q; ++it) fm = max4_abs(sl.v[it], fm);
-                m = f2u(fm);
-            } else {
-                m = slow_absmax<NT, TEAM>(px, un.len, tl);
-            }
-            m = wave_max_u32(m);
-            if (WPB > 1) {
-                if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
-                __syncthreads();  // every wavefront of the workgroup walks the same units
-                const uint32_t *sp = slots + phase * kWavesPerWg;
-                uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
-                m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
-                phase ^= 1;  // the other half of slots next time: one barrier per unit is enough
-            }
-            s = u2f(m);
-            if (tl == 0) scales[un.block] = s;
-        } else {
-            s = scales[un.block];
-        }
-        const float d = s == 0.0f ? 1.0f : s;  // a zero scale leaves the value as it is
-        const float r = 1.0f / d;
-        const bool recip = reciprocal_ok(d);
-        if (sl.fast) {
-            uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
-            const uint32_t nq = un.len >> 2;
-#pragma unroll
-            for (int it = 0; it < Q; ++it) {
-                const uint32_t cw = encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip);
-                if (it * TEAM + tl < nq) stg<NT>(c4 + it * TEAM + tl, cw);
-            }
-        } else {
-            // a misaligned unit or one that does not consist of whole quads: whole quads where the addresses allow (the lanes of the team take quads
-            // tl, tl + TEAM, ...), the rest element by element
-            uint32_t done = 0;
-            if ((((uintptr_t)px & 15) | ((uintptr_t)pc & 3)) == 0) {
-                const v4f *p4 = reinterpret_cast<const v4f *>(px);
-                uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
-                const uint32_t nq = un.len >> 2;
-                for (uint32_t q = tl; q < nq; q += TEAM) stg<NT>(c4 + q, encode_quad<FASTDIV>(sr, ldg<NT>(p4 + q), d, r, recip));
-                done = nq << 2;
-            }
-            for (uint32_t i = done + tl; i < un.len; i += TEAM) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
-        }
-    }
-};
-
-template <int WPB, int QL, int NT, bool FUSED, bool FASTDIV>
-__global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
-                                               size_t B, size_t nb, size_t upb, size_t n_units, size_t n_teams,
-                                               float *__restrict__ scales, uint8_t *__restrict__ codes)
-{
-    static_assert(WPB == 1 || WPB == kWavesPerWg, "a team is one wavefront or the whole workgroup");
-    using Enc = Encoder<WPB, QL, NT, FUSED, FASTDIV>;
-    extern __shared__ uint32_t lds[];
-    Enc e;
-    e.x = x;
-    e.codes = codes;
-    e.scales = scales;
-    e.n = n;
-    e.B = B;
-    e.nb = nb;
-    e.upb = upb;
-    e.slots = lds;  // kTeamSlots words, then the bucket table
-    e.lane = threadIdx.x & 63;
-    e.wave = wave_in_wg();
-    e.tl = WPB == 1 ? e.lane : threadIdx.x;
-    e.phase = 0;
-    size_t u = WPB == 1 ? first_unit() : (size_t)blockIdx.x;
-    typename Enc::Slot a, b;
-    if (u < n_units) e.fetch(u, a);  // the first loads are in flight while the table is copied
-    e.sr = load_bucket_table(tab, lds + kTeamSlots);
-    __syncthreads();
-    while (u < n_units) {
-        size_t nx = u + n_teams;
-        if (nx < n_units) e.fetch(nx, b);
-        e.process(a);
-        u = nx;
-        if (!(u < n_units)) break;
-        nx = u + n_teams;
-        if (nx < n_units) e.fetch(nx, a);
-        e.process(b);
-        u = nx;
-    }
-}
-
-// Compression of whole, aligned blocks of 4096 elements: the common case of k_encode<4, NT, true,
-// FASTDIV> (a team of four wavefronts per block, maximum and quantisation from registers) with
-// nothing else in the loop.  Block b starts at element 4096 b, x is 16-byte and codes 4-byte
-// aligned, so unit geometry is a multiplication and there is no slow path to branch around.
-// A ragged last block of tail_len elements is done by the last workgroup after its loop.
-// REMAP = false promises a type without a rank-to-code table: the test for one drops out of the loop.
-template <int NT, bool FASTDIV, bool REMAP>
-__global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict__ tab, const float *__restrict__ x,
-                                                    uint32_t n_full, uint32_t n_teams, uint32_t tail_len,
-                                                    float *__restrict__ scales, uint8_t *__restrict__ codes)
-{
-    constexpr int Q = kUnitQuads / kWavesPerWg;
-    extern __shared__ uint32_t lds[];
-    uint32_t *slots = lds;  // kTeamSlots words, then the bucket table
-    const uint32_t lane = threadIdx.x & 63, wave = wave_in_wg(), tl = threadIdx.x;
-    uint32_t phase = 0;
-    Search sr;
-    auto fetch = [&](uint32_t u, v4f(&v)[Q]) {
-        const v4f *p4 = reinterpret_cast<const v4f *>(x) + (size_t)u * (kUnit / 4);
-#pragma unroll
-        for (int it = 0; it < Q; ++it) v[it] = ldg_at<NT>(p4, it * kWg + tl);
-    };
-    // Maximum over the team of the wave maxima m, through LDS; one barrier per call.
-    auto team_max = [&](uint32_t m) {
-        if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
-        __syncthreads();
-        const uint32_t *sp = slots + phase * kWavesPerWg;
-        const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
-        phase ^= 1;  // the other half of slots next time
-        return (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
-    };
-    auto process = [&](uint32_t u, v4f(&v)[Q]) {
-        float fm = 0.0f;
-#pragma unroll
-        for (int it = 0; it < Q; ++it) fm = max4_abs(v[it], fm);
-        const float s = u2f(team_max(wave_max_u32(f2u(fm))));
-        if (tl == 0) scales[u] = s;
-        const float d = s == 0.0f ? 1.0f : s;
-        const float r = 1.0f / d;
-        const bool recip = reciprocal_ok(d);
-        uint32_t *c4 = reinterpret_cast<uint32_t *>(codes) + (size_t)u * (kUnit / 4);
-#pragma unroll
-        for (int it = 0; it < Q; ++it) stg_at<NT>(c4, it * kWg + tl, encode_quad<FASTDIV>(sr, v[it], d, r, recip));
-    };
-    uint32_t u = blockIdx.x;
-    v4f a[Q], b[Q];
-    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is copied
-    sr = load_bucket_table(tab, lds + kTeamSlots);
-    if (!REMAP) sr.remap = nullptr;
-    __syncthreads();
-    // Steady state: the fetch of the next block is unconditional and comes before the work on the
-    // current one, so at the point where the current block's registers are first read the compiler
-    // knows exactly how many younger loads are outstanding and waits for the older ones only.  (A
-    // fetch under "if there is a next block" merges with the path that has none, and the merged
-    // state makes it wait for the loads it has just issued.)  The last block of a team is done
-    // outside the steady state.
-    if (u < n_full) {
-        for (;;) {
-            uint32_t nx = u + n_teams;
-            if (!(nx < n_full)) {
-                process(u, a);
-                break;
-            }
-            fetch(nx, b);
-            process(u, a);
-            u = nx;
-            nx = u + n_teams;
-            if (!(nx < n_full)) {
-                process(u, b);
-                break;
-            }
-            fetch(nx, a);
-            process(u, b);
-            u = nx;
-        }
-    }
-    if (tail_len != 0 && blockIdx.x == gridDim.x - 1) {
-        const float *px = x + (size_t)n_full * kUnit;
-        uint8_t *pc = codes + (size_t)n_full * kUnit;
-        uint32_t m = 0;
-        for (uint32_t i = tl; i < tail_len; i += kWg) {
-            const uint32_t v = abs_bits(px[i]);
-            m = m > v ? m : v;
-        }
-        const float s = u2f(team_max(wave_max_u32(m)));
-        if (tl == 0) scales[n_full] = s;
-        const float d = s == 0.0f ? 1.0f : s;
-        const float r = 1.0f / d;
-        const bool recip = reciprocal_ok(d);
-        for (uint32_t i = tl; i < tail_len; i += kWg) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
-    }
-}
-
-// Decompression of one buffer: out = table[code] * scale.  One wavefront per unit of Q * 256
-// elements: Q code words (4 codes each) per lane; the next unit's words are loaded before the
-// current ones are expanded.
-// RAGGED = true (chosen by the host when blocks are not whole units): a unit of fewer whole aligned
-// quads stays on this path; a lane whose quad lies past the end loads the unit's last code word
-// instead (unconditional, valid memory) and stores nothing.
-template <int Q, int NT, int WPW, bool RAGGED>
-__global__ __launch_bounds__(kWave * WPW) void k_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
-                                                       const float *__restrict__ scales, size_t n, size_t B, size_t nb,
-                                                       size_t upb, size_t n_units, size_t n_waves, float *__restrict__ out)
-{
-    __shared__ __align__(256) float lut[256 * kLutCopies];
-    constexpr int U = Q * 4 * kWave;
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t lane4 = lane * 4;
-    size_t u = first_unit(WPW);
-    Unit un;
-    bool fast = false;
-    uint32_t w[Q];
-    auto open_unit = [&](size_t uu, Unit &q, bool &f) {
-        q = unit_of<U>(uu, n, B, nb, upb);
-        f = ((uintptr_t)(out + q.start) & 15) == 0 && ((uintptr_t)(codes + q.start) & 3) == 0;
-        f = f && (RAGGED ? (q.len >= 4 && (q.len & 3) == 0) : q.len == U);
-        if (f) {
-            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes + q.start);
-            const uint32_t last = (q.len >> 2) - 1;
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                const uint32_t i = j * kWave + lane;
-                w[j] = ldg<NT>(c4 + (RAGGED ? (i < last ? i : last) : i));
-            }
-        }
-    };
-    if (u < n_units) open_unit(u, un, fast);  // the first loads are in flight while the table is built
-    load_lut(tab, lut);
-    __syncthreads();
-    while (u < n_units) {
-        const float s = scales[un.block];
-        float *po = out + un.start;
-        if (fast) {
-            uint32_t cur[Q];
-#pragma unroll
-            for (int j = 0; j < Q; ++j) cur[j] = w[j];
-            const uint32_t nq = un.len >> 2;
-            u += n_waves;
-            if (u < n_units) open_unit(u, un, fast);
-            v4f *o4 = reinterpret_cast<v4f *>(po);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                v4f r;
-                r.x = lut_at<0>(lut, cur[j], lane4) * s;
-                r.y = lut_at<1>(lut, cur[j], lane4) * s;
-                r.z = lut_at<2>(lut, cur[j], lane4) * s;
-                r.w = lut_at<3>(lut, cur[j], lane4) * s;
-                if (!RAGGED || j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, r);
-            }
-        } else {
-            // a short or misaligned unit: whole quads with 128-bit stores where the addresses allow, the rest
-            // element by element
-            const uint8_t *pc = codes + un.start;
-            uint32_t done = 0;
-            if ((((uintptr_t)po & 15) | ((uintptr_t)pc & 3)) == 0) {
-                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(pc);
-                v4f *o4 = reinterpret_cast<v4f *>(po);
-                const uint32_t nq = un.len >> 2;
-                for (uint32_t q = lane; q < nq; q += kWave) {
-                    const uint32_t cw = ldg<NT>(c4 + q);
-                    v4f r;
-                    r.x = lut_at<0>(lut, cw, lane4) * s;
-                    r.y = lut_at<1>(lut, cw, lane4) * s;
-                    r.z = lut_at<2>(lut, cw, lane4) * s;
-                    r.w = lut_at<3>(lut, cw, lane4) * s;
-                    stg<NT>(o4 + q, r);
-                }
-                done = nq << 2;
-            }
-            for (uint32_t i = done + lane; i < un.len; i += kWave) po[i] = lut_code(lut, pc[i], lane4) * s;
-            u += n_waves;
-            if (u < n_units) open_unit(u, un, fast);
-        }
-    }
-}
-
-// Decompress K buffers and average: acc = +0; acc += table[code_k] * scale_k for k = 0..K-1
-// in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled, Q code words per
-// lane and worker per unit, next unit's words requested before the current ones are used);
-// KT == 0 reads K from the argument.
-template <int KT, int Q, int NT, int WPW>
-__global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt,
-                                                           size_t n, size_t B, size_t nb, size_t upb, size_t n_units,
-                                                           size_t n_waves, float *__restrict__ out)
-{
-    __shared__ __align__(256) float lut[256 * kLutCopies];
-    constexpr int KA = KT > 0 ? KT : 1;
-    constexpr int U = Q * 4 * kWave;
-    const int K = KT > 0 ? KT : K_rt;
-    const float fk = (float)K;
-    // For K a power of two, 1/K is exact and acc * (1/K) is the correctly rounded value of the
-    // same real number as acc / K (subnormal results and signed zeros included), at the cost
-    // of one multiplication instead of a division sequence.
-    const bool pow2 = (K & (K - 1)) == 0;
-    const float rk = 1.0f / fk;
-    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t lane4 = lane * 4;
-    size_t u = first_unit(WPW);
-    Unit un;
-    bool fast = false;     // whole quads at aligned addresses
-    bool aligned = false;  // 128-bit stores and 32-bit code loads are possible
-    uint32_t w[KA][Q];
-    auto open_unit = [&](size_t uu, Unit &q, bool &f, bool &al) {
-        q = unit_of<U>(uu, n, B, nb, upb);
-        al = ((uintptr_t)(out + q.start) & 15) == 0;
-        for (int k = 0; k < K; ++k) al = al && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
-        // a unit of fewer whole quads stays on the pipelined path: a lane whose quad lies past the end loads
-        // the unit's last code word instead (unconditional, valid memory) and stores nothing
-        f = al && q.len >= 4 && (q.len & 3) == 0;
-        if (KT > 0 && f) {
-            const uint32_t last = (q.len >> 2) - 1;
-#pragma unroll
-            for (int k = 0; k < KA; ++k) {
-                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + q.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    const uint32_t i = j * kWave + lane;
-                    w[k][j] = ldg<NT>(c4 + (i < last ? i : last));
-                }
-            }
-        }
-    };
-    if (u < n_units) open_unit(u, un, fast, aligned);
-    load_lut(tab, lut);
-    __syncthreads();
-    while (u < n_units) {
-        float *po = out + un.start;
-        if (fast && KT > 0) {
-            float sc[KA];
-#pragma unroll
-            for (int k = 0; k < KA; ++k) sc[k] = p.scales[k][un.block];
-            uint32_t cur[KA][Q];
-#pragma unroll
-            for (int k = 0; k < KA; ++k)
-#pragma unroll
-                for (int j = 0; j < Q; ++j) cur[k][j] = w[k][j];
-            const uint32_t nq = un.len >> 2;
-            u += n_waves;
-            if (u < n_units) open_unit(u, un, fast, aligned);
-            v4f *o4 = reinterpret_cast<v4f *>(po);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-                for (int k = 0; k < KA; ++k) {
-                    a.x = a.x + lut_at<0>(lut, cur[k][j], lane4) * sc[k];
-                    a.y = a.y + lut_at<1>(lut, cur[k][j], lane4) * sc[k];
-                    a.z = a.z + lut_at<2>(lut, cur[k][j], lane4) * sc[k];
-                    a.w = a.w + lut_at<3>(lut, cur[k][j], lane4) * sc[k];
-                }
-                a.x = mean_of(a.x);
-                a.y = mean_of(a.y);
-                a.z = mean_of(a.z);
-                a.w = mean_of(a.w);
-                if (j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, a);
-            }
-        } else {
-            // any K, and misaligned units or units that are not whole quads: whole quads where the addresses allow (lanes take quads
-            // lane, lane + 64, ...), the rest element by element
-            uint32_t done = 0;
-            if (aligned) {
-                v4f *o4 = reinterpret_cast<v4f *>(po);
-                const uint32_t nq = un.len >> 2;
-                for (uint32_t q = lane; q < nq; q += kWave) {
-                    v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-                    for (int k = 0; k < K; ++k) {
-                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
-                        const float s = p.scales[k][un.block];
-                        a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
-                        a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
-                        a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
-                        a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
-                    }
-                    a.x = mean_of(a.x);
-                    a.y = mean_of(a.y);
-                    a.z = mean_of(a.z);
-                    a.w = mean_of(a.w);
-                    stg<NT>(o4 + q, a);
-                }
-                done = nq << 2;
-            }
-            for (uint32_t i = done + lane; i < un.len; i += kWave) {
-                float a = 0.0f;
-                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
-                po[i] = mean_of(a);
-            }
-            u += n_waves;
-            if (u < n_units) open_unit(u, un, fast, aligned);
-        }
-    }
-}
-
-// K-way decode-and-average of whole, aligned units, K = 2, 4 or 8: the common case of
-// k_decode_avg with nothing else in the loop.  Unit u covers elements [U u, U (u + 1)), U divides
-// the block size and block / U is a power of two, so a unit's block is u >> block_shift; out is
-// 16-byte and every code buffer 4-byte aligned.  The K scales of a unit travel with its code
-// words (read at the start of the unit's work they would cost a memory round trip per unit),
-// and the fetch of the next unit is unconditional in the steady state, so the compiler waits
-// for exactly the loads it needs.  A ragged last unit of tail_len elements is done by one
-// wavefront of the last workgroup after its loop.
-// LOCAL: an fp32 array (16-byte aligned) is the first term of every sum and the divisor is K + 1.
-template <int KT, int Q, int NT, int WPW, bool LOCAL>
-__global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t *__restrict__ tab, WorkerPtrs p,
-                                                                const float *__restrict__ local, uint32_t n_full,
-                                                                uint32_t n_waves, uint32_t block_shift, uint32_t tail_len,
-                                                                float *__restrict__ out)
-{
-    static_assert(KT == 2 || KT == 4 || KT == 8, "unrolled for these K");
-    __shared__ __align__(256) float lut[256 * kLutCopies];
-    constexpr int U = Q * 4 * kWave;
-    constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
-    constexpr float rk = 1.0f / (float)KT;  // acc * (1 / K) equals acc / K exactly for a power of two
-    auto mean_of = [&](float acc) { return LOCAL ? acc / fk : acc * rk; };
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t lane4 = lane * 4;
-    struct Slot {
-        uint32_t w[KT][Q];
-        float sw[KT];
-        v4f loc[LOCAL ? Q : 1];
-    };
-    auto fetch = [&](uint32_t u, Slot &sl) {
-        if (LOCAL) {
-            const v4f *l4 = reinterpret_cast<const v4f *>(local) + (size_t)u * (U / 4);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) sl.loc[j] = ldg_at<NT>(l4, j * kWave + lane);
-        }
-#pragma unroll
-        for (int k = 0; k < KT; ++k) sl.sw[k] = p.scales[k][u >> block_shift];
-#pragma unroll
-        for (int k = 0; k < KT; ++k) {
-            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) sl.w[k][j] = ldg_at<NT>(c4, j * kWave + lane);
-        }
-    };
-    auto process = [&](uint32_t u, Slot &sl) {
-        float sc[KT];
-#pragma unroll
-        for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[k])));
-        v4f *o4 = reinterpret_cast<v4f *>(out) + (size_t)u * (U / 4);
-#pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (LOCAL) {  // the sum starts at +0: a local -0 becomes +0
-                a.x = a.x + sl.loc[j].x;
-                a.y = a.y + sl.loc[j].y;
-                a.z = a.z + sl.loc[j].z;
-                a.w = a.w + sl.loc[j].w;
-            }
-#pragma unroll
-            for (int k = 0; k < KT; ++k) {
-                a.x = a.x + lut_at<0>(lut, sl.w[k][j], lane4) * sc[k];
-                a.y = a.y + lut_at<1>(lut, sl.w[k][j], lane4) * sc[k];
-                a.z = a.z + lut_at<2>(lut, sl.w[k][j], lane4) * sc[k];
-                a.w = a.w + lut_at<3>(lut, sl.w[k][j], lane4) * sc[k];
-            }
-            a.x = mean_of(a.x);
-            a.y = mean_of(a.y);
-            a.z = mean_of(a.z);
-            a.w = mean_of(a.w);
-            stg<NT>(o4 + j * kWave + lane, a);
-        }
-    };
-    uint32_t u = (uint32_t)first_unit(WPW);
-    Slot a, b;
-    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is built
-    load_lut(tab, lut);
-    __syncthreads();
-    if (u < n_full) {
-        for (;;) {
-            uint32_t nx = u + n_waves;
-            if (!(nx < n_full)) {
-                process(u, a);
-                break;
-            }
-            fetch(nx, b);
-            process(u, a);
-            u = nx;
-            nx = u + n_waves;
-            if (!(nx < n_full)) {
-                process(u, b);
-                break;
-            }
-            fetch(nx, a);
-            process(u, b);
-            u = nx;
-        }
-    }
-    if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
-        const size_t start = (size_t)n_full * U;
-        const size_t blk = n_full >> block_shift;
-        for (uint32_t i = lane; i < tail_len; i += kWave) {
-            float acc = 0.0f;
-            if (LOCAL) acc = acc + local[start + i];
-#pragma unroll
-            for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
-            out[start + i] = mean_of(acc);
-        }
-    }
-}
-
-// Average of K workers' buffers (plus, optionally, a local fp32 array as the first term) with a
-// whole unit of 4096 elements held in one wavefront's registers: 16 quads of running sums per
-// lane, the workers added one after the other while the next worker's code words are in flight.
-// The means can be stored as fp32 (mean_out) and / or compressed again from the registers
-// (codes_out, scales_out; needs a unit to be a whole scale block, upb == 1): the second round of
-// the gradient exchange then reads K bytes and writes one byte per element instead of going
-// through an fp32 array in memory.  Arithmetic and order are those of k_decode_avg followed by
-// k_encode, so the results are identical to the two calls.
-// Two workgroups of WPW wavefronts share a compute unit (each holds the 64 KiB decode table),
-// so the register budget per lane is 512 / (WPW / 2): 170 for six wavefronts, 128 for eight.
-// The unit is QL * 256 elements (the host picks the smallest that holds a block, up to 4096).
-// RAGGED = true (chosen by the host when blocks are not whole units): a unit of fewer whole aligned
-// quads stays on the register path; a lane whose quad lies past the end loads the unit's last quad
-// instead (unconditional loads of valid memory; the maximum does not change) and stores nothing.
-// This costs a register per quad for the clamped offsets, which the kernel for whole units cannot spare.
-template <int QL, int NT, bool FASTDIV, int WPW, bool RAGGED>
-__global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
-                                                          const float *__restrict__ local, size_t n, size_t B,
-                                                          size_t nb, size_t upb, size_t n_units, size_t n_waves,
-                                                          float *__restrict__ mean_out, float *__restrict__ scales_out,
-                                                          uint8_t *__restrict__ codes_out)
-{
-    static_assert(WPW >= 4, "the decode table is filled by 256 threads");
-    __shared__ __align__(256) float lut[256 * kLutCopies];
-    extern __shared__ uint32_t bucket_lds[];
-    constexpr int Q = QL;
-    constexpr int U = QL * 4 * kWave;
-    const int terms = K + (local ? 1 : 0);
-    const float fk = (float)terms;
-    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
-    const float rk = 1.0f / fk;
-    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t lane4 = lane * 4;
-    load_lut(tab, lut);
-    Search sr = make_search(bucket_lds, tab[kLoKeyOff], tab[kNBucketOff]);
-    if (codes_out) sr = load_bucket_table(tab, bucket_lds, kWave * WPW);
-    __syncthreads();
-    for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
-        const Unit un = unit_of<U>(u, n, B, nb, upb);
-        bool aligned = true;  // 128-bit accesses to the fp32 arrays and 32-bit ones to the codes are possible
-        for (int k = 0; k < K; ++k) aligned = aligned && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
-        if (local) aligned = aligned && (((uintptr_t)(local + un.start) & 15) == 0);
-        if (mean_out) aligned = aligned && (((uintptr_t)(mean_out + un.start) & 15) == 0);
-        if (codes_out) aligned = aligned && (((uintptr_t)(codes_out + un.start) & 3) == 0);
-        const bool fast = aligned && (RAGGED ? (un.len >= 4 && (un.len & 3) == 0) : un.len == (uint32_t)U);
-        if (fast) {
-            const uint32_t nq = un.len >> 2, last = nq - 1;
-            auto qi = [&](int j) {  // this lane's j-th quad, clamped to the unit
-                const uint32_t i = j * kWave + lane;
-                return RAGGED ? (i < last ? i : last) : i;
-            };
-            v4f acc[Q];
-            uint32_t wa[Q], wb[Q];
-            auto load_w = [&](uint32_t(&w)[Q], int k) {
-                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) w[j] = ldg_at<NT>(c4, qi(j));  // scalar base + 32-bit offset
-            };
-            auto add_w = [&](const uint32_t(&w)[Q], int k) {
-                const float s = p.scales[k][un.block];
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    acc[j].x = acc[j].x + lut_at<0>(lut, w[j], lane4) * s;
-                    acc[j].y = acc[j].y + lut_at<1>(lut, w[j], lane4) * s;
-                    acc[j].z = acc[j].z + lut_at<2>(lut, w[j], lane4) * s;
-                    acc[j].w = acc[j].w + lut_at<3>(lut, w[j], lane4) * s;
-                }
-                // pin the sums here, or the compiler defers them and holds the products of several workers
-#pragma unroll
-                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-            };
-            if (K > 0) load_w(wa, 0);
-            if (local) {
-                const v4f *l4 = reinterpret_cast<const v4f *>(local + un.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = ldg_at<NT>(l4, qi(j));
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
-                    acc[j].x = 0.0f + acc[j].x;
-                    acc[j].y = 0.0f + acc[j].y;
-                    acc[j].z = 0.0f + acc[j].z;
-                    acc[j].w = 0.0f + acc[j].w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-            }
-            for (int k = 0; k < K; k += 2) {
-                const bool more = k + 1 < K;
-                if (more) load_w(wb, k + 1);
-                add_w(wa, k);
-                if (more) {
-                    if (k + 2 < K) load_w(wa, k + 2);
-                    add_w(wb, k + 1);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                acc[j].x = mean_of(acc[j].x);
-                acc[j].y = mean_of(acc[j].y);
-                acc[j].z = mean_of(acc[j].z);
-                acc[j].w = mean_of(acc[j].w);
-            }
-            if (mean_out) {
-                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j)
-                    if (!RAGGED || j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, acc[j]);
-            }
-            if (codes_out) {
-                float fm = 0.0f;
-#pragma unroll
-                for (int j = 0; j < Q; ++j) fm = max4_abs(acc[j], fm);
-                const float s = u2f(wave_max_u32(f2u(fm)));
-                if (lane == 0) scales_out[un.block] = s;
-                const float d = s == 0.0f ? 1.0f : s;
-                const float r = 1.0f / d;
-                const bool recip = reciprocal_ok(d);
-                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
-                    if (!RAGGED || j * kWave + lane < nq) stg<1>(c4 + j * kWave + lane, cw);
-                }
-            }
-        } else {
-            // A misaligned unit or one that is not whole quads.  Whole quads where the addresses allow (lanes take quads lane,
-            // lane + 64, ...), the remaining elements one by one.  The means are formed again for each use
-            // (store, maximum, compression) rather than kept.
-            const uint32_t nq = aligned ? un.len >> 2 : 0;
-            const uint32_t done = nq << 2;
-            auto mean_at = [&](uint32_t i) {
-                float a = 0.0f;
-                if (local) a = a + local[un.start + i];
-                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
-                return mean_of(a);
-            };
-            auto mean_quad = [&](uint32_t q) {
-                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (local) {
-                    const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + un.start) + q);
-                    a.x = a.x + l.x;
-                    a.y = a.y + l.y;
-                    a.z = a.z + l.z;
-                    a.w = a.w + l.w;
-                }
-                for (int k = 0; k < K; ++k) {
-                    const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
-                    const float s = p.scales[k][un.block];
-                    a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
-                    a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
-                    a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
-                    a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
-                }
-                a.x = mean_of(a.x);
-                a.y = mean_of(a.y);
-                a.z = mean_of(a.z);
-                a.w = mean_of(a.w);
-                return a;
-            };
-            if (mean_out) {
-                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
-                for (uint32_t q = lane; q < nq; q += kWave) stg<NT>(o4 + q, mean_quad(q));
-                for (uint32_t i = done + lane; i < un.len; i += kWave) mean_out[un.start + i] = mean_at(i);
-            }
-            if (codes_out) {
-                float fm = 0.0f;
-                for (uint32_t q = lane; q < nq; q += kWave) fm = max4_abs(mean_quad(q), fm);
-                uint32_t m = f2u(fm);
-                for (uint32_t i = done + lane; i < un.len; i += kWave) {
-                    const uint32_t a = abs_bits(mean_at(i));
-                    m = m > a ? m : a;
-                }
-                const float s = u2f(wave_max_u32(m));
-                if (lane == 0) scales_out[un.block] = s;
-                const float d = s == 0.0f ? 1.0f : s;
-                const float r = 1.0f / d;
-                const bool recip = reciprocal_ok(d);
-                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
-                for (uint32_t q = lane; q < nq; q += kWave) stg<1>(c4 + q, encode_quad<FASTDIV>(sr, mean_quad(q), d, r, recip));
-                for (uint32_t i = done + lane; i < un.len; i += kWave)
-                    codes_out[un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(i), d, r, recip);
-            }
-        }
-    }
-}
-
-// The same average-then-compress round for K = 2, 4 or 8 workers at full speed.  A team of four
-// wavefronts owns a unit of 4096 elements (one scale block): every lane holds four quads of
-// running sums and K x 4 code words.  The code words are one register set that is refilled
-// in place: as soon as worker k's words of the current unit have been decoded and added, the
-// loads of worker k's words of the team's next unit are issued into the same registers, so
-// loads are in flight all through the reduction to the block maximum (wave reduction, then one
-// LDS exchange between the team's wavefronts) and the compression from the registers.
-// TEAMS teams share a workgroup and its tables; the workgroup barrier that separates the
-// exchange of the maxima from their use is executed by every wavefront the same number of
-// times (`iters`), whether or not its team still has a unit.
-// RAGGED = true (chosen by the host for blocks shorter than 4096): a unit of fewer whole aligned quads
-// takes the register path as well.
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED>
-struct AvgTeam {
-    static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
-
-    WorkerPtrs p;
-    const float *local;
-    float *scales_out;
-    uint8_t *codes_out;
-    size_t n, B, nb, n_units;
-    const float *lut;
-    uint32_t *slots;
-    Search sr;
-    uint32_t lane4, lane, team, wv, tl, phase;
-    float fk, rk;
-    bool pow2;
-    uint32_t w[KT][Q];  // code words: of the current unit until used, then of the next one
-
-    struct Slot {
-        Unit un;
-        bool active, fast;
-    };
-
-    __device__ __forceinline__ float mean_of(float acc) const { return pow2 ? acc * rk : acc / fk; }
-
-    // Element i of the unit, the slow way.
-    __device__ __forceinline__ float mean_at(const Unit &un, uint32_t i) const
-    {
-        float a = 0.0f;
-        if (local) a = a + local[un.start + i];
-#pragma unroll
-        for (int k = 0; k < KT; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
-        return mean_of(a);
-    }
-
-    // Geometry of unit u and whether it can take the register path.
-    __device__ __forceinline__ void open(size_t u, Slot &sl) const
-    {
-        sl.active = u < n_units;
-        sl.fast = false;
-        if (!sl.active) return;
-        sl.un = unit_of<kUnit>(u, n, B, nb, 1);
-        // whole aligned quads: a short unit takes the register path too (see load_worker)
-        bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == kUnit) &&
-                 (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
-#pragma unroll
-        for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
-        if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
-        sl.fast = f;
-    }
-
-    // This lane's j-th quad of the unit; WHOLE promises a unit of 4096 elements, otherwise a quad past the
-    // end of a shorter unit becomes the unit's last one (an unconditional load of valid memory whose result
-    // is not stored and cannot change the maximum).
-    template <bool WHOLE>
-    __device__ __forceinline__ uint32_t quad_of(const Slot &sl, int j) const
-    {
-        const uint32_t i = j * kWg + tl;
-        if (WHOLE || !RAGGED) return i;
-        const uint32_t last = (sl.un.len >> 2) - 1;
-        return i < last ? i : last;
-    }
-
-    template <bool WHOLE>
-    __device__ __forceinline__ void load_worker(const Slot &sl, int k)
-    {
-        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start);
-#pragma unroll
-        for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, quad_of<WHOLE>(sl, j));
-    }
-
-    __device__ __forceinline__ void load_all(const Slot &sl)
-    {
-        if (sl.fast) {
-#pragma unroll
-            for (int k = 0; k < KT; ++k) load_worker<false>(sl, k);
-        }
-    }
-
-    // Processes unit `sl`, whose code words are in w if it is fast, and leaves the words of `nx` there.
-    // STEADY: the caller knows that both units exist and are whole and aligned (true for all but a
-    // team's last two units when the host found the buffers aligned), so nothing here is
-    // conditional and the compiler waits for exactly the loads each step needs.
-    template <bool STEADY>
-    __device__ __forceinline__ void process(const Slot &sl, const Slot &nx)
-    {
-        v4f acc[Q];
-        uint32_t m = 0;
-        if (STEADY || (sl.active && sl.fast)) {
-            if (local) {  // not prefetched: the code words take the registers
-                const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
-                    const v4f l = ldg<NT>(l4 + quad_of<STEADY>(sl, j));
-                    acc[j].x = 0.0f + l.x;
-                    acc[j].y = 0.0f + l.y;
-                    acc[j].z = 0.0f + l.z;
-                    acc[j].w = 0.0f + l.w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-            }
-            float sc[KT];  // the K scales of this block, moved to scalar registers
-#pragma unroll
-            for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(p.scales[k][sl.un.block])));
-#pragma unroll
-            for (int k = 0; k < KT; ++k) {
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    acc[j].x = acc[j].x + lut_at<0>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].y = acc[j].y + lut_at<1>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].z = acc[j].z + lut_at<2>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].w = acc[j].w + lut_at<3>(lut, w[k][j], lane4) * sc[k];
-                }
-                // Pin the sums here.  Otherwise the compiler starts the lookups of every worker
-                // at once and holds all K x 16 products in registers until the ordered sums get
-                // to them, which costs a wavefront per SIMD.
-#pragma unroll
-                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place
-            }
-            float fm = 0.0f;
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                acc[j].x = mean_of(acc[j].x);
-                acc[j].y = mean_of(acc[j].y);
-                acc[j].z = mean_of(acc[j].z);
-                acc[j].w = mean_of(acc[j].w);
-                fm = max4_abs(acc[j], fm);
-            }
-            m = f2u(fm);
-        } else {
-            if (sl.active) {
-                for (uint32_t i = tl; i < sl.un.len; i += kWg) {
-                    const uint32_t a = abs_bits(mean_at(sl.un, i));
-                    m = m > a ? m : a;
-                }
-            }
-            load_all(nx);
-        }
-        m = wave_max_u32(m);
-        uint32_t *sp = slots + (phase * TEAMS + team) * kWavesPerWg;
-        if (lane == 0) sp[wv] = m;
-        __syncthreads();
-        {
-            const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
-            m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
-        }
-        phase ^= 1;  // the other half of the slots next time: one barrier per unit is enough
-        if (!STEADY && !sl.active) return;
-        const float s = u2f(m);
-        if (tl == 0) scales_out[sl.un.block] = s;
-        const float d = s == 0.0f ? 1.0f : s;
-        const float r = 1.0f / d;
-        const bool recip = reciprocal_ok(d);
-        if (STEADY || sl.fast) {
-            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
-                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
-            }
-        } else {
-            for (uint32_t i = tl; i < sl.un.len; i += kWg)
-                codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);
-        }
-    }
-};
-
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED>
-__global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
-                                                            const float *__restrict__ local, size_t n, size_t B, size_t nb,
-                                                            size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
-                                                            float *__restrict__ scales_out, uint8_t *__restrict__ codes_out)
-{
-    __shared__ __align__(256) float lut[256 * kLutCopies];
-    extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
-    constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
-    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED>;
-    Avg e;
-    e.p = p;
-    e.local = local;
-    e.scales_out = scales_out;
-    e.codes_out = codes_out;
-    e.n = n;
-    e.B = B;
-    e.nb = nb;
-    e.n_units = n_units;
-    e.lut = lut;
-    e.slots = dyn_lds;
-    e.lane = threadIdx.x & 63;
-    e.lane4 = e.lane * 4;
-    const uint32_t wave = wave_in_wg();
-    e.team = wave / kWavesPerWg;
-    e.wv = wave % kWavesPerWg;
-    e.tl = threadIdx.x & (kWg - 1);  // lane within the team
-    e.phase = 0;
-    const int terms = KT + (local ? 1 : 0);
-    e.fk = (float)terms;
-    e.rk = 1.0f / e.fk;
-    e.pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
-    size_t u = (size_t)blockIdx.x * TEAMS + e.team;
-    typename Avg::Slot a, b;
-    e.open(u, a);
-    e.load_all(a);  // the first loads are in flight while the tables are copied
-    load_lut(tab, lut);
-    {
-        e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWg * TEAMS);
-        if (!REMAP) e.sr.remap = nullptr;  // a type without a rank-to-code table: no test for one in the loop
-    }
-    __syncthreads();
-    // `steady` (even) leading iterations in which this and the next unit of every team are whole
-    // aligned units, then the general ones.
-    uint32_t it = 0;
-    for (; it < steady; it += 2) {
-        e.open(u + n_teams, b);
-        e.template process<true>(a, b);
-        u += n_teams;
-        e.open(u + n_teams, a);
-        e.template process<true>(b, a);
-        u += n_teams;
-    }
-    for (; it < iters; it += 2) {
-        e.open(u + n_teams, b);
-        e.template process<false>(a, b);
-        u += n_teams;
-        if (it + 1 >= iters) break;
-        e.open(u + n_teams, a);
-        e.template process<false>(b, a);
-        u += n_teams;
-    }
-}
-
-// Approximation-error statistics of compress-then-decompress (Sec. 3.4, Table 2).  Per block b,
-// stats[4 b + 0] = sum of e, [1] = sum of e / |x| over x != 0, [2] = number of x != 0,
-// [3] = largest e, with q = fl32(cb[code] * s) and e = |(double) q - (double) x| (one binary64
-// subtraction; the quotient one correctly rounded binary64 division).  stats[] was zeroed.
-// A wavefront walks a contiguous run of units of Q * 256 elements, keeps binary64 running sums per
-// lane while the block stays the same, and merges them into stats[] with atomics when the block
-// changes and at the end: the count and the maximum are exact in any order (integers below 2^53,
-// and non-negative binary64 numbers order like their bit patterns); the two sums depend on the
-// order only in their last bits.
-template <int Q>
-__global__ __launch_bounds__(kWg) void k_error_stats(const uint32_t *__restrict__ tab, const float *__restrict__ x, size_t n,
-                                                    size_t B, size_t nb, size_t upb, size_t n_units, size_t per_wave,
-                                                    const float *__restrict__ scales, double *__restrict__ stats)
-{
-    constexpr int U = Q * 4 * kWave;
-    extern __shared__ uint32_t lds[];  // 256 table values, then the search tables
-    for (uint32_t i = threadIdx.x; i < 256; i += kWg) lds[i] = tab[kCbOff + i];
-    const Search sr = load_bucket_table(tab, lds + 256);
-    __syncthreads();
-    const uint32_t lane = threadIdx.x & 63;
-    const size_t u0 = first_unit() * per_wave;
-    const size_t u1 = u0 + per_wave < n_units ? u0 + per_wave : n_units;
-    double sum_abs = 0.0, sum_rel = 0.0, count = 0.0, worst = 0.0;
-    auto add = [&](float xv, uint32_t code, float s) {
-        const float q = u2f(lds[code & 0xFFu]) * s;
-        const double e = __builtin_fabs((double)q - (double)xv);
-        const double rel = e / __builtin_fabs((double)xv);  // not used when xv is a zero
-        sum_abs += e;
-        sum_rel += xv != 0.0f ? rel : 0.0;
-        count += xv != 0.0f ? 1.0 : 0.0;
-        worst = e > worst ? e : worst;
-    };
-    auto flush = [&](size_t blk) {
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {  // the same tree in every launch
-            sum_abs += __shfl_xor(sum_abs, m);
-            sum_rel += __shfl_xor(sum_rel, m);
-            count += __shfl_xor(count, m);
-            const double o = __shfl_xor(worst, m);
-            worst = o > worst ? o : worst;
-        }
-        if (lane == 0) {
-            double *p = stats + 4 * blk;
-            atomicAdd(p, sum_abs);
-            atomicAdd(p + 1, sum_rel);
-            atomicAdd(p + 2, count);
-            atomicMax(reinterpret_cast<unsigned long long *>(p + 3), (unsigned long long)__double_as_longlong(worst));
-        }
-        sum_abs = sum_rel = count = worst = 0.0;
-    };
-    bool open = false;
-    size_t cur = 0;
-    for (size_t u = u0; u < u1; ++u) {
-        const Unit un = unit_of<U>(u, n, B, nb, upb);
-        if (open && un.block != cur) flush(cur);
-        open = true;
-        cur = un.block;
-        const float s = scales[un.block];
-        const float d = s == 0.0f ? 1.0f : s;
-        const float r = 1.0f / d;
-        const bool recip = reciprocal_ok(d);
-        const float *px = x + un.start;
-        if (un.len == U && ((uintptr_t)px & 15) == 0) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(px);
-            v4f v[Q];
-#pragma unroll
-            for (int j = 0; j < Q; ++j) v[j] = ldg<1>(p4 + j * kWave + lane);
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                const uint32_t c = encode_quad<true>(sr, v[j], d, r, recip);
-                add(v[j].x, c, s);
-                add(v[j].y, c >> 8, s);
-                add(v[j].z, c >> 16, s);
-                add(v[j].w, c >> 24, s);
-            }
-        } else {
-            for (uint32_t i = lane; i < un.len; i += kWave) add(px[i], encode_one<true>(sr, px[i], d, r, recip), s);
-        }
-    }
-    if (open) flush(cur);
-}
-
-// Means over all blocks from the per-block statistics: means[0] = (sum of absolute errors) / n,
-// means[1] = (sum of relative errors) / (number of non-zero inputs), 0 when there is none.
-// One workgroup of 1024 threads; thread t adds blocks t, t + 1024, ... in that order and the threads'
-// sums are combined by a fixed tree, so the result is the same in every launch.
-constexpr uint32_t kMeansThreads = 1024;
-__global__ __launch_bounds__(kMeansThreads) void k_error_means(const double *__restrict__ stats, size_t nb, size_t n,
-                                                              double *__restrict__ means)
-{
-    __shared__ double part[3][kMeansThreads];
-    double a = 0.0, r = 0.0, c = 0.0;
-#pragma unroll 4
-    for (size_t b = threadIdx.x; b < nb; b += kMeansThreads) {
-        a += stats[4 * b];
-        r += stats[4 * b + 1];
-        c += stats[4 * b + 2];
-    }
-    part[0][threadIdx.x] = a;
-    part[1][threadIdx.x] = r;
-    part[2][threadIdx.x] = c;
-    __syncthreads();
-    for (uint32_t w = kMeansThreads / 2; w >= 1; w >>= 1) {
-        if (threadIdx.x < w) {
-            part[0][threadIdx.x] += part[0][threadIdx.x + w];
-            part[1][threadIdx.x] += part[1][threadIdx.x + w];
-            part[2][threadIdx.x] += part[2][threadIdx.x + w];
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        means[0] = part[0][0] / (double)n;
-        means[1] = part[2][0] > 0.0 ? part[1][0] / part[2][0] : 0.0;
-    }
-}
 
 // ---------------------------------------------------------------- host side
 

@@ -1,0 +1,387 @@
+// Device-side building blocks of the dq8 kernels for gfx950: constants, memory access policies,
+// wavefront reductions, unit geometry, the encoder's code search and the decoder's lookup table.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "dq8.h"
+#include "dq8_tables.hpp"
+
+namespace {
+
+using dq8::kBucketOff;
+using dq8::kHasRemapOff;
+using dq8::kRemapOff;
+using dq8::kRemapWords;
+using dq8::kCbOff;
+using dq8::kLoKeyOff;
+using dq8::kNBucketOff;
+using dq8::kNearWindow;
+using dq8::kTableWords;
+
+constexpr int kWave = 64;
+constexpr int kWavesPerWg = 4;
+constexpr int kWg = kWave * kWavesPerWg;
+constexpr int kUnit = 4096;                      // elements per unit
+constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
+constexpr int kKinds = 4;
+constexpr int kLutCopies = 64;                   // one copy of the decode table per lane
+constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// Tables of the data types, one image per device (each GPU holds its own copy).
+__device__ __align__(256) uint32_t g_tables[kKinds][kTableWords];
+
+struct WorkerPtrs {
+    const uint8_t *codes[DQ8_MAX_K];
+    const float *scales[DQ8_MAX_K];
+};
+
+// Streaming accesses: every byte is touched once, so loads and stores carry cache-policy
+// bits that keep them from displacing each other in the caches.  NT is the policy:
+//   0  plain loads and stores;
+//   1  non-temporal loads and stores (the nt bit);
+//   2  non-temporal loads; 128-bit stores with nt plus system scope (sc0 sc1), i.e. streamed
+//      through every cache level; 32-bit stores as in policy 1.
+// The scope bits only strengthen coherence, so every policy gives the same memory contents.
+//
+// The compiler has no way to ask for "sc0 sc1 nt" on an ordinary store (a volatile store gets
+// sc0 sc1 but is also made to wait for completion), so policy 2 writes the instruction out.
+// A 128-bit store keeps reading its data registers for two cycles after issue; the compiler
+// cannot see that this statement is such a store, so the two wait states it would otherwise
+// insert before the next vector write to those registers are part of the statement.
+template <int NT, typename T>
+__device__ __forceinline__ T ldg(const T *p)
+{
+    if constexpr (NT != 0)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <int NT, typename T>
+__device__ __forceinline__ void stg(T *p, T v)
+{
+    if constexpr (NT == 0)
+        *p = v;
+    else if constexpr (NT == 2 && sizeof(T) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+    else
+        __builtin_nontemporal_store(v, p);
+}
+
+// Maximum over the 64 lanes, returned in a scalar register.  Six data-parallel-primitive steps
+// on the vector unit (no LDS traffic): exchange inside quads, mirror inside half rows and rows
+// of 16 lanes, then carry lane 15 of a row into the next row and lane 31 into the upper half;
+// lane 63 ends up with the maximum of all lanes.  A step leaves lanes it does not write at
+// their own value, which is the identity of max.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t max_dpp(uint32_t v)
+{
+    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
+    return o > v ? o : v;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = max_dpp<0xB1, 0xF>(v);   // quad_perm [1,0,3,2]
+    v = max_dpp<0x4E, 0xF>(v);   // quad_perm [2,3,0,1]
+    v = max_dpp<0x141, 0xF>(v);  // row_half_mirror
+    v = max_dpp<0x140, 0xF>(v);  // row_mirror
+    v = max_dpp<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+    v = max_dpp<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+__host__ __device__ __forceinline__ uint32_t f2u(float f)
+{
+    uint32_t u;
+    __builtin_memcpy(&u, &f, 4);
+    return u;
+}
+
+__host__ __device__ __forceinline__ float u2f(uint32_t u)
+{
+    float f;
+    __builtin_memcpy(&f, &u, 4);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t abs_bits(float f) { return f2u(f) & 0x7FFFFFFFu; }
+
+// Running maximum of |v|.  Exact for finite inputs, subnormals included.
+__device__ __forceinline__ float max4_abs(v4f v, float m)
+{
+    float a = __builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y));
+    float b = __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w));
+    return __builtin_fmaxf(m, __builtin_fmaxf(a, b));
+}
+
+// Geometry of unit u.  All values are wave-uniform.
+struct Unit {
+    size_t block;   // scale index
+    size_t start;   // first element
+    uint32_t len;   // 1..kUnit
+};
+
+// min(v, U) of a 64-bit count as 32 bits, U a power of two.  Written with a shift and a compare
+// against zero so that it stays on the scalar unit: a 64-bit ordered compare of uniform values
+// is done on the vector unit, and the compiler has been seen to drop the copy of such a result
+// into the scalar condition bit when a branch on the same result follows, leaving a select
+// that reads a stale condition (wrong unit lengths, accesses past the end of the arrays).
+template <int U>
+__device__ __forceinline__ uint32_t cap_to_unit(size_t v)
+{
+    static_assert(U > 0 && (U & (U - 1)) == 0, "unit sizes are powers of two");
+    return (v >> __builtin_ctz(U)) != 0 ? (uint32_t)U : (uint32_t)v;
+}
+
+template <int U>
+__device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb, size_t upb)
+{
+    Unit r;
+    size_t c;
+    if (upb == 1) {
+        r.block = u;
+        c = 0;
+    } else if (nb == 1) {
+        r.block = 0;
+        c = u;
+    } else {
+        r.block = u / upb;
+        c = u - r.block * upb;
+    }
+    const size_t off = c * (size_t)U;
+    r.start = r.block * B + off;
+    const uint32_t in_block = cap_to_unit<U>(B - off), in_array = cap_to_unit<U>(n - r.start);
+    r.len = in_block < in_array ? in_block : in_array;
+    return r;
+}
+
+// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and
+// for a data type with repeated values the table that turns a rank into its code.
+struct Search {
+    const uint32_t *bucket;  // LDS on the device
+    const uint32_t *remap;   // NULL when every rank is its own code
+    uint32_t lo_key;         // key of the first bucket
+    float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
+};
+
+__host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket,
+                                                       const uint32_t *remap = nullptr)
+{
+    Search s;
+    s.bucket = bucket;
+    s.remap = remap;
+    s.lo_key = lo_key;
+    s.lo_f = u2f((lo_key << 16) + 0x8000u);
+    s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
+    return s;
+}
+
+// sum >> 16 = rank of the nearest table value (the number of thresholds <= |xn|), which is its
+// magnitude field except for a type with a rank-to-code table (see finish_sum); the low half of
+// sum measures the distance to the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
+// so the clamp is done on the value.
+__host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const float c = __builtin_amdgcn_fmed3f(__builtin_fabsf(xn), s.lo_f, s.hi_f);
+#else
+    float c = __builtin_fabsf(xn);
+    c = c >= s.lo_f ? c : s.lo_f;  // also takes NaN to the low end; inputs are finite anyway
+    c = c <= s.hi_f ? c : s.hi_f;
+#endif
+    const uint32_t a = f2u(c);  // the low 16 bits of lo_base are zero: subtracting it only moves the key
+    return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
+}
+
+// Rank to magnitude field in bits 16..22, for the types where the two differ.  Kept out of
+// search_sum so that an encoder takes this (wavefront-uniform) branch once per group of sums.
+__host__ __device__ __forceinline__ uint32_t finish_sum(const Search &s, uint32_t sum) { return s.remap[sum >> 16] << 16; }
+
+// (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
+__host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (sum + kNearWindow) & 0xFFFFu; }
+
+// Code = magnitude index, bit 7 = sign bit of the input (the divisor is positive).
+__host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
+
+__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, uint32_t sum, float x)
+{
+    if (s.remap) sum = finish_sum(s, sum);
+    return code_from(sum, x);
+}
+
+__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_of(s, search_sum(s, x / d), x); }
+
+// Four codes in one word: byte i = magnitude index of sum i (its byte 2) with the sign bit of
+// x i (top bit of its byte 3).  v_perm_b32 gathers the bytes: selector byte 0..3 picks a byte
+// of the second operand, 4..7 of the first, 0x0C gives zero.
+__device__ __forceinline__ uint32_t pack_codes(const Search &sr, uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
+{
+    if (sr.remap) {
+        s0 = finish_sum(sr, s0);
+        s1 = finish_sum(sr, s1);
+        s2 = finish_sum(sr, s2);
+        s3 = finish_sum(sr, s3);
+    }
+    const uint32_t m01 = __builtin_amdgcn_perm(s1, s0, 0x0C0C0602u);
+    const uint32_t m23 = __builtin_amdgcn_perm(s3, s2, 0x06020C0Cu);
+    const uint32_t g01 = __builtin_amdgcn_perm(f2u(v.y), f2u(v.x), 0x0C0C0703u);
+    const uint32_t g23 = __builtin_amdgcn_perm(f2u(v.w), f2u(v.z), 0x07030C0Cu);
+    return ((g01 | g23) & 0x80808080u) | m01 | m23;
+}
+
+// A scale qualifies for the reciprocal path when 1/d and every product x * (1/d) that can
+// reach a threshold are normal numbers: 2^-100 <= d <= 2^100.
+__host__ __device__ __forceinline__ bool reciprocal_ok(float d)
+{
+    uint32_t b = f2u(d);
+    return b >= 0x0D800000u && b <= 0x71800000u;
+}
+
+// Four codes packed into one word.  With `recip` the quotients are first taken as x * r with
+// r = fl(1/d): that differs from the correctly rounded x / d by at most 3 binary32 steps, so
+// the code is already right unless the product lies within kNearWindow steps of a threshold;
+// if any lane of the wavefront sees such a value the quad is redone with true divisions.
+template <bool FASTDIV>
+__device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d, float r, bool recip)
+{
+    if (FASTDIV && recip) {
+        const uint32_t s0 = search_sum(sr, v.x * r), s1 = search_sum(sr, v.y * r);
+        const uint32_t s2 = search_sum(sr, v.z * r), s3 = search_sum(sr, v.w * r);
+        uint32_t k0 = near_key(s0), k1 = near_key(s1), k2 = near_key(s2), k3 = near_key(s3);
+        k0 = k0 < k1 ? k0 : k1;
+        k2 = k2 < k3 ? k2 : k3;
+        k0 = k0 < k2 ? k0 : k2;
+        if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(sr, s0, s1, s2, s3, v);
+    }
+    return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
+}
+
+template <bool FASTDIV>
+__device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float d, float r, bool recip)
+{
+    if (FASTDIV && recip) {
+        uint32_t s0 = search_sum(sr, x * r);
+        if (near_key(s0) > 2 * kNearWindow) return code_of(sr, s0, x);
+    }
+    return code_exact(sr, x, d);
+}
+
+// Copies the bucket table (and the rank-to-code table of a type that has one, right behind it)
+// to LDS with all `n_threads` threads of the workgroup; the caller synchronises the workgroup
+// before using it.
+__device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds, uint32_t n_threads = kWg)
+{
+    const uint32_t nbk = tab[kNBucketOff];
+    for (uint32_t i = threadIdx.x; i < nbk; i += n_threads) lds[i] = tab[kBucketOff + i];
+    const uint32_t *remap = nullptr;
+    if (tab[kHasRemapOff]) {
+        for (uint32_t i = threadIdx.x; i < (uint32_t)kRemapWords; i += n_threads) lds[nbk + i] = tab[kRemapOff + i];
+        remap = lds + nbk;
+    }
+    return make_search(lds, tab[kLoKeyOff], nbk, remap);
+}
+
+// Decode table in LDS, one copy per lane: entry (code, lane) at byte address code * 256 +
+// lane * 4.  Lanes L and L + 32 share a bank but are served in different halves of the access,
+// so a lookup never conflicts, and the address is two byte fields - code in byte 1, lane * 4 in
+// byte 0 - which one v_perm_b32 assembles straight from a packed word of four codes.
+// Thread t < 256 owns code t (workgroups have at least 256 threads).  The caller synchronises before the
+// first lookup.
+__device__ __forceinline__ void load_lut(const uint32_t *tab, float *lds)
+{
+    if (threadIdx.x < 256) {
+        const float val = u2f(tab[kCbOff + threadIdx.x]);
+        const v4f four = {val, val, val, val};
+        v4f *row = reinterpret_cast<v4f *>(lds + threadIdx.x * kLutCopies);
+#pragma unroll
+        for (int c = 0; c < kLutCopies / 4; ++c) row[c] = four;
+    }
+}
+
+// Table value of code number J (0..3) of the packed word w, for the lane whose byte offset
+// into a table row is lane4 = lane * 4.
+template <int J>
+__device__ __forceinline__ float lut_at(const float *lut, uint32_t w, uint32_t lane4)
+{
+    const uint32_t addr = __builtin_amdgcn_perm(w, lane4, 0x0C0C0400u + (J << 8));
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + addr);
+}
+
+__device__ __forceinline__ float lut_code(const float *lut, uint32_t code, uint32_t lane4)
+{
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + ((code << 8) | lane4));
+}
+
+// Element idx of an array whose base pointer is wave-uniform, addressed as "scalar base +
+// 32-bit vector offset": the base is pinned to scalar registers, so that the compiler neither
+// keeps a 64-bit address per lane nor hoists one out of the loop for every array it walks.
+// The pointer goes through an integer on the way, which would make it a generic pointer; the
+// cast names the global address space again (address space 1), so the access stays a global one.
+#define DQ8_GLOBAL __attribute__((address_space(1)))
+
+template <typename T>
+__device__ __forceinline__ DQ8_GLOBAL T *uniform_global(T *p)
+{
+    const uintptr_t v = (uintptr_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (DQ8_GLOBAL T *)(((uintptr_t)hi << 32) | lo);
+}
+
+template <int NT, typename T>
+__device__ __forceinline__ T ldg_at(const T *uniform_base, uint32_t idx)
+{
+    const DQ8_GLOBAL T *g = uniform_global(uniform_base);
+    if constexpr (NT != 0)
+        return __builtin_nontemporal_load(g + idx);
+    else
+        return g[idx];
+}
+
+// Store with the plain or non-temporal policy (the write-through policy of stg keeps its own form).
+template <int NT, typename T>
+__device__ __forceinline__ void stg_at(T *uniform_base, uint32_t idx, T v)
+{
+    DQ8_GLOBAL T *g = uniform_global(uniform_base);
+    if constexpr (NT != 0)
+        __builtin_nontemporal_store(v, g + idx);
+    else
+        g[idx] = v;
+}
+
+__device__ __forceinline__ uint32_t wave_in_wg() { return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
+// Index of this wavefront in the grid = the first unit it owns; held in scalar registers.
+__device__ __forceinline__ size_t first_unit(int waves_per_wg = kWavesPerWg) { return (size_t)blockIdx.x * waves_per_wg + wave_in_wg(); }
+
+// Maximum of |x[0..len)| over the elements this lane takes, for a unit that is short or not
+// 16-byte aligned: whole quads with 128-bit loads when the start is aligned (the STRIDE lanes that
+// share the unit take quads lane, lane + STRIDE, ...; a tail of fewer than four elements goes one by
+// one), else element by element.
+template <int NT, uint32_t STRIDE = kWave>
+__device__ __forceinline__ uint32_t slow_absmax(const float *px, uint32_t len, uint32_t lane)
+{
+    uint32_t m = 0;
+    uint32_t done = 0;
+    if (((uintptr_t)px & 15) == 0) {
+        const v4f *p4 = reinterpret_cast<const v4f *>(px);
+        const uint32_t nq = len >> 2;
+        float fm = 0.0f;
+#pragma unroll 4
+        for (uint32_t q = lane; q < nq; q += STRIDE) fm = max4_abs(ldg<NT>(p4 + q), fm);
+        m = f2u(fm);
+        done = nq << 2;
+    }
+    for (uint32_t i = done + lane; i < len; i += STRIDE) {
+        const uint32_t a = abs_bits(px[i]);
+        m = m > a ? m : a;
+    }
+    return m;
+}
+
+}  // namespace

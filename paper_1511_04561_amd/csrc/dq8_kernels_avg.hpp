@@ -1,0 +1,233 @@
+// dq8 kernels that decompress K workers' buffers and average them into an fp32 array.
+#pragma once
+#include "dq8_device.hpp"
+
+namespace {
+
+// Decompress K buffers and average: acc = +0; acc += table[code_k] * scale_k for k = 0..K-1
+// in order; out = acc / K.  KT > 0 fixes K at compile time (fully unrolled, Q code words per
+// lane and worker per unit, next unit's words requested before the current ones are used);
+// KT == 0 reads K from the argument.
+template <int KT, int Q, int NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt,
+                                                           size_t n, size_t B, size_t nb, size_t upb, size_t n_units,
+                                                           size_t n_waves, float *__restrict__ out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int KA = KT > 0 ? KT : 1;
+    constexpr int U = Q * 4 * kWave;
+    const int K = KT > 0 ? KT : K_rt;
+    const float fk = (float)K;
+    // For K a power of two, 1/K is exact and acc * (1/K) is the correctly rounded value of the
+    // same real number as acc / K (subnormal results and signed zeros included), at the cost
+    // of one multiplication instead of a division sequence.
+    const bool pow2 = (K & (K - 1)) == 0;
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    size_t u = first_unit(WPW);
+    Unit un;
+    bool fast = false;     // whole quads at aligned addresses
+    bool aligned = false;  // 128-bit stores and 32-bit code loads are possible
+    uint32_t w[KA][Q];
+    auto open_unit = [&](size_t uu, Unit &q, bool &f, bool &al) {
+        q = unit_of<U>(uu, n, B, nb, upb);
+        al = ((uintptr_t)(out + q.start) & 15) == 0;
+        for (int k = 0; k < K; ++k) al = al && (((uintptr_t)(p.codes[k] + q.start) & 3) == 0);
+        // a unit of fewer whole quads stays on the pipelined path: a lane whose quad lies past the end loads
+        // the unit's last code word instead (unconditional, valid memory) and stores nothing
+        f = al && q.len >= 4 && (q.len & 3) == 0;
+        if (KT > 0 && f) {
+            const uint32_t last = (q.len >> 2) - 1;
+#pragma unroll
+            for (int k = 0; k < KA; ++k) {
+                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + q.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t i = j * kWave + lane;
+                    w[k][j] = ldg<NT>(c4 + (i < last ? i : last));
+                }
+            }
+        }
+    };
+    if (u < n_units) open_unit(u, un, fast, aligned);
+    load_lut(tab, lut);
+    __syncthreads();
+    while (u < n_units) {
+        float *po = out + un.start;
+        if (fast && KT > 0) {
+            float sc[KA];
+#pragma unroll
+            for (int k = 0; k < KA; ++k) sc[k] = p.scales[k][un.block];
+            uint32_t cur[KA][Q];
+#pragma unroll
+            for (int k = 0; k < KA; ++k)
+#pragma unroll
+                for (int j = 0; j < Q; ++j) cur[k][j] = w[k][j];
+            const uint32_t nq = un.len >> 2;
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast, aligned);
+            v4f *o4 = reinterpret_cast<v4f *>(po);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int k = 0; k < KA; ++k) {
+                    a.x = a.x + lut_at<0>(lut, cur[k][j], lane4) * sc[k];
+                    a.y = a.y + lut_at<1>(lut, cur[k][j], lane4) * sc[k];
+                    a.z = a.z + lut_at<2>(lut, cur[k][j], lane4) * sc[k];
+                    a.w = a.w + lut_at<3>(lut, cur[k][j], lane4) * sc[k];
+                }
+                a.x = mean_of(a.x);
+                a.y = mean_of(a.y);
+                a.z = mean_of(a.z);
+                a.w = mean_of(a.w);
+                if (j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, a);
+            }
+        } else {
+            // any K, and misaligned units or units that are not whole quads: whole quads where the addresses allow (lanes take quads
+            // lane, lane + 64, ...), the rest element by element
+            uint32_t done = 0;
+            if (aligned) {
+                v4f *o4 = reinterpret_cast<v4f *>(po);
+                const uint32_t nq = un.len >> 2;
+                for (uint32_t q = lane; q < nq; q += kWave) {
+                    v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+                    for (int k = 0; k < K; ++k) {
+                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
+                        const float s = p.scales[k][un.block];
+                        a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
+                        a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
+                        a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
+                        a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
+                    }
+                    a.x = mean_of(a.x);
+                    a.y = mean_of(a.y);
+                    a.z = mean_of(a.z);
+                    a.w = mean_of(a.w);
+                    stg<NT>(o4 + q, a);
+                }
+                done = nq << 2;
+            }
+            for (uint32_t i = done + lane; i < un.len; i += kWave) {
+                float a = 0.0f;
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+                po[i] = mean_of(a);
+            }
+            u += n_waves;
+            if (u < n_units) open_unit(u, un, fast, aligned);
+        }
+    }
+}
+
+// K-way decode-and-average of whole, aligned units, K = 2, 4 or 8: the common case of
+// k_decode_avg with nothing else in the loop.  Unit u covers elements [U u, U (u + 1)), U divides
+// the block size and block / U is a power of two, so a unit's block is u >> block_shift; out is
+// 16-byte and every code buffer 4-byte aligned.  The K scales of a unit travel with its code
+// words (read at the start of the unit's work they would cost a memory round trip per unit),
+// and the fetch of the next unit is unconditional in the steady state, so the compiler waits
+// for exactly the loads it needs.  A ragged last unit of tail_len elements is done by one
+// wavefront of the last workgroup after its loop.
+// LOCAL: an fp32 array (16-byte aligned) is the first term of every sum and the divisor is K + 1.
+template <int KT, int Q, int NT, int WPW, bool LOCAL>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t *__restrict__ tab, WorkerPtrs p,
+                                                                const float *__restrict__ local, uint32_t n_full,
+                                                                uint32_t n_waves, uint32_t block_shift, uint32_t tail_len,
+                                                                float *__restrict__ out)
+{
+    static_assert(KT == 2 || KT == 4 || KT == 8, "unrolled for these K");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int U = Q * 4 * kWave;
+    constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
+    constexpr float rk = 1.0f / (float)KT;  // acc * (1 / K) equals acc / K exactly for a power of two
+    auto mean_of = [&](float acc) { return LOCAL ? acc / fk : acc * rk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    struct Slot {
+        uint32_t w[KT][Q];
+        float sw[KT];
+        v4f loc[LOCAL ? Q : 1];
+    };
+    auto fetch = [&](uint32_t u, Slot &sl) {
+        if (LOCAL) {
+            const v4f *l4 = reinterpret_cast<const v4f *>(local) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.loc[j] = ldg_at<NT>(l4, j * kWave + lane);
+        }
+#pragma unroll
+        for (int k = 0; k < KT; ++k) sl.sw[k] = p.scales[k][u >> block_shift];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.w[k][j] = ldg_at<NT>(c4, j * kWave + lane);
+        }
+    };
+    auto process = [&](uint32_t u, Slot &sl) {
+        float sc[KT];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[k])));
+        v4f *o4 = reinterpret_cast<v4f *>(out) + (size_t)u * (U / 4);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (LOCAL) {  // the sum starts at +0: a local -0 becomes +0
+                a.x = a.x + sl.loc[j].x;
+                a.y = a.y + sl.loc[j].y;
+                a.z = a.z + sl.loc[j].z;
+                a.w = a.w + sl.loc[j].w;
+            }
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                a.x = a.x + lut_at<0>(lut, sl.w[k][j], lane4) * sc[k];
+                a.y = a.y + lut_at<1>(lut, sl.w[k][j], lane4) * sc[k];
+                a.z = a.z + lut_at<2>(lut, sl.w[k][j], lane4) * sc[k];
+                a.w = a.w + lut_at<3>(lut, sl.w[k][j], lane4) * sc[k];
+            }
+            a.x = mean_of(a.x);
+            a.y = mean_of(a.y);
+            a.z = mean_of(a.z);
+            a.w = mean_of(a.w);
+            stg<NT>(o4 + j * kWave + lane, a);
+        }
+    };
+    uint32_t u = (uint32_t)first_unit(WPW);
+    Slot a, b;
+    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    if (u < n_full) {
+        for (;;) {
+            uint32_t nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
+    }
+    if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
+        const size_t start = (size_t)n_full * U;
+        const size_t blk = n_full >> block_shift;
+        for (uint32_t i = lane; i < tail_len; i += kWave) {
+            float acc = 0.0f;
+            if (LOCAL) acc = acc + local[start + i];
+#pragma unroll
+            for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+            out[start + i] = mean_of(acc);
+        }
+    }
+}
+
+}  // namespace

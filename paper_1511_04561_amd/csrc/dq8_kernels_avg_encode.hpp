@@ -1,0 +1,441 @@
+// dq8 kernels that average K workers' buffers in registers and store the mean and / or compress it
+// again (the second round of the gradient exchange).
+#pragma once
+#include "dq8_device.hpp"
+
+namespace {
+
+// Average of K workers' buffers (plus, optionally, a local fp32 array as the first term) with a
+// whole unit of 4096 elements held in one wavefront's registers: 16 quads of running sums per
+// lane, the workers added one after the other while the next worker's code words are in flight.
+// The means can be stored as fp32 (mean_out) and / or compressed again from the registers
+// (codes_out, scales_out; needs a unit to be a whole scale block, upb == 1): the second round of
+// the gradient exchange then reads K bytes and writes one byte per element instead of going
+// through an fp32 array in memory.  Arithmetic and order are those of k_decode_avg followed by
+// k_encode, so the results are identical to the two calls.
+// Two workgroups of WPW wavefronts share a compute unit (each holds the 64 KiB decode table),
+// so the register budget per lane is 512 / (WPW / 2): 170 for six wavefronts, 128 for eight.
+// The unit is QL * 256 elements (the host picks the smallest that holds a block, up to 4096).
+// RAGGED = true (chosen by the host when blocks are not whole units): a unit of fewer whole aligned
+// quads stays on the register path; a lane whose quad lies past the end loads the unit's last quad
+// instead (unconditional loads of valid memory; the maximum does not change) and stores nothing.
+// This costs a register per quad for the clamped offsets, which the kernel for whole units cannot spare.
+template <int QL, int NT, bool FASTDIV, int WPW, bool RAGGED>
+__global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+                                                          const float *__restrict__ local, size_t n, size_t B,
+                                                          size_t nb, size_t upb, size_t n_units, size_t n_waves,
+                                                          float *__restrict__ mean_out, float *__restrict__ scales_out,
+                                                          uint8_t *__restrict__ codes_out)
+{
+    static_assert(WPW >= 4, "the decode table is filled by 256 threads");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint32_t bucket_lds[];
+    constexpr int Q = QL;
+    constexpr int U = QL * 4 * kWave;
+    const int terms = K + (local ? 1 : 0);
+    const float fk = (float)terms;
+    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    load_lut(tab, lut);
+    Search sr = make_search(bucket_lds, tab[kLoKeyOff], tab[kNBucketOff]);
+    if (codes_out) sr = load_bucket_table(tab, bucket_lds, kWave * WPW);
+    __syncthreads();
+    for (size_t u = first_unit(WPW); u < n_units; u += n_waves) {
+        const Unit un = unit_of<U>(u, n, B, nb, upb);
+        bool aligned = true;  // 128-bit accesses to the fp32 arrays and 32-bit ones to the codes are possible
+        for (int k = 0; k < K; ++k) aligned = aligned && (((uintptr_t)(p.codes[k] + un.start) & 3) == 0);
+        if (local) aligned = aligned && (((uintptr_t)(local + un.start) & 15) == 0);
+        if (mean_out) aligned = aligned && (((uintptr_t)(mean_out + un.start) & 15) == 0);
+        if (codes_out) aligned = aligned && (((uintptr_t)(codes_out + un.start) & 3) == 0);
+        const bool fast = aligned && (RAGGED ? (un.len >= 4 && (un.len & 3) == 0) : un.len == (uint32_t)U);
+        if (fast) {
+            const uint32_t nq = un.len >> 2, last = nq - 1;
+            auto qi = [&](int j) {  // this lane's j-th quad, clamped to the unit
+                const uint32_t i = j * kWave + lane;
+                return RAGGED ? (i < last ? i : last) : i;
+            };
+            v4f acc[Q];
+            uint32_t wa[Q], wb[Q];
+            auto load_w = [&](uint32_t(&w)[Q], int k) {
+                const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) w[j] = ldg_at<NT>(c4, qi(j));  // scalar base + 32-bit offset
+            };
+            auto add_w = [&](const uint32_t(&w)[Q], int k) {
+                const float s = p.scales[k][un.block];
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lut_at<0>(lut, w[j], lane4) * s;
+                    acc[j].y = acc[j].y + lut_at<1>(lut, w[j], lane4) * s;
+                    acc[j].z = acc[j].z + lut_at<2>(lut, w[j], lane4) * s;
+                    acc[j].w = acc[j].w + lut_at<3>(lut, w[j], lane4) * s;
+                }
+                // pin the sums here, or the compiler defers them and holds the products of several workers
+#pragma unroll
+                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+            };
+            if (K > 0) load_w(wa, 0);
+            if (local) {
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = ldg_at<NT>(l4, qi(j));
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                    acc[j].x = 0.0f + acc[j].x;
+                    acc[j].y = 0.0f + acc[j].y;
+                    acc[j].z = 0.0f + acc[j].z;
+                    acc[j].w = 0.0f + acc[j].w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            for (int k = 0; k < K; k += 2) {
+                const bool more = k + 1 < K;
+                if (more) load_w(wb, k + 1);
+                add_w(wa, k);
+                if (more) {
+                    if (k + 2 < K) load_w(wa, k + 2);
+                    add_w(wb, k + 1);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
+            }
+            if (mean_out) {
+                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j)
+                    if (!RAGGED || j * kWave + lane < nq) stg<NT>(o4 + j * kWave + lane, acc[j]);
+            }
+            if (codes_out) {
+                float fm = 0.0f;
+#pragma unroll
+                for (int j = 0; j < Q; ++j) fm = max4_abs(acc[j], fm);
+                const float s = u2f(wave_max_u32(f2u(fm)));
+                if (lane == 0) scales_out[un.block] = s;
+                const float d = s == 0.0f ? 1.0f : s;
+                const float r = 1.0f / d;
+                const bool recip = reciprocal_ok(d);
+                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
+                    if (!RAGGED || j * kWave + lane < nq) stg<1>(c4 + j * kWave + lane, cw);
+                }
+            }
+        } else {
+            // A misaligned unit or one that is not whole quads.  Whole quads where the addresses allow (lanes take quads lane,
+            // lane + 64, ...), the remaining elements one by one.  The means are formed again for each use
+            // (store, maximum, compression) rather than kept.
+            const uint32_t nq = aligned ? un.len >> 2 : 0;
+            const uint32_t done = nq << 2;
+            auto mean_at = [&](uint32_t i) {
+                float a = 0.0f;
+                if (local) a = a + local[un.start + i];
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+                return mean_of(a);
+            };
+            auto mean_quad = [&](uint32_t q) {
+                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (local) {
+                    const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + un.start) + q);
+                    a.x = a.x + l.x;
+                    a.y = a.y + l.y;
+                    a.z = a.z + l.z;
+                    a.w = a.w + l.w;
+                }
+                for (int k = 0; k < K; ++k) {
+                    const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
+                    const float s = p.scales[k][un.block];
+                    a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
+                    a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
+                    a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
+                    a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
+                }
+                a.x = mean_of(a.x);
+                a.y = mean_of(a.y);
+                a.z = mean_of(a.z);
+                a.w = mean_of(a.w);
+                return a;
+            };
+            if (mean_out) {
+                v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
+                for (uint32_t q = lane; q < nq; q += kWave) stg<NT>(o4 + q, mean_quad(q));
+                for (uint32_t i = done + lane; i < un.len; i += kWave) mean_out[un.start + i] = mean_at(i);
+            }
+            if (codes_out) {
+                float fm = 0.0f;
+                for (uint32_t q = lane; q < nq; q += kWave) fm = max4_abs(mean_quad(q), fm);
+                uint32_t m = f2u(fm);
+                for (uint32_t i = done + lane; i < un.len; i += kWave) {
+                    const uint32_t a = abs_bits(mean_at(i));
+                    m = m > a ? m : a;
+                }
+                const float s = u2f(wave_max_u32(m));
+                if (lane == 0) scales_out[un.block] = s;
+                const float d = s == 0.0f ? 1.0f : s;
+                const float r = 1.0f / d;
+                const bool recip = reciprocal_ok(d);
+                uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
+                for (uint32_t q = lane; q < nq; q += kWave) stg<1>(c4 + q, encode_quad<FASTDIV>(sr, mean_quad(q), d, r, recip));
+                for (uint32_t i = done + lane; i < un.len; i += kWave)
+                    codes_out[un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(i), d, r, recip);
+            }
+        }
+    }
+}
+
+// The same average-then-compress round for K = 2, 4 or 8 workers at full speed.  A team of four
+// wavefronts owns a unit of 4096 elements (one scale block): every lane holds four quads of
+// running sums and K x 4 code words.  The code words are one register set that is refilled
+// in place: as soon as worker k's words of the current unit have been decoded and added, the
+// loads of worker k's words of the team's next unit are issued into the same registers, so
+// loads are in flight all through the reduction to the block maximum (wave reduction, then one
+// LDS exchange between the team's wavefronts) and the compression from the registers.
+// TEAMS teams share a workgroup and its tables; the workgroup barrier that separates the
+// exchange of the maxima from their use is executed by every wavefront the same number of
+// times (`iters`), whether or not its team still has a unit.
+// RAGGED = true (chosen by the host for blocks shorter than 4096): a unit of fewer whole aligned quads
+// takes the register path as well.
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED>
+struct AvgTeam {
+    static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
+
+    WorkerPtrs p;
+    const float *local;
+    float *scales_out;
+    uint8_t *codes_out;
+    size_t n, B, nb, n_units;
+    const float *lut;
+    uint32_t *slots;
+    Search sr;
+    uint32_t lane4, lane, team, wv, tl, phase;
+    float fk, rk;
+    bool pow2;
+    uint32_t w[KT][Q];  // code words: of the current unit until used, then of the next one
+
+    struct Slot {
+        Unit un;
+        bool active, fast;
+    };
+
+    __device__ __forceinline__ float mean_of(float acc) const { return pow2 ? acc * rk : acc / fk; }
+
+    // Element i of the unit, the slow way.
+    __device__ __forceinline__ float mean_at(const Unit &un, uint32_t i) const
+    {
+        float a = 0.0f;
+        if (local) a = a + local[un.start + i];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+        return mean_of(a);
+    }
+
+    // Geometry of unit u and whether it can take the register path.
+    __device__ __forceinline__ void open(size_t u, Slot &sl) const
+    {
+        sl.active = u < n_units;
+        sl.fast = false;
+        if (!sl.active) return;
+        sl.un = unit_of<kUnit>(u, n, B, nb, 1);
+        // whole aligned quads: a short unit takes the register path too (see load_worker)
+        bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == kUnit) &&
+                 (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
+#pragma unroll
+        for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
+        if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
+        sl.fast = f;
+    }
+
+    // This lane's j-th quad of the unit; WHOLE promises a unit of 4096 elements, otherwise a quad past the
+    // end of a shorter unit becomes the unit's last one (an unconditional load of valid memory whose result
+    // is not stored and cannot change the maximum).
+    template <bool WHOLE>
+    __device__ __forceinline__ uint32_t quad_of(const Slot &sl, int j) const
+    {
+        const uint32_t i = j * kWg + tl;
+        if (WHOLE || !RAGGED) return i;
+        const uint32_t last = (sl.un.len >> 2) - 1;
+        return i < last ? i : last;
+    }
+
+    template <bool WHOLE>
+    __device__ __forceinline__ void load_worker(const Slot &sl, int k)
+    {
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, quad_of<WHOLE>(sl, j));
+    }
+
+    __device__ __forceinline__ void load_all(const Slot &sl)
+    {
+        if (sl.fast) {
+#pragma unroll
+            for (int k = 0; k < KT; ++k) load_worker<false>(sl, k);
+        }
+    }
+
+    // Processes unit `sl`, whose code words are in w if it is fast, and leaves the words of `nx` there.
+    // STEADY: the caller knows that both units exist and are whole and aligned (true for all but a
+    // team's last two units when the host found the buffers aligned), so nothing here is
+    // conditional and the compiler waits for exactly the loads each step needs.
+    template <bool STEADY>
+    __device__ __forceinline__ void process(const Slot &sl, const Slot &nx)
+    {
+        v4f acc[Q];
+        uint32_t m = 0;
+        if (STEADY || (sl.active && sl.fast)) {
+            if (local) {  // not prefetched: the code words take the registers
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                    const v4f l = ldg<NT>(l4 + quad_of<STEADY>(sl, j));
+                    acc[j].x = 0.0f + l.x;
+                    acc[j].y = 0.0f + l.y;
+                    acc[j].z = 0.0f + l.z;
+                    acc[j].w = 0.0f + l.w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            float sc[KT];  // the K scales of this block, moved to scalar registers
+#pragma unroll
+            for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(p.scales[k][sl.un.block])));
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lut_at<0>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].y = acc[j].y + lut_at<1>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].z = acc[j].z + lut_at<2>(lut, w[k][j], lane4) * sc[k];
+                    acc[j].w = acc[j].w + lut_at<3>(lut, w[k][j], lane4) * sc[k];
+                }
+                // Pin the sums here.  Otherwise the compiler starts the lookups of every worker
+                // at once and holds all K x 16 products in registers until the ordered sums get
+                // to them, which costs a wavefront per SIMD.
+#pragma unroll
+                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place
+            }
+            float fm = 0.0f;
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
+                fm = max4_abs(acc[j], fm);
+            }
+            m = f2u(fm);
+        } else {
+            if (sl.active) {
+                for (uint32_t i = tl; i < sl.un.len; i += kWg) {
+                    const uint32_t a = abs_bits(mean_at(sl.un, i));
+                    m = m > a ? m : a;
+                }
+            }
+            load_all(nx);
+        }
+        m = wave_max_u32(m);
+        uint32_t *sp = slots + (phase * TEAMS + team) * kWavesPerWg;
+        if (lane == 0) sp[wv] = m;
+        __syncthreads();
+        {
+            const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
+            m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+        }
+        phase ^= 1;  // the other half of the slots next time: one barrier per unit is enough
+        if (!STEADY && !sl.active) return;
+        const float s = u2f(m);
+        if (tl == 0) scales_out[sl.un.block] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        if (STEADY || sl.fast) {
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
+                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
+            }
+        } else {
+            for (uint32_t i = tl; i < sl.un.len; i += kWg)
+                codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);
+        }
+    }
+};
+
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED>
+__global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
+                                                            const float *__restrict__ local, size_t n, size_t B, size_t nb,
+                                                            size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
+                                                            float *__restrict__ scales_out, uint8_t *__restrict__ codes_out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
+    constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
+    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED>;
+    Avg e;
+    e.p = p;
+    e.local = local;
+    e.scales_out = scales_out;
+    e.codes_out = codes_out;
+    e.n = n;
+    e.B = B;
+    e.nb = nb;
+    e.n_units = n_units;
+    e.lut = lut;
+    e.slots = dyn_lds;
+    e.lane = threadIdx.x & 63;
+    e.lane4 = e.lane * 4;
+    const uint32_t wave = wave_in_wg();
+    e.team = wave / kWavesPerWg;
+    e.wv = wave % kWavesPerWg;
+    e.tl = threadIdx.x & (kWg - 1);  // lane within the team
+    e.phase = 0;
+    const int terms = KT + (local ? 1 : 0);
+    e.fk = (float)terms;
+    e.rk = 1.0f / e.fk;
+    e.pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    size_t u = (size_t)blockIdx.x * TEAMS + e.team;
+    typename Avg::Slot a, b;
+    e.open(u, a);
+    e.load_all(a);  // the first loads are in flight while the tables are copied
+    load_lut(tab, lut);
+    {
+        e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWg * TEAMS);
+        if (!REMAP) e.sr.remap = nullptr;  // a type without a rank-to-code table: no test for one in the loop
+    }
+    __syncthreads();
+    // `steady` (even) leading iterations in which this and the next unit of every team are whole
+    // aligned units, then the general ones.
+    uint32_t it = 0;
+    for (; it < steady; it += 2) {
+        e.open(u + n_teams, b);
+        e.template process<true>(a, b);
+        u += n_teams;
+        e.open(u + n_teams, a);
+        e.template process<true>(b, a);
+        u += n_teams;
+    }
+    for (; it < iters; it += 2) {
+        e.open(u + n_teams, b);
+        e.template process<false>(a, b);
+        u += n_teams;
+        if (it + 1 >= iters) break;
+        e.open(u + n_teams, a);
+        e.template process<false>(b, a);
+        u += n_teams;
+    }
+}
+
+}  // namespace
