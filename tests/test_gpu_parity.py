@@ -360,6 +360,48 @@ def test_decode_avg_encode(dq8, kind, K, with_local):
         gs.check("avg->encode scales")
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_through_every_call(dq8, seed):
+    """Seeded random sizes, block lengths, pointer offsets, worker counts and data types through every call:
+    the launch logic picks unit sizes and kernel variants from these, so this sweeps their combinations."""
+    rng = np.random.Generator(np.random.PCG64(8800 + seed))
+    for case in range(10):
+        n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 6000), rng.integers(6000, 40000)]))
+        pick = rng.integers(0, 6)
+        block = [0, int(rng.integers(1, n + 1)), 4 * int(rng.integers(1, max(2, n // 4 + 1))),
+                 1 << int(rng.integers(0, 14)), 4096, int(rng.integers(1, 9)) * 1000][pick]
+        kind = int(rng.integers(0, 4))
+        x_off, c_off = int(rng.integers(0, 4)) * int(rng.integers(0, 2)), int(rng.integers(0, 4)) * int(rng.integers(0, 2))
+        K = int(rng.choice([1, 2, 3, 4, 5, 8, 9]))
+        with_local = bool(rng.integers(0, 2))
+        tag = "random seed=%d case=%d n=%d block=%d kind=%d x_off=%d c_off=%d K=%d local=%d" % (
+            seed, case, n, block, kind, x_off, c_off, K, with_local)
+        x = (rng.standard_normal(n) * np.exp(rng.uniform(-9, 2, n))).astype(np.float32)
+        x[rng.random(n) < 0.05] = 0.0
+        check_encode_decode(dq8, kind, x, block, x_off=x_off, c_off=c_off, tag=tag)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
+        local = (rng.standard_normal(n) * np.exp(rng.uniform(-8, 8, n))).astype(np.float32) if with_local else None
+        want = oracle.decode_accumulate_avg(kind, cl, sl, block, local=local)
+        go = Guarded(n, np.float32, x_off)
+        got = dq8.decode_accumulate_avg(kind, [dev(c, c_off) for c in cl], [dev(s_) for s_ in sl], block, out=go.t,
+                                        local=None if local is None else dev(local, x_off))
+        same_bits(got, want, "avg " + tag)
+        go.check("avg " + tag)
+        if (n if block == 0 or block > n else block) <= 4096:
+            want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)
+            gc, gs = Guarded(n, np.uint8, c_off), Guarded(nb, np.float32)
+            codes, scales = dq8.decode_avg_encode(kind, [dev(c, c_off) for c in cl], [dev(s_) for s_ in sl], block,
+                                                  local=None if local is None else dev(local, x_off), scales=gs.t,
+                                                  codes=gc.t)
+            same_bits(scales, want_scales, "avg->encode scales " + tag)
+            same_bits(codes, want_codes, "avg->encode codes " + tag)
+            gc.check("avg->encode " + tag)
+            gs.check("avg->encode " + tag)
+        check_error_stats(dq8, kind, x, block, tag=tag)
+
+
 def test_decode_avg_encode_rejects_blocks_that_do_not_fit(dq8):
     c = torch.zeros(10000, dtype=torch.uint8, device="cuda")
     s = torch.ones(1, device="cuda")
