@@ -145,3 +145,53 @@ def test_error_statistics_of_a_25_million_sample(dq8):
         # search gives about 0.75 of the paper's errors on every row
         paper = 2.46 if kind == oracle.DYNAMIC_TREE else 6.89
         assert 0.6 < 100 * got_means[1] / paper < 0.9
+
+
+def test_more_than_two_to_the_32_elements(dq8):
+    """Sizes beyond 32-bit element indices: 2^32 + 3 blocks + 17 elements (17 GB of fp32 on the device).
+    The input is generated on the device from a seed; the oracle checks sampled blocks, among them the first,
+    the ragged last and the ones on both sides of element 2^32."""
+    n = (1 << 32) + 3 * B + 17
+    nb = (n + B - 1) // B
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+    x = torch.empty(n, dtype=torch.float32, device="cuda")
+    step = 1 << 28
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        x[lo:hi].normal_(0.0, 1e-3, generator=gen)
+    print("2^32+: generated", flush=True)
+    codes, scales = dq8.encode(KIND, x, B)
+    amax = dq8.absmax(x, B)
+    torch.cuda.synchronize()
+    assert torch.equal(amax, scales)
+    out = dq8.decode(KIND, codes, scales, B)
+    whole = dq8.absmax(x, 0)
+    torch.cuda.synchronize()
+    print("2^32+: kernels done", flush=True)
+    assert float(whole[0]) == float(scales.max())
+    rng = np.random.Generator(np.random.PCG64(99))
+    edge = (1 << 32) // B
+    blocks = sorted(set([0, 1, nb - 2, nb - 1, edge - 1, edge, edge + 1] + [int(b) for b in rng.integers(0, nb, 40)]))
+    for b in blocks:
+        lo, hi = b * B, min(n, (b + 1) * B)
+        xb = x[lo:hi].cpu().numpy()
+        wc, ws = oracle.encode(KIND, xb, 0)
+        assert codes[lo:hi].cpu().numpy().tobytes() == wc.tobytes(), "codes of block %d" % b
+        assert scales[b:b + 1].cpu().numpy().tobytes() == ws.tobytes(), "scale of block %d" % b
+        assert out[lo:hi].cpu().numpy().tobytes() == oracle.decode(KIND, wc, ws, 0).tobytes(), "decoded block %d" % b
+    del out
+    # two workers: the same codes with the second worker's scales doubled; mean = 1.5 x the decoded value
+    scales2 = scales * 2
+    mean = dq8.decode_accumulate_avg(KIND, [codes, codes], [scales, scales2], B)
+    fc, fs = dq8.decode_avg_encode(KIND, [codes, codes], [scales, scales2], B)
+    torch.cuda.synchronize()
+    print("2^32+: averages done", flush=True)
+    for b in blocks:
+        lo, hi = b * B, min(n, (b + 1) * B)
+        cb_, sb, sb2 = codes[lo:hi].cpu().numpy(), scales[b:b + 1].cpu().numpy(), scales2[b:b + 1].cpu().numpy()
+        want = oracle.decode_accumulate_avg(KIND, [cb_, cb_], [sb, sb2], 0)
+        assert mean[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "mean of block %d" % b
+        wc, ws = oracle.encode(KIND, want, 0)
+        assert fc[lo:hi].cpu().numpy().tobytes() == wc.tobytes() and fs[b:b + 1].cpu().numpy().tobytes() == ws.tobytes(), \
+            "compressed mean of block %d" % b
