@@ -85,6 +85,9 @@ int dq8_codebook(int kind, float *cb256_host);
 /*
  * Uploads the tables of every data type to the current device (blocking).  Optional: the
  * other calls do it on first use.  Safe to call repeatedly and from several threads.
+ * Once the tables are on a device the other calls only launch kernels on the given stream (no
+ * allocation, no memset, no copy, no synchronisation), so they can be recorded into a HIP graph:
+ * call dq8_init() on the device before the capture starts.
  */
 int dq8_init(void);
 

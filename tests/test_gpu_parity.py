@@ -446,3 +446,70 @@ def test_errors_are_reported(dq8):
         rc = dq8.lib().dq8_decode(0, x.data_ptr(), x.data_ptr(), 100, 0, x.data_ptr(), None)
         dq8._check(rc, "dq8_decode")
     del codes
+
+
+def test_a_captured_graph_of_the_whole_path_replays_exactly(dq8):
+    """The calls launch kernels only (no allocation, no memset, no synchronisation once the tables are on the
+    device), so a caller can capture them in a HIP graph.  A graph of the whole path is replayed several times
+    on new inputs, with eager work and synchronisations in between, and every replay must equal the oracle."""
+    kind, B, K = oracle.DYNAMIC_TREE, 4096, 4
+    n = 6 * B + 1000
+    nb = oracle.dq8_oracle.n_blocks(n, B)
+    x = torch.zeros(n, device="cuda")
+    codes_in = [torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(K)]
+    scales_in = [torch.ones(nb, device="cuda") for _ in range(K)]
+    amax = torch.empty(nb, device="cuda")
+    codes, scales = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(nb, device="cuda")
+    dec, mean = torch.empty(n, device="cuda"), torch.empty(n, device="cuda")
+    rcodes, rscales = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(nb, device="cuda")
+    fcodes, fscales = torch.empty(n, dtype=torch.uint8, device="cuda"), torch.empty(nb, device="cuda")
+    whole = torch.empty(1, device="cuda")
+    stats, means = torch.empty((nb, 4), dtype=torch.float64, device="cuda"), torch.empty(2, dtype=torch.float64, device="cuda")
+    sscales = torch.empty(nb, device="cuda")
+
+    def path():
+        dq8.absmax(x, B, scales=amax)
+        dq8.absmax(x, 0, scales=whole)  # several units per block: zero fill + atomics
+        dq8.encode(kind, x, B, scales=scales, codes=codes)
+        dq8.decode(kind, codes, scales, B, out=dec)
+        dq8.decode_accumulate_avg(kind, codes_in, scales_in, B, out=mean)
+        dq8.encode(kind, mean, B, scales=rscales, codes=rcodes)
+        dq8.decode_avg_encode(kind, codes_in, scales_in, B, scales=fscales, codes=fcodes)
+        dq8.error_stats(kind, x, B, scales=sscales, stats=stats, means=means)
+
+    path()  # warm-up outside the capture: tables are uploaded on first use
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        path()
+    for rep in range(3):
+        xs = workloads.tensor(5, 2, worker=rep, limit=n)
+        enc = [oracle.encode(kind, workloads.tensor(5, 2, worker=10 * (rep + 1) + k, limit=n), B) for k in range(K)]
+        x.copy_(torch.from_numpy(xs))
+        for k in range(K):
+            codes_in[k].copy_(torch.from_numpy(enc[k][0]))
+            scales_in[k].copy_(torch.from_numpy(enc[k][1]))
+        for t in (amax, codes, scales, dec, mean, rcodes, rscales, fcodes, fscales, whole, sscales):
+            t.zero_()  # eager work between replays; stale results would show
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        print("graph replay %d" % rep, flush=True)
+        wc, ws = oracle.encode(kind, xs, B)
+        same_bits(amax, ws, "graph absmax")
+        same_bits(whole, oracle.absmax(xs, 0), "graph absmax of the whole array")
+        same_bits(codes, wc, "graph codes")
+        same_bits(scales, ws, "graph scales")
+        same_bits(dec, oracle.decode(kind, wc, ws, B), "graph decode")
+        wm = oracle.decode_accumulate_avg(kind, [e[0] for e in enc], [e[1] for e in enc], B)
+        same_bits(mean, wm, "graph mean")
+        wrc, wrs = oracle.encode(kind, wm, B)
+        same_bits(rcodes, wrc, "graph re-encoded codes")
+        same_bits(rscales, wrs, "graph re-encoded scales")
+        same_bits(fcodes, wrc, "graph one-call codes")
+        same_bits(fscales, wrs, "graph one-call scales")
+        wst, wmeans = oracle.error_stats(kind, xs, B)
+        got = stats.cpu().numpy()
+        assert got[:, 2:].tobytes() == wst[:, 2:].tobytes()
+        assert np.allclose(got[:, :2], wst[:, :2], rtol=1e-12, atol=0)
+        assert np.allclose(means.cpu().numpy(), wmeans, rtol=1e-12, atol=0)
