@@ -4,6 +4,8 @@ Codes and scales are compared byte for byte; decoded and averaged fp32 values ar
 as raw bit patterns (0 ulp, -0 differs from +0).  Every input comes from the seeded
 generators or from the oracle's own outputs, never from the HIP path.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -513,3 +515,27 @@ def test_a_captured_graph_of_the_whole_path_replays_exactly(dq8):
         assert got[:, 2:].tobytes() == wst[:, 2:].tobytes()
         assert np.allclose(got[:, :2], wst[:, :2], rtol=1e-12, atol=0)
         assert np.allclose(means.cpu().numpy(), wmeans, rtol=1e-12, atol=0)
+
+
+def test_table_2_script_rows(dq8):
+    """The script that reproduces the synthetic rows of Table 2 (Sec. 3.4): 16 rows, the dynamic tree has the
+    smallest relative error on every distribution (the paper's bold entries), ratios to the printed values
+    in the same band as the oracle's."""
+    from paper_1511_04561_amd import table2
+    rows = table2.rows(samples=400000, seed=7)
+    assert len(rows) == 16
+    by_dist = {}
+    for name, label, mae, mre, worst in rows:
+        by_dist.setdefault(name, {})[label] = mre
+        assert mae > 0 and worst >= mae
+    for name, d in by_dist.items():
+        assert min(d, key=d.get) == "8-bit dynamic tree", (name, d)
+    printed = {}
+    for l in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "table2_mre_all_types.txt")):
+        if l.strip() and l[0] != "#":
+            dist, typ, v, _ = l.split()
+            printed[(dist, typ)] = float(v)
+    names = {"8-bit dynamic tree": "dynamic_tree", "8-bit linear quant": "linear", "8-bit mantissa": "mantissa",
+             "8-bit static tree": "static_tree"}
+    for name, label, mae, mre, worst in rows:
+        assert 0.6 < mre / printed[(name, names[label])] < 0.9, (name, label, mre)
