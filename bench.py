@@ -39,7 +39,8 @@ N_SETS = 4
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs on this script, each scaled by what the same counter reads for the calibration
 # copy kernel: 1.99980 and 1.00000); the runs are recorded in profiles/hbm_traffic_bench_c5.md.
-MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481263 + 238675) * 1024)}
+GROUPS = 5  # per-kernel timing: median of this many groups of `steps` launches
+MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481269 + 238675) * 1024)}
 
 
 def algorithmic_bytes(n, nb):
@@ -56,6 +57,17 @@ def algorithmic_bytes(n, nb):
         # the approximation-error statistics with the scales handed in: one pass over the fp32 input
         "error_stats": 4 * n + 4 * nb + 32 * nb,
     }
+
+
+def device_info():
+    """Name, compute units and clocks of the GPU as the runtime reports them."""
+    import torch
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
+    for key in ("clock_rate", "memory_clock_rate"):
+        if hasattr(p, key):
+            info[key + "_MHz"] = round(getattr(p, key) / 1000.0, 1)
+    return info
 
 
 def cpu_baseline(host_buckets):
@@ -194,13 +206,16 @@ def main():
             continue
         for i in range(3):
             all_calls(i)[idx][1]()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for i in range(args.steps):
-            all_calls(3 + i)[idx][1]()
-        b.record()
-        torch.cuda.synchronize()
-        tot[nm] = a.elapsed_time(b)
+        groups = []
+        for g in range(GROUPS):  # median over several groups of `steps` consecutive launches
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for i in range(args.steps):
+                all_calls(3 + g * args.steps + i)[idx][1]()
+            b.record()
+            torch.cuda.synchronize()
+            groups.append(a.elapsed_time(b))
+        tot[nm] = sorted(groups)[len(groups) // 2]
     alg = algorithmic_bytes(n, nb)
     kernels = {}
     for nm in names:
@@ -237,6 +252,8 @@ def main():
                    "n": n, "block": BLOCK, "K": K_WORKERS, "kind": "dynamic_tree", "buffer_sets": N_SETS},
         "roofline": roof,
         "kernels": kernels,
+        "kernel_timing": "median of %d groups of %d consecutive launches between HIP events" % (GROUPS, args.steps),
+        "device": device_info(),
         "copy_kernel_GBps": round(copy_gbps, 1),
     }
     if not args.no_cpu_baseline:
