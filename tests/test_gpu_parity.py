@@ -539,3 +539,39 @@ def test_table_2_script_rows(dq8):
              "8-bit static tree": "static_tree"}
     for name, label, mae, mre, worst in rows:
         assert 0.6 < mre / printed[(name, names[label])] < 0.9, (name, label, mre)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_non_finite_inputs_stay_inside_their_block(dq8, kind):
+    """Inputs are required to be finite.  NaN and infinities must still leave every call in bounds (the code
+    search clamps its key) and must not disturb other blocks: those still equal the oracle."""
+    B = 4096
+    n = 5 * B + 100
+    x = workloads.edge_case_block("wide", n, seed=300 + kind)
+    bad = x.copy()
+    bad[B + 5] = np.nan
+    bad[B + 900] = -np.inf
+    bad[3 * B + 1] = np.inf
+    codes, scales = dq8.encode(kind, dev(bad), B)
+    amax = dq8.absmax(dev(bad), B)
+    out = dq8.decode(kind, codes, scales, B)
+    mean = dq8.decode_accumulate_avg(kind, [codes, codes], [scales, scales], B)
+    fc, fs = dq8.decode_avg_encode(kind, [codes, codes], [scales, scales], B)
+    stats, _ = dq8.error_stats(kind, dev(bad), B)
+    torch.cuda.synchronize()
+    wc, ws = oracle.encode(kind, x, B)
+    wo = oracle.decode(kind, wc, ws, B)
+    wm = oracle.decode_accumulate_avg(kind, [wc, wc], [ws, ws], B)
+    wfc, wfs = oracle.encode(kind, wm, B)
+    wst, _ = oracle.error_stats(kind, x, B)
+    for b in (0, 2, 4, 5):  # the blocks without a non-finite value
+        lo, hi = b * B, min(n, (b + 1) * B)
+        same_bits(codes[lo:hi], wc[lo:hi], "codes of a clean block")
+        same_bits(scales[b:b + 1], ws[b:b + 1], "scale of a clean block")
+        same_bits(amax[b:b + 1], ws[b:b + 1], "absmax of a clean block")
+        same_bits(out[lo:hi], wo[lo:hi], "decode of a clean block")
+        same_bits(mean[lo:hi], wm[lo:hi], "mean of a clean block")
+        same_bits(fc[lo:hi], wfc[lo:hi], "compressed mean of a clean block")
+        same_bits(fs[b:b + 1], wfs[b:b + 1], "scale of the compressed mean of a clean block")
+        got = stats[b].cpu().numpy()
+        assert got[2:].tobytes() == wst[b, 2:].tobytes() and np.allclose(got[:2], wst[b, :2], rtol=1e-12, atol=0)
