@@ -142,6 +142,29 @@ struct Tuning {
 };
 Tuning g_tune;
 
+// Elements per scale block: `block` as the caller passed it, the whole array for 0 or a longer block.
+size_t block_length(size_t n, size_t block) { return (block == 0 || block > n) ? n : block; }
+
+// Unit for the kernels in which units are pieces of a block: starting from *quads per lane, the largest
+// power of two of them whose unit (quads * 256 elements) is no longer than a block, at least one; every
+// halving doubles *waves_per_cu (up to 32) so that the bytes in flight per compute unit stay the same.
+void fit_unit_to_block(size_t block_len, int *quads, int *waves_per_cu)
+{
+    while (*quads > 1 && (size_t)*quads * 4 * kWave > block_len) {
+        *quads >>= 1;
+        *waves_per_cu = *waves_per_cu * 2 > 32 ? 32 : *waves_per_cu * 2;
+    }
+}
+
+// Unit for the kernels that hold a whole block in registers: the smallest power of two of elements
+// between 256 and 4096 that holds a block (4096 for longer blocks).
+size_t holding_unit(size_t block_len)
+{
+    size_t unit = 256;
+    while (unit < block_len && unit < (size_t)kUnit) unit <<= 1;
+    return unit;
+}
+
 struct Plan {
     size_t B, nb, upb, n_units, n_teams;
     unsigned grid;
@@ -152,7 +175,7 @@ Plan make_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, int w
                size_t unit = kUnit)
 {
     Plan p;
-    p.B = (block == 0 || block > n) ? n : block;
+    p.B = block_length(n, block);
     p.nb = (n + p.B - 1) / p.B;
     p.upb = (p.B + unit - 1) / unit;
     if (p.nb == 1) {
@@ -195,13 +218,10 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
 {
     // Units no longer than a block (so that whole blocks are whole units when the block is a power of two),
     // and the more wavefronts per compute unit the smaller the unit: the bytes in flight stay the same.
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
     int wpc = g_tune.amax_wpc;
-    while (q > 1 && (size_t)q * 4 * kWave > Bq) {
-        q >>= 1;
-        wpc = wpc * 2 > 32 ? 32 : wpc * 2;
-    }
+    fit_unit_to_block(Bq, &q, &wpc);
     Plan p = make_plan(n, block, st.cus, wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
     size_t per_wave = 0;
     if (p.upb > 1) {
@@ -238,9 +258,8 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.  4096: a team of four
     // wavefronts per unit, four quads per lane.  Smaller: one wavefront per unit (1, 2, 4 or 8 quads per lane) and
     // every wavefront slot of the compute units in use.
-    const size_t Bq = (block == 0 || block > n) ? n : block;
-    size_t unit = 256;
-    while (unit < Bq && unit < (size_t)kUnit) unit <<= 1;
+    const size_t Bq = block_length(n, block);
+    const size_t unit = holding_unit(Bq);
     const bool small = unit < (size_t)kUnit;
     const int wpb = small ? 1 : (g_tune.enc_wpb == 4 ? 4 : 1);
     const int ql = (int)(unit / (size_t)(4 * kWave * wpb));
@@ -351,7 +370,7 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
 int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                     size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
     const int teams = ragged ? 3 : ((g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2);
     const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
@@ -401,9 +420,8 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
                      size_t block, float *mean_out, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
     // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.
-    const size_t Bq = (block == 0 || block > n) ? n : block;
-    size_t unit = 256;
-    while (unit < Bq && unit < (size_t)kUnit) unit <<= 1;
+    const size_t Bq = block_length(n, block);
+    const size_t unit = holding_unit(Bq);
     // K = 2, 4, 8 and blocks that need a 4096-element unit: the team kernel
     if (codes_out && !mean_out && (K == 2 || K == 4 || K == 8) && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
@@ -547,7 +565,7 @@ int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, 
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     const size_t nbq = (n + Bq - 1) / Bq;
     if (overlaps(x, n * 4, codes, n) || overlaps(x, n * 4, scales, nbq * 4) || overlaps(codes, n, scales, nbq * 4))
         return fail(DQ8_ERR_ARG, "dq8_encode: buffers overlap");
@@ -574,13 +592,10 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     if (rc) return rc;
     // Units no longer than a block, and the smaller the unit the more wavefronts per compute unit (the bytes
     // in flight stay the same); 16 wavefronts share a workgroup's 64 KiB table when there are that many.
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 4 || g_tune.dec_q == 8) ? g_tune.dec_q : 16;
     int wpc = g_tune.dec_wpc;
-    while (q > 1 && (size_t)q * 4 * kWave > Bq) {
-        q >>= 1;
-        wpc = wpc * 2 > 32 ? 32 : wpc * 2;
-    }
+    fit_unit_to_block(Bq, &q, &wpc);
     const int wpw = q == 16 ? (g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4)) : (q == 8 ? 8 : 16);
     Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
@@ -629,10 +644,11 @@ int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float
     if (rc) return rc;
     const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
     const bool fixed_k = K == 2 || K == 4 || K == 8;
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
-    while (q > 1 && (size_t)q * 4 * kWave > Bq) q >>= 1;  // units no longer than a block
-    Plan p = make_plan(n, block, st->cus, g_tune.avg_wpc, 1, wpw, (size_t)q * 4 * kWave);
+    int wpc = g_tune.avg_wpc;
+    fit_unit_to_block(Bq, &q, &wpc);
+    Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     WorkerPtrs wp;
     std::memset(&wp, 0, sizeof(wp));
     for (int k = 0; k < K; ++k) {
@@ -686,7 +702,7 @@ int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const
     if (n == 0) return DQ8_OK;
     if (!local || !out) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
     if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     const size_t nbq = (n + Bq - 1) / Bq;
     if (overlaps(out, n * 4, local, n * 4)) return fail(DQ8_ERR_ARG, "%s: out overlaps local", who);
     WorkerPtrs wp;
@@ -715,7 +731,7 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     if (n == 0) return DQ8_OK;
     if (!out_scales || !out_codes) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
     if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     const size_t nbq = (n + Bq - 1) / Bq;
     if (Bq > (size_t)kUnit)
         return fail(DQ8_ERR_ARG, "%s: a scale block of %zu elements does not fit the registers of a wavefront (at most %d); "
@@ -746,7 +762,7 @@ int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *sca
     if (!x || !scales || !stats) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
     if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
     if (((uintptr_t)stats & 7) || ((uintptr_t)means & 7)) return fail(DQ8_ERR_ARG, "%s: stats and means must be 8-byte aligned", who);
-    const size_t Bq = (block == 0 || block > n) ? n : block;
+    const size_t Bq = block_length(n, block);
     const size_t nbq = (n + Bq - 1) / Bq;
     if (overlaps(stats, nbq * 32, x, n * 4) || overlaps(stats, nbq * 32, scales, nbq * 4) || overlaps(scales, nbq * 4, x, n * 4) ||
         (means && (overlaps(means, 16, x, n * 4) || overlaps(means, 16, scales, nbq * 4) || overlaps(means, 16, stats, nbq * 32))))
@@ -819,6 +835,19 @@ int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128)
     if (dq8::build_tables(kind, &t)) return fail(DQ8_ERR_KIND, "table construction failed for kind %d", kind);
     if (n_mag) *n_mag = t.n_mag;
     if (canon128) std::memcpy(canon128, t.canon, sizeof(t.canon));
+    return DQ8_OK;
+}
+
+int dq8_internal_units(size_t n, size_t block, int quads, int waves_per_cu, size_t *out4)
+{
+    if (!out4 || quads < 1 || quads > 16 || (quads & (quads - 1)) || waves_per_cu < 1 || n == 0)
+        return fail(DQ8_ERR_ARG, "dq8_internal_units: bad argument");
+    const size_t Bq = block_length(n, block);
+    fit_unit_to_block(Bq, &quads, &waves_per_cu);
+    out4[0] = Bq;
+    out4[1] = (size_t)quads * 4 * kWave;
+    out4[2] = (size_t)waves_per_cu;
+    out4[3] = holding_unit(Bq);
     return DQ8_OK;
 }
 

@@ -18,6 +18,12 @@ int dq8_internal_tables(int kind, float *cb256, float *thr127, uint32_t *lo_key,
 // thr127 of dq8_internal_tables has n_mag - 1 thresholds followed by +inf.
 int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128);
 
+// Unit sizes the launch logic derives from a block length: out4 = {elements per scale block, the unit for
+// kernels whose units are pieces of a block when they start from `quads` quads per lane (a power of two up
+// to 16) and `waves_per_cu` wavefronts per compute unit, the wavefronts per compute unit that go with it,
+// the unit for kernels that hold a whole block}.
+int dq8_internal_units(size_t n, size_t block, int quads, int waves_per_cu, size_t *out4);
+
 // Launch plan for n elements with the given block on a device with `cus` compute units,
 // `waves_per_cu` resident wavefronts per compute unit, teams of `wpb` wavefronts and units of
 // `unit` elements: out6 = {B, nb, units per block, units, teams, workgroups}.

@@ -262,3 +262,28 @@ def test_tuning_keys(L):
     assert L.dq8_internal_tune(b"enc_wpc", 8) == 0
     assert L.dq8_internal_tune(b"enc_wpc", 99) == 3
     assert L.dq8_internal_tune(b"nonsense", 1) == 3
+
+
+def test_units_follow_the_block_length(L):
+    """Units of the piecewise kernels are no longer than a block (and the wavefronts per compute unit grow as
+    they shrink); the kernels that hold a block take the smallest power of two that holds it, up to 4096."""
+    def units(n, block, quads=16, wpc=4):
+        out = (ctypes.c_size_t * 4)()
+        assert L.dq8_internal_units(ctypes.c_size_t(n), ctypes.c_size_t(block), quads, wpc, out) == 0
+        return list(out)
+    n = 1 << 20
+    assert units(n, 0) == [n, 4096, 4, 4096]            # one scale for the array
+    assert units(n, 2 * n) == [n, 4096, 4, 4096]        # a block longer than the array is the array
+    assert units(n, 4096) == [4096, 4096, 4, 4096]
+    assert units(n, 4095) == [4095, 2048, 8, 4096]
+    assert units(n, 3000) == [3000, 2048, 8, 4096]
+    assert units(n, 2048) == [2048, 2048, 8, 2048]
+    assert units(n, 1025) == [1025, 1024, 16, 2048]
+    assert units(n, 1000) == [1000, 512, 32, 1024]
+    assert units(n, 256) == [256, 256, 32, 256]
+    assert units(n, 100) == [100, 256, 32, 256]          # never below one quad per lane
+    assert units(n, 1) == [1, 256, 32, 256]
+    assert units(n, 100000) == [100000, 4096, 4, 4096]
+    assert units(n, 1000, quads=2, wpc=32) == [1000, 512, 32, 1024]
+    assert units(100, 0) == [100, 256, 32, 256]
+    assert L.dq8_internal_units(ctypes.c_size_t(n), ctypes.c_size_t(0), 3, 4, (ctypes.c_size_t * 4)()) == 3
