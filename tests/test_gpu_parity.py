@@ -575,3 +575,42 @@ def test_non_finite_inputs_stay_inside_their_block(dq8, kind):
         same_bits(fs[b:b + 1], wfs[b:b + 1], "scale of the compressed mean of a clean block")
         got = stats[b].cpu().numpy()
         assert got[2:].tobytes() == wst[b, 2:].tobytes() and np.allclose(got[:2], wst[b, :2], rtol=1e-12, atol=0)
+
+
+def test_calls_from_several_threads_on_their_own_streams(dq8):
+    """The library keeps no per-call state outside the caller's buffers: threads that launch on their own
+    streams at the same time (ctypes releases the interpreter lock during a call) get the same bits as the
+    oracle."""
+    import threading
+    kind, B, n, rounds = oracle.DYNAMIC_TREE, 4096, 9 * 4096 + 123, 12
+    xs = [workloads.tensor(5, 2, worker=40 + t, limit=n) for t in range(4)]
+    want = [oracle.encode(kind, x, B) for x in xs]
+    want_dec = [oracle.decode(kind, c, s, B) for c, s in want]
+    errors = []
+
+    def work(t):
+        try:
+            stream = torch.cuda.Stream()
+            xd = torch.from_numpy(xs[t]).cuda()
+            with torch.cuda.stream(stream):
+                for r in range(rounds):
+                    codes, scales = dq8.encode(kind, xd, B)
+                    out = dq8.decode(kind, codes, scales, B)
+                    mean = dq8.decode_accumulate_avg(kind, [codes, codes], [scales, scales], B)
+                    stream.synchronize()
+                    if codes.cpu().numpy().tobytes() != want[t][0].tobytes() or \
+                            scales.cpu().numpy().tobytes() != want[t][1].tobytes() or \
+                            out.cpu().numpy().tobytes() != want_dec[t].tobytes() or \
+                            mean.cpu().numpy().tobytes() != (want_dec[t] + np.float32(0)).tobytes():
+                        errors.append("thread %d round %d differs from the oracle" % (t, r))
+                        return
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append("thread %d: %r" % (t, e))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not any(th.is_alive() for th in threads), "a thread did not finish"
+    assert errors == []
