@@ -141,14 +141,20 @@ def test_mean_relative_errors_are_in_the_band_of_table_2(golden_dir):
     data = {"U(0,1)": rng.random(n), "N(0,1)": rng.standard_normal(n), "N(0,10^2)": 10 * rng.standard_normal(n),
             "N(0,0.2^2)": 0.2 * rng.standard_normal(n)}
     kind_of = {v: k for k, v in NAMES.items()}
-    ours = {}
+    ours, ours_abs = {}, {}
     for dist, typ, paper, off in rows:
         x = data[dist].astype(np.float32)
         scales = None if off == "-" else np.array([10.0 ** int(off)], np.float32)
         _, means = oracle.error_stats(kind_of[typ], x, 0, scales=scales)
         ours[(dist, typ)] = 100 * means[1]
+        ours_abs[(dist, typ)] = means[0]
         assert 0.6 < ours[(dist, typ)] / paper < 0.9, (dist, typ, ours[(dist, typ)], paper)
     for dist in data:
         best = min(NAMES.values(), key=lambda t: ours[(dist, t)])
         assert best == "dynamic_tree", (dist, ours)  # the paper's bold entries
     assert ours[("U(0,1)", "linear")] < ours[("U(0,1)", "static_tree")] < ours[("U(0,1)", "mantissa")]
+    # the absolute-error column: on the three normal samples the linear type has the smallest mean absolute
+    # error (bold in the paper), the dynamic tree comes second and the static-exponent types are far behind
+    for dist in ("N(0,1)", "N(0,10^2)", "N(0,0.2^2)"):
+        a = {t: ours_abs[(dist, t)] for t in NAMES.values()}
+        assert a["linear"] < a["dynamic_tree"] < min(a["mantissa"], a["static_tree"]), (dist, a)
