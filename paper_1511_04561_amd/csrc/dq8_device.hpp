@@ -261,6 +261,41 @@ __device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d
     return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
 }
 
+// Q quads at once: all 4 Q table lookups of the reciprocal path are issued before the first result is
+// used, so their latencies overlap; then each quad is checked, and redone with true divisions, on its own.
+template <bool FASTDIV, int Q>
+__device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q], float d, float r, bool recip,
+                                             uint32_t (&cw)[Q])
+{
+    if (FASTDIV && recip) {
+        uint32_t s[Q][4];
+#pragma unroll
+        for (int it = 0; it < Q; ++it) {
+            s[it][0] = search_sum(sr, v[it].x * r);
+            s[it][1] = search_sum(sr, v[it].y * r);
+            s[it][2] = search_sum(sr, v[it].z * r);
+            s[it][3] = search_sum(sr, v[it].w * r);
+        }
+#pragma unroll
+        for (int it = 0; it < Q; ++it) {
+            uint32_t k0 = near_key(s[it][0]), k1 = near_key(s[it][1]), k2 = near_key(s[it][2]), k3 = near_key(s[it][3]);
+            k0 = k0 < k1 ? k0 : k1;
+            k2 = k2 < k3 ? k2 : k3;
+            k0 = k0 < k2 ? k0 : k2;
+            if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) != 0) {
+                s[it][0] = search_sum(sr, v[it].x / d);
+                s[it][1] = search_sum(sr, v[it].y / d);
+                s[it][2] = search_sum(sr, v[it].z / d);
+                s[it][3] = search_sum(sr, v[it].w / d);
+            }
+            cw[it] = pack_codes(sr, s[it][0], s[it][1], s[it][2], s[it][3], v[it]);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < Q; ++it) cw[it] = encode_quad<false>(sr, v[it], d, r, recip);
+    }
+}
+
 template <bool FASTDIV>
 __device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float d, float r, bool recip)
 {

@@ -362,11 +362,11 @@ struct AvgTeam {
         const bool recip = reciprocal_ok(d);
         if (STEADY || sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
+            uint32_t cw[Q];
+            encode_quads<FASTDIV, Q>(sr, acc, d, r, recip, cw);
 #pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
-                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw);
-            }
+            for (int j = 0; j < Q; ++j)
+                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw[j]);
         } else {
             for (uint32_t i = tl; i < sl.un.len; i += kWg)
                 codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);

@@ -282,8 +282,10 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
         const float r = 1.0f / d;
         const bool recip = reciprocal_ok(d);
         uint32_t *c4 = reinterpret_cast<uint32_t *>(codes) + (size_t)u * (kUnit / 4);
+        uint32_t cw[Q];
+        encode_quads<FASTDIV, Q>(sr, v, d, r, recip, cw);
 #pragma unroll
-        for (int it = 0; it < Q; ++it) stg_at<NT>(c4, it * kWg + tl, encode_quad<FASTDIV>(sr, v[it], d, r, recip));
+        for (int it = 0; it < Q; ++it) stg_at<NT>(c4, it * kWg + tl, cw[it]);
     };
     uint32_t u = blockIdx.x;
     v4f a[Q], b[Q];
