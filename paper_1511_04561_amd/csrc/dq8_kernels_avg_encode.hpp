@@ -125,10 +125,17 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                 const float r = 1.0f / d;
                 const bool recip = reciprocal_ok(d);
                 uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + un.start);
+                constexpr int G = Q < 4 ? Q : 4;  // quads whose table lookups are issued together
 #pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    const uint32_t cw = encode_quad<FASTDIV>(sr, acc[j], d, r, recip);
-                    if (!RAGGED || j * kWave + lane < nq) stg<1>(c4 + j * kWave + lane, cw);
+                for (int g = 0; g < Q; g += G) {
+                    v4f vv[G];
+                    uint32_t cw[G];
+#pragma unroll
+                    for (int j = 0; j < G; ++j) vv[j] = acc[g + j];
+                    encode_quads<FASTDIV, G>(sr, vv, d, r, recip, cw);
+#pragma unroll
+                    for (int j = 0; j < G; ++j)
+                        if (!RAGGED || (g + j) * kWave + lane < nq) stg<1>(c4 + (g + j) * kWave + lane, cw[j]);
                 }
             }
         } else {

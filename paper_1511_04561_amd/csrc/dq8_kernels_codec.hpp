@@ -181,10 +181,19 @@ struct Encoder {
         if (sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(pc);
             const uint32_t nq = un.len >> 2;
+            // quads whose table lookups are issued together; the team variant runs six teams per compute unit
+            // and has no registers to spare for that
+            constexpr int G = WPB > 1 ? 1 : (Q < 4 ? Q : 4);
 #pragma unroll
-            for (int it = 0; it < Q; ++it) {
-                const uint32_t cw = encode_quad<FASTDIV>(sr, sl.v[it], d, r, recip);
-                if (it * TEAM + tl < nq) stg<NT>(c4 + it * TEAM + tl, cw);
+            for (int g = 0; g < Q; g += G) {
+                v4f vv[G];
+                uint32_t cw[G];
+#pragma unroll
+                for (int it = 0; it < G; ++it) vv[it] = sl.v[g + it];
+                encode_quads<FASTDIV, G>(sr, vv, d, r, recip, cw);
+#pragma unroll
+                for (int it = 0; it < G; ++it)
+                    if ((g + it) * TEAM + tl < nq) stg<NT>(c4 + (g + it) * TEAM + tl, cw[it]);
             }
         } else {
             // a misaligned unit or one that does not consist of whole quads: whole quads where the addresses allow (the lanes of the team take quads
