@@ -317,21 +317,37 @@ struct AvgTeam {
             float sc[KT];  // the K scales of this block, moved to scalar registers
 #pragma unroll
             for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(p.scales[k][sl.un.block])));
-#pragma unroll
-            for (int k = 0; k < KT; ++k) {
+            // The table lookups run one worker ahead of the sums: worker k + 1's sixteen lookups are issued
+            // before worker k's values are multiplied and added, so the LDS latency of one worker hides behind
+            // the arithmetic of the one before.  The scheduling barriers keep that order.
+            float lv[2][Q][4];
+            auto lookup = [&](int k, float(&dst)[Q][4]) {
 #pragma unroll
                 for (int j = 0; j < Q; ++j) {
-                    acc[j].x = acc[j].x + lut_at<0>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].y = acc[j].y + lut_at<1>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].z = acc[j].z + lut_at<2>(lut, w[k][j], lane4) * sc[k];
-                    acc[j].w = acc[j].w + lut_at<3>(lut, w[k][j], lane4) * sc[k];
+                    dst[j][0] = lut_at<0>(lut, w[k][j], lane4);
+                    dst[j][1] = lut_at<1>(lut, w[k][j], lane4);
+                    dst[j][2] = lut_at<2>(lut, w[k][j], lane4);
+                    dst[j][3] = lut_at<3>(lut, w[k][j], lane4);
                 }
-                // Pin the sums here.  Otherwise the compiler starts the lookups of every worker
-                // at once and holds all K x 16 products in registers until the ordered sums get
-                // to them, which costs a wavefront per SIMD.
+            };
+            lookup(0, lv[0]);
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                if (k + 1 < KT) lookup(k + 1, lv[(k + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lv[k & 1][j][0] * sc[k];
+                    acc[j].y = acc[j].y + lv[k & 1][j][1] * sc[k];
+                    acc[j].z = acc[j].z + lv[k & 1][j][2] * sc[k];
+                    acc[j].w = acc[j].w + lv[k & 1][j][3] * sc[k];
+                }
+                // Pin the sums here.  Otherwise the compiler holds the products of several workers in
+                // registers until the ordered sums get to them, which costs a wavefront per SIMD.
 #pragma unroll
                 for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place
+                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place: the lookups of worker k are issued
+                __builtin_amdgcn_sched_barrier(0);
             }
             float fm = 0.0f;
 #pragma unroll
