@@ -16,14 +16,16 @@
  *     length.  nb = ceil(n / block) scales are read or written; the last block may be short.
  *   - `hip_stream` is a hipStream_t passed as void*; NULL is the default stream.  Work is
  *     enqueued on that stream and the call returns without waiting for it.  The first call
- *     for a given device and kind uploads that kind's tables with a blocking copy; call
+ *     on a device uploads the tables of all data types with a blocking copy; call
  *     dq8_init() beforehand where that must not happen (e.g. before stream capture).
  *   - Every function returns DQ8_OK or an error code and never throws or aborts.  After an
  *     error dq8_last_error() describes it.  n == 0 is DQ8_OK and launches nothing.
  *   - Inputs must be finite.  With DQ8_SCALES_GIVEN the quotient x / scale must be finite.
- *   - Any pointer alignment and any n / block are accepted.  The fast kernels need
+ *   - Any pointer alignment and any n / block are accepted.  The fast paths need
  *     16-byte aligned `x` / `out`, 4-byte aligned `codes`, and block % 4 == 0 (or a single
- *     block); anything else runs on slower kernels with the same results.
+ *     block); anything else runs on slower paths with the same results.  Blocks of 4096
+ *     elements are the fastest; other lengths from 256 up come close (units follow the block),
+ *     shorter ones use a fraction of each wavefront.
  *   - Results are deterministic and independent of launch configuration: codes and scales
  *     are exact functions of the input, and the average adds workers in index order.
  *
