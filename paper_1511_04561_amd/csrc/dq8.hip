@@ -22,8 +22,8 @@
 // Files: dq8_device.hpp (access policies, reductions, unit geometry, code search, decode table),
 // dq8_kernels_codec.hpp (absmax, encode, decode), dq8_kernels_avg.hpp (decode-and-average),
 // dq8_kernels_avg_encode.hpp (average in registers, store and / or compress), dq8_kernels_stats.hpp
-// (error statistics), dq8_tables.cpp (host-side table construction); this file holds the launch
-// logic and the C ABI.
+// (error statistics), dq8_kernels_small.hpp (blocks shorter than 256 elements), dq8_tables.cpp
+// (host-side table construction); this file holds the launch logic and the C ABI.
 //
 // Built with -ffp-contract=off: the decode-and-average sum must round the product and the sum
 // separately.  Divisions are the compiler's correctly rounded ones.
@@ -42,6 +42,7 @@
 #include "dq8_kernels_avg.hpp"
 #include "dq8_kernels_avg_encode.hpp"
 #include "dq8_kernels_codec.hpp"
+#include "dq8_kernels_small.hpp"
 #include "dq8_kernels_stats.hpp"
 
 namespace {
@@ -214,11 +215,177 @@ int after_launch(const char *what)
     return DQ8_OK;
 }
 
+// ---- blocks of 4 .. 128 elements (powers of two): kernels that pack many blocks into a wavefront's unit
+
+constexpr int kSmallQ = 4;                          // quads per lane
+constexpr size_t kSmallUnit = kSmallQ * 4 * kWave;  // 1024 elements
+
+// Lanes per block for those kernels, 0 when the block length does not qualify.  Blocks of 256 elements
+// (a whole wavefront per block and row) qualify where the general kernel would hold the block in a
+// team's registers without pipelining: with_256.
+int small_block_lanes(size_t n, size_t block_len, bool with_256 = false)
+{
+    const size_t longest = with_256 ? 256 : 128;
+    if (block_len < 4 || block_len > longest || (block_len & (block_len - 1)) != 0 || block_len >= n) return 0;
+    return (int)(block_len / 4);
+}
+
+struct SmallPlan {
+    size_t n_units = 0, n_waves = 0, done = 0;  // whole units, wavefronts in the grid, elements they cover
+    unsigned grid = 0;
+};
+
+// Whole leading units of the array on `waves_per_cu` wavefronts per compute unit, `wpw` per workgroup.
+SmallPlan make_small_plan(size_t n, int cus, int waves_per_cu, int wpw)
+{
+    SmallPlan p;
+    p.n_units = n / kSmallUnit;
+    if (p.n_units == 0) return p;
+    size_t waves = (size_t)cus * (size_t)waves_per_cu;
+    const size_t per = (p.n_units + waves - 1) / waves;
+    waves = (p.n_units + per - 1) / per;
+    p.grid = (unsigned)((waves + wpw - 1) / wpw);
+    p.n_waves = (size_t)p.grid * wpw;
+    p.done = p.n_units * kSmallUnit;
+    return p;
+}
+
+#define DQ8_SMALL_G(lanes, CALL) \
+    switch (lanes) {             \
+    case 1: CALL(1); break;      \
+    case 2: CALL(2); break;      \
+    case 4: CALL(4); break;      \
+    case 8: CALL(8); break;      \
+    case 16: CALL(16); break;    \
+    default: CALL(32); break;    \
+    }
+#define DQ8_SMALL_G64(lanes, CALL) \
+    if (lanes == 64) {             \
+        CALL(64);                  \
+    } else {                       \
+        DQ8_SMALL_G(lanes, CALL)   \
+    }
+
+// Each of these launches the short-block kernel on the leading whole units when the block length and the
+// alignment allow it and returns in *done the number of elements covered (0: nothing was launched); the caller
+// hands the rest, which starts on a block boundary, to the general kernels.
+int small_absmax(const DeviceState &st, const float *x, size_t n, size_t block_len, float *scales, hipStream_t stream,
+                 size_t *done)
+{
+    *done = 0;
+    const int lanes = small_block_lanes(n, block_len);
+    if (!lanes || ((uintptr_t)x & 15)) return DQ8_OK;
+    const SmallPlan p = make_small_plan(n, st.cus, 32, kWavesPerWg);
+    if (!p.n_units) return DQ8_OK;
+#define DQ8_CALL(G) hipLaunchKernelGGL((k_small_absmax<kSmallQ, G>), dim3(p.grid), dim3(kWg), 0, stream, x, p.n_units, p.n_waves, scales)
+    DQ8_SMALL_G(lanes, DQ8_CALL)
+#undef DQ8_CALL
+    *done = p.done;
+    return after_launch("k_small_absmax");
+}
+
+int small_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block_len, float *scales, uint8_t *codes,
+                 bool given, hipStream_t stream, size_t *done)
+{
+    *done = 0;
+    const int lanes = small_block_lanes(n, block_len, true);
+    if (!lanes || ((uintptr_t)x & 15) || ((uintptr_t)codes & 3)) return DQ8_OK;
+    const SmallPlan p = make_small_plan(n, st.cus, 32, kWavesPerWg);
+    if (!p.n_units) return DQ8_OK;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = (size_t)st.search_words[kind] * sizeof(uint32_t);
+#define DQ8_CALL(G)                                                                                                      \
+    if (given)                                                                                                           \
+        hipLaunchKernelGGL((k_small_encode<kSmallQ, G, true>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, p.n_units,   \
+                           p.n_waves, scales, codes);                                                                    \
+    else                                                                                                                 \
+        hipLaunchKernelGGL((k_small_encode<kSmallQ, G, false>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, p.n_units,  \
+                           p.n_waves, scales, codes)
+    DQ8_SMALL_G64(lanes, DQ8_CALL)
+#undef DQ8_CALL
+    *done = p.done;
+    return after_launch("k_small_encode");
+}
+
+int small_decode(const DeviceState &st, int kind, const uint8_t *codes, const float *scales, size_t n, size_t block_len,
+                 float *out, hipStream_t stream, size_t *done)
+{
+    *done = 0;
+    const int lanes = small_block_lanes(n, block_len);
+    if (!lanes || ((uintptr_t)out & 15) || ((uintptr_t)codes & 3)) return DQ8_OK;
+    const SmallPlan p = make_small_plan(n, st.cus, 32, 16);
+    if (!p.n_units) return DQ8_OK;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+#define DQ8_CALL(G) \
+    hipLaunchKernelGGL((k_small_decode<kSmallQ, G, 16>), dim3(p.grid), dim3(kWave * 16), 0, stream, tab, codes, scales, p.n_units, p.n_waves, out)
+    DQ8_SMALL_G(lanes, DQ8_CALL)
+#undef DQ8_CALL
+    *done = p.done;
+    return after_launch("k_small_decode");
+}
+
+int small_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n, size_t block_len,
+              float *out, hipStream_t stream, size_t *done)
+{
+    *done = 0;
+    const int lanes = small_block_lanes(n, block_len);
+    bool ok = lanes != 0 && ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
+    if (!ok) return DQ8_OK;
+    const SmallPlan p = make_small_plan(n, st.cus, 32, 16);
+    if (!p.n_units) return DQ8_OK;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+#define DQ8_CALL(G) \
+    hipLaunchKernelGGL((k_small_avg<kSmallQ, G, 16>), dim3(p.grid), dim3(kWave * 16), 0, stream, tab, wp, K, local, p.n_units, p.n_waves, out)
+    DQ8_SMALL_G(lanes, DQ8_CALL)
+#undef DQ8_CALL
+    *done = p.done;
+    return after_launch("k_small_avg");
+}
+
+int small_avg_encode(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                     size_t block_len, float *scales_out, uint8_t *codes_out, hipStream_t stream, size_t *done)
+{
+    *done = 0;
+    const int lanes = small_block_lanes(n, block_len, true);
+    bool ok = lanes != 0 && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
+    if (!ok) return DQ8_OK;
+    const SmallPlan p = make_small_plan(n, st.cus, 32, 16);
+    if (!p.n_units) return DQ8_OK;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = (size_t)st.search_words[kind] * sizeof(uint32_t);
+#define DQ8_CALL(G)                                                                                                       \
+    hipLaunchKernelGGL((k_small_avg_encode<kSmallQ, G, 16>), dim3(p.grid), dim3(kWave * 16), lds, stream, tab, wp, K, local, \
+                       p.n_units, p.n_waves, scales_out, codes_out)
+    DQ8_SMALL_G64(lanes, DQ8_CALL)
+#undef DQ8_CALL
+    *done = p.done;
+    return after_launch("k_small_avg_encode");
+}
+
+// The worker pointers advanced by `done` elements (`done` a multiple of the block length).
+WorkerPtrs advance_workers(const WorkerPtrs &wp, int K, size_t done, size_t block_len)
+{
+    WorkerPtrs r = wp;
+    for (int k = 0; k < K; ++k) {
+        r.codes[k] = wp.codes[k] + done;
+        r.scales[k] = wp.scales[k] + done / block_len;
+    }
+    return r;
+}
+
 int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block, float *scales, hipStream_t stream)
 {
+    const size_t Bq = block_length(n, block);
+    size_t done = 0;
+    int rc0 = small_absmax(st, x, n, Bq, scales, stream, &done);
+    if (rc0 || done == n) return rc0;
+    x += done;  // the rest starts on a block boundary
+    scales += done / Bq;
+    n -= done;
     // Units no longer than a block (so that whole blocks are whole units when the block is a power of two),
     // and the more wavefronts per compute unit the smaller the unit: the bytes in flight stay the same.
-    const size_t Bq = block_length(n, block);
     int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
     int wpc = g_tune.amax_wpc;
     fit_unit_to_block(Bq, &q, &wpc);
@@ -345,6 +512,46 @@ int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n
     if (rc || !means) return rc;
     hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kMeansThreads), 0, stream, stats, p.nb, n, means);
     return after_launch("k_error_means");
+}
+
+int launch_decode(const DeviceState &st, int kind, const uint8_t *codes, const float *scales, size_t n, size_t block,
+                  float *out, hipStream_t stream)
+{
+    // Units no longer than a block, and the smaller the unit the more wavefronts per compute unit (the bytes
+    // in flight stay the same); 16 wavefronts share a workgroup's 64 KiB table when there are that many.
+    const size_t Bq = block_length(n, block);
+    int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 4 || g_tune.dec_q == 8) ? g_tune.dec_q : 16;
+    int wpc = g_tune.dec_wpc;
+    fit_unit_to_block(Bq, &q, &wpc);
+    const int wpw = q == 16 ? (g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4)) : (q == 8 ? 8 : 16);
+    Plan p = make_plan(n, block, st.cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const bool ragged = p.nb > 1 && p.B % ((size_t)q * 4 * kWave) != 0;  // blocks end inside units
+#define DQ8_DEC(Q, WPW, RG)                                                                                          \
+    hipLaunchKernelGGL((k_decode<Q, 2, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
+                       p.nb, p.upb, p.n_units, p.n_teams, out)
+#define DQ8_DEC_R(Q, WPW)        \
+    if (ragged) {                \
+        DQ8_DEC(Q, WPW, true);   \
+    } else {                     \
+        DQ8_DEC(Q, WPW, false);  \
+    }
+    switch (q) {
+    case 1: DQ8_DEC_R(1, 16) break;
+    case 2: DQ8_DEC_R(2, 16) break;
+    case 4: DQ8_DEC_R(4, 16) break;
+    case 8: DQ8_DEC_R(8, 8) break;
+    default:
+        switch (wpw) {
+        case 16: DQ8_DEC_R(16, 16) break;
+        case 8: DQ8_DEC_R(16, 8) break;
+        default: DQ8_DEC_R(16, 4) break;
+        }
+        break;
+    }
+#undef DQ8_DEC_R
+#undef DQ8_DEC
+    return after_launch("k_decode");
 }
 
 // Copies and checks the K (codes, scales) pairs of a call; `out` / `out_bytes` is a buffer the
@@ -519,6 +726,50 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     return after_launch("k_decode_avg_full");
 }
 
+// K-way decode-and-average into an fp32 array with the general kernels.
+int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, size_t n, size_t block, float *out,
+                      hipStream_t stream)
+{
+    const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
+    const bool fixed_k = K == 2 || K == 4 || K == 8;
+    const size_t Bq = block_length(n, block);
+    int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
+    int wpc = g_tune.avg_wpc;
+    fit_unit_to_block(Bq, &q, &wpc);
+    Plan p = make_plan(n, block, st.cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    if (fixed_k && g_tune.avg_lean) {
+        bool launched = false;
+        int rc = launch_avg_full(st, kind, wp, K, nullptr, n, p, out, stream, &launched);
+        if (rc || launched) return rc;
+    }
+#define DQ8_AVG(KT, Q, WPW)                                                                                      \
+    hipLaunchKernelGGL((k_decode_avg<KT, Q, 2, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
+                       p.nb, p.upb, p.n_units, p.n_teams, out)
+#define DQ8_AVG_W(KT, Q)                 \
+    switch (wpw) {                       \
+    case 16: DQ8_AVG(KT, Q, 16); break;  \
+    case 8: DQ8_AVG(KT, Q, 8); break;    \
+    default: DQ8_AVG(KT, Q, 4); break;   \
+    }
+#define DQ8_AVG_Q(KT)                    \
+    switch (q) {                         \
+    case 1: DQ8_AVG_W(KT, 1) break;      \
+    case 4: DQ8_AVG_W(KT, 4) break;      \
+    default: DQ8_AVG_W(KT, 2) break;     \
+    }
+    switch (K) {
+    case 2: DQ8_AVG_Q(2) break;
+    case 4: DQ8_AVG_Q(4) break;
+    case 8: DQ8_AVG_Q(8) break;
+    default: DQ8_AVG_W(0, 1) break;
+    }
+#undef DQ8_AVG_Q
+#undef DQ8_AVG_W
+#undef DQ8_AVG
+    return after_launch("k_decode_avg");
+}
+
 }  // namespace
 
 extern "C" {
@@ -571,6 +822,13 @@ int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, 
         return fail(DQ8_ERR_ARG, "dq8_encode: buffers overlap");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool given = (flags & DQ8_SCALES_GIVEN) != 0;
+    size_t done = 0;
+    rc = small_encode(*st, kind, x, n, Bq, scales, codes, given, stream, &done);
+    if (rc || done == n) return rc;
+    x += done;  // the rest starts on a block boundary
+    codes += done;
+    scales += done / Bq;
+    n -= done;
     const bool fused = !given && Bq <= (size_t)kUnit;  // the block fits one unit: absmax and encode in one kernel
     if (!given && !fused) {
         rc = launch_absmax(*st, x, n, block, scales, stream);
@@ -587,109 +845,43 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
     if (n == 0) return DQ8_OK;
     if (!codes || !scales || !out) return fail(DQ8_ERR_NULL, "dq8_decode: NULL pointer");
     if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "dq8_decode: n too large");
+    const size_t Bq = block_length(n, block);
+    const size_t nbq = (n + Bq - 1) / Bq;
+    if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, nbq * 4))
+        return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    // Units no longer than a block, and the smaller the unit the more wavefronts per compute unit (the bytes
-    // in flight stay the same); 16 wavefronts share a workgroup's 64 KiB table when there are that many.
-    const size_t Bq = block_length(n, block);
-    int q = (g_tune.dec_q == 1 || g_tune.dec_q == 2 || g_tune.dec_q == 4 || g_tune.dec_q == 8) ? g_tune.dec_q : 16;
-    int wpc = g_tune.dec_wpc;
-    fit_unit_to_block(Bq, &q, &wpc);
-    const int wpw = q == 16 ? (g_tune.dec_wpw == 16 ? 16 : (g_tune.dec_wpw == 8 ? 8 : 4)) : (q == 8 ? 8 : 16);
-    Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
-    if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, p.nb * 4))
-        return fail(DQ8_ERR_ARG, "dq8_decode: out overlaps an input");
-    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const bool ragged = p.nb > 1 && p.B % ((size_t)q * 4 * kWave) != 0;  // blocks end inside units
-#define DQ8_DEC(Q, WPW, RG)                                                                                          \
-    hipLaunchKernelGGL((k_decode<Q, 2, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
-                       p.nb, p.upb, p.n_units, p.n_teams, out)
-#define DQ8_DEC_R(Q, WPW)        \
-    if (ragged) {                \
-        DQ8_DEC(Q, WPW, true);   \
-    } else {                     \
-        DQ8_DEC(Q, WPW, false);  \
-    }
-    switch (q) {
-    case 1: DQ8_DEC_R(1, 16) break;
-    case 2: DQ8_DEC_R(2, 16) break;
-    case 4: DQ8_DEC_R(4, 16) break;
-    case 8: DQ8_DEC_R(8, 8) break;
-    default:
-        switch (wpw) {
-        case 16: DQ8_DEC_R(16, 16) break;
-        case 8: DQ8_DEC_R(16, 8) break;
-        default: DQ8_DEC_R(16, 4) break;
-        }
-        break;
-    }
-#undef DQ8_DEC_R
-#undef DQ8_DEC
-    return after_launch("k_decode");
+    size_t done = 0;
+    rc = small_decode(*st, kind, codes, scales, n, Bq, out, stream, &done);
+    if (rc || done == n) return rc;
+    return launch_decode(*st, kind, codes + done, scales + done / Bq, n - done, block, out + done, stream);
 }
 
 int dq8_decode_accumulate_avg(int kind, const uint8_t *const *codes, const float *const *scales, int K, size_t n,
                               size_t block, float *out, void *hip_stream)
 {
+    static const char who[] = "dq8_decode_accumulate_avg";
     int rc = check_kind(kind);
     if (rc) return rc;
-    if (K < 1 || K > DQ8_MAX_K) return fail(DQ8_ERR_ARG, "dq8_decode_accumulate_avg: K = %d outside 1..%d", K, DQ8_MAX_K);
+    if (K < 1 || K > DQ8_MAX_K) return fail(DQ8_ERR_ARG, "%s: K = %d outside 1..%d", who, K, DQ8_MAX_K);
     if (n == 0) return DQ8_OK;
-    if (!codes || !scales || !out) return fail(DQ8_ERR_NULL, "dq8_decode_accumulate_avg: NULL pointer");
-    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "dq8_decode_accumulate_avg: n too large");
+    if (!codes || !scales || !out) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
+    const size_t Bq = block_length(n, block);
+    const size_t nbq = (n + Bq - 1) / Bq;
+    WorkerPtrs wp;
+    rc = gather_workers(who, codes, scales, K, n, nbq, out, n * 4, &wp);
+    if (rc) return rc;
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
-    const bool fixed_k = K == 2 || K == 4 || K == 8;
-    const size_t Bq = block_length(n, block);
-    int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
-    int wpc = g_tune.avg_wpc;
-    fit_unit_to_block(Bq, &q, &wpc);
-    Plan p = make_plan(n, block, st->cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
-    WorkerPtrs wp;
-    std::memset(&wp, 0, sizeof(wp));
-    for (int k = 0; k < K; ++k) {
-        if (!codes[k] || !scales[k]) return fail(DQ8_ERR_NULL, "dq8_decode_accumulate_avg: worker %d has a NULL buffer", k);
-        if (overlaps(out, n * 4, codes[k], n) || overlaps(out, n * 4, scales[k], p.nb * 4))
-            return fail(DQ8_ERR_ARG, "dq8_decode_accumulate_avg: out overlaps worker %d", k);
-        wp.codes[k] = codes[k];
-        wp.scales[k] = scales[k];
-    }
-    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (fixed_k && g_tune.avg_lean) {
-        bool launched = false;
-        rc = launch_avg_full(*st, kind, wp, K, nullptr, n, p, out, stream, &launched);
-        if (rc || launched) return rc;
-    }
-#define DQ8_AVG(KT, Q, WPW)                                                                                      \
-    hipLaunchKernelGGL((k_decode_avg<KT, Q, 2, WPW>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, wp, K, n, p.B, \
-                       p.nb, p.upb, p.n_units, p.n_teams, out)
-#define DQ8_AVG_W(KT, Q)                 \
-    switch (wpw) {                       \
-    case 16: DQ8_AVG(KT, Q, 16); break;  \
-    case 8: DQ8_AVG(KT, Q, 8); break;    \
-    default: DQ8_AVG(KT, Q, 4); break;   \
-    }
-#define DQ8_AVG_Q(KT)                    \
-    switch (q) {                         \
-    case 1: DQ8_AVG_W(KT, 1) break;      \
-    case 4: DQ8_AVG_W(KT, 4) break;      \
-    default: DQ8_AVG_W(KT, 2) break;     \
-    }
-    switch (K) {
-    case 2: DQ8_AVG_Q(2) break;
-    case 4: DQ8_AVG_Q(4) break;
-    case 8: DQ8_AVG_Q(8) break;
-    default: DQ8_AVG_W(0, 1) break;
-    }
-#undef DQ8_AVG_Q
-#undef DQ8_AVG_W
-#undef DQ8_AVG
-    return after_launch("k_decode_avg");
+    size_t done = 0;
+    rc = small_avg(*st, kind, wp, K, nullptr, n, Bq, out, stream, &done);
+    if (rc || done == n) return rc;
+    return launch_decode_avg(*st, kind, advance_workers(wp, K, done, Bq), K, n - done, block, out + done, stream);
 }
 
 int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const float *const *scales, int K,
@@ -711,13 +903,23 @@ int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    size_t done = 0;
+    rc = small_avg(*st, kind, wp, K, local, n, Bq, out, stream, &done);
+    if (rc || done == n) return rc;
+    if (done) {  // the rest starts on a block boundary
+        wp = advance_workers(wp, K, done, Bq);
+        local += done;
+        out += done;
+        n -= done;
+    }
     if ((K == 2 || K == 4 || K == 8) && g_tune.avg_lean) {
         const Plan p = make_plan(n, block, st->cus, 1, 1);
         bool launched = false;
-        rc = launch_avg_full(*st, kind, wp, K, local, n, p, out, static_cast<hipStream_t>(hip_stream), &launched);
+        rc = launch_avg_full(*st, kind, wp, K, local, n, p, out, stream, &launched);
         if (rc || launched) return rc;
     }
-    return launch_avg_block(*st, kind, wp, K, local, n, block, out, nullptr, nullptr, static_cast<hipStream_t>(hip_stream));
+    return launch_avg_block(*st, kind, wp, K, local, n, block, out, nullptr, nullptr, stream);
 }
 
 int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *const *scales, int K, const float *local,
@@ -747,8 +949,18 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     DeviceState *st;
     rc = device_state(&st);
     if (rc) return rc;
-    return launch_avg_block(*st, kind, wp, K, local, n, block, nullptr, out_scales, out_codes,
-                            static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    size_t done = 0;
+    rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
+    if (rc || done == n) return rc;
+    if (done) {  // the rest starts on a block boundary
+        wp = advance_workers(wp, K, done, Bq);
+        if (local) local += done;
+        out_codes += done;
+        out_scales += done / Bq;
+        n -= done;
+    }
+    return launch_avg_block(*st, kind, wp, K, local, n, block, nullptr, out_scales, out_codes, stream);
 }
 
 int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *scales, unsigned flags, double *stats,

@@ -112,6 +112,9 @@ SHAPES = [  # (n, block)
     (20000, 10 ** 9),         # block larger than the array
     (100 * 64 + 20, 64), (50 * 256 + 8, 256), (7 * 1024 + 4, 1024), (9 * 516 + 2, 516),  # short aligned blocks:
     (3 * 12000 + 40, 12000),  # whole quads, partly with a tail; a block of two whole units and a short aligned one
+    # blocks of 4 .. 128 elements: many blocks per wavefront for the whole 1024-element units, the rest as above
+    (5 * 1024 + 300, 64), (3 * 1024, 4), (2 * 1024 + 8, 8), (4 * 1024 + 100, 16), (7 * 1024 + 96, 32),
+    (3 * 1024 + 640, 128), (40 * 1024 + 64, 64), (1024, 64), (1023, 64), (1025, 128),
 ]
 
 
@@ -279,7 +282,9 @@ AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (300
              (3 * 1536, 1536, 0),         # three units per block: not a power of two
              (3 * 2048 + 7, 2048, 0), (40 * 512, 512, 0), (511, 0, 0), (512, 0, 0), (513, 0, 0),
              (20 * 256 + 12, 256, 0), (64 * 64, 64, 0), (7 * 1000 + 4, 1000, 0), (5 * 516 + 2, 516, 0),
-             (3 * 1000, 1000, 2)]     # short blocks: aligned (whole quads), with a tail, and misaligned
+             (3 * 1000, 1000, 2),     # short blocks: aligned (whole quads), with a tail, and misaligned
+             (5 * 1024 + 300, 64, 0), (3 * 1024 + 12, 4, 0), (4 * 1024, 128, 0), (2 * 1024 + 64, 32, 1),
+             (6 * 1024 + 8, 8, 0), (2 * 1024 + 16, 16, 0)]  # blocks of 4 .. 128 elements
 
 
 @pytest.mark.parametrize("kind", KINDS)
