@@ -635,7 +635,7 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     const int ql = (int)(unit / (size_t)(4 * kWave));
     // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave
     const bool ragged = Bq < n && Bq % unit != 0;  // blocks end inside units
-    const int wpw = (ql == 16 && (ragged || g_tune.blk_wpw != 8)) ? 6 : 8;
+    const int wpw = ql <= 4 ? 16 : ((ql == 16 && (ragged || g_tune.blk_wpw != 8)) ? 6 : 8);
     Plan p = make_plan(n, block, st.cus, 2 * wpw, 1, wpw, unit);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = codes_out ? (size_t)st.search_words[kind] * sizeof(uint32_t) : 0;
@@ -649,9 +649,9 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
         DQ8_BLK(QL, WPW, false); \
     }
     switch (ql) {
-    case 1: DQ8_BLK_R(1, 8) break;
-    case 2: DQ8_BLK_R(2, 8) break;
-    case 4: DQ8_BLK_R(4, 8) break;
+    case 1: DQ8_BLK_R(1, 16) break;
+    case 2: DQ8_BLK_R(2, 16) break;
+    case 4: DQ8_BLK_R(4, 16) break;
     case 8: DQ8_BLK_R(8, 8) break;
     default:
         if (wpw == 8) {
