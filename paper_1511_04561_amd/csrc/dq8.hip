@@ -220,12 +220,11 @@ int after_launch(const char *what)
 constexpr int kSmallQ = 4;                          // quads per lane
 constexpr size_t kSmallUnit = kSmallQ * 4 * kWave;  // 1024 elements
 
-// Lanes per block for those kernels, 0 when the block length does not qualify.  Blocks of 256 elements
-// (a whole wavefront per block and row) qualify where the general kernel would hold the block in a
-// team's registers without pipelining: with_256.
-int small_block_lanes(size_t n, size_t block_len, bool with_256 = false)
+// Quads per block for those kernels, 0 when the block length does not qualify.  Blocks of 256 to 1024
+// elements (one, two or four whole rows of a unit) qualify in the kernels that have to hold a block, up to
+// the length from which the general kernel for that call is at least as fast: `longest`.
+int small_block_lanes(size_t n, size_t block_len, size_t longest = 128)
 {
-    const size_t longest = with_256 ? 256 : 128;
     if (block_len < 4 || block_len > longest || (block_len & (block_len - 1)) != 0 || block_len >= n) return 0;
     return (int)(block_len / 4);
 }
@@ -259,11 +258,15 @@ SmallPlan make_small_plan(size_t n, int cus, int waves_per_cu, int wpw)
     case 16: CALL(16); break;    \
     default: CALL(32); break;    \
     }
-#define DQ8_SMALL_G64(lanes, CALL) \
-    if (lanes == 64) {             \
-        CALL(64);                  \
-    } else {                       \
-        DQ8_SMALL_G(lanes, CALL)   \
+#define DQ8_SMALL_G256(lanes, CALL) \
+    if (lanes == 64) {              \
+        CALL(64);                   \
+    } else if (lanes == 128) {      \
+        CALL(128);                  \
+    } else if (lanes == 256) {      \
+        CALL(256);                  \
+    } else {                        \
+        DQ8_SMALL_G(lanes, CALL)    \
     }
 
 // Each of these launches the short-block kernel on the leading whole units when the block length and the
@@ -288,7 +291,7 @@ int small_encode(const DeviceState &st, int kind, const float *x, size_t n, size
                  bool given, hipStream_t stream, size_t *done)
 {
     *done = 0;
-    const int lanes = small_block_lanes(n, block_len, true);
+    const int lanes = small_block_lanes(n, block_len, 512);
     if (!lanes || ((uintptr_t)x & 15) || ((uintptr_t)codes & 3)) return DQ8_OK;
     const SmallPlan p = make_small_plan(n, st.cus, 32, kWavesPerWg);
     if (!p.n_units) return DQ8_OK;
@@ -301,7 +304,7 @@ int small_encode(const DeviceState &st, int kind, const float *x, size_t n, size
     else                                                                                                                 \
         hipLaunchKernelGGL((k_small_encode<kSmallQ, G, false>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, p.n_units,  \
                            p.n_waves, scales, codes)
-    DQ8_SMALL_G64(lanes, DQ8_CALL)
+    DQ8_SMALL_G256(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
     return after_launch("k_small_encode");
@@ -347,7 +350,7 @@ int small_avg_encode(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
                      size_t block_len, float *scales_out, uint8_t *codes_out, hipStream_t stream, size_t *done)
 {
     *done = 0;
-    const int lanes = small_block_lanes(n, block_len, true);
+    const int lanes = small_block_lanes(n, block_len, kSmallUnit);
     bool ok = lanes != 0 && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
     for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
     if (!ok) return DQ8_OK;
@@ -358,7 +361,7 @@ int small_avg_encode(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
 #define DQ8_CALL(G)                                                                                                       \
     hipLaunchKernelGGL((k_small_avg_encode<kSmallQ, G, 16>), dim3(p.grid), dim3(kWave * 16), lds, stream, tab, wp, K, local, \
                        p.n_units, p.n_waves, scales_out, codes_out)
-    DQ8_SMALL_G64(lanes, DQ8_CALL)
+    DQ8_SMALL_G256(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
     return after_launch("k_small_avg_encode");

@@ -1,5 +1,5 @@
-// dq8 kernels for short scale blocks: 4, 8, 16, 32, 64 or 128 elements per block (256 where a block has to be
-// held: compression and average-then-compress).
+// dq8 kernels for short scale blocks: 4, 8, 16, 32, 64 or 128 elements per block (up to 1024 where a block has
+// to be held: compression and average-then-compress; a block is then one, two or four whole rows of a unit).
 //
 // The other kernels give a wavefront one piece of one block at a time, which leaves most lanes idle
 // when a block has fewer than 256 elements.  Here a wavefront takes units of Q * 256 elements that
@@ -83,6 +83,9 @@ __global__ __launch_bounds__(kWg) void k_small_encode(const uint32_t *__restrict
                                                      uint8_t *__restrict__ codes)
 {
     constexpr int U = Q * 4 * kWave;
+    constexpr int R = G > kWave ? G / kWave : 1;  // rows of 64 quads per block
+    constexpr int GL = G > kWave ? kWave : G;     // lanes of a row that belong to one block
+    static_assert(Q % R == 0, "a block does not straddle units");
     extern __shared__ uint32_t lds[];
     const Search sr = load_bucket_table(tab, lds);
     __syncthreads();
@@ -94,17 +97,21 @@ __global__ __launch_bounds__(kWg) void k_small_encode(const uint32_t *__restrict
 #pragma unroll
         for (int j = 0; j < Q; ++j) v[j] = ldg_at<1>(p4, j * kWave + lane);
 #pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            const size_t blk = small_block_of<Q, G>(u, j, lane);
+        for (int j0 = 0; j0 < Q; j0 += R) {  // R rows of the unit share a block when a block is longer than a row
+            const size_t blk = small_block_of<Q, G>(u, j0, lane);
             float s;
             if (GIVEN) {
                 s = scales[blk];
             } else {
-                s = u2f(group_max_u32<G>(f2u(max4_abs(v[j], 0.0f))));
-                if (lane % G == 0) scales[blk] = s;
+                float fm = 0.0f;
+#pragma unroll
+                for (int r = 0; r < R; ++r) fm = max4_abs(v[j0 + r], fm);
+                s = u2f(group_max_u32<GL>(f2u(fm)));
+                if (lane % GL == 0) scales[blk] = s;
             }
             const float d = s == 0.0f ? 1.0f : s;  // a zero scale leaves the value as it is
-            stg_at<1>(c4, j * kWave + lane, encode_quad_own_scale(sr, v[j], d));
+#pragma unroll
+            for (int r = 0; r < R; ++r) stg_at<1>(c4, (j0 + r) * kWave + lane, encode_quad_own_scale(sr, v[j0 + r], d));
         }
     }
 }
@@ -211,6 +218,9 @@ __global__ __launch_bounds__(kWave * WPW) void k_small_avg_encode(const uint32_t
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t bucket_lds[];
     constexpr int U = Q * 4 * kWave;
+    constexpr int R = G > kWave ? G / kWave : 1;  // rows of 64 quads per block
+    constexpr int GL = G > kWave ? kWave : G;     // lanes of a row that belong to one block
+    static_assert(Q % R == 0, "a block does not straddle units");
     load_lut(tab, lut);
     const Search sr = load_bucket_table(tab, bucket_lds, kWave * WPW);
     __syncthreads();
@@ -257,10 +267,17 @@ __global__ __launch_bounds__(kWave * WPW) void k_small_avg_encode(const uint32_t
             acc[j].y = mean_of(acc[j].y);
             acc[j].z = mean_of(acc[j].z);
             acc[j].w = mean_of(acc[j].w);
-            const float s = u2f(group_max_u32<G>(f2u(max4_abs(acc[j], 0.0f))));
-            if (lane % G == 0) scales_out[small_block_of<Q, G>(u, j, lane)] = s;
+        }
+#pragma unroll
+        for (int j0 = 0; j0 < Q; j0 += R) {  // R rows of the unit share a block when a block is longer than a row
+            float fm = 0.0f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) fm = max4_abs(acc[j0 + r], fm);
+            const float s = u2f(group_max_u32<GL>(f2u(fm)));
+            if (lane % GL == 0) scales_out[small_block_of<Q, G>(u, j0, lane)] = s;
             const float d = s == 0.0f ? 1.0f : s;
-            stg_at<1>(c4, j * kWave + lane, encode_quad_own_scale(sr, acc[j], d));
+#pragma unroll
+            for (int r = 0; r < R; ++r) stg_at<1>(c4, (j0 + r) * kWave + lane, encode_quad_own_scale(sr, acc[j0 + r], d));
         }
     }
 }

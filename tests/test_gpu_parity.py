@@ -114,7 +114,8 @@ SHAPES = [  # (n, block)
     (3 * 12000 + 40, 12000),  # whole quads, partly with a tail; a block of two whole units and a short aligned one
     # blocks of 4 .. 128 elements: many blocks per wavefront for the whole 1024-element units, the rest as above
     (5 * 1024 + 300, 64), (3 * 1024, 4), (2 * 1024 + 8, 8), (4 * 1024 + 100, 16), (7 * 1024 + 96, 32),
-    (3 * 1024 + 640, 128), (40 * 1024 + 64, 64), (1024, 64), (1023, 64), (1025, 128),
+    (3 * 1024 + 640, 128), (40 * 1024 + 64, 64), (1024, 64), (1023, 64), (1025, 128), (9 * 512 + 100, 512),
+    (6 * 1024 + 24, 1024),
 ]
 
 
