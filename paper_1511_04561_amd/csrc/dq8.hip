@@ -117,6 +117,7 @@ struct Tuning {
     int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
+    int avg_chunk_wpc = 8;  //   wavefronts per compute unit of the kernel that takes the workers four at a time
     int avg_lean_wpw = 4;
     int copy_nt = 1;
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
@@ -669,8 +670,9 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     return after_launch("k_avg_block");
 }
 
-// K-way decode-and-average (K = 2, 4, 8; optional local term) of whole aligned units with a power-of-two
-// number of them per block (or a single block): the kernel without slow paths in its loop.
+// K-way decode-and-average (optional local term) of whole aligned units with a power-of-two number of them
+// per block (or a single block): the kernels without slow paths in their loops, one unrolled for K = 2, 4, 8,
+// one that takes any number of workers four at a time.
 // *launched = false (and nothing done) when the buffers do not qualify.
 int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                     const Plan &p, float *out, hipStream_t stream, bool *launched)
@@ -690,11 +692,54 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         while (((size_t)1 << shift) < upb_l) ++shift;
     }
     const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    if (K != 2 && K != 4 && K != 8) {
+        // Any other number of workers, CH at a time: the CH from 3 to 8 with the fewest empty places in the last
+        // chunk (an empty place repeats a load), the largest such CH; K = 0 (the local term alone) has no chunks.
+        int ch = K < 3 ? (K < 1 ? 1 : K) : 3;
+        for (int c = ch, waste = DQ8_MAX_K; c <= 8 && K >= 3; ++c) {
+            const int w = (K + c - 1) / c * c - K;
+            if (w <= waste) {
+                waste = w;
+                ch = c;
+            }
+        }
+        if (lq != 2) return DQ8_OK;
+        // eight wavefronts per compute unit measured best for every CH from 3 up
+        const int wpc = ch <= 2 ? 2 * g_tune.avg_chunk_wpc : g_tune.avg_chunk_wpc;
+        size_t waves = (size_t)st.cus * (size_t)wpc;
+        if (waves > n_full) waves = n_full;
+        const int cw = wpc >= 8 ? 8 : 4;  // wavefronts per workgroup (they share the decode table)
+        const unsigned grid = (unsigned)((waves + cw - 1) / cw);
+        const uint32_t n_waves = grid * (uint32_t)cw;
+#define DQ8_CHUNK(CH, WPW)                                                                                              \
+    hipLaunchKernelGGL((k_decode_avg_chunks<CH, 2, 2, WPW>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, K, local, \
+                       n_full, n_waves, shift, tail, out)
+#define DQ8_CHUNK_W(CH)       \
+    if (cw == 8) {            \
+        DQ8_CHUNK(CH, 8);     \
+    } else {                  \
+        DQ8_CHUNK(CH, 4);     \
+    }
+        switch (ch) {
+        case 1: DQ8_CHUNK_W(1) break;
+        case 2: DQ8_CHUNK_W(2) break;
+        case 3: DQ8_CHUNK_W(3) break;
+        case 4: DQ8_CHUNK_W(4) break;
+        case 5: DQ8_CHUNK_W(5) break;
+        case 6: DQ8_CHUNK_W(6) break;
+        case 7: DQ8_CHUNK_W(7) break;
+        default: DQ8_CHUNK_W(8) break;
+        }
+#undef DQ8_CHUNK_W
+#undef DQ8_CHUNK
+        *launched = true;
+        return after_launch("k_decode_avg_chunks");
+    }
     size_t waves = (size_t)st.cus * (size_t)g_tune.avg_lean_wpc;
     if (waves > n_full) waves = n_full;
     const unsigned grid = (unsigned)((waves + lw - 1) / lw);
     const uint32_t n_waves = grid * (uint32_t)lw;
-    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
 #define DQ8_AVGL(KT, Q, WPW, LOC)                                                                                     \
     hipLaunchKernelGGL((k_decode_avg_full<KT, Q, 2, WPW, LOC>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, local, \
                        n_full, n_waves, shift, tail, out)
@@ -741,7 +786,7 @@ int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int
     fit_unit_to_block(Bq, &q, &wpc);
     Plan p = make_plan(n, block, st.cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    if (fixed_k && g_tune.avg_lean) {
+    if (g_tune.avg_lean) {
         bool launched = false;
         int rc = launch_avg_full(st, kind, wp, K, nullptr, n, p, out, stream, &launched);
         if (rc || launched) return rc;
@@ -916,7 +961,7 @@ int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const
         out += done;
         n -= done;
     }
-    if ((K == 2 || K == 4 || K == 8) && g_tune.avg_lean) {
+    if (g_tune.avg_lean) {
         const Plan p = make_plan(n, block, st->cus, 1, 1);
         bool launched = false;
         rc = launch_avg_full(*st, kind, wp, K, local, n, p, out, stream, &launched);
@@ -1086,7 +1131,7 @@ int dq8_internal_tune(const char *key, int value)
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
-        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},

@@ -94,13 +94,24 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
                 const uint32_t nq = un.len >> 2;
                 for (uint32_t q = lane; q < nq; q += kWave) {
                     v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-                    for (int k = 0; k < K; ++k) {
-                        const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
-                        const float s = p.scales[k][un.block];
-                        a.x = a.x + lut_at<0>(lut, ww, lane4) * s;
-                        a.y = a.y + lut_at<1>(lut, ww, lane4) * s;
-                        a.z = a.z + lut_at<2>(lut, ww, lane4) * s;
-                        a.w = a.w + lut_at<3>(lut, ww, lane4) * s;
+                    for (int k0 = 0; k0 < K; k0 += 4) {  // four workers' loads in flight at a time
+                        uint32_t ww[4];
+                        float ss[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int k = k0 + i < K ? k0 + i : K - 1;  // past the last worker: a valid, unused load
+                            ww[i] = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + un.start) + q);
+                            ss[i] = p.scales[k][un.block];
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (k0 + i < K) {
+                                a.x = a.x + lut_at<0>(lut, ww[i], lane4) * ss[i];
+                                a.y = a.y + lut_at<1>(lut, ww[i], lane4) * ss[i];
+                                a.z = a.z + lut_at<2>(lut, ww[i], lane4) * ss[i];
+                                a.w = a.w + lut_at<3>(lut, ww[i], lane4) * ss[i];
+                            }
+                        }
                     }
                     a.x = mean_of(a.x);
                     a.y = mean_of(a.y);
@@ -226,6 +237,143 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
 #pragma unroll
             for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
             out[start + i] = mean_of(acc);
+        }
+    }
+}
+
+// K-way decode-and-average of whole, aligned units for any K (and an optional local fp32 first term): the
+// workers are taken CH at a time (the host picks the CH <= 8 that leaves the fewest empty places in the last
+// chunk).  Work items are (unit, chunk of CH workers) pairs in order; the code
+// words and scales of the next item are requested before the current one is added to the running sums, which
+// stay in registers from a unit's first chunk to its last.  Every request is unconditional (the item after
+// the last one is the last one again, a worker index past K - 1 is K - 1 with scale 0), so the compiler waits
+// for exactly the loads an item needs.  Geometry as in k_decode_avg_full.
+template <int CH, int Q, int NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+                                                                  const float *__restrict__ local, uint32_t n_full,
+                                                                  uint32_t n_waves, uint32_t block_shift,
+                                                                  uint32_t tail_len, float *__restrict__ out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int U = Q * 4 * kWave;
+    const int terms = K + (local ? 1 : 0);
+    const float fk = (float)terms;
+    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    const uint32_t n_chunks = (uint32_t)(K + CH - 1) / CH;  // 0 when K == 0: the local term alone
+    struct Slot {
+        uint32_t w[CH][Q];
+        float sw[CH];
+    };
+    auto fetch = [&](uint32_t u, uint32_t c, Slot &sl) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int k = (int)(c * CH) + i;
+            const bool empty = !(k < K);  // an empty place of the last chunk: worker K - 1 again, with scale 0
+            k = empty ? K - 1 : k;
+            const float s = p.scales[k][u >> block_shift];
+            sl.sw[i] = empty ? 0.0f : s;
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.w[i][j] = ldg_at<NT>(c4, j * kWave + lane);
+        }
+    };
+    v4f acc[Q];
+    auto start_unit = [&](uint32_t u) {
+        if (local) {  // not prefetched: once per unit
+            const v4f *l4 = reinterpret_cast<const v4f *>(local) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                const v4f l = ldg_at<NT>(l4, j * kWave + lane);
+                acc[j] = v4f{0.0f + l.x, 0.0f + l.y, 0.0f + l.z, 0.0f + l.w};
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+    };
+    auto finish_unit = [&](uint32_t u) {
+        v4f *o4 = reinterpret_cast<v4f *>(out) + (size_t)u * (U / 4);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            v4f a = acc[j];
+            a.x = mean_of(a.x);
+            a.y = mean_of(a.y);
+            a.z = mean_of(a.z);
+            a.w = mean_of(a.w);
+            stg<NT>(o4 + j * kWave + lane, a);
+        }
+    };
+    // Adds chunk c of unit u from its slot; opens the unit's sums at its first chunk and stores the means at its last.
+    auto process = [&](uint32_t u, uint32_t c, const Slot &sl) {
+        if (c == 0) start_unit(u);
+        // No branch around an empty place: its scale is 0, the product is a zero of either sign, and adding
+        // that changes nothing (a running sum that starts at +0 is never -0).
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const float s = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[i])));
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = acc[j].x + lut_at<0>(lut, sl.w[i][j], lane4) * s;
+                acc[j].y = acc[j].y + lut_at<1>(lut, sl.w[i][j], lane4) * s;
+                acc[j].z = acc[j].z + lut_at<2>(lut, sl.w[i][j], lane4) * s;
+                acc[j].w = acc[j].w + lut_at<3>(lut, sl.w[i][j], lane4) * s;
+            }
+        }
+        if (c + 1 == n_chunks) finish_unit(u);
+    };
+    // The item after (u, c), and whether there is one; without one the same item again.
+    auto advance = [&](uint32_t &u, uint32_t &c) {
+        if (c + 1 < n_chunks) {
+            ++c;
+            return true;
+        }
+        if (u + n_waves < n_full) {
+            u += n_waves;
+            c = 0;
+            return true;
+        }
+        return false;
+    };
+    uint32_t u = (uint32_t)first_unit(WPW), c = 0;
+    Slot a, b;
+    const bool any = u < n_full && n_chunks > 0;
+    if (any) fetch(u, 0, a);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    if (any) {
+        for (;;) {
+            uint32_t un = u, cn = c;
+            bool more = advance(un, cn);
+            fetch(un, cn, b);
+            process(u, c, a);
+            if (!more) break;
+            u = un;
+            c = cn;
+            more = advance(un, cn);
+            fetch(un, cn, a);
+            process(u, c, b);
+            if (!more) break;
+            u = un;
+            c = cn;
+        }
+    } else if (n_chunks == 0) {  // K == 0: the local values alone
+        for (; u < n_full; u += n_waves) {
+            start_unit(u);
+            finish_unit(u);
+        }
+    }
+    if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
+        const size_t start = (size_t)n_full * U;
+        const size_t blk = n_full >> block_shift;
+        for (uint32_t i = lane; i < tail_len; i += kWave) {
+            float s = 0.0f;
+            if (local) s = s + local[start + i];
+            for (int k = 0; k < K; ++k) s = s + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+            out[start + i] = mean_of(s);
         }
     }
 }
