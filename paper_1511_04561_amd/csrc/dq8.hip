@@ -135,7 +135,7 @@ struct Tuning {
     int avg_wpc = 32;
     int avg_wpw = 16;
     int blk_wpw = 8;     // register-resident average: wavefronts per workgroup (two workgroups per compute unit)
-    int avg_team = 1;    // average-then-compress with K = 2, 4, 8: the team kernel (0: the wave-per-block kernel)
+    int avg_team = 1;    // average-then-compress with up to 8 workers: the team kernel (0: the wave-per-block kernel)
     int avg_steady = 1;  //   unconditional steady-state iterations when the buffers are aligned
     int avg_teams = 3;   //   teams per workgroup: 2, 3 or 4
     int avg_wgpc = 1;    //   workgroups per compute unit (2 only with 2 teams)
@@ -575,7 +575,7 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
     return DQ8_OK;
 }
 
-// Average-then-compress for K = 2, 4, 8: teams of four wavefronts; two teams per workgroup and two
+// Average-then-compress for up to 8 workers: teams of four wavefronts; two teams per workgroup and two
 // workgroups per compute unit (128 registers per lane), or three teams in one workgroup per compute
 // unit (170 registers per lane).
 int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
@@ -583,7 +583,8 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 {
     const size_t Bq = block_length(n, block);
     const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
-    const int teams = ragged ? 3 : ((g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2);
+    const bool tuned_k = K == 2 || K == 4 || K == 8;  // the worker counts with variants for 2 and 4 teams
+    const int teams = (ragged || !tuned_k) ? 3 : ((g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2);
     const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
     Plan p = make_plan(n, block, st.cus, 4 * teams * wgs_per_cu, 4, 4 * teams, kUnit);
     const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
@@ -616,11 +617,30 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     } else {                     \
         DQ8_TEAM_T(KT, false)    \
     }
+    // K = 1, 3, 5, 6, 7: three teams per workgroup only
+#define DQ8_TEAM_3(KT)                       \
+    if (st.has_remap[kind]) {                \
+        if (ragged) {                        \
+            DQ8_TEAM(KT, true, 3, true);     \
+        } else {                             \
+            DQ8_TEAM(KT, true, 3, false);    \
+        }                                    \
+    } else if (ragged) {                     \
+        DQ8_TEAM(KT, false, 3, true);        \
+    } else {                                 \
+        DQ8_TEAM(KT, false, 3, false);       \
+    }
     switch (K) {
+    case 1: DQ8_TEAM_3(1) break;
     case 2: DQ8_TEAM_RM(2) break;
+    case 3: DQ8_TEAM_3(3) break;
     case 4: DQ8_TEAM_RM(4) break;
+    case 5: DQ8_TEAM_3(5) break;
+    case 6: DQ8_TEAM_3(6) break;
+    case 7: DQ8_TEAM_3(7) break;
     default: DQ8_TEAM_RM(8) break;
     }
+#undef DQ8_TEAM_3
 #undef DQ8_TEAM_RM
 #undef DQ8_TEAM_T
 #undef DQ8_TEAM
@@ -633,8 +653,8 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.
     const size_t Bq = block_length(n, block);
     const size_t unit = holding_unit(Bq);
-    // K = 2, 4, 8 and blocks that need a 4096-element unit: the team kernel
-    if (codes_out && !mean_out && (K == 2 || K == 4 || K == 8) && g_tune.avg_team && unit == (size_t)kUnit)
+    // up to 8 workers and blocks that need a 4096-element unit: the team kernel
+    if (codes_out && !mean_out && K >= 1 && K <= 8 && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const int ql = (int)(unit / (size_t)(4 * kWave));
     // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
     }
 }
 
-// The same average-then-compress round for K = 2, 4 or 8 workers at full speed.  A team of four
+// The same average-then-compress round for up to eight workers (K fixed at compile time) at full speed.  A team of four
 // wavefronts owns a unit of 4096 elements (one scale block): every lane holds four quads of
 // running sums and K x 4 code words.  The code words are one register set that is refilled
 // in place: as soon as worker k's words of the current unit have been decoded and added, the
