@@ -801,7 +801,7 @@ int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int
     const int wpw = g_tune.avg_wpw == 16 ? 16 : (g_tune.avg_wpw == 8 ? 8 : 4);
     const bool fixed_k = K == 2 || K == 4 || K == 8;
     const size_t Bq = block_length(n, block);
-    int q = !fixed_k ? 1 : ((g_tune.avg_q == 1 || g_tune.avg_q == 4) ? g_tune.avg_q : 2);
+    int q = K > 8 ? 1 : ((fixed_k && (g_tune.avg_q == 1 || g_tune.avg_q == 4)) ? g_tune.avg_q : 2);
     int wpc = g_tune.avg_wpc;
     fit_unit_to_block(Bq, &q, &wpc);
     Plan p = make_plan(n, block, st.cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
@@ -826,12 +826,25 @@ int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int
     case 4: DQ8_AVG_W(KT, 4) break;      \
     default: DQ8_AVG_W(KT, 2) break;     \
     }
+    // The other worker counts up to 8 are unrolled too, for the default shape only; beyond that K is a loop.
+#define DQ8_AVG_ODD(KT)          \
+    if (q == 2 && wpw == 16) {   \
+        DQ8_AVG(KT, 2, 16);      \
+    } else {                     \
+        DQ8_AVG_W(0, 1)          \
+    }
     switch (K) {
+    case 1: DQ8_AVG_ODD(1) break;
     case 2: DQ8_AVG_Q(2) break;
+    case 3: DQ8_AVG_ODD(3) break;
     case 4: DQ8_AVG_Q(4) break;
+    case 5: DQ8_AVG_ODD(5) break;
+    case 6: DQ8_AVG_ODD(6) break;
+    case 7: DQ8_AVG_ODD(7) break;
     case 8: DQ8_AVG_Q(8) break;
     default: DQ8_AVG_W(0, 1) break;
     }
+#undef DQ8_AVG_ODD
 #undef DQ8_AVG_Q
 #undef DQ8_AVG_W
 #undef DQ8_AVG
