@@ -117,6 +117,7 @@ struct Tuning {
     int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
+    int avg_chunk_all = 0;  //   1: that kernel for K = 2, 4, 8 as well
     int avg_chunk_wpc = 8;  //   wavefronts per compute unit of the kernel that takes the workers four at a time
     int avg_lean_wpw = 4;
     int copy_nt = 1;
@@ -713,7 +714,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     }
     const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    if (K != 2 && K != 4 && K != 8) {
+    if ((K != 2 && K != 4 && K != 8) || g_tune.avg_chunk_all) {
         // Any other number of workers, CH at a time: the CH from 3 to 8 with the fewest empty places in the last
         // chunk (an empty place repeats a load), the largest such CH; K = 0 (the local term alone) has no chunks.
         int ch = K < 3 ? (K < 1 ? 1 : K) : 3;
@@ -1164,7 +1165,7 @@ int dq8_internal_tune(const char *key, int value)
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
-        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
