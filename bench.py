@@ -56,6 +56,8 @@ def algorithmic_bytes(n, nb):
         "decode_accumulate_avg_local": K_WORKERS * (n + 4 * nb) + 4 * n + 4 * n,
         # the approximation-error statistics with the scales handed in: one pass over the fp32 input
         "error_stats": 4 * n + 4 * nb + 32 * nb,
+        # one GPU's share of the second round on an 8-GPU node: 7 received buffers + its own fp32 slice, compressed
+        "decode_avg_encode_7_local": 7 * (n + 4 * nb) + 4 * n + n + 4 * nb,
         # compression into the 8-bit mantissa type (ranks of distinct magnitudes mapped to codes)
         "encode_mantissa": 4 * n + n + 4 * nb,
     }
@@ -174,6 +176,8 @@ def main():
                                                                               out=st["dec"], local=nxt["x"])),
             ("error_stats", lambda: dq8.error_stats(KIND, st["x"], BLOCK, scales=st["s_out"], scales_given=True,
                                                     stats=st["stats"], means=st["means"])),
+            ("decode_avg_encode_7_local", lambda: dq8.decode_avg_encode(KIND, st["codes"][:7], st["scales"][:7], BLOCK,
+                                                                        local=nxt["x"], scales=st["rs"], codes=st["rc"])),
             ("encode_mantissa", lambda: dq8.encode(dq8.MANTISSA, st["x"], BLOCK, scales=st["rs"], codes=st["rc"])),
         ]
 
