@@ -128,7 +128,7 @@ struct Tuning {
     int enc_lean_wpc = 8;  //   which keeps its loads in flight with this many wavefronts per compute unit
     int enc_fill = 1;    //   and puts a team on every resident slot, even if some then get one block fewer
     int amax_q = 16;     // absmax: quads per lane in flight (unit = 256 q elements)
-    int amax_wpc = 4;
+    int amax_wpc = 3;    //   wavefronts per compute unit: 3 measured best (36.2 us against 37.5 with 4 on 61 M elements)
     int dec_q = 16;      // decode: code words per lane in flight
     int dec_wpc = 4;
     int dec_wpw = 4;     // decode: wavefronts per workgroup (they share one table in LDS)
