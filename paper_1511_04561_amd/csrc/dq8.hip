@@ -159,6 +159,23 @@ void fit_unit_to_block(size_t block_len, int *quads, int *waves_per_cu)
     }
 }
 
+// Workers per chunk for the decode-and-average kernel that takes any number of workers a chunk at a time: the
+// size from 3 to 8 with the fewest empty places in the last chunk (an empty place repeats a load), the largest
+// such size; fewer than 3 workers are one chunk; K = 0 (the local term alone) has no chunks at all.
+int chunk_size(int K)
+{
+    if (K < 3) return K < 1 ? 1 : K;
+    int best = 3;
+    for (int c = 3, waste = DQ8_MAX_K; c <= 8; ++c) {
+        const int w = (K + c - 1) / c * c - K;
+        if (w <= waste) {
+            waste = w;
+            best = c;
+        }
+    }
+    return best;
+}
+
 // Unit for the kernels that hold a whole block in registers: the smallest power of two of elements
 // between 256 and 4096 that holds a block (4096 for longer blocks).
 size_t holding_unit(size_t block_len)
@@ -715,17 +732,8 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     if ((K != 2 && K != 4 && K != 8) || g_tune.avg_chunk_all) {
-        // Any other number of workers, CH at a time: the CH from 3 to 8 with the fewest empty places in the last
-        // chunk (an empty place repeats a load), the largest such CH; K = 0 (the local term alone) has no chunks.
-        int ch = K < 3 ? (K < 1 ? 1 : K) : 3;
-        for (int c = ch, waste = DQ8_MAX_K; c <= 8 && K >= 3; ++c) {
-            const int w = (K + c - 1) / c * c - K;
-            if (w <= waste) {
-                waste = w;
-                ch = c;
-            }
-        }
-        if (lq != 2) return DQ8_OK;
+        if (lq != 2) return DQ8_OK;  // that kernel exists for two code words per lane and worker only
+        const int ch = chunk_size(K);
         // eight wavefronts per compute unit measured best for every CH from 3 up
         const int wpc = ch <= 2 ? 2 * g_tune.avg_chunk_wpc : g_tune.avg_chunk_wpc;
         size_t waves = (size_t)st.cus * (size_t)wpc;
@@ -1131,6 +1139,8 @@ int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128)
     if (canon128) std::memcpy(canon128, t.canon, sizeof(t.canon));
     return DQ8_OK;
 }
+
+int dq8_internal_chunk_size(int K) { return chunk_size(K); }
 
 int dq8_internal_units(size_t n, size_t block, int quads, int waves_per_cu, size_t *out4)
 {

@@ -24,6 +24,9 @@ int dq8_internal_ranks(int kind, uint32_t *n_mag, uint8_t *canon128);
 // the unit for kernels that hold a whole block}.
 int dq8_internal_units(size_t n, size_t block, int quads, int waves_per_cu, size_t *out4);
 
+// Workers per chunk that the decode-and-average kernel for arbitrary worker counts is launched with.
+int dq8_internal_chunk_size(int K);
+
 // Launch plan for n elements with the given block on a device with `cus` compute units,
 // `waves_per_cu` resident wavefronts per compute unit, teams of `wpb` wavefronts and units of
 // `unit` elements: out6 = {B, nb, units per block, units, teams, workgroups}.

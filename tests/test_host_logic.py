@@ -287,3 +287,17 @@ def test_units_follow_the_block_length(L):
     assert units(n, 1000, quads=2, wpc=32) == [1000, 512, 32, 1024]
     assert units(100, 0) == [100, 256, 32, 256]
     assert L.dq8_internal_units(ctypes.c_size_t(n), ctypes.c_size_t(0), 3, 4, (ctypes.c_size_t * 4)()) == 3
+
+
+def test_chunk_sizes_leave_few_empty_places(L):
+    """Workers are averaged a chunk at a time: the chunk size wastes at most one place in eight and is as
+    large as possible among the sizes that waste least."""
+    got = {K: L.dq8_internal_chunk_size(K) for K in range(0, 33)}
+    assert got[0] == 1 and got[1] == 1 and got[2] == 2
+    for K in range(3, 33):
+        c = got[K]
+        assert 3 <= c <= 8
+        waste = -K % c
+        assert all(waste <= (-K % d) for d in range(3, 9)), (K, c)
+        assert all(d <= c for d in range(3, 9) if (-K % d) == waste), (K, c)
+    assert [got[K] for K in (3, 4, 5, 6, 7, 8, 10, 16, 24, 32)] == [3, 4, 5, 6, 7, 8, 5, 8, 8, 8]
