@@ -250,7 +250,7 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
     }
 }
 
-// Compression of whole, aligned blocks of 4096 elements: the common case of k_encode<4, NT, true,
+// Compression of whole, aligned blocks of 4096 elements: the common case of k_encode<4, 4, NT, true,
 // FASTDIV> (a team of four wavefronts per block, maximum and quantisation from registers) with
 // nothing else in the loop.  Block b starts at element 4096 b, x is 16-byte and codes 4-byte
 // aligned, so unit geometry is a multiplication and there is no slow path to branch around.
