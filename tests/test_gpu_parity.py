@@ -368,13 +368,15 @@ def test_decode_avg_encode(dq8, kind, K, with_local):
         gs.check("avg->encode scales")
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("DQ8_RANDOM_SEEDS", "6"))))
 def test_random_shapes_through_every_call(dq8, seed):
     """Seeded random sizes, block lengths, pointer offsets, worker counts and data types through every call:
     the launch logic picks unit sizes and kernel variants from these, so this sweeps their combinations."""
     rng = np.random.Generator(np.random.PCG64(8800 + seed))
     for case in range(10):
         n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 6000), rng.integers(6000, 40000)]))
+        if case == 0:  # one size per seed at which every wavefront walks several units
+            n = int(rng.integers(1_500_000, 3_000_000))
         pick = rng.integers(0, 6)
         block = [0, int(rng.integers(1, n + 1)), 4 * int(rng.integers(1, max(2, n // 4 + 1))),
                  1 << int(rng.integers(0, 14)), 4096, int(rng.integers(1, 9)) * 1000][pick]
