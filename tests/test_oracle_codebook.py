@@ -117,7 +117,7 @@ def test_paper_worked_examples_fall_in_the_oracle_leaf(golden_dir):
 
 def test_regression_hashes(golden_dir):
     want = dict(l.split() for l in open(os.path.join(golden_dir, "codebook_sha256.txt")) if l[0] != "#")
-    for kind in KINDS:
+    for kind in KINDS + [oracle.MANTISSA]:
         assert hashlib.sha256(oracle.codebook(kind).astype("<f4").tobytes()).hexdigest() == want[str(kind)]
 
 
