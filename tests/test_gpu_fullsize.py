@@ -112,6 +112,23 @@ def test_config5_aggregation_pipeline(dq8):
     bound = np.repeat(np.mean(np.stack(scales_h).astype(np.float64), axis=0), B)[:n]
     assert np.all(np.abs(mean_h) <= bound * (1 + 1e-6))
     assert np.array_equal((rcodes_h >> 7).astype(bool), np.signbit(mean_h))
+    del mean, mean_h, rcodes, rcodes_h
+    # the shapes with a local fp32 term that bench.py times: 8 workers + local into fp32, and 7 workers + local
+    # averaged and compressed in one call (one GPU's share of the second round on an 8-GPU node)
+    print("C5: local-term variants", flush=True)
+    local = torch.from_numpy(workloads.bucket(5, worker=0)).cuda()
+    mean_l = dq8.decode_accumulate_avg(KIND, codes_d, scales_d, B, local=local)
+    fc7, fs7 = dq8.decode_avg_encode(KIND, codes_d[:7], scales_d[:7], B, local=local)
+    torch.cuda.synchronize()
+    mean_l_h, fc7_h, fs7_h = mean_l.cpu().numpy(), fc7.cpu().numpy(), fs7.cpu().numpy()
+    for i, b in enumerate(sample):
+        lo, hi = b * B, min((b + 1) * B, n)
+        oc = [codes_h[w][lo:hi] for w in range(K)]
+        os_ = [scales_h[w][b:b + 1] for w in range(K)]
+        m = oracle.decode_accumulate_avg(KIND, oc, os_, B, local=xs[0][i])
+        assert mean_l_h[lo:hi].tobytes() == m.tobytes(), ("mean with local term", b)
+        c7, s7 = oracle.decode_avg_encode(KIND, oc[:7], os_[:7], B, local=xs[0][i])
+        assert fc7_h[lo:hi].tobytes() == c7.tobytes() and fs7_h[b:b + 1].tobytes() == s7.tobytes(), ("7 + local", b)
 
 
 def test_error_statistics_of_a_25_million_sample(dq8):
