@@ -67,6 +67,21 @@ def test_config3_full_bucket(dq8):
     assert np.all(err <= 0.5 * 0.9 / 64 * s * 1.0001 + 1e-30)  # never worse than half the widest leaf (top decade)
 
 
+@pytest.mark.parametrize("kind", [oracle.LINEAR, oracle.STATIC_TREE, oracle.MANTISSA])
+def test_config3_full_bucket_other_types(dq8, kind):
+    """The other three data types on the full bucket, in the launch configuration of the benchmark."""
+    x = workloads.bucket(3)
+    xd = torch.from_numpy(x).cuda()
+    codes, scales = dq8.encode(kind, xd, B)
+    out = dq8.decode(kind, codes, scales, B)
+    torch.cuda.synchronize()
+    print("C3 kind %d: oracle encode" % kind, flush=True)
+    want_codes, want_scales = oracle.encode(kind, x, B)
+    bits_equal(scales, want_scales, "C3 scales")
+    bits_equal(codes, want_codes, "C3 codes")
+    bits_equal(out, oracle.decode(kind, want_codes, want_scales, B), "C3 decode")
+
+
 def test_config5_aggregation_pipeline(dq8):
     K = workloads.C5_WORKERS
     n = workloads.C3_NUMEL
