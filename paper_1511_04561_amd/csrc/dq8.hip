@@ -409,7 +409,10 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
     // Units no longer than a block (so that whole blocks are whole units when the block is a power of two),
     // and the more wavefronts per compute unit the smaller the unit: the bytes in flight stay the same.
     int q = (g_tune.amax_q == 1 || g_tune.amax_q == 2 || g_tune.amax_q == 8 || g_tune.amax_q == 16) ? g_tune.amax_q : 4;
-    int wpc = g_tune.amax_wpc;
+    // three wavefronts per compute unit are the best when every unit is a whole full-size one; four otherwise
+    // (smaller units, or blocks that end inside units)
+    const size_t full_unit = (size_t)q * 4 * kWave;
+    int wpc = (Bq >= n || Bq % full_unit == 0) ? g_tune.amax_wpc : 4;
     fit_unit_to_block(Bq, &q, &wpc);
     Plan p = make_plan(n, block, st.cus, wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
     size_t per_wave = 0;
