@@ -83,6 +83,24 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+class _NoSwitch:
+    def __enter__(self):
+        return None
+
+    def __exit__(self, *exc):
+        return False
+
+
+_NO_SWITCH = _NoSwitch()
+
+
+def _on(device):
+    """Makes `device` current for the call; nothing to do (and nothing spent) when it already is."""
+    if device.index is None or device.index == torch.cuda.current_device():
+        return _NO_SWITCH
+    return torch.cuda.device(device)
+
+
 def codebook(kind):
     """The 256 table values of a data type as a CPU float32 tensor."""
     cb = torch.empty(256, dtype=torch.float32)
@@ -102,7 +120,7 @@ def absmax(x, block=0, scales=None):
     _dev(scales, torch.float32, "scales")
     if scales.numel() < n_blocks(n, block):
         raise ValueError("scales too small")
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dq8_absmax(x.data_ptr(), n, int(block), scales.data_ptr(), _stream()), "dq8_absmax")
     return scales
 
@@ -121,7 +139,7 @@ def encode(kind, x, block=0, scales=None, codes=None, scales_given=False):
     _dev(codes, torch.uint8, "codes")
     if scales.numel() < n_blocks(n, block) or codes.numel() < n:
         raise ValueError("output buffers too small")
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dq8_encode(int(kind), x.data_ptr(), n, int(block), scales.data_ptr(), codes.data_ptr(),
                                 SCALES_GIVEN if scales_given else 0, _stream()), "dq8_encode")
     return codes, scales
@@ -138,7 +156,7 @@ def decode(kind, codes, scales, block=0, out=None):
     _dev(out, torch.float32, "out")
     if out.numel() < n:
         raise ValueError("out too small")
-    with torch.cuda.device(codes.device):
+    with _on(codes.device):
         _check(lib().dq8_decode(int(kind), codes.data_ptr(), scales.data_ptr(), n, int(block), out.data_ptr(),
                                 _stream()), "dq8_decode")
     return out
@@ -173,7 +191,7 @@ def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None, loca
     _dev(out, torch.float32, "out")
     if out.numel() < n:
         raise ValueError("out too small")
-    with torch.cuda.device(out.device):
+    with _on(out.device):
         if local is None:
             _check(lib().dq8_decode_accumulate_avg(int(kind), cp, sp, K, n, int(block), out.data_ptr(), _stream()),
                    "dq8_decode_accumulate_avg")
@@ -197,7 +215,7 @@ def decode_avg_encode(kind, codes_list, scales_list, block=0, local=None, scales
     _dev(codes, torch.uint8, "codes")
     if scales.numel() < n_blocks(n, block) or codes.numel() < n:
         raise ValueError("output buffers too small")
-    with torch.cuda.device(codes.device):
+    with _on(codes.device):
         _check(lib().dq8_decode_avg_encode(int(kind), cp, sp, K, None if local is None else local.data_ptr(), n,
                                            int(block), scales.data_ptr(), codes.data_ptr(), _stream()),
                "dq8_decode_avg_encode")
@@ -226,7 +244,7 @@ def error_stats(kind, x, block=0, scales=None, scales_given=False, stats=None, m
     _dev(means, torch.float64, "means")
     if scales.numel() < nb or stats.numel() < 4 * nb or means.numel() < 2:
         raise ValueError("output buffers too small")
-    with torch.cuda.device(x.device):
+    with _on(x.device):
         _check(lib().dq8_error_stats(int(kind), x.data_ptr(), n, int(block), scales.data_ptr(),
                                      SCALES_GIVEN if scales_given else 0, stats.data_ptr(), means.data_ptr(), _stream()),
                "dq8_error_stats")
@@ -258,7 +276,7 @@ def calibration_copy(dst, src):
     dst = _dev(dst, torch.float32, "dst")
     if dst.numel() < src.numel():
         raise ValueError("dst too small")
-    with torch.cuda.device(src.device):
+    with _on(src.device):
         _check(lib().dq8_internal_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream()), "dq8_internal_copy")
     return dst
 
