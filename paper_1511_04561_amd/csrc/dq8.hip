@@ -619,9 +619,10 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     }
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
-#define DQ8_TEAM(KT, RM, T, RG)                                                                                          \
-    hipLaunchKernelGGL((k_avg_team<KT, 1, true, T, RM, RG>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, local, n, \
-                       p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
+#define DQ8_TEAM_M(KT, RM, T, RG, MU)                                                                                     \
+    hipLaunchKernelGGL((k_avg_team<KT, 1, true, T, RM, RG, MU>), dim3(p.grid), dim3(kWg * T), lds, stream, tab, wp, K, local, \
+                       n, p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
+#define DQ8_TEAM(KT, RM, T, RG) DQ8_TEAM_M(KT, RM, T, RG, false)
 #define DQ8_TEAM_T(KT, RM)              \
     if (ragged) {                       \
         DQ8_TEAM(KT, RM, 3, true);      \
@@ -651,6 +652,32 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     } else {                                 \
         DQ8_TEAM(KT, false, 3, false);       \
     }
+    if (K > 8) {
+        // more than 8 workers (whole 4096-blocks only): 5 to 8 at a time over the same registers, the count with the
+        // fewest empty places in the last pass, the largest such
+        int ch = 8;
+        for (int c = 5, waste = DQ8_MAX_K; c <= 8; ++c) {
+            const int w = (K + c - 1) / c * c - K;
+            if (w <= waste) {
+                waste = w;
+                ch = c;
+            }
+        }
+#define DQ8_TEAM_MULTI(KT)                           \
+    if (st.has_remap[kind]) {                        \
+        DQ8_TEAM_M(KT, true, 3, false, true);        \
+    } else {                                         \
+        DQ8_TEAM_M(KT, false, 3, false, true);       \
+    }
+        switch (ch) {
+        case 5: DQ8_TEAM_MULTI(5) break;
+        case 6: DQ8_TEAM_MULTI(6) break;
+        case 7: DQ8_TEAM_MULTI(7) break;
+        default: DQ8_TEAM_MULTI(8) break;
+        }
+#undef DQ8_TEAM_MULTI
+        return after_launch("k_avg_team");
+    }
     switch (K) {
     case 1: DQ8_TEAM_3(1) break;
     case 2: DQ8_TEAM_RM(2) break;
@@ -665,6 +692,7 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #undef DQ8_TEAM_RM
 #undef DQ8_TEAM_T
 #undef DQ8_TEAM
+#undef DQ8_TEAM_M
     return after_launch("k_avg_team");
 }
 
@@ -674,8 +702,8 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.
     const size_t Bq = block_length(n, block);
     const size_t unit = holding_unit(Bq);
-    // up to 8 workers and blocks that need a 4096-element unit: the team kernel
-    if (codes_out && !mean_out && K >= 1 && K <= 8 && g_tune.avg_team && unit == (size_t)kUnit)
+    // blocks that need a 4096-element unit with up to 8 workers, or exactly 4096 elements with more: the team kernel
+    if (codes_out && !mean_out && K >= 1 && (K <= 8 || Bq == (size_t)kUnit) && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const int ql = (int)(unit / (size_t)(4 * kWave));
     // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave

@@ -212,11 +212,14 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
 // times (`iters`), whether or not its team still has a unit.
 // RAGGED = true (chosen by the host for blocks shorter than 4096): a unit of fewer whole aligned quads
 // takes the register path as well.
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED>
+// MULTI = true: more workers than KT, taken KT at a time in `passes` passes over the same registers; a
+// place of the last pass that has no worker repeats worker K - 1 with scale 0 (the product is a zero, and
+// adding a zero leaves a sum that started at +0 unchanged).  K is then a run-time value.
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED, bool MULTI>
 struct AvgTeam {
     static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
 
-    WorkerPtrs p;
+    const WorkerPtrs &p;  // the kernel's argument itself: a copy would have to live in scratch memory to be indexed
     const float *local;
     float *scales_out;
     uint8_t *codes_out;
@@ -228,11 +231,15 @@ struct AvgTeam {
     float fk, rk;
     bool pow2;
     uint32_t w[KT][Q];  // code words: of the current unit until used, then of the next one
+    int K;              // number of workers: KT unless MULTI
+    int passes;         // ceil(K / KT)
 
     struct Slot {
         Unit un;
         bool active, fast;
     };
+
+    __device__ __forceinline__ explicit AvgTeam(const WorkerPtrs &workers) : p(workers) {}
 
     __device__ __forceinline__ float mean_of(float acc) const { return pow2 ? acc * rk : acc / fk; }
 
@@ -241,8 +248,12 @@ struct AvgTeam {
     {
         float a = 0.0f;
         if (local) a = a + local[un.start + i];
+        if (MULTI) {
+            for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+        } else {
 #pragma unroll
-        for (int k = 0; k < KT; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+            for (int k = 0; k < KT; ++k) a = a + lut_code(lut, p.codes[k][un.start + i], lane4) * p.scales[k][un.block];
+        }
         return mean_of(a);
     }
 
@@ -256,8 +267,12 @@ struct AvgTeam {
         // whole aligned quads: a short unit takes the register path too (see load_worker)
         bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == kUnit) &&
                  (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
+        if (MULTI) {
+            for (int k = 0; k < K; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
+        } else {
 #pragma unroll
-        for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
+            for (int k = 0; k < KT; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
+        }
         if (local) f = f && (((uintptr_t)(local + sl.un.start) & 15) == 0);
         sl.fast = f;
     }
@@ -274,10 +289,11 @@ struct AvgTeam {
         return i < last ? i : last;
     }
 
+    // Code words of `worker` for unit sl into place k.
     template <bool WHOLE>
-    __device__ __forceinline__ void load_worker(const Slot &sl, int k)
+    __device__ __forceinline__ void load_worker(const Slot &sl, int k, int worker)
     {
-        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + sl.un.start);
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[worker] + sl.un.start);
 #pragma unroll
         for (int j = 0; j < Q; ++j) w[k][j] = ldg_at<NT>(c4, quad_of<WHOLE>(sl, j));
     }
@@ -286,7 +302,7 @@ struct AvgTeam {
     {
         if (sl.fast) {
 #pragma unroll
-            for (int k = 0; k < KT; ++k) load_worker<false>(sl, k);
+            for (int k = 0; k < KT; ++k) load_worker<false>(sl, k, k);
         }
     }
 
@@ -314,9 +330,17 @@ struct AvgTeam {
 #pragma unroll
                 for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
             }
-            float sc[KT];  // the K scales of this block, moved to scalar registers
+          for (int pass = 0; pass < (MULTI ? passes : 1); ++pass) {
+            const int base = pass * KT;
+            const bool last_pass = !MULTI || pass + 1 == passes;
+            float sc[KT];  // the scales of this pass's workers for this block, moved to scalar registers
 #pragma unroll
-            for (int k = 0; k < KT; ++k) sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(p.scales[k][sl.un.block])));
+            for (int k = 0; k < KT; ++k) {
+                const bool empty = MULTI && !(base + k < K);
+                const int worker = empty ? K - 1 : base + k;
+                const float sv = p.scales[worker][sl.un.block];
+                sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(empty ? 0.0f : sv)));
+            }
             // The table lookups run one worker ahead of the sums: worker k + 1's sixteen lookups are issued
             // before worker k's values are multiplied and added, so the LDS latency of one worker hides behind
             // the arithmetic of the one before.  The scheduling barriers keep that order.
@@ -346,9 +370,17 @@ struct AvgTeam {
                 // registers until the ordered sums get to them, which costs a wavefront per SIMD.
 #pragma unroll
                 for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
-                if (STEADY || nx.fast) load_worker<STEADY>(nx, k);  // refill in place: the lookups of worker k are issued
+                // refill in place (the lookups of this place are issued): the next pass's worker of this unit, or
+                // after the last pass the next unit's worker k
+                if (!last_pass) {
+                    const int next_worker = base + KT + k < K ? base + KT + k : K - 1;
+                    load_worker<STEADY>(sl, k, next_worker);
+                } else if (STEADY || nx.fast) {
+                    load_worker<STEADY>(nx, k, k);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
+          }
             float fm = 0.0f;
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
@@ -397,18 +429,18 @@ struct AvgTeam {
     }
 };
 
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED>
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED, bool MULTI>
 __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
-                                                            const float *__restrict__ local, size_t n, size_t B, size_t nb,
+                                                            int K_rt, const float *__restrict__ local, size_t n, size_t B,
+                                                            size_t nb,
                                                             size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
                                                             float *__restrict__ scales_out, uint8_t *__restrict__ codes_out)
 {
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
     constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
-    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED>;
-    Avg e;
-    e.p = p;
+    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED, MULTI>;
+    Avg e(p);
     e.local = local;
     e.scales_out = scales_out;
     e.codes_out = codes_out;
@@ -425,7 +457,9 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     e.wv = wave % kWavesPerWg;
     e.tl = threadIdx.x & (kWg - 1);  // lane within the team
     e.phase = 0;
-    const int terms = KT + (local ? 1 : 0);
+    e.K = MULTI ? K_rt : KT;
+    e.passes = (e.K + KT - 1) / KT;
+    const int terms = e.K + (local ? 1 : 0);
     e.fk = (float)terms;
     e.rk = 1.0f / e.fk;
     e.pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
