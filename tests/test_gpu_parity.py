@@ -327,10 +327,13 @@ def test_decode_accumulate_avg_with_local_term(dq8, kind, K):
         go.check("avg+local")
 
 
-@pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("K,with_local", [(1, False), (2, False), (3, False), (8, False), (32, False), (0, True),
-                                          (3, True), (7, True), (9, False), (12, True), (13, False), (16, False),
-                                          (31, True)])
+# every type with up to 8 workers and with 32; the worker counts that take several passes with two types
+FUSED_CASES = [(kind, K, wl) for kind in KINDS for K, wl in [(1, False), (2, False), (3, False), (8, False), (32, False),
+                                                             (0, True), (3, True), (7, True)]] + \
+              [(kind, K, wl) for kind in (0, 3) for K, wl in [(9, False), (12, True), (13, False), (16, False), (31, True)]]
+
+
+@pytest.mark.parametrize("kind,K,with_local", FUSED_CASES)
 def test_decode_avg_encode(dq8, kind, K, with_local):
     """One call: average, then compress the average.  Inputs are codes of seeded gradients (so that the means
     spread over the whole table) and, for the ragged shapes, random codes."""
