@@ -740,15 +740,18 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
 }
 
 // K-way decode-and-average (optional local term) of whole aligned units with a power-of-two number of them
-// per block (or a single block): the kernels without slow paths in their loops, one unrolled for K = 2, 4, 8,
-// one that takes any number of workers four at a time.
+// per block (or a single block): the kernels without slow paths in their loops, one unrolled for up to 8
+// workers, one that takes any number of workers a chunk at a time.
 // *launched = false (and nothing done) when the buffers do not qualify.
 int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                     const Plan &p, float *out, hipStream_t stream, bool *launched)
 {
     *launched = false;
     const int lq = g_tune.avg_lean_q == 4 ? 4 : 2;
-    const int lw = g_tune.avg_lean_wpw == 16 ? 16 : (g_tune.avg_lean_wpw == 8 ? 8 : 4);
+    // wavefronts per workgroup (they share the 64 KiB decode table, two workgroups fit a compute unit): eight where
+    // eight or more wavefronts per compute unit are wanted (up to 5 workers, see kWavesForK), else four
+    const int lw_tuned = g_tune.avg_lean_wpw == 16 ? 16 : (g_tune.avg_lean_wpw == 8 ? 8 : 4);
+    const int lw = (K >= 1 && K <= 5 && lw_tuned < 8) ? 8 : lw_tuned;
     const size_t U = (size_t)lq * 4 * kWave;
     const size_t upb_l = p.B / U;
     bool ok = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);
@@ -762,7 +765,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     }
     const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    if ((K != 2 && K != 4 && K != 8) || g_tune.avg_chunk_all) {
+    if (K < 1 || K > 8 || g_tune.avg_chunk_all) {
         if (lq != 2) return DQ8_OK;  // that kernel exists for two code words per lane and worker only
         const int ch = chunk_size(K);
         // eight wavefronts per compute unit measured best for every CH from 3 up
@@ -796,7 +799,10 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         *launched = true;
         return after_launch("k_decode_avg_chunks");
     }
-    size_t waves = (size_t)st.cus * (size_t)g_tune.avg_lean_wpc;
+    // Wavefronts per compute unit: four with 8 workers' code words in flight per lane; more with fewer workers
+    // (measured per K; avg_lean_wpc scales all of them).
+    static const int kWavesForK[9] = {0, 16, 8, 8, 8, 8, 4, 4, 4};
+    size_t waves = (size_t)st.cus * (size_t)(kWavesForK[K] * g_tune.avg_lean_wpc / 4);
     if (waves > n_full) waves = n_full;
     const unsigned grid = (unsigned)((waves + lw - 1) / lw);
     const uint32_t n_waves = grid * (uint32_t)lw;
@@ -821,9 +827,15 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     } else {                               \
         DQ8_AVGL_W(KT, 2)                  \
     }
+    if (lq != 2 && K != 2 && K != 4 && K != 8) return DQ8_OK;  // four code words per lane: K = 2, 4, 8 only
     switch (K) {
+    case 1: DQ8_AVGL_W(1, 2) break;
     case 2: DQ8_AVGL_Q(2) break;
+    case 3: DQ8_AVGL_W(3, 2) break;
     case 4: DQ8_AVGL_Q(4) break;
+    case 5: DQ8_AVGL_W(5, 2) break;
+    case 6: DQ8_AVGL_W(6, 2) break;
+    case 7: DQ8_AVGL_W(7, 2) break;
     default: DQ8_AVGL_Q(8) break;
     }
 #undef DQ8_AVGL_Q

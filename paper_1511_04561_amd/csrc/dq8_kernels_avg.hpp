@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     }
 }
 
-// K-way decode-and-average of whole, aligned units, K = 2, 4 or 8: the common case of
+// K-way decode-and-average of whole, aligned units, K up to 8 (fixed at compile time): the common case of
 // k_decode_avg with nothing else in the loop.  Unit u covers elements [U u, U (u + 1)), U divides
 // the block size and block / U is a power of two, so a unit's block is u >> block_shift; out is
 // 16-byte and every code buffer 4-byte aligned.  The K scales of a unit travel with its code
@@ -147,12 +147,14 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
                                                                 uint32_t n_waves, uint32_t block_shift, uint32_t tail_len,
                                                                 float *__restrict__ out)
 {
-    static_assert(KT == 2 || KT == 4 || KT == 8, "unrolled for these K");
+    static_assert(KT >= 1 && KT <= 8, "unrolled for up to eight workers");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     constexpr int U = Q * 4 * kWave;
     constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
-    constexpr float rk = 1.0f / (float)KT;  // acc * (1 / K) equals acc / K exactly for a power of two
-    auto mean_of = [&](float acc) { return LOCAL ? acc / fk : acc * rk; };
+    constexpr int terms = KT + (LOCAL ? 1 : 0);
+    constexpr bool pow2 = (terms & (terms - 1)) == 0;
+    constexpr float rk = 1.0f / fk;  // acc * (1 / K) equals acc / K exactly for a power of two
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t lane4 = lane * 4;
     struct Slot {

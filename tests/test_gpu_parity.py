@@ -289,7 +289,7 @@ AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (300
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 32])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8, 32])
 def test_decode_accumulate_avg(dq8, kind, K):
     rng = np.random.Generator(np.random.PCG64(900 + 10 * K + kind))
     for n, block, off in AVG_CASES:
@@ -307,7 +307,7 @@ def test_decode_accumulate_avg(dq8, kind, K):
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("K", [0, 1, 2, 3, 7, 8, 32])
+@pytest.mark.parametrize("K", [0, 1, 2, 3, 4, 5, 6, 7, 8, 32])
 def test_decode_accumulate_avg_with_local_term(dq8, kind, K):
     """The caller's own fp32 gradient is the first of K + 1 terms."""
     rng = np.random.Generator(np.random.PCG64(1900 + 10 * K + kind))
