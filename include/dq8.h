@@ -109,6 +109,9 @@ int dq8_absmax(const float *x, size_t n, size_t block, float *scales, void *hip_
  * x: n floats (read).  codes: n bytes (written).  scales: nb floats, written with the block
  * maxima unless flags has DQ8_SCALES_GIVEN, in which case they are read.
  * `codes` and `scales` must not overlap `x`.
+ * x is read once when a block has at most 16384 elements (a block is held in registers between
+ * the maximum and the quantisation); longer blocks, block == 0 on a longer array included,
+ * take a maximum pass and a quantisation pass: x is read twice.
  */
 int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
                unsigned flags, void *hip_stream);

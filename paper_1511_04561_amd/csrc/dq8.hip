@@ -124,6 +124,11 @@ struct Tuning {
     int fastdiv = 1;     // reciprocal multiply with exact fallback near thresholds
     int enc_wpb = 4;     // wavefronts per unit in the encoder: 1 or 4
     int enc_wpc = 24;    // encoder wavefronts per compute unit (general kernel)
+    int enc_long = 1;    // blocks of 4097 .. 16384 elements: held by a team (0: absmax pass + encode pass, 2: general kernel only)
+    int enc_wpc8 = 8;    //   wavefronts per compute unit with 8 quads per lane (measured: 8: 55, 12: 57, 16: 57 us at block 8192),
+    int enc_wpc6 = 12;   //   6 (12: 59, 20: 62 us at block 5000)
+    int enc_wpc12 = 12;  //   and 12 (12: 56, 8: 57, 16: 57-59 us at block 9216 and 12288)
+    int enc_wpc16 = 8;   //   16 (8: 57, 4: 64 us at block 16384),
     int enc_lean = 1;    // whole aligned 4096-element blocks go to the kernel without slow paths in its loop,
     int enc_lean_wpc = 8;  //   which keeps its loads in flight with this many wavefronts per compute unit
     int enc_fill = 1;    //   and puts a team on every resident slot, even if some then get one block fewer
@@ -183,6 +188,17 @@ size_t holding_unit(size_t block_len)
     size_t unit = 256;
     while (unit < block_len && unit < (size_t)kUnit) unit <<= 1;
     return unit;
+}
+
+// The longest block that dq8_encode holds in a team's registers (maximum and quantisation from one read of x).
+constexpr size_t kLongestHeldBlock = 16384;
+
+// Elements per unit for compression: the smallest power of two that holds a block, up to 4096 when the scales
+// are given and up to 16384 when the kernel computes them.
+size_t encode_unit(size_t block_len, bool fused)
+{
+    if (fused && block_len > (size_t)kUnit && block_len <= kLongestHeldBlock) return block_len <= 8192 ? 8192 : 16384;
+    return holding_unit(block_len);
 }
 
 struct Plan {
@@ -451,11 +467,13 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     // wavefronts per unit, four quads per lane.  Smaller: one wavefront per unit (1, 2, 4 or 8 quads per lane) and
     // every wavefront slot of the compute units in use.
     const size_t Bq = block_length(n, block);
-    const size_t unit = holding_unit(Bq);
+    const size_t unit = encode_unit(Bq, fused);
     const bool small = unit < (size_t)kUnit;
-    const int wpb = small ? 1 : (g_tune.enc_wpb == 4 ? 4 : 1);
+    const int wpb = small ? 1 : ((g_tune.enc_wpb == 4 || unit > (size_t)kUnit) ? 4 : 1);
     const int ql = (int)(unit / (size_t)(4 * kWave * wpb));
-    Plan p = make_plan(n, block, st.cus, small ? 32 : g_tune.enc_wpc, wpb, kWavesPerWg, unit);
+    // resident wavefronts per compute unit: what the registers of the longer units leave room for
+    const int wpc = small ? 32 : (unit == 8192 ? 16 : (unit == 16384 ? 8 : g_tune.enc_wpc));
+    Plan p = make_plan(n, block, st.cus, wpc, wpb, kWavesPerWg, unit);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + kTeamSlots) * sizeof(uint32_t);
     // Whole aligned blocks of exactly one unit: the kernel without slow paths in its loop.
@@ -481,6 +499,36 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
 #undef DQ8_ENC_FULL
         return after_launch("k_encode_full");
     }
+    // Blocks of 4097 .. 16384 elements in whole quads, aligned buffers: the team holds a block in 8, 12 or 16
+    // quads per lane.
+    const size_t tail = n % p.B;
+    if (fused && g_tune.enc_long == 1 && unit > (size_t)kUnit && (p.B & 3) == 0 && (tail & 3) == 0 && p.nb < 0xFFFFFFFFull &&
+        ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
+        const uint32_t bq = (uint32_t)(p.B / 4), tail_q = (uint32_t)(tail / 4);
+        const int qpl = bq <= 1536 ? 6 : (bq <= 2048 ? 8 : (bq <= 3072 ? 12 : 16));
+        const int lwpc = qpl == 6 ? g_tune.enc_wpc6 : (qpl == 8 ? g_tune.enc_wpc8 : (qpl == 12 ? g_tune.enc_wpc12 : g_tune.enc_wpc16));
+        size_t teams = (size_t)st.cus * (size_t)lwpc / 4;
+        if (teams > p.nb) teams = p.nb;
+#define DQ8_ENC_LONG(QPL)                                                                                             \
+    if (st.has_remap[kind]) {                                                                                         \
+        hipLaunchKernelGGL((k_encode_long<QPL, 1, true>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x,      \
+                           (uint32_t)p.nb, (uint32_t)teams, bq, tail_q, scales, codes);                               \
+    } else {                                                                                                          \
+        hipLaunchKernelGGL((k_encode_long<QPL, 1, false>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x,     \
+                           (uint32_t)p.nb, (uint32_t)teams, bq, tail_q, scales, codes);                               \
+    }
+        if (qpl == 6) {
+            DQ8_ENC_LONG(6)
+        } else if (qpl == 8) {
+            DQ8_ENC_LONG(8)
+        } else if (qpl == 12) {
+            DQ8_ENC_LONG(12)
+        } else {
+            DQ8_ENC_LONG(16)
+        }
+#undef DQ8_ENC_LONG
+        return after_launch("k_encode_long");
+    }
 #define DQ8_ENC(WPB, QL, FUSED, FD)                                                                               \
     hipLaunchKernelGGL((k_encode<WPB, QL, 1, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
                        p.upb, p.n_units, p.n_teams, scales, codes)
@@ -491,7 +539,11 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
         DQ8_ENC(WPB, QL, false, FD); \
     }
     const bool fd = g_tune.fastdiv != 0;
-    if (wpb == 4) {
+    if (wpb == 4 && ql == 8) {
+        DQ8_ENC(4, 8, true, true);
+    } else if (wpb == 4 && ql == 16) {
+        DQ8_ENC(4, 16, true, true);
+    } else if (wpb == 4) {
         if (fd) {
             DQ8_ENC_F(4, 4, true)
         } else {
@@ -962,7 +1014,8 @@ int dq8_encode(int kind, const float *x, size_t n, size_t block, float *scales, 
     codes += done;
     scales += done / Bq;
     n -= done;
-    const bool fused = !given && Bq <= (size_t)kUnit;  // the block fits one unit: absmax and encode in one kernel
+    // the block fits one unit: absmax and encode in one kernel
+    const bool fused = !given && Bq <= (g_tune.enc_long ? kLongestHeldBlock : (size_t)kUnit);
     if (!given && !fused) {
         rc = launch_absmax(*st, x, n, block, scales, stream);
         if (rc) return rc;
@@ -1219,6 +1272,7 @@ int dq8_internal_tune(const char *key, int value)
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},

@@ -113,6 +113,9 @@ struct Encoder {
     static constexpr int Q = QL;
     static constexpr uint32_t TEAM = kWave * WPB;
     static constexpr int U = QL * 4 * (int)TEAM;
+    // Units of 8192 and 16384 elements serve every block length above 4096: a short block leaves whole rows
+    // of a unit empty, which are neither loaded nor quantised.
+    static constexpr bool kSkipRows = WPB > 1 && QL > 4;
 
     const float *x;
     uint8_t *codes;
@@ -140,6 +143,10 @@ struct Encoder {
 #pragma unroll
             for (int it = 0; it < Q; ++it) {
                 const uint32_t q = it * TEAM + tl;
+                if (kSkipRows && it * TEAM > last) {  // the same for the whole team: a row past the end of the unit
+                    sl.v[it] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                    continue;
+                }
                 sl.v[it] = ldg<NT>(p4 + (q < last ? q : last));
             }
         }
@@ -186,6 +193,7 @@ struct Encoder {
             constexpr int G = WPB > 1 ? 1 : (Q < 4 ? Q : 4);
 #pragma unroll
             for (int g = 0; g < Q; g += G) {
+                if (kSkipRows && g * TEAM >= nq) continue;
                 v4f vv[G];
                 uint32_t cw[G];
 #pragma unroll
@@ -342,6 +350,98 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
         const float r = 1.0f / d;
         const bool recip = reciprocal_ok(d);
         for (uint32_t i = tl; i < tail_len; i += kWg) pc[i] = (uint8_t)encode_one<FASTDIV>(sr, px[i], d, r, recip);
+    }
+}
+
+// Compression of blocks of 4097 .. 16384 elements from one read of x: the scheme of k_encode_full with QPL
+// quads per lane (a team of four wavefronts holds up to QPL * 1024 elements) and a block length given
+// at run time.  Blocks are whole quads (bq of them) and x is 16-byte, codes 4-byte aligned, so every block
+// starts on aligned addresses.  A lane whose quad lies past the end of the block loads the block's last quad
+// instead (an unconditional load of valid memory: the maximum does not change and the lane stores nothing).
+// The last block may be shorter (tail_q quads, 0: none): it is one more unit, with its own length.
+template <int QPL, int NT, bool REMAP>
+__global__ __launch_bounds__(kWg) void k_encode_long(const uint32_t *__restrict__ tab, const float *__restrict__ x,
+                                                    uint32_t n_units, uint32_t n_teams, uint32_t bq, uint32_t tail_q,
+                                                    float *__restrict__ scales, uint8_t *__restrict__ codes)
+{
+    constexpr int Q = QPL;
+    constexpr int G = Q % 4 == 0 ? 4 : 2;  // quads whose table lookups are issued together
+    static_assert(Q % G == 0, "whole groups of quads");
+    extern __shared__ uint32_t lds[];
+    uint32_t *slots = lds;  // kTeamSlots words, then the bucket table
+    const uint32_t lane = threadIdx.x & 63, wave = wave_in_wg(), tl = threadIdx.x;
+    uint32_t phase = 0;
+    Search sr;
+    auto quads_of = [&](uint32_t u) { return (tail_q != 0 && u == n_units - 1) ? tail_q : bq; };
+    auto fetch = [&](uint32_t u, v4f(&v)[Q]) {
+        const v4f *p4 = reinterpret_cast<const v4f *>(x) + (size_t)u * bq;
+        const uint32_t last = quads_of(u) - 1;
+#pragma unroll
+        for (int it = 0; it < Q; ++it) {
+            const uint32_t q = it * kWg + tl;
+            v[it] = ldg_at<NT>(p4, q < last ? q : last);
+        }
+    };
+    auto team_max = [&](uint32_t m) {
+        if (lane == 0) slots[phase * kWavesPerWg + wave] = m;
+        __syncthreads();
+        const uint32_t *sp = slots + phase * kWavesPerWg;
+        const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
+        phase ^= 1;  // the other half of slots next time
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+    };
+    auto process = [&](uint32_t u, v4f(&v)[Q]) {
+        float fm = 0.0f;
+#pragma unroll
+        for (int it = 0; it < Q; ++it) fm = max4_abs(v[it], fm);
+        const float s = u2f(team_max(wave_max_u32(f2u(fm))));
+        if (tl == 0) scales[u] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        uint32_t *c4 = reinterpret_cast<uint32_t *>(codes) + (size_t)u * bq;
+        const uint32_t nq = quads_of(u);
+#pragma unroll
+        for (int g = 0; g < Q; g += G) {
+            v4f vv[G];
+            uint32_t cw[G];
+#pragma unroll
+            for (int it = 0; it < G; ++it) vv[it] = v[g + it];
+            encode_quads<true, G>(sr, vv, d, r, recip, cw);
+#pragma unroll
+            for (int it = 0; it < G; ++it) {
+                const uint32_t q = (g + it) * kWg + tl;
+                if (q < nq) stg_at<NT>(c4, q, cw[it]);
+            }
+        }
+    };
+    uint32_t u = blockIdx.x;
+    v4f a[Q], b[Q];
+    if (u < n_units) fetch(u, a);  // the first loads are in flight while the table is copied
+    sr = load_bucket_table(tab, lds + kTeamSlots);
+    if (!REMAP) sr.remap = nullptr;
+    __syncthreads();
+    // steady state as in k_encode_full: the next block's loads are issued unconditionally before the work on
+    // the current one
+    if (u < n_units) {
+        for (;;) {
+            uint32_t nx = u + n_teams;
+            if (!(nx < n_units)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_teams;
+            if (!(nx < n_units)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
     }
 }
 

@@ -82,6 +82,26 @@ def test_config3_full_bucket_other_types(dq8, kind):
     bits_equal(out, oracle.decode(kind, want_codes, want_scales, B), "C3 decode")
 
 
+@pytest.mark.parametrize("block", [8192, 9216, 16384])
+def test_config3_full_bucket_long_blocks(dq8, block):
+    """Blocks that a team holds in 8 to 16 quads per lane: every scale, and the codes of a sample of blocks
+    (the first ones, the ragged last one, 60 drawn ones), against the oracle."""
+    x = workloads.bucket(3)
+    xd = torch.from_numpy(x).cuda()
+    print("C3 block %d: gpu encode" % block, flush=True)
+    codes, scales = dq8.encode(KIND, xd, block)
+    torch.cuda.synchronize()
+    bits_equal(scales, oracle.absmax(x, block), "scales at block %d" % block)
+    nb = oracle.dq8_oracle.n_blocks(x.size, block)
+    rng = np.random.Generator(np.random.PCG64(77 + block))
+    sample = sorted(set([0, 1, 2, nb - 2, nb - 1]) | set(rng.integers(0, nb, 60).tolist()))
+    got = codes.cpu().numpy()
+    for b in sample:
+        lo, hi = b * block, min((b + 1) * block, x.size)
+        want_codes, _ = oracle.encode(KIND, x[lo:hi], block)
+        assert got[lo:hi].tobytes() == want_codes.tobytes(), "codes of block %d at block length %d" % (b, block)
+
+
 def test_config5_aggregation_pipeline(dq8):
     K = workloads.C5_WORKERS
     n = workloads.C3_NUMEL

@@ -116,6 +116,9 @@ SHAPES = [  # (n, block)
     (5 * 1024 + 300, 64), (3 * 1024, 4), (2 * 1024 + 8, 8), (4 * 1024 + 100, 16), (7 * 1024 + 96, 32),
     (3 * 1024 + 640, 128), (40 * 1024 + 64, 64), (1024, 64), (1023, 64), (1025, 128), (9 * 512 + 100, 512),
     (6 * 1024 + 24, 1024),
+    # blocks of 4097 .. 16384 elements are held by a team in units of 8192 / 16384 elements
+    (3 * 16384 + 5000, 16384), (2 * 9216 + 4, 9216), (3 * 4100, 4100), (2 * 8196 + 3, 8196), (16384, 0),
+    (2 * 8191, 8191), (2 * 16385, 16385), (4 * 8192, 8192), (5 * 12288, 12288),
 ]
 
 
@@ -132,6 +135,9 @@ def test_misaligned_pointers(dq8, kind):
     x = workloads.edge_case_block("wide", n, seed=50 + kind)
     for x_off, c_off in [(1, 0), (0, 1), (3, 2), (2, 3)]:
         check_encode_decode(dq8, kind, x, 4096, x_off=x_off, c_off=c_off, tag="misaligned")
+    x = workloads.edge_case_block("wide", 2 * 9216 + 100, seed=60 + kind)  # blocks held in a 16384-element unit
+    for x_off, c_off in [(1, 0), (0, 2)]:
+        check_encode_decode(dq8, kind, x, 9216, x_off=x_off, c_off=c_off, tag="misaligned-long")
         check_encode_decode(dq8, kind, x, 0, x_off=x_off, c_off=c_off, tag="misaligned-pertensor")
 
 
@@ -145,6 +151,8 @@ def test_degenerate_blocks(dq8, kind):
     check_encode_decode(dq8, kind, x, B, tag="degenerate")
     check_encode_decode(dq8, kind, x, 0, tag="degenerate-pertensor")
     check_encode_decode(dq8, kind, x, 64, tag="degenerate-64")
+    check_encode_decode(dq8, kind, x, 8192, tag="degenerate-8192")
+    check_encode_decode(dq8, kind, x, 3 * 4096, tag="degenerate-12288")
 
 
 @pytest.mark.parametrize("kind", KINDS)
