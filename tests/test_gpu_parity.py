@@ -389,12 +389,13 @@ def test_random_shapes_through_every_call(dq8, seed):
         n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 6000), rng.integers(6000, 40000)]))
         if case == 0:  # one size per seed at which every wavefront walks several units
             n = int(rng.integers(1_500_000, 3_000_000))
-        pick = rng.integers(0, 6)
+        pick = rng.integers(0, 7)
         block = [0, int(rng.integers(1, n + 1)), 4 * int(rng.integers(1, max(2, n // 4 + 1))),
-                 1 << int(rng.integers(0, 14)), 4096, int(rng.integers(1, 9)) * 1000][pick]
+                 1 << int(rng.integers(0, 15)), 4096, int(rng.integers(1, 9)) * 1000,
+                 4 * int(rng.integers(1025, 4097))][pick]  # the last: blocks that a team holds in 6 to 16 quads per lane
         kind = int(rng.integers(0, 4))
         x_off, c_off = int(rng.integers(0, 4)) * int(rng.integers(0, 2)), int(rng.integers(0, 4)) * int(rng.integers(0, 2))
-        K = int(rng.choice([1, 2, 3, 4, 5, 8, 9]))
+        K = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 17]))
         with_local = bool(rng.integers(0, 2))
         tag = "random seed=%d case=%d n=%d block=%d kind=%d x_off=%d c_off=%d K=%d local=%d" % (
             seed, case, n, block, kind, x_off, c_off, K, with_local)
