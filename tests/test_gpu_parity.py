@@ -314,6 +314,24 @@ def test_decode_accumulate_avg(dq8, kind, K):
 
 
 
+@pytest.mark.parametrize("K", range(9, 33))
+def test_decode_accumulate_avg_many_workers(dq8, K):
+    """Every worker count above 8: the workers are taken a chunk at a time over the same sums, the last chunk
+    with empty places; several units per wavefront and a ragged tail."""
+    kind = KINDS[K % len(KINDS)]
+    rng = np.random.Generator(np.random.PCG64(5900 + K))
+    for n, block in [(40 * 4096 + 333, 4096), (9 * 1024 + 5, 1024), (3 * 512, 0), (2100 * 512 + 12, 2048)]:
+        print("avg many kind=%d K=%d n=%d block=%d" % (kind, K, n, block), flush=True)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-8, 8, nb)).astype(np.float32) for _ in range(K)]
+        want = oracle.decode_accumulate_avg(kind, cl, sl, block)
+        go = Guarded(n, np.float32, 0)
+        got = dq8.decode_accumulate_avg(kind, [dev(c) for c in cl], [dev(s) for s in sl], block, out=go.t)
+        same_bits(got, want, "avg many")
+        go.check("avg many")
+
+
 @pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("K", [0, 1, 2, 3, 4, 5, 6, 7, 8, 32])
 def test_decode_accumulate_avg_with_local_term(dq8, kind, K):
