@@ -143,7 +143,8 @@ struct Tuning {
     int blk_wpw = 8;     // register-resident average: wavefronts per workgroup (two workgroups per compute unit)
     int avg_team = 1;    // average-then-compress with up to 8 workers: the team kernel (0: the wave-per-block kernel)
     int avg_steady = 1;  //   unconditional steady-state iterations when the buffers are aligned
-    int avg_teams = 3;   //   teams per workgroup: 2, 3 or 4
+    int avg_teams = 0;   //   teams per workgroup: 2, 3 or 4 (0: by the number of workers)
+    int avg_teams4_upto = 6;  //   four teams for up to this many workers (K = 3: 79 -> 69 us, K = 6: 94 -> 92 us), three beyond (K = 8: 105 against 120 us)
     int avg_wgpc = 1;    //   workgroups per compute unit (2 only with 2 teams)
     int copy_q = 2;
     int copy_wpc = 8;
@@ -463,9 +464,10 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
 int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
                   bool fused, hipStream_t stream)
 {
-    // Unit = the smallest power of two that holds a block, between 256 and 4096 elements.  4096: a team of four
-    // wavefronts per unit, four quads per lane.  Smaller: one wavefront per unit (1, 2, 4 or 8 quads per lane) and
-    // every wavefront slot of the compute units in use.
+    // Unit = the smallest power of two that holds a block, from 256 elements up to 4096 (scales given) or 16384
+    // (scales computed here).  4096 and more: a team of four wavefronts per unit with 4, 8 or 16 quads per lane.
+    // Smaller: one wavefront per unit (1, 2, 4 or 8 quads per lane) and every wavefront slot of the compute
+    // units in use.
     const size_t Bq = block_length(n, block);
     const size_t unit = encode_unit(Bq, fused);
     const bool small = unit < (size_t)kUnit;
@@ -656,8 +658,13 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 {
     const size_t Bq = block_length(n, block);
     const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
-    const bool tuned_k = K == 2 || K == 4 || K == 8;  // the worker counts with variants for 2 and 4 teams
-    const int teams = (ragged || !tuned_k) ? 3 : ((g_tune.avg_teams == 3 || g_tune.avg_teams == 4) ? g_tune.avg_teams : 2);
+    const bool tuned_k = K == 2 || K == 4 || K == 8;  // the worker counts with a variant for 2 teams
+    // Teams per workgroup: 3; 4 when each team has few code words in flight (up to `avg_teams4_upto` workers);
+    // avg_teams overrides this where the variant exists.
+    int teams = (K >= 1 && K <= g_tune.avg_teams4_upto && K <= 6) ? 4 : 3;
+    if (g_tune.avg_teams == 3 || g_tune.avg_teams == 4) teams = g_tune.avg_teams;
+    if (g_tune.avg_teams == 2 && tuned_k) teams = 2;
+    if (ragged || K == 7 || K > 8) teams = 3;
     const int wgs_per_cu = (teams == 2 && g_tune.avg_wgpc == 2) ? 2 : 1;
     Plan p = make_plan(n, block, st.cus, 4 * teams * wgs_per_cu, 4, 4 * teams, kUnit);
     const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
@@ -691,8 +698,22 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     } else {                     \
         DQ8_TEAM_T(KT, false)    \
     }
-    // K = 1, 3, 5, 6, 7: three teams per workgroup only
+    // K = 1, 3, 5, 6: three or four teams per workgroup; K = 7: three
+#define DQ8_TEAM_34(KT, RM)                  \
+    if (ragged) {                            \
+        DQ8_TEAM(KT, RM, 3, true);           \
+    } else if (teams == 4) {                 \
+        DQ8_TEAM(KT, RM, 4, false);          \
+    } else {                                 \
+        DQ8_TEAM(KT, RM, 3, false);          \
+    }
 #define DQ8_TEAM_3(KT)                       \
+    if (st.has_remap[kind]) {                \
+        DQ8_TEAM_34(KT, true)                \
+    } else {                                 \
+        DQ8_TEAM_34(KT, false)               \
+    }
+#define DQ8_TEAM_7(KT)                       \
     if (st.has_remap[kind]) {                \
         if (ragged) {                        \
             DQ8_TEAM(KT, true, 3, true);     \
@@ -737,10 +758,12 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     case 4: DQ8_TEAM_RM(4) break;
     case 5: DQ8_TEAM_3(5) break;
     case 6: DQ8_TEAM_3(6) break;
-    case 7: DQ8_TEAM_3(7) break;
+    case 7: DQ8_TEAM_7(7) break;
     default: DQ8_TEAM_RM(8) break;
     }
+#undef DQ8_TEAM_7
 #undef DQ8_TEAM_3
+#undef DQ8_TEAM_34
 #undef DQ8_TEAM_RM
 #undef DQ8_TEAM_T
 #undef DQ8_TEAM
@@ -1275,7 +1298,7 @@ int dq8_internal_tune(const char *key, int value)
         {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
-        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 2, 4}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
+        {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 0, 4}, {"avg_teams4_upto", &g_tune.avg_teams4_upto, 0, 6}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)
         if (!std::strcmp(k.name, key)) {
