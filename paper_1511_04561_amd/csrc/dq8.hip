@@ -126,6 +126,9 @@ struct Tuning {
     int enc_wpc = 24;    // encoder wavefronts per compute unit (general kernel)
     int enc_long = 1;    // blocks of 4097 .. 16384 elements: held by a team (0: absmax pass + encode pass, 2: general kernel only)
     int enc_wpc8 = 8;    //   wavefronts per compute unit with 8 quads per lane (measured: 8: 55, 12: 57, 16: 57 us at block 8192),
+    int enc_mid = 1536;  // blocks longer than this, up to 3072 elements: the same kernel (0: off; measured 1500: 62 -> 63 us,
+                         //   2000: 60 -> 58, 2048: 57.5 -> 55, 3000: 62 -> 57.5, 3072: 58 -> 55, 4000: 56 -> 58)
+    int enc_wpc4 = 16;   //   its wavefronts per compute unit with 2 or 3 quads per lane (8: 72, 16: 55, 24: 55, 32: 56 us at 2048)
     int enc_wpc6 = 12;   //   6 (12: 59, 20: 62 us at block 5000)
     int enc_wpc12 = 12;  //   and 12 (12: 56, 8: 57, 16: 57-59 us at block 9216 and 12288)
     int enc_wpc16 = 8;   //   16 (8: 57, 4: 64 us at block 16384),
@@ -504,11 +507,14 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     // Blocks of 4097 .. 16384 elements in whole quads, aligned buffers: the team holds a block in 8, 12 or 16
     // quads per lane.
     const size_t tail = n % p.B;
-    if (fused && g_tune.enc_long == 1 && unit > (size_t)kUnit && (p.B & 3) == 0 && (tail & 3) == 0 && p.nb < 0xFFFFFFFFull &&
-        ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
+    const bool long_block = unit > (size_t)kUnit;
+    // blocks of 1537 .. 3072 elements too: 2 or 3 quads per lane (2 to 7 % faster than a wavefront per block there)
+    const bool mid_block = g_tune.enc_mid && p.B > (size_t)g_tune.enc_mid && p.B <= 3072;
+    if (fused && g_tune.enc_long == 1 && (long_block || mid_block) && (p.B & 3) == 0 &&
+        (tail & 3) == 0 && p.nb < 0xFFFFFFFFull && ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
         const uint32_t bq = (uint32_t)(p.B / 4), tail_q = (uint32_t)(tail / 4);
-        const int qpl = bq <= 1536 ? 6 : (bq <= 2048 ? 8 : (bq <= 3072 ? 12 : 16));
-        const int lwpc = qpl == 6 ? g_tune.enc_wpc6 : (qpl == 8 ? g_tune.enc_wpc8 : (qpl == 12 ? g_tune.enc_wpc12 : g_tune.enc_wpc16));
+        const int qpl = bq <= 512 ? 2 : (bq <= 768 ? 3 : (bq <= 1536 ? 6 : (bq <= 2048 ? 8 : (bq <= 3072 ? 12 : 16))));  // quads per lane
+        const int lwpc = qpl <= 3 ? g_tune.enc_wpc4 : (qpl == 6 ? g_tune.enc_wpc6 : (qpl == 8 ? g_tune.enc_wpc8 : (qpl == 12 ? g_tune.enc_wpc12 : g_tune.enc_wpc16)));
         size_t teams = (size_t)st.cus * (size_t)lwpc / 4;
         if (teams > p.nb) teams = p.nb;
 #define DQ8_ENC_LONG(QPL)                                                                                             \
@@ -519,7 +525,11 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
         hipLaunchKernelGGL((k_encode_long<QPL, 1, false>), dim3((unsigned)teams), dim3(kWg), lds, stream, tab, x,     \
                            (uint32_t)p.nb, (uint32_t)teams, bq, tail_q, scales, codes);                               \
     }
-        if (qpl == 6) {
+        if (qpl == 2) {
+            DQ8_ENC_LONG(2)
+        } else if (qpl == 3) {
+            DQ8_ENC_LONG(3)
+        } else if (qpl == 6) {
             DQ8_ENC_LONG(6)
         } else if (qpl == 8) {
             DQ8_ENC_LONG(8)
@@ -1295,7 +1305,7 @@ int dq8_internal_tune(const char *key, int value)
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
-        {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
+        {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 0, 4}, {"avg_teams4_upto", &g_tune.avg_teams4_upto, 0, 6}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},

@@ -353,7 +353,7 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
     }
 }
 
-// Compression of blocks of 4097 .. 16384 elements from one read of x: the scheme of k_encode_full with QPL
+// Compression of blocks of up to 16384 elements from one read of x: the scheme of k_encode_full with QPL
 // quads per lane (a team of four wavefronts holds up to QPL * 1024 elements) and a block length given
 // at run time.  Blocks are whole quads (bq of them) and x is 16-byte, codes 4-byte aligned, so every block
 // starts on aligned addresses.  A lane whose quad lies past the end of the block loads the block's last quad
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kWg) void k_encode_long(const uint32_t *__restrict_
                                                     float *__restrict__ scales, uint8_t *__restrict__ codes)
 {
     constexpr int Q = QPL;
-    constexpr int G = Q % 4 == 0 ? 4 : 2;  // quads whose table lookups are issued together
+    constexpr int G = Q < 4 ? Q : (Q % 4 == 0 ? 4 : 2);  // quads whose table lookups are issued together
     static_assert(Q % G == 0, "whole groups of quads");
     extern __shared__ uint32_t lds[];
     uint32_t *slots = lds;  // kTeamSlots words, then the bucket table
