@@ -137,6 +137,7 @@ struct Tuning {
     int enc_fill = 1;    //   and puts a team on every resident slot, even if some then get one block fewer
     int amax_q = 16;     // absmax: quads per lane in flight (unit = 256 q elements)
     int amax_wpc = 3;    //   wavefronts per compute unit: 3 measured best (36.2 us against 37.5 with 4 on 61 M elements)
+    int dec_flat = 1;    // decode: units by position for blocks that are not whole units (0: off, 2: for every block length)
     int dec_q = 16;      // decode: code words per lane in flight
     int dec_wpc = 4;
     int dec_wpw = 4;     // decode: wavefronts per workgroup (they share one table in LDS)
@@ -616,6 +617,45 @@ int launch_decode(const DeviceState &st, int kind, const uint8_t *codes, const f
     Plan p = make_plan(n, block, st.cus, wpc, 1, wpw, (size_t)q * 4 * kWave);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const bool ragged = p.nb > 1 && p.B % ((size_t)q * 4 * kWave) != 0;  // blocks end inside units
+    // Blocks that do not consist of whole units (or, dec_flat == 2, any): units by position, not by block, with up
+    // to eight blocks' scales per unit.  Needs blocks of whole quads and aligned buffers.
+    const size_t bq = p.B / 4;
+    if (g_tune.dec_flat && (ragged || g_tune.dec_flat == 2) && p.nb > 1 && (p.B & 3) == 0 && bq >= 10 && bq < (1u << 28) &&
+        ((uintptr_t)out & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
+        int fq = 16, fwpc = g_tune.dec_wpc;
+        while ((size_t)fq * kWave > 7 * bq) {  // at most eight blocks per unit
+            fq >>= 1;
+            fwpc = fwpc * 2 > 32 ? 32 : fwpc * 2;
+        }
+        const bool four = (size_t)fq * kWave <= 3 * bq;  // at most four: fewer compares per quad
+        const int fw = fq == 16 ? 4 : (fq == 8 ? 8 : 16);  // wavefronts per workgroup (they share the table)
+        const uint64_t nq = n / 4, uq = (uint64_t)fq * kWave, n_units = (nq + uq - 1) / uq;
+        uint64_t waves = (uint64_t)st.cus * (uint64_t)fwpc;
+        if (waves > n_units) waves = n_units;
+        if (waves < 1) waves = 1;
+        const unsigned grid = (unsigned)((waves + fw - 1) / fw);
+        const uint32_t n_waves = grid * (uint32_t)fw;
+        const uint64_t step = (uint64_t)n_waves * uq;
+#define DQ8_DEC_FLAT_N(Q, NS, WPW)                                                                                       \
+    hipLaunchKernelGGL((k_decode_flat<Q, NS, 2, WPW>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, nq, \
+                       (uint32_t)(n & 3), (uint32_t)bq, (uint64_t)p.nb, n_units, n_waves, step / bq, (uint32_t)(step % bq), out)
+#define DQ8_DEC_FLAT(Q, WPW)           \
+    if (four) {                        \
+        DQ8_DEC_FLAT_N(Q, 4, WPW);     \
+    } else {                           \
+        DQ8_DEC_FLAT_N(Q, 8, WPW);     \
+    }
+        switch (fq) {
+        case 1: DQ8_DEC_FLAT(1, 16); break;
+        case 2: DQ8_DEC_FLAT(2, 16); break;
+        case 4: DQ8_DEC_FLAT(4, 16); break;
+        case 8: DQ8_DEC_FLAT(8, 8); break;
+        default: DQ8_DEC_FLAT(16, 4); break;
+        }
+#undef DQ8_DEC_FLAT
+#undef DQ8_DEC_FLAT_N
+        return after_launch("k_decode_flat");
+    }
 #define DQ8_DEC(Q, WPW, RG)                                                                                          \
     hipLaunchKernelGGL((k_decode<Q, 2, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
                        p.nb, p.upb, p.n_units, p.n_teams, out)
@@ -1307,7 +1347,7 @@ int dq8_internal_tune(const char *key, int value)
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
-        {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
+        {"dec_flat", &g_tune.dec_flat, 0, 2}, {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 0, 4}, {"avg_teams4_upto", &g_tune.avg_teams4_upto, 0, 6}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
     for (auto &k : keys)

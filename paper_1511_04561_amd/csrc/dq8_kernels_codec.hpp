@@ -353,6 +353,87 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
     }
 }
 
+// Decompression with units that do not follow the blocks: unit u is quads [u Q 64, (u + 1) Q 64) of the array
+// (a quad = 4 consecutive elements; blocks are whole quads, bq of them, so a quad never straddles two blocks),
+// whatever the block length.  The host picks Q and NS with Q 64 <= (NS - 1) bq: a unit then touches at most NS
+// blocks, whose scales are NS scalar loads (indices clamped to the last block), and every quad selects its own
+// by comparing its offset from the start of the unit's first block with bq, 2 bq, ...  The block index and
+// offset of a wavefront's unit advance by the same step every iteration (step_b blocks and step_r < bq
+// quads), so there is one division per wavefront.  out is 16-byte, codes 4-byte aligned; the last unit may be
+// short (a lane past the end repeats the last code word's load and stores nothing); `left` elements after the
+// last whole quad (they belong to the last block) are done one by one by the wavefront that has the last unit.
+template <int Q, int NS, int NT, int WPW>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_flat(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
+                                                            const float *__restrict__ scales, uint64_t nq, uint32_t left,
+                                                            uint32_t bq, uint64_t nb, uint64_t n_units, uint32_t n_waves,
+                                                            uint64_t step_b, uint32_t step_r, float *__restrict__ out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr uint32_t UQ = Q * kWave;  // quads per unit
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    uint64_t u = first_unit(WPW);
+    uint64_t b0 = (u * UQ) / bq;               // block of the unit's first quad
+    uint32_t r0 = (uint32_t)((u * UQ) % bq);   // and that quad's offset in it
+    uint32_t w[Q], len = 0;
+    float sc[NS];
+    auto open_unit = [&](uint64_t uu, uint64_t bb) {
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes) + uu * UQ;
+        const uint64_t rest = nq - uu * UQ;
+        len = rest < UQ ? (uint32_t)rest : UQ;
+        const uint32_t last = len - 1;
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint32_t i = j * kWave + lane;
+            w[j] = ldg_at<NT>(c4, i < last ? i : last);
+        }
+#pragma unroll
+        for (int t = 0; t < NS; ++t) sc[t] = scales[bb + t < nb ? bb + t : nb - 1];
+    };
+    if (u < n_units) open_unit(u, b0);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    while (u < n_units) {
+        uint32_t cur[Q];
+#pragma unroll
+        for (int j = 0; j < Q; ++j) cur[j] = w[j];
+        float cs[NS];
+#pragma unroll
+        for (int t = 0; t < NS; ++t) cs[t] = sc[t];
+        const uint32_t nqu = len, base = r0 + lane;
+        v4f *o4 = reinterpret_cast<v4f *>(out) + u * UQ;
+        const bool last_unit = u == n_units - 1;
+        const uint64_t last_block = nb - 1;
+        u += n_waves;
+        b0 += step_b;
+        r0 += step_r;
+        if (r0 >= bq) {
+            r0 -= bq;
+            b0 += 1;
+        }
+        if (u < n_units) open_unit(u, b0);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint32_t o = base + j * kWave;
+            float s = cs[0];
+#pragma unroll
+            for (int t = 1; t < NS; ++t) s = o >= (uint32_t)t * bq ? cs[t] : s;
+            v4f r;
+            r.x = lut_at<0>(lut, cur[j], lane4) * s;
+            r.y = lut_at<1>(lut, cur[j], lane4) * s;
+            r.z = lut_at<2>(lut, cur[j], lane4) * s;
+            r.w = lut_at<3>(lut, cur[j], lane4) * s;
+            if (j * kWave + lane < nqu) stg<NT>(o4 + j * kWave + lane, r);
+        }
+        if (last_unit && lane < left) {
+            const uint64_t e = nq * 4 + lane;
+            out[e] = lut_code(lut, codes[e], lane4) * scales[last_block];
+        }
+    }
+    // an array shorter than a quad has no unit at all
+    if (n_units == 0 && blockIdx.x == 0 && wave_in_wg() == 0 && lane < left) out[lane] = lut_code(lut, codes[lane], lane4) * scales[0];
+}
+
 // Compression of blocks of up to 16384 elements from one read of x: the scheme of k_encode_full with QPL
 // quads per lane (a team of four wavefronts holds up to QPL * 1024 elements) and a block length given
 // at run time.  Blocks are whole quads (bq of them) and x is 16-byte, codes 4-byte aligned, so every block

@@ -120,6 +120,8 @@ SHAPES = [  # (n, block)
     (3 * 16384 + 5000, 16384), (2 * 9216 + 4, 9216), (3 * 4100, 4100), (2 * 8196 + 3, 8196), (16384, 0),
     (2 * 8191, 8191), (2 * 16385, 16385), (4 * 8192, 8192), (5 * 12288, 12288),
     (5 * 2048 + 8, 2048), (4 * 3000, 3000), (3 * 2000 + 4, 2000), (2 * 3072 + 100, 3072), (3 * 1540, 1540),  # and in 2 or 3
+    # blocks of whole quads that are not whole units: decompression walks units by position, up to 8 blocks per unit
+    (500 * 40 + 3, 40), (300 * 100, 100), (70 * 200 + 1, 200), (900 * 36 + 2, 36), (33 * 588 + 7, 588), (40 * 340, 340),
 ]
 
 
