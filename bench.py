@@ -38,7 +38,7 @@ N_SETS = 4
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs on this script, each scaled by what the same counter reads for the calibration
-# copy kernel: 1.99980 and 1.00000); the runs are recorded in profiles/hbm_traffic_bench_c5.md.
+# copy kernel: 1.99982 and 1.00000); the runs are recorded in profiles/hbm_traffic_bench_c5.md.
 GROUPS = 5  # per-kernel timing: median of this many groups of `steps` launches
 MEASURED_TRAFFIC_BYTES = {"decode_accumulate_avg": int((481267 + 238675) * 1024)}
 
