@@ -117,6 +117,7 @@ struct Tuning {
     int avg_lean = 1;    // decode-and-average of whole aligned units: the kernel without slow paths in its loop
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
+    int avg_flat = 1;       //   up to 8 workers, blocks of whole quads that are not a power-of-two number of units: units by position
     int avg_chunk_all = 0;  //   1: that kernel for K = 2, 4, 8 as well
     int avg_chunk_wpc = 8;  //   wavefronts per compute unit of the kernel that takes the workers four at a time
     int avg_lean_wpw = 4;
@@ -879,7 +880,12 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     const int lw = (K >= 1 && K <= 5 && lw_tuned < 8) ? 8 : lw_tuned;
     const size_t U = (size_t)lq * 4 * kWave;
     const size_t upb_l = p.B / U;
-    bool ok = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);
+    const bool by_shift = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);  // a unit's block is u >> shift
+    // otherwise, for up to 8 workers: blocks of whole quads, no shorter than a unit, two blocks' scales per unit
+    const size_t bq = p.B / 4;
+    const bool flat = !by_shift && g_tune.avg_flat && !g_tune.avg_chunk_all && K >= 1 && K <= 8 && lq == 2 && (p.B & 3) == 0 && bq >= U / 4 &&
+                      bq < 0x7FFFFFFFull && p.nb < 0xFFFFFFFFull;
+    bool ok = by_shift || flat;
     ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
     for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
     if (!ok) return DQ8_OK;
@@ -927,6 +933,40 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     // Wavefronts per compute unit: four with 8 workers' code words in flight per lane; more with fewer workers
     // (measured per K; avg_lean_wpc scales all of them).
     static const int kWavesForK[9] = {0, 16, 8, 8, 8, 8, 4, 4, 4};
+    if (flat) {
+        const int fw = K <= 5 ? 8 : 4;  // wavefronts per workgroup
+        // the selects between two scales make 6 and 7 workers want eight wavefronts as well (K = 7: 132 -> 121 us)
+        static const int kFlatWavesForK[9] = {0, 16, 8, 8, 8, 8, 8, 8, 4};
+        size_t waves = (size_t)st.cus * (size_t)(kFlatWavesForK[K] * g_tune.avg_lean_wpc / 4);
+        if (waves > n_full) waves = n_full;
+        const unsigned grid = (unsigned)((waves + fw - 1) / fw);
+        const uint32_t n_waves = grid * (uint32_t)fw;
+        const uint64_t step = (uint64_t)n_waves * (U / 4);
+        const FlatGeom geom = {(uint32_t)bq, (uint32_t)(p.nb - 1), (uint32_t)(step / bq), (uint32_t)(step % bq)};
+#define DQ8_AVGF(KT, WPW, LOC)                                                                                          \
+    hipLaunchKernelGGL((k_decode_avg_flat<KT, 2, WPW, LOC>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, local, \
+                       n_full, n_waves, geom, tail, out)
+#define DQ8_AVGF_L(KT, WPW)        \
+    if (local) {                   \
+        DQ8_AVGF(KT, WPW, true);   \
+    } else {                       \
+        DQ8_AVGF(KT, WPW, false);  \
+    }
+        switch (K) {
+        case 1: DQ8_AVGF_L(1, 8) break;
+        case 2: DQ8_AVGF_L(2, 8) break;
+        case 3: DQ8_AVGF_L(3, 8) break;
+        case 4: DQ8_AVGF_L(4, 8) break;
+        case 5: DQ8_AVGF_L(5, 8) break;
+        case 6: DQ8_AVGF_L(6, 4) break;
+        case 7: DQ8_AVGF_L(7, 4) break;
+        default: DQ8_AVGF_L(8, 4) break;
+        }
+#undef DQ8_AVGF_L
+#undef DQ8_AVGF
+        *launched = true;
+        return after_launch("k_decode_avg_flat");
+    }
     size_t waves = (size_t)st.cus * (size_t)(kWavesForK[K] * g_tune.avg_lean_wpc / 4);
     if (waves > n_full) waves = n_full;
     const unsigned grid = (unsigned)((waves + lw - 1) / lw);
@@ -1344,7 +1384,7 @@ int dq8_internal_tune(const char *key, int value)
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
-        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_flat", &g_tune.avg_flat, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
         {"dec_flat", &g_tune.dec_flat, 0, 2}, {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},

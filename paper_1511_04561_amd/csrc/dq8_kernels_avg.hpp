@@ -243,6 +243,145 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
     }
 }
 
+// k_decode_avg_full for block lengths that are whole quads (bq of them, at least as many as a unit has) but not
+// a power-of-two number of units: unit u is still quads [u Q 64, (u + 1) Q 64) of the array, so it touches at most
+// two blocks.  Both blocks' scales travel with the unit's code words (two scalar loads per worker, the second
+// index clamped to the last block) and every quad selects by comparing its offset from the start of the first
+// block with bq.  The block index b and offset r of a wavefront's units advance by the same step every
+// iteration (step_b blocks and step_r < bq quads): one division per wavefront.
+struct FlatGeom {
+    uint32_t bq, last_block, step_b, step_r;
+};
+
+template <int KT, int NT, int WPW, bool LOCAL>
+__global__ __launch_bounds__(kWave * WPW) void k_decode_avg_flat(const uint32_t *__restrict__ tab, WorkerPtrs p,
+                                                                const float *__restrict__ local, uint32_t n_full,
+                                                                uint32_t n_waves, FlatGeom g, uint32_t tail_len,
+                                                                float *__restrict__ out)
+{
+    static_assert(KT >= 1 && KT <= 8, "unrolled for up to eight workers");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    constexpr int Q = 2;
+    constexpr int U = Q * 4 * kWave;
+    constexpr uint32_t UQ = Q * kWave;
+    constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
+    constexpr int terms = KT + (LOCAL ? 1 : 0);
+    constexpr bool pow2 = (terms & (terms - 1)) == 0;
+    constexpr float rk = 1.0f / fk;  // acc * (1 / K) equals acc / K exactly for a power of two
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t lane4 = lane * 4;
+    struct Slot {
+        uint32_t w[KT][Q];
+        float s0[KT], s1[KT];
+        uint32_t r;
+        v4f loc[LOCAL ? Q : 1];
+    };
+    uint32_t fb = 0, fr = 0;  // block and offset of the first quad of the next unit to fetch
+    auto fetch = [&](uint32_t u, Slot &sl) {
+        if (LOCAL) {
+            const v4f *l4 = reinterpret_cast<const v4f *>(local) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.loc[j] = ldg_at<NT>(l4, j * kWave + lane);
+        }
+        const uint32_t b1 = fb < g.last_block ? fb + 1 : g.last_block;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            sl.s0[k] = p.scales[k][fb];
+            sl.s1[k] = p.scales[k][b1];
+        }
+        sl.r = fr;
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) sl.w[k][j] = ldg_at<NT>(c4, j * kWave + lane);
+        }
+        fb += g.step_b;
+        fr += g.step_r;
+        if (fr >= g.bq) {
+            fr -= g.bq;
+            fb += 1;
+        }
+    };
+    auto process = [&](uint32_t u, Slot &sl) {
+        float a0[KT], a1[KT];
+#pragma unroll
+        for (int k = 0; k < KT; ++k) {
+            a0[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.s0[k])));
+            a1[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.s1[k])));
+        }
+        const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)sl.r) + lane;
+        v4f *o4 = reinterpret_cast<v4f *>(out) + (size_t)u * (U / 4);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const bool second = base + j * kWave >= g.bq;  // this quad lies in the unit's second block
+            v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (LOCAL) {  // the sum starts at +0: a local -0 becomes +0
+                a.x = a.x + sl.loc[j].x;
+                a.y = a.y + sl.loc[j].y;
+                a.z = a.z + sl.loc[j].z;
+                a.w = a.w + sl.loc[j].w;
+            }
+#pragma unroll
+            for (int k = 0; k < KT; ++k) {
+                const float sc = second ? a1[k] : a0[k];
+                a.x = a.x + lut_at<0>(lut, sl.w[k][j], lane4) * sc;
+                a.y = a.y + lut_at<1>(lut, sl.w[k][j], lane4) * sc;
+                a.z = a.z + lut_at<2>(lut, sl.w[k][j], lane4) * sc;
+                a.w = a.w + lut_at<3>(lut, sl.w[k][j], lane4) * sc;
+            }
+            a.x = mean_of(a.x);
+            a.y = mean_of(a.y);
+            a.z = mean_of(a.z);
+            a.w = mean_of(a.w);
+            stg<NT>(o4 + j * kWave + lane, a);
+        }
+    };
+    uint32_t u = (uint32_t)first_unit(WPW);
+    {
+        const uint64_t q0 = (uint64_t)u * UQ;
+        fb = (uint32_t)(q0 / g.bq);
+        fr = (uint32_t)(q0 % g.bq);
+    }
+    Slot a, b;
+    if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is built
+    load_lut(tab, lut);
+    __syncthreads();
+    if (u < n_full) {
+        for (;;) {
+            uint32_t nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_waves;
+            if (!(nx < n_full)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
+    }
+    if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
+        const size_t start = (size_t)n_full * U;
+        const size_t B = (size_t)g.bq * 4;
+        for (uint32_t i = lane; i < tail_len; i += kWave) {
+            const size_t blk = (start + i) / B;
+            float acc = 0.0f;
+            if (LOCAL) acc = acc + local[start + i];
+#pragma unroll
+            for (int k = 0; k < KT; ++k) acc = acc + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+            out[start + i] = mean_of(acc);
+        }
+    }
+}
+
 // K-way decode-and-average of whole, aligned units for any K (and an optional local fp32 first term): the
 // workers are taken CH at a time (the host picks the CH <= 8 that leaves the fewest empty places in the last
 // chunk).  Work items are (unit, chunk of CH workers) pairs in order; the code

@@ -296,7 +296,9 @@ AVG_CASES = [(2 * 4096 + 333, 4096, 0), (3 * 4096, 4096, 0), (10000, 0, 0), (300
              (20 * 256 + 12, 256, 0), (64 * 64, 64, 0), (7 * 1000 + 4, 1000, 0), (5 * 516 + 2, 516, 0),
              (3 * 1000, 1000, 2),     # short blocks: aligned (whole quads), with a tail, and misaligned
              (5 * 1024 + 300, 64, 0), (3 * 1024 + 12, 4, 0), (4 * 1024, 128, 0), (2 * 1024 + 64, 32, 1),
-             (6 * 1024 + 8, 8, 0), (2 * 1024 + 16, 16, 0)]  # blocks of 4 .. 128 elements
+             (6 * 1024 + 8, 8, 0), (2 * 1024 + 16, 16, 0),  # blocks of 4 .. 128 elements
+             # blocks of whole quads that are not a power-of-two number of units: units by position, two scales each
+             (40 * 1000 + 300, 1000, 0), (9 * 3000 + 8, 3000, 0), (5 * 9216 + 100, 9216, 0), (24 * 516, 516, 0)]
 
 
 @pytest.mark.parametrize("kind", KINDS)
