@@ -881,9 +881,10 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     const size_t U = (size_t)lq * 4 * kWave;
     const size_t upb_l = p.B / U;
     const bool by_shift = p.nb == 1 || (p.B % U == 0 && (upb_l & (upb_l - 1)) == 0);  // a unit's block is u >> shift
-    // otherwise, for up to 8 workers: blocks of whole quads, no shorter than a unit, two blocks' scales per unit
+    // otherwise, for up to 8 workers: blocks of whole quads, no shorter than a unit (or exactly half a unit), two
+    // blocks' scales per unit
     const size_t bq = p.B / 4;
-    const bool flat = !by_shift && g_tune.avg_flat && !g_tune.avg_chunk_all && K >= 1 && K <= 8 && lq == 2 && (p.B & 3) == 0 && bq >= U / 4 &&
+    const bool flat = !by_shift && g_tune.avg_flat && !g_tune.avg_chunk_all && K >= 1 && K <= 8 && lq == 2 && (p.B & 3) == 0 && (bq >= U / 4 || bq * 2 == U / 4) &&
                       bq < 0x7FFFFFFFull && p.nb < 0xFFFFFFFFull;
     bool ok = by_shift || flat;
     ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;

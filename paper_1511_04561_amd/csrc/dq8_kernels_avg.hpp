@@ -243,9 +243,9 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
     }
 }
 
-// k_decode_avg_full for block lengths that are whole quads (bq of them, at least as many as a unit has) but not
-// a power-of-two number of units: unit u is still quads [u Q 64, (u + 1) Q 64) of the array, so it touches at most
-// two blocks.  Both blocks' scales travel with the unit's code words (two scalar loads per worker, the second
+// k_decode_avg_full for block lengths that are whole quads (bq of them, at least as many as a unit has, or
+// exactly half as many) but not a power-of-two number of units: unit u is still quads [u Q 64, (u + 1) Q 64) of
+// the array, so it touches at most two blocks.  Both blocks' scales travel with the unit's code words (two scalar loads per worker, the second
 // index clamped to the last block) and every quad selects by comparing its offset from the start of the first
 // block with bq.  The block index b and offset r of a wavefront's units advance by the same step every
 // iteration (step_b blocks and step_r < bq quads): one division per wavefront.
