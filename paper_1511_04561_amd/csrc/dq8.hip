@@ -884,9 +884,11 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     // otherwise, for up to 8 workers: blocks of whole quads, no shorter than a unit (or exactly half a unit), two
     // blocks' scales per unit
     const size_t bq = p.B / 4;
-    const bool flat = !by_shift && g_tune.avg_flat && !g_tune.avg_chunk_all && K >= 1 && K <= 8 && lq == 2 && (p.B & 3) == 0 && (bq >= U / 4 || bq * 2 == U / 4) &&
-                      bq < 0x7FFFFFFFull && p.nb < 0xFFFFFFFFull;
-    bool ok = by_shift || flat;
+    const bool flat_ok = !by_shift && g_tune.avg_flat && lq == 2 && (p.B & 3) == 0 && (bq >= U / 4 || bq * 2 == U / 4) &&
+                         bq < 0x7FFFFFFFull && p.nb < 0xFFFFFFFFull;
+    const bool flat = flat_ok && !g_tune.avg_chunk_all && K >= 1 && K <= 8;
+    const bool flat_chunks = flat_ok && K > 8;  // more workers: the chunk kernel with the same geometry
+    bool ok = by_shift || flat || flat_chunks;
     ok = ok && n / U >= 1 && n / U < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
     for (int k = 0; k < K; ++k) ok = ok && ((uintptr_t)wp.codes[k] & 3) == 0;
     if (!ok) return DQ8_OK;
@@ -907,9 +909,26 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         const int cw = wpc >= 8 ? 8 : 4;  // wavefronts per workgroup (they share the decode table)
         const unsigned grid = (unsigned)((waves + cw - 1) / cw);
         const uint32_t n_waves = grid * (uint32_t)cw;
-#define DQ8_CHUNK(CH, WPW)                                                                                              \
-    hipLaunchKernelGGL((k_decode_avg_chunks<CH, 2, 2, WPW>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, K, local, \
-                       n_full, n_waves, shift, tail, out)
+        const uint64_t step = (uint64_t)n_waves * (U / 4);
+        FlatGeom geom = {1, 0, 0, 0};
+        if (flat_chunks) geom = FlatGeom{(uint32_t)bq, (uint32_t)(p.nb - 1), (uint32_t)(step / bq), (uint32_t)(step % bq)};
+#define DQ8_CHUNK_F(CH, WPW, FL)                                                                                          \
+    hipLaunchKernelGGL((k_decode_avg_chunks<CH, 2, 2, WPW, FL>), dim3(grid), dim3(kWave * WPW), 0, stream, tab, wp, K, local, \
+                       n_full, n_waves, shift, geom, tail, out)
+#define DQ8_CHUNK(CH, WPW) DQ8_CHUNK_F(CH, WPW, false)
+        if (flat_chunks) {  // 3 to 8 workers per chunk, eight wavefronts per workgroup
+            if (cw != 8) return DQ8_OK;
+            switch (ch) {
+            case 3: DQ8_CHUNK_F(3, 8, true); break;
+            case 4: DQ8_CHUNK_F(4, 8, true); break;
+            case 5: DQ8_CHUNK_F(5, 8, true); break;
+            case 6: DQ8_CHUNK_F(6, 8, true); break;
+            case 7: DQ8_CHUNK_F(7, 8, true); break;
+            default: DQ8_CHUNK_F(8, 8, true); break;
+            }
+            *launched = true;
+            return after_launch("k_decode_avg_chunks");
+        }
 #define DQ8_CHUNK_W(CH)       \
     if (cw == 8) {            \
         DQ8_CHUNK(CH, 8);     \
@@ -928,6 +947,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         }
 #undef DQ8_CHUNK_W
 #undef DQ8_CHUNK
+#undef DQ8_CHUNK_F
         *launched = true;
         return after_launch("k_decode_avg_chunks");
     }

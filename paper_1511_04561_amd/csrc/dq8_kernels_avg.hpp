@@ -389,12 +389,15 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_flat(const uint32_t 
 // stay in registers from a unit's first chunk to its last.  Every request is unconditional (the item after
 // the last one is the last one again, a worker index past K - 1 is K - 1 with scale 0), so the compiler waits
 // for exactly the loads an item needs.  Geometry as in k_decode_avg_full.
-template <int CH, int Q, int NT, int WPW>
+// FLAT: the geometry of k_decode_avg_flat instead (blocks of whole quads, at most two per unit; Q = 2): every
+// place of a chunk carries both blocks' scales, and the block and offset of a unit advance with the unit.
+template <int CH, int Q, int NT, int WPW, bool FLAT>
 __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
                                                                   const float *__restrict__ local, uint32_t n_full,
-                                                                  uint32_t n_waves, uint32_t block_shift,
+                                                                  uint32_t n_waves, uint32_t block_shift, FlatGeom g,
                                                                   uint32_t tail_len, float *__restrict__ out)
 {
+    static_assert(!FLAT || Q == 2, "the position-based geometry is laid out for two code words per lane");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     constexpr int U = Q * 4 * kWave;
     const int terms = K + (local ? 1 : 0);
@@ -408,15 +411,26 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_
     struct Slot {
         uint32_t w[CH][Q];
         float sw[CH];
+        float sw1[FLAT ? CH : 1];
+        uint32_t r;
     };
+    // FLAT: block and offset of the first quad of the unit whose chunks are being fetched
+    uint32_t fb = 0, fr = 0;
     auto fetch = [&](uint32_t u, uint32_t c, Slot &sl) {
+        const uint32_t b0 = FLAT ? fb : (u >> block_shift);
+        const uint32_t b1 = FLAT ? (fb < g.last_block ? fb + 1 : g.last_block) : 0;
+        sl.r = fr;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             int k = (int)(c * CH) + i;
             const bool empty = !(k < K);  // an empty place of the last chunk: worker K - 1 again, with scale 0
             k = empty ? K - 1 : k;
-            const float s = p.scales[k][u >> block_shift];
+            const float s = p.scales[k][b0];
             sl.sw[i] = empty ? 0.0f : s;
+            if (FLAT) {
+                const float s1 = p.scales[k][b1];
+                sl.sw1[i] = empty ? 0.0f : s1;
+            }
             const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k]) + (size_t)u * (U / 4);
 #pragma unroll
             for (int j = 0; j < Q; ++j) sl.w[i][j] = ldg_at<NT>(c4, j * kWave + lane);
@@ -453,11 +467,14 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_
         if (c == 0) start_unit(u);
         // No branch around an empty place: its scale is 0, the product is a zero of either sign, and adding
         // that changes nothing (a running sum that starts at +0 is never -0).
+        const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)sl.r) + lane;
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const float s = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[i])));
+            const float s0 = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw[i])));
+            const float s1 = FLAT ? u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(sl.sw1[i]))) : 0.0f;
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
+                const float s = (FLAT && base + j * kWave >= g.bq) ? s1 : s0;  // the quad lies in the unit's second block
                 acc[j].x = acc[j].x + lut_at<0>(lut, sl.w[i][j], lane4) * s;
                 acc[j].y = acc[j].y + lut_at<1>(lut, sl.w[i][j], lane4) * s;
                 acc[j].z = acc[j].z + lut_at<2>(lut, sl.w[i][j], lane4) * s;
@@ -475,11 +492,24 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_
         if (u + n_waves < n_full) {
             u += n_waves;
             c = 0;
+            if (FLAT) {  // the fetches that follow belong to that unit
+                fb += g.step_b;
+                fr += g.step_r;
+                if (fr >= g.bq) {
+                    fr -= g.bq;
+                    fb += 1;
+                }
+            }
             return true;
         }
         return false;
     };
     uint32_t u = (uint32_t)first_unit(WPW), c = 0;
+    if (FLAT) {
+        const uint64_t q0 = (uint64_t)u * (Q * kWave);
+        fb = (uint32_t)(q0 / g.bq);
+        fr = (uint32_t)(q0 % g.bq);
+    }
     Slot a, b;
     const bool any = u < n_full && n_chunks > 0;
     if (any) fetch(u, 0, a);  // the first loads are in flight while the table is built
@@ -509,8 +539,8 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_chunks(const uint32_
     }
     if (tail_len != 0 && blockIdx.x == gridDim.x - 1 && wave_in_wg() == 0) {
         const size_t start = (size_t)n_full * U;
-        const size_t blk = n_full >> block_shift;
         for (uint32_t i = lane; i < tail_len; i += kWave) {
+            const size_t blk = FLAT ? (start + i) / ((size_t)g.bq * 4) : (size_t)(n_full >> block_shift);
             float s = 0.0f;
             if (local) s = s + local[start + i];
             for (int k = 0; k < K; ++k) s = s + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];

@@ -325,7 +325,8 @@ def test_decode_accumulate_avg_many_workers(dq8, K):
     with empty places; several units per wavefront and a ragged tail."""
     kind = KINDS[K % len(KINDS)]
     rng = np.random.Generator(np.random.PCG64(5900 + K))
-    for n, block in [(40 * 4096 + 333, 4096), (9 * 1024 + 5, 1024), (3 * 512, 0), (2100 * 512 + 12, 2048)]:
+    for n, block in [(40 * 4096 + 333, 4096), (9 * 1024 + 5, 1024), (3 * 512, 0), (2100 * 512 + 12, 2048),
+                     (30 * 1000 + 100, 1000), (7 * 3000, 3000), (20 * 256 + 4, 256)]:  # and units by position
         print("avg many kind=%d K=%d n=%d block=%d" % (kind, K, n, block), flush=True)
         nb = oracle.dq8_oracle.n_blocks(n, block)
         cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
