@@ -158,7 +158,7 @@ int dq8_decode_accumulate_avg_local(int kind, const uint8_t *const *codes, const
  * in between.  Results are identical to dq8_decode_accumulate_avg[_local] followed by
  * dq8_encode of its output with the same kind and block.
  * out_scales: nb floats (written), out_codes: n bytes (written); neither may overlap an input.
- * A scale block must fit the registers of one wavefront: block (or n when block == 0) <= 4096,
+ * A scale block must fit the registers of one workgroup: block (or n when block == 0) <= 16384,
  * otherwise DQ8_ERR_ARG (use the two separate calls).  1 <= K <= DQ8_MAX_K, or 0 <= K with local.
  */
 int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *const *scales, int K,

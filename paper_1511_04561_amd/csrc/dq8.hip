@@ -822,6 +822,32 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     return after_launch("k_avg_team");
 }
 
+// Average-then-compress for blocks of 4097 .. kLongestHeldBlock elements: a workgroup per block.
+int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                    size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
+{
+    const size_t B = block_length(n, block);
+    const size_t nb = (n + B - 1) / B;
+    size_t teams = (size_t)st.cus * 2;  // two workgroups' tables fit the LDS of a compute unit
+    if (teams > nb) teams = nb;
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = ((size_t)st.search_words[kind] + kLongSlots) * sizeof(uint32_t);
+#define DQ8_AVG_LONG(QL, NB)                                                                                             \
+    hipLaunchKernelGGL((k_avg_long<QL, NB, 2>), dim3((unsigned)teams), dim3(kLongTeam), lds, stream, tab, wp, K, local, n, \
+                       B, nb, (uint32_t)teams, scales_out, codes_out)
+    // quads per lane that hold the block in a workgroup of 512 threads, four sets of code words in flight
+    switch ((int)((B + 4 * kLongTeam - 1) / (4 * kLongTeam))) {
+    case 3: DQ8_AVG_LONG(3, 8); break;
+    case 4: DQ8_AVG_LONG(4, 8); break;
+    case 5: DQ8_AVG_LONG(5, 6); break;
+    case 6: DQ8_AVG_LONG(6, 6); break;
+    case 7: DQ8_AVG_LONG(7, 4); break;
+    default: DQ8_AVG_LONG(8, 4); break;
+    }
+#undef DQ8_AVG_LONG
+    return after_launch("k_avg_long");
+}
+
 int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                      size_t block, float *mean_out, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
@@ -1255,9 +1281,9 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
     const size_t Bq = block_length(n, block);
     const size_t nbq = (n + Bq - 1) / Bq;
-    if (Bq > (size_t)kUnit)
-        return fail(DQ8_ERR_ARG, "%s: a scale block of %zu elements does not fit the registers of a wavefront (at most %d); "
-                    "use dq8_decode_accumulate_avg and dq8_encode", who, Bq, kUnit);
+    if (Bq > kLongestHeldBlock)
+        return fail(DQ8_ERR_ARG, "%s: a scale block of %zu elements does not fit the registers of a workgroup (at most %zu); "
+                    "use dq8_decode_accumulate_avg and dq8_encode", who, Bq, kLongestHeldBlock);
     if (overlaps(out_codes, n, out_scales, nbq * 4)) return fail(DQ8_ERR_ARG, "%s: outputs overlap", who);
     if (local && (overlaps(out_codes, n, local, n * 4) || overlaps(out_scales, nbq * 4, local, n * 4)))
         return fail(DQ8_ERR_ARG, "%s: an output overlaps local", who);
@@ -1270,6 +1296,7 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     rc = device_state(&st);
     if (rc) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (Bq > (size_t)kUnit) return launch_avg_long(*st, kind, wp, K, local, n, block, out_scales, out_codes, stream);
     size_t done = 0;
     rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
     if (rc || done == n) return rc;

@@ -1,6 +1,8 @@
 // dq8 kernels that average K workers' buffers in registers and store the mean and / or compress it
 // again (the second round of the gradient exchange).
 #pragma once
+#include <type_traits>
+
 #include "dq8_device.hpp"
 
 namespace {
@@ -197,6 +199,225 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                     codes_out[un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(i), d, r, recip);
             }
         }
+    }
+}
+
+// Average-then-compress for scale blocks of 4097 .. 16384 elements: the scheme of k_avg_block with a workgroup of
+// eight wavefronts per block (two such workgroups share a compute unit: each holds the 64 KiB decode table).
+// Every lane holds QL quads of running sums (quad it * 512 + t of the block for thread t), the workers are added
+// one after the other while the next workers' code words are in flight, and the block maximum of the means is a
+// wave reduction plus one LDS exchange between the eight wavefronts.  Blocks are handed
+// out by position (block b to workgroup b mod n_teams), so every wavefront of a workgroup walks the same blocks
+// and meets the same barriers.  A block of whole quads at aligned addresses stays in registers (a lane whose quad
+// lies past the end of the block loads the block's last quad instead and stores nothing); any other block goes
+// quad by quad or element by element and forms its means once for the maximum and once for the compression.
+constexpr int kLongWaves = 8;                  // wavefronts per block in k_avg_long
+constexpr int kLongTeam = kLongWaves * kWave;  // its threads
+constexpr int kLongSlots = 2 * kLongWaves;     // LDS words for the maxima (two phases)
+
+template <int QL, int NB, int NT>
+__global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+                                                 const float *__restrict__ local, size_t n, size_t B, size_t nb,
+                                                 uint32_t n_teams, float *__restrict__ scales_out,
+                                                 uint8_t *__restrict__ codes_out)
+{
+    static_assert(NB >= 2, "at least two sets of code words");
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint32_t dyn_lds[];  // kLongSlots words for the maxima, then the bucket table
+    constexpr int Q = QL;
+    const int terms = K + (local ? 1 : 0);
+    const float fk = (float)terms;
+    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    const uint32_t lane = threadIdx.x & 63, wave = wave_in_wg(), tl = threadIdx.x;
+    const uint32_t lane4 = lane * 4;
+    uint32_t *slots = dyn_lds;
+    uint32_t phase = 0;
+    load_lut(tab, lut);
+    const Search sr = load_bucket_table(tab, dyn_lds + kLongSlots, kLongTeam);
+    __syncthreads();
+    // Maximum over the workgroup of the wave maxima m, through LDS; one barrier per call.
+    auto team_max = [&](uint32_t m) {
+        if (lane == 0) slots[phase * kLongWaves + wave] = m;
+        __syncthreads();
+        const uint32_t *sp = slots + phase * kLongWaves;
+        uint32_t a = sp[0];
+#pragma unroll
+        for (int i = 1; i < kLongWaves; ++i) a = a > sp[i] ? a : sp[i];
+        phase ^= 1;  // the other half of slots next time
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
+    };
+    auto length_of = [&](size_t blk) { return (uint32_t)(n - blk * B < B ? n - blk * B : B); };
+    // A block of whole quads whose addresses allow 128-bit accesses to local and 32-bit ones to the codes.
+    auto is_fast = [&](size_t blk) {
+        const size_t start = blk * B;
+        const uint32_t len = length_of(blk);
+        bool ok = len >= 4 && (len & 3) == 0 && ((uintptr_t)(codes_out + start) & 3) == 0;
+        for (int k = 0; k < K; ++k) ok = ok && (((uintptr_t)(p.codes[k] + start) & 3) == 0);
+        if (local) ok = ok && (((uintptr_t)(local + start) & 15) == 0);
+        return ok;
+    };
+    // NB sets of code words: worker k of a block uses set k mod NB, and the sets of the NB - 1 workers after the
+    // one being added are in flight, also across the end of a block (the first NB - 1 workers of the workgroup's
+    // next block are requested before the maximum and the compression of the current one).
+    uint32_t w[NB][Q];
+    // Worker k's code words of block blk (a fast one); a quad past its end is the block's last quad.
+    auto load_w = [&](uint32_t(&ww)[Q], int k, size_t blk) {
+        const uint32_t nq = length_of(blk) >> 2, last = nq - 1;
+        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + blk * B);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint32_t i = j * kLongTeam + tl;
+            ww[j] = ldg_at<NT>(c4, i < last ? i : last);
+        }
+    };
+    bool primed = false;  // the sets hold the first NB - 1 workers of the coming block
+    for (size_t blk = blockIdx.x; blk < nb; blk += n_teams) {
+        const size_t start = blk * B;
+        const uint32_t len = length_of(blk);
+        float s;
+        if (is_fast(blk)) {
+            const uint32_t nq = len >> 2, last = nq - 1;
+            if (!primed) {
+#pragma unroll
+                for (int i = 0; i < NB - 1; ++i)
+                    if (i < K) load_w(w[i], i, blk);
+            }
+            v4f acc[Q];
+            if (local) {
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + start);
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t i = j * kLongTeam + tl;
+                    acc[j] = ldg_at<NT>(l4, i < last ? i : last);
+                }
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {  // the sum starts at +0: a local -0 becomes +0
+                    acc[j].x = 0.0f + acc[j].x;
+                    acc[j].y = 0.0f + acc[j].y;
+                    acc[j].z = 0.0f + acc[j].z;
+                    acc[j].w = 0.0f + acc[j].w;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            auto add_w = [&](const uint32_t(&ww)[Q], int k) {
+                const float sk = p.scales[k][blk];
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    acc[j].x = acc[j].x + lut_at<0>(lut, ww[j], lane4) * sk;
+                    acc[j].y = acc[j].y + lut_at<1>(lut, ww[j], lane4) * sk;
+                    acc[j].z = acc[j].z + lut_at<2>(lut, ww[j], lane4) * sk;
+                    acc[j].w = acc[j].w + lut_at<3>(lut, ww[j], lane4) * sk;
+                }
+                // pin the sums here, or the compiler defers them and holds the products of several workers
+#pragma unroll
+                for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+            };
+            for (int k = 0; k < K; k += NB) {
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    if (k + i < K) {
+                        if (k + i + NB - 1 < K) load_w(w[(i + NB - 1) % NB], k + i + NB - 1, blk);
+                        add_w(w[i], k + i);
+                    }
+                }
+            }
+            const size_t next = blk + n_teams;
+            primed = next < nb && is_fast(next);
+            if (primed) {
+#pragma unroll
+                for (int i = 0; i < NB - 1; ++i)
+                    if (i < K) load_w(w[i], i, next);
+            }
+            float fm = 0.0f;
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
+                fm = max4_abs(acc[j], fm);
+            }
+            s = u2f(team_max(wave_max_u32(f2u(fm))));
+            const float d = s == 0.0f ? 1.0f : s;
+            const float r = 1.0f / d;
+            const bool recip = reciprocal_ok(d);
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + start);
+            // quads whose table lookups are issued together: four, and what is left of Q after the groups of four
+            auto encode_group = [&](auto first, auto count) {
+                constexpr int g = decltype(first)::value, G = decltype(count)::value;
+                v4f vv[G];
+                uint32_t cw[G];
+#pragma unroll
+                for (int j = 0; j < G; ++j) vv[j] = acc[g + j];
+                encode_quads<true, G>(sr, vv, d, r, recip, cw);
+#pragma unroll
+                for (int j = 0; j < G; ++j)
+                    if ((g + j) * kLongTeam + tl < nq) stg<1>(c4 + (g + j) * kLongTeam + tl, cw[j]);
+            };
+            if constexpr (Q >= 4) encode_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+            if constexpr (Q >= 8) encode_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+            if constexpr (Q % 4 != 0)
+                encode_group(std::integral_constant<int, Q / 4 * 4>{}, std::integral_constant<int, Q % 4>{});
+        } else {
+            // primed is false here: a block is only requested ahead when it is a fast one
+            const bool aligned = [&] {
+                bool ok = ((uintptr_t)(codes_out + start) & 3) == 0;
+                for (int k = 0; k < K; ++k) ok = ok && (((uintptr_t)(p.codes[k] + start) & 3) == 0);
+                if (local) ok = ok && (((uintptr_t)(local + start) & 15) == 0);
+                return ok;
+            }();
+            const uint32_t nq = aligned ? len >> 2 : 0;
+            const uint32_t done = nq << 2;
+            auto mean_at = [&](uint32_t i) {
+                float a = 0.0f;
+                if (local) a = a + local[start + i];
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+                return mean_of(a);
+            };
+            auto mean_quad = [&](uint32_t q) {
+                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (local) {
+                    const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + start) + q);
+                    a.x = a.x + l.x;
+                    a.y = a.y + l.y;
+                    a.z = a.z + l.z;
+                    a.w = a.w + l.w;
+                }
+                for (int k = 0; k < K; ++k) {
+                    const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + start) + q);
+                    const float sk = p.scales[k][blk];
+                    a.x = a.x + lut_at<0>(lut, ww, lane4) * sk;
+                    a.y = a.y + lut_at<1>(lut, ww, lane4) * sk;
+                    a.z = a.z + lut_at<2>(lut, ww, lane4) * sk;
+                    a.w = a.w + lut_at<3>(lut, ww, lane4) * sk;
+                }
+                a.x = mean_of(a.x);
+                a.y = mean_of(a.y);
+                a.z = mean_of(a.z);
+                a.w = mean_of(a.w);
+                return a;
+            };
+            float fm = 0.0f;
+            for (uint32_t q = tl; q < nq; q += kLongTeam) fm = max4_abs(mean_quad(q), fm);
+            uint32_t m = f2u(fm);
+            for (uint32_t i = done + tl; i < len; i += kLongTeam) {
+                const uint32_t a = abs_bits(mean_at(i));
+                m = m > a ? m : a;
+            }
+            s = u2f(team_max(wave_max_u32(m)));
+            const float d = s == 0.0f ? 1.0f : s;
+            const float r = 1.0f / d;
+            const bool recip = reciprocal_ok(d);
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + start);
+            for (uint32_t q = tl; q < nq; q += kLongTeam) stg<1>(c4 + q, encode_quad<true>(sr, mean_quad(q), d, r, recip));
+            for (uint32_t i = done + tl; i < len; i += kLongTeam)
+                codes_out[start + i] = (uint8_t)encode_one<true>(sr, mean_at(i), d, r, recip);
+        }
+        if (tl == 0) scales_out[blk] = s;
     }
 }
 

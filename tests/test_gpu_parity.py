@@ -436,7 +436,7 @@ def test_random_shapes_through_every_call(dq8, seed):
                                         local=None if local is None else dev(local, x_off))
         same_bits(got, want, "avg " + tag)
         go.check("avg " + tag)
-        if (n if block == 0 or block > n else block) <= 4096:
+        if (n if block == 0 or block > n else block) <= 16384:
             want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)
             gc, gs = Guarded(n, np.uint8, c_off), Guarded(nb, np.float32)
             codes, scales = dq8.decode_avg_encode(kind, [dev(c, c_off) for c in cl], [dev(s_) for s_ in sl], block,
@@ -450,10 +450,42 @@ def test_random_shapes_through_every_call(dq8, seed):
 
 
 def test_decode_avg_encode_rejects_blocks_that_do_not_fit(dq8):
-    c = torch.zeros(10000, dtype=torch.uint8, device="cuda")
+    c = torch.zeros(20000, dtype=torch.uint8, device="cuda")
     s = torch.ones(1, device="cuda")
-    with pytest.raises(dq8.Dq8Error, match="4096"):
+    with pytest.raises(dq8.Dq8Error, match="16384"):
         dq8.decode_avg_encode(0, [c, c], [s, s], 0)
+
+
+LONG_FUSED_SHAPES = [(3 * 8192 + 100, 8192, 0), (2 * 16384 + 5000, 16384, 0), (3 * 9216 + 4, 9216, 0), (10000, 0, 0),
+                     (2 * 4100, 4100, 0), (2 * 8191 + 3, 8191, 0),  # blocks that are not whole quads
+                     (2 * 12288 + 40, 12288, 1), (5000, 0, 3)]      # misaligned buffers
+
+
+@pytest.mark.parametrize("kind,K,with_local", [(0, 1, False), (0, 2, False), (1, 3, True), (2, 8, False), (3, 7, True),
+                                               (0, 0, True), (3, 13, False), (0, 32, True)])
+def test_decode_avg_encode_long_blocks(dq8, kind, K, with_local):
+    """Blocks of 4097 .. 16384 elements: a workgroup per block."""
+    rng = np.random.Generator(np.random.PCG64(7900 + 10 * K + kind))
+    for n, block, off in LONG_FUSED_SHAPES:
+        print("avg->encode long kind=%d K=%d local=%d n=%d block=%d off=%d" % (kind, K, with_local, n, block, off), flush=True)
+        nb = oracle.dq8_oracle.n_blocks(n, block)
+        enc = [oracle.encode(kind, workloads.tensor(5, 2, worker=w, limit=n), block) for w in range(K)]
+        cl, sl = [e[0] for e in enc], [e[1] for e in enc]
+        local = workloads.tensor(5, 4, worker=9, limit=n) if with_local else None
+        if K >= 2 and not with_local:  # the first block's average is zero everywhere
+            B = n if block == 0 else block
+            cl[1][:B] = cl[0][:B] ^ np.uint8(0x80)
+            sl[1][0] = sl[0][0]
+            for k in range(2, K):
+                sl[k][0] = 0.0
+        want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)
+        gc, gs = Guarded(n, np.uint8, off), Guarded(nb, np.float32)
+        codes, scales = dq8.decode_avg_encode(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], block,
+                                              local=None if local is None else dev(local, off), scales=gs.t, codes=gc.t)
+        same_bits(scales, want_scales, "avg->encode long scales")
+        same_bits(codes, want_codes, "avg->encode long codes")
+        gc.check("avg->encode long codes")
+        gs.check("avg->encode long scales")
 
 
 def test_average_order_is_worker_zero_first(dq8):
