@@ -73,10 +73,11 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode_avg_encode(0, arr, arr, 0, None, n, z, p, p, None) == 3  # no worker and no local term
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, None, p, None) == 1
     assert L.dq8_decode_avg_encode(4, arr, arr, 2, None, n, z, p, p, None) == 2
-    big = ctypes.c_size_t(10000)
-    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, z, p, p, None) == 3  # one block of 10000 > 4096
-    assert b"4096" in L.dq8_last_error()
-    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, ctypes.c_size_t(5000), p, p, None) == 3
+    big = ctypes.c_size_t(40000)
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, z, p, p, None) == 3  # one block of 40000 > 16384
+    assert b"16384" in L.dq8_last_error()
+    assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, big, ctypes.c_size_t(20000), p, p, None) == 3
+    assert b"16384" in L.dq8_last_error()
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, n, z, p, p, None) == 3  # outputs overlap each other
     assert L.dq8_decode_avg_encode(0, arr, arr, 2, None, z, z, None, None, None) == 0
     # approximation-error statistics
