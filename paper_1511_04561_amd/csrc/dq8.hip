@@ -137,6 +137,7 @@ struct Tuning {
     int enc_lean_wpc = 8;  //   which keeps its loads in flight with this many wavefronts per compute unit
     int enc_fill = 1;    //   and puts a team on every resident slot, even if some then get one block fewer
     int amax_q = 16;     // absmax: quads per lane in flight (unit = 256 q elements)
+    int amax_waste = 1;  //   smaller units for blocks whose last unit would be mostly empty
     int amax_wpc = 3;    //   wavefronts per compute unit: 3 measured best (36.2 us against 37.5 with 4 on 61 M elements)
     int dec_flat = 1;    // decode: units by position for blocks that are not whole units (0: off, 2: for every block length)
     int dec_q = 16;      // decode: code words per lane in flight
@@ -436,6 +437,22 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
     const size_t full_unit = (size_t)q * 4 * kWave;
     int wpc = (Bq >= n || Bq % full_unit == 0) ? g_tune.amax_wpc : 4;
     fit_unit_to_block(Bq, &q, &wpc);
+    if (g_tune.amax_waste && Bq < n) {
+        // A block that is not whole units ends in a short unit, whose lanes repeat loads.  Smaller units (down to
+        // 1024 elements) when they cut what the units of a block cover beyond the block by more than 5 %.
+        auto covered = [&](int quads) {
+            const size_t unit = (size_t)quads * 4 * kWave;
+            return (Bq + unit - 1) / unit * unit;
+        };
+        int best = q, best_wpc = wpc;
+        for (int qq = q / 2, ww = wpc * 2; qq >= 4; qq /= 2, ww *= 2)
+            if (covered(qq) * 100 < covered(best) * 95) {
+                best = qq;
+                best_wpc = ww > 32 ? 32 : ww;
+            }
+        q = best;
+        wpc = best_wpc;
+    }
     Plan p = make_plan(n, block, st.cus, wpc, 1, kWavesPerWg, (size_t)q * 4 * kWave);
     size_t per_wave = 0;
     if (p.upb > 1) {
@@ -1434,7 +1451,7 @@ int dq8_internal_tune(const char *key, int value)
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_flat", &g_tune.avg_flat, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
-        {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32},
+        {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32}, {"amax_waste", &g_tune.amax_waste, 0, 1},
         {"dec_flat", &g_tune.dec_flat, 0, 2}, {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 0, 4}, {"avg_teams4_upto", &g_tune.avg_teams4_upto, 0, 6}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},
     };
