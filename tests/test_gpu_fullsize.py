@@ -247,3 +247,27 @@ def test_more_than_two_to_the_32_elements(dq8):
         wc, ws = oracle.encode(KIND, want, 0)
         assert fc[lo:hi].cpu().numpy().tobytes() == wc.tobytes() and fs[b:b + 1].cpu().numpy().tobytes() == ws.tobytes(), \
             "compressed mean of block %d" % b
+    del mean, fc, fs, codes, scales, scales2
+    # the same array with blocks of 5000 elements: the kernels whose units follow positions, not blocks
+    B2 = 5000
+    nb2 = (n + B2 - 1) // B2
+    codes, scales = dq8.encode(KIND, x, B2)
+    out = dq8.decode(KIND, codes, scales, B2)
+    scales2 = scales * 2
+    mean = dq8.decode_accumulate_avg(KIND, [codes, codes], [scales, scales2], B2)
+    fc, fs = dq8.decode_avg_encode(KIND, [codes, codes], [scales, scales2], B2)
+    torch.cuda.synchronize()
+    print("2^32+: block 5000 done", flush=True)
+    edge = (1 << 32) // B2
+    blocks = sorted(set([0, 1, nb2 - 2, nb2 - 1, edge - 1, edge, edge + 1] + [int(b) for b in rng.integers(0, nb2, 30)]))
+    for b in blocks:
+        lo, hi = b * B2, min(n, (b + 1) * B2)
+        wc, ws = oracle.encode(KIND, x[lo:hi].cpu().numpy(), 0)
+        assert codes[lo:hi].cpu().numpy().tobytes() == wc.tobytes(), "codes of block %d (5000)" % b
+        assert scales[b:b + 1].cpu().numpy().tobytes() == ws.tobytes(), "scale of block %d (5000)" % b
+        assert out[lo:hi].cpu().numpy().tobytes() == oracle.decode(KIND, wc, ws, 0).tobytes(), "decoded block %d (5000)" % b
+        want = oracle.decode_accumulate_avg(KIND, [wc, wc], [ws, ws * 2], 0)
+        assert mean[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "mean of block %d (5000)" % b
+        wc2, ws2 = oracle.encode(KIND, want, 0)
+        assert fc[lo:hi].cpu().numpy().tobytes() == wc2.tobytes() and fs[b:b + 1].cpu().numpy().tobytes() == ws2.tobytes(), \
+            "compressed mean of block %d (5000)" % b
