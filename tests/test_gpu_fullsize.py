@@ -199,6 +199,27 @@ def test_error_statistics_of_a_25_million_sample(dq8):
         assert 0.6 < 100 * got_means[1] / paper < 0.9
 
 
+@pytest.mark.parametrize("K,block", [(5, 3000), (9, 3000), (16, 1000), (7, 256)])
+def test_position_based_average_over_many_units(dq8, K, block):
+    """Block lengths whose units follow positions, on an array long enough for every wavefront to walk many units
+    (the block index and offset of a unit advance by a fixed step per iteration).  Codes and scales are drawn on
+    the device by torch; the oracle checks the first and last blocks and 60 drawn ones."""
+    n = 20_000_000 + 52
+    nb = (n + block - 1) // block
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 * K + block)
+    cl = [torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(K)]
+    sl = [torch.rand(nb, device="cuda", generator=gen) * 4 + 0.01 for _ in range(K)]
+    mean = dq8.decode_accumulate_avg(KIND, cl, sl, block)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(K + block))
+    for b in sorted(set([0, 1, nb - 2, nb - 1] + [int(v) for v in rng.integers(0, nb, 60)])):
+        lo, hi = b * block, min(n, (b + 1) * block)
+        want = oracle.decode_accumulate_avg(KIND, [c[lo:hi].cpu().numpy() for c in cl],
+                                            [s_[b:b + 1].cpu().numpy() for s_ in sl], 0)
+        assert mean[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "mean of block %d (K=%d, block %d)" % (b, K, block)
+
+
 def test_more_than_two_to_the_32_elements(dq8):
     """Sizes beyond 32-bit element indices: 2^32 + 3 blocks + 17 elements (17 GB of fp32 on the device).
     The input is generated on the device from a seed; the oracle checks sampled blocks, among them the first,
