@@ -220,6 +220,24 @@ def test_position_based_average_over_many_units(dq8, K, block):
         assert mean[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "mean of block %d (K=%d, block %d)" % (b, K, block)
 
 
+@pytest.mark.parametrize("block", [40, 200, 1000, 6000])
+def test_position_based_decode_over_many_units(dq8, block):
+    """The same for decompression: up to eight blocks per unit (block 40, 200), up to four (1000), two (6000)."""
+    n = 20_000_000 + 51
+    nb = (n + block - 1) // block
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77 + block)
+    codes = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=gen)
+    scales = torch.rand(nb, device="cuda", generator=gen) * 4 + 0.01
+    out = dq8.decode(KIND, codes, scales, block)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(block))
+    for b in sorted(set([0, 1, nb - 2, nb - 1] + [int(v) for v in rng.integers(0, nb, 200)])):
+        lo, hi = b * block, min(n, (b + 1) * block)
+        want = oracle.decode(KIND, codes[lo:hi].cpu().numpy(), scales[b:b + 1].cpu().numpy(), 0)
+        assert out[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "decoded block %d (block %d)" % (b, block)
+
+
 def test_more_than_two_to_the_32_elements(dq8):
     """Sizes beyond 32-bit element indices: 2^32 + 3 blocks + 17 elements (17 GB of fp32 on the device).
     The input is generated on the device from a seed; the oracle checks sampled blocks, among them the first,
