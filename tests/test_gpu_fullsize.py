@@ -238,6 +238,29 @@ def test_position_based_decode_over_many_units(dq8, block):
         assert out[lo:hi].cpu().numpy().tobytes() == want.tobytes(), "decoded block %d (block %d)" % (b, block)
 
 
+@pytest.mark.parametrize("K,block,with_local", [(3, 5000, False), (8, 8192, False), (7, 16384, True), (12, 9216, False)])
+def test_one_call_second_round_with_long_blocks_over_many_blocks(dq8, K, block, with_local):
+    """Blocks of 4097 .. 16384 elements, a workgroup per block, every workgroup walking several blocks (code words
+    of the next block are requested before the current one is compressed)."""
+    n = 20_000_000 + 48
+    nb = (n + block - 1) // block
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(31 * K + block)
+    cl = [torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=gen) for _ in range(K)]
+    sl = [torch.rand(nb, device="cuda", generator=gen) * 4 + 0.01 for _ in range(K)]
+    local = torch.randn(n, device="cuda", generator=gen) if with_local else None
+    codes, scales = dq8.decode_avg_encode(KIND, cl, sl, block, local=local)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(K * block))
+    for b in sorted(set([0, 1, nb - 2, nb - 1] + [int(v) for v in rng.integers(0, nb, 40)])):
+        lo, hi = b * block, min(n, (b + 1) * block)
+        wc, ws = oracle.decode_avg_encode(KIND, [c[lo:hi].cpu().numpy() for c in cl],
+                                          [s_[b:b + 1].cpu().numpy() for s_ in sl], 0,
+                                          local=None if local is None else local[lo:hi].cpu().numpy())
+        assert codes[lo:hi].cpu().numpy().tobytes() == wc.tobytes(), "codes of block %d (K=%d, block %d)" % (b, K, block)
+        assert scales[b:b + 1].cpu().numpy().tobytes() == ws.tobytes(), "scale of block %d (K=%d, block %d)" % (b, K, block)
+
+
 def test_more_than_two_to_the_32_elements(dq8):
     """Sizes beyond 32-bit element indices: 2^32 + 3 blocks + 17 elements (17 GB of fp32 on the device).
     The input is generated on the device from a seed; the oracle checks sampled blocks, among them the first,
