@@ -118,6 +118,7 @@ struct Tuning {
     int avg_lean_q = 2;  //   its code words per lane and worker, wavefronts per compute unit and per workgroup
     int avg_lean_wpc = 4;
     int avg_flat = 1;       //   up to 8 workers, blocks of whole quads that are not a power-of-two number of units: units by position
+    int avg_wide = 8;       //   9 to 12 workers: the unrolled kernel with this many wavefronts per compute unit (0: the chunk kernel)
     int avg_chunk_all = 0;  //   1: that kernel for K = 2, 4, 8 as well
     int avg_chunk_wpc = 8;  //   wavefronts per compute unit of the kernel that takes the workers four at a time
     int avg_lean_wpw = 4;
@@ -942,6 +943,38 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     }
     const uint32_t n_full = (uint32_t)(n / U), tail = (uint32_t)(n % U);
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    if (K >= 9 && K <= 12 && !local && g_tune.avg_wide) {
+        // 9 to 12 workers unrolled as well, one code word per lane and worker: units of 256 elements (K = 9: 141
+        // against 156 us for the chunk kernel, K = 12: 178 against 185 us; from 13 workers on the chunk kernel wins)
+        const size_t U1 = 4 * kWave, upb1 = p.B / U1;
+        bool wide = p.nb == 1 || (p.B % U1 == 0 && (upb1 & (upb1 - 1)) == 0);
+        wide = wide && n / U1 >= 1 && n / U1 < 0x7FFFFFFFull && ((uintptr_t)out & 15) == 0;
+        for (int k = 0; k < K; ++k) wide = wide && ((uintptr_t)wp.codes[k] & 3) == 0;
+        if (wide) {
+            uint32_t shift1 = 31;
+            if (p.nb > 1) {
+                shift1 = 0;
+                while (((size_t)1 << shift1) < upb1) ++shift1;
+            }
+            const uint32_t n_full1 = (uint32_t)(n / U1), tail1 = (uint32_t)(n % U1);
+            size_t waves = (size_t)st.cus * (size_t)g_tune.avg_wide;
+            if (waves > n_full1) waves = n_full1;
+            const unsigned grid = (unsigned)((waves + 3) / 4);
+            const uint32_t n_waves = grid * 4u;
+#define DQ8_AVGW(KT)                                                                                                    \
+    hipLaunchKernelGGL((k_decode_avg_full<KT, 1, 2, 4, false>), dim3(grid), dim3(kWave * 4), 0, stream, tab, wp, local, \
+                       n_full1, n_waves, shift1, tail1, out)
+            switch (K) {
+            case 9: DQ8_AVGW(9); break;
+            case 10: DQ8_AVGW(10); break;
+            case 11: DQ8_AVGW(11); break;
+            default: DQ8_AVGW(12); break;
+            }
+#undef DQ8_AVGW
+            *launched = true;
+            return after_launch("k_decode_avg_full");
+        }
+    }
     if (K < 1 || K > 8 || g_tune.avg_chunk_all) {
         if (lq != 2) return DQ8_OK;  // that kernel exists for two code words per lane and worker only
         const int ch = chunk_size(K);
@@ -1449,7 +1482,7 @@ int dq8_internal_tune(const char *key, int value)
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
-        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_flat", &g_tune.avg_flat, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
+        {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_wide", &g_tune.avg_wide, 0, 32}, {"avg_flat", &g_tune.avg_flat, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
         {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32}, {"amax_waste", &g_tune.amax_waste, 0, 1},
         {"dec_flat", &g_tune.dec_flat, 0, 2}, {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},

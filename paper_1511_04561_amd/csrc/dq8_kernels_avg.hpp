@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg(const uint32_t *__re
     }
 }
 
-// K-way decode-and-average of whole, aligned units, K up to 8 (fixed at compile time): the common case of
+// K-way decode-and-average of whole, aligned units, K up to 12 (fixed at compile time; above 8 with Q = 1): the common case of
 // k_decode_avg with nothing else in the loop.  Unit u covers elements [U u, U (u + 1)), U divides
 // the block size and block / U is a power of two, so a unit's block is u >> block_shift; out is
 // 16-byte and every code buffer 4-byte aligned.  The K scales of a unit travel with its code
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_decode_avg_full(const uint32_t 
                                                                 uint32_t n_waves, uint32_t block_shift, uint32_t tail_len,
                                                                 float *__restrict__ out)
 {
-    static_assert(KT >= 1 && KT <= 8, "unrolled for up to eight workers");
+    static_assert(KT >= 1 && KT <= 12 && KT * Q <= 32, "up to twelve workers and 32 code words per lane and set");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     constexpr int U = Q * 4 * kWave;
     constexpr float fk = (float)(KT + (LOCAL ? 1 : 0));
