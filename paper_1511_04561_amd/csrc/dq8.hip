@@ -128,6 +128,11 @@ struct Tuning {
     int enc_wpc = 24;    // encoder wavefronts per compute unit (general kernel)
     int enc_long = 1;    // blocks of 4097 .. 16384 elements: held by a team (0: absmax pass + encode pass, 2: general kernel only)
     int enc_wpc8 = 8;    //   wavefronts per compute unit with 8 quads per lane (measured: 8: 55, 12: 57, 16: 57 us at block 8192),
+    int enc_wave_min = 8;   // blocks of this many
+    int enc_wave = 1024;    //   up to this many elements: the wave-per-block kernel whose loads are a block ahead (0: off;
+                            //   block 200: 114 -> 63 us, 600: 75 -> 56, 1000: 65 -> 57, 1024: 60 -> 54, 100: 202 -> 101)
+    int enc_wave_wpc = 32;  //   its wavefronts per compute unit with 1 to 4 quads per lane,
+    int enc_wave_wpc8 = 16; //   and with 8
     int enc_mid = 1536;  // blocks longer than this, up to 3072 elements: the same kernel (0: off; measured 1500: 62 -> 63 us,
                          //   2000: 60 -> 58, 2048: 57.5 -> 55, 3000: 62 -> 57.5, 3072: 58 -> 55, 4000: 56 -> 58)
     int enc_wpc4 = 16;   //   its wavefronts per compute unit with 2 or 3 quads per lane (8: 72, 16: 55, 24: 55, 32: 56 us at 2048)
@@ -527,6 +532,35 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     // Blocks of 4097 .. 16384 elements in whole quads, aligned buffers: the team holds a block in 8, 12 or 16
     // quads per lane.
     const size_t tail = n % p.B;
+    // Blocks of up to 1024 elements in whole quads, aligned buffers: one wavefront per block with its loads
+    // always a block ahead (blocks of 4 .. 128 elements that are powers of two went to the small kernels before).
+    if (fused && g_tune.enc_wave && p.B >= (size_t)g_tune.enc_wave_min && p.B <= (size_t)g_tune.enc_wave && (p.B & 3) == 0 && (tail & 3) == 0 &&
+        p.nb > 1 && p.nb < 0xFFFFFFFFull && ((uintptr_t)x & 15) == 0 && ((uintptr_t)codes & 3) == 0) {
+        const uint32_t bq = (uint32_t)(p.B / 4), tail_q = (uint32_t)(tail / 4);
+        const int wq = bq <= 64 ? 1 : (bq <= 128 ? 2 : (bq <= 256 ? 4 : 8));  // quads per lane
+        const int ww = 16;                                                     // wavefronts per workgroup
+        size_t waves = (size_t)st.cus * (size_t)(wq == 8 ? g_tune.enc_wave_wpc8 : g_tune.enc_wave_wpc);
+        if (waves > p.nb) waves = p.nb;
+        const unsigned grid = (unsigned)((waves + ww - 1) / ww);
+        const uint32_t n_waves = grid * (uint32_t)ww;
+        const size_t wlds = (size_t)st.search_words[kind] * sizeof(uint32_t);
+#define DQ8_ENC_WAVE(QL)                                                                                              \
+    if (st.has_remap[kind]) {                                                                                         \
+        hipLaunchKernelGGL((k_encode_wave<QL, 1, 16, true>), dim3(grid), dim3(kWave * 16), wlds, stream, tab, x,      \
+                           (uint32_t)p.nb, n_waves, bq, tail_q, scales, codes);                                       \
+    } else {                                                                                                          \
+        hipLaunchKernelGGL((k_encode_wave<QL, 1, 16, false>), dim3(grid), dim3(kWave * 16), wlds, stream, tab, x,     \
+                           (uint32_t)p.nb, n_waves, bq, tail_q, scales, codes);                                       \
+    }
+        switch (wq) {
+        case 1: DQ8_ENC_WAVE(1) break;
+        case 2: DQ8_ENC_WAVE(2) break;
+        case 4: DQ8_ENC_WAVE(4) break;
+        default: DQ8_ENC_WAVE(8) break;
+        }
+#undef DQ8_ENC_WAVE
+        return after_launch("k_encode_wave");
+    }
     const bool long_block = unit > (size_t)kUnit;
     // blocks of 1537 .. 3072 elements too: 2 or 3 quads per lane (2 to 7 % faster than a wavefront per block there)
     const bool mid_block = g_tune.enc_mid && p.B > (size_t)g_tune.enc_mid && p.B <= 3072;
@@ -1483,7 +1517,7 @@ int dq8_internal_tune(const char *key, int value)
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
         {"avg_lean_wpc", &g_tune.avg_lean_wpc, 1, 32}, {"avg_chunk_wpc", &g_tune.avg_chunk_wpc, 1, 32}, {"avg_chunk_all", &g_tune.avg_chunk_all, 0, 1}, {"avg_wide", &g_tune.avg_wide, 0, 32}, {"avg_flat", &g_tune.avg_flat, 0, 1}, {"avg_lean_wpw", &g_tune.avg_lean_wpw, 4, 16}, {"copy_nt", &g_tune.copy_nt, 0, 2},           {"fastdiv", &g_tune.fastdiv, 0, 1},   {"enc_wpb", &g_tune.enc_wpb, 1, 4},
-        {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
+        {"enc_long", &g_tune.enc_long, 0, 2}, {"enc_wpc12", &g_tune.enc_wpc12, 4, 32}, {"enc_wpc6", &g_tune.enc_wpc6, 4, 32}, {"enc_wpc4", &g_tune.enc_wpc4, 4, 32}, {"enc_mid", &g_tune.enc_mid, 0, 4095}, {"enc_wave", &g_tune.enc_wave, 0, 2048}, {"enc_wave_min", &g_tune.enc_wave_min, 4, 2048}, {"enc_wave_wpc", &g_tune.enc_wave_wpc, 4, 32}, {"enc_wave_wpc8", &g_tune.enc_wave_wpc8, 4, 32}, {"enc_wpc8", &g_tune.enc_wpc8, 4, 32}, {"enc_wpc16", &g_tune.enc_wpc16, 4, 32},
         {"enc_wpc", &g_tune.enc_wpc, 1, 32}, {"enc_lean", &g_tune.enc_lean, 0, 1}, {"enc_lean_wpc", &g_tune.enc_lean_wpc, 4, 32}, {"enc_fill", &g_tune.enc_fill, 0, 1}, {"amax_q", &g_tune.amax_q, 1, 16},    {"amax_wpc", &g_tune.amax_wpc, 1, 32}, {"amax_waste", &g_tune.amax_waste, 0, 1},
         {"dec_flat", &g_tune.dec_flat, 0, 2}, {"dec_q", &g_tune.dec_q, 1, 16},     {"dec_wpc", &g_tune.dec_wpc, 1, 32},  {"avg_q", &g_tune.avg_q, 1, 4},
         {"avg_wpc", &g_tune.avg_wpc, 1, 32}, {"avg_wpw", &g_tune.avg_wpw, 4, 16}, {"dec_wpw", &g_tune.dec_wpw, 4, 16}, {"blk_wpw", &g_tune.blk_wpw, 6, 8}, {"avg_team", &g_tune.avg_team, 0, 1}, {"avg_steady", &g_tune.avg_steady, 0, 1}, {"avg_teams", &g_tune.avg_teams, 0, 4}, {"avg_teams4_upto", &g_tune.avg_teams4_upto, 0, 6}, {"avg_wgpc", &g_tune.avg_wgpc, 1, 2}, {"copy_q", &g_tune.copy_q, 1, 16},    {"copy_wpc", &g_tune.copy_wpc, 1, 32},

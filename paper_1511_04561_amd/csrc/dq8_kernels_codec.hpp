@@ -353,6 +353,87 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
     }
 }
 
+// Compression of blocks of up to QL * 256 elements, one wavefront per block: k_encode_long without the exchange
+// between wavefronts.  Blocks are whole quads (bq of them), x is 16-byte and codes 4-byte aligned; a lane whose
+// quad lies past the end of the block loads the block's last quad instead and stores nothing; the last block
+// may be shorter (tail_q quads, 0: none).  Wavefront w of the grid takes blocks w, w + n_waves, ...
+template <int QL, int NT, int WPW, bool REMAP>
+__global__ __launch_bounds__(kWave * WPW) void k_encode_wave(const uint32_t *__restrict__ tab, const float *__restrict__ x,
+                                                            uint32_t n_units, uint32_t n_waves, uint32_t bq,
+                                                            uint32_t tail_q, float *__restrict__ scales,
+                                                            uint8_t *__restrict__ codes)
+{
+    constexpr int Q = QL;
+    constexpr int G = Q < 4 ? Q : 4;  // quads whose table lookups are issued together
+    static_assert(Q % G == 0, "whole groups of quads");
+    extern __shared__ uint32_t lds[];  // the bucket table
+    const uint32_t lane = threadIdx.x & 63;
+    Search sr;
+    auto quads_of = [&](uint32_t u) { return (tail_q != 0 && u == n_units - 1) ? tail_q : bq; };
+    auto fetch = [&](uint32_t u, v4f(&v)[Q]) {
+        const v4f *p4 = reinterpret_cast<const v4f *>(x) + (size_t)u * bq;
+        const uint32_t last = quads_of(u) - 1;
+#pragma unroll
+        for (int it = 0; it < Q; ++it) {
+            const uint32_t q = it * kWave + lane;
+            v[it] = ldg_at<NT>(p4, q < last ? q : last);
+        }
+    };
+    auto process = [&](uint32_t u, v4f(&v)[Q]) {
+        float fm = 0.0f;
+#pragma unroll
+        for (int it = 0; it < Q; ++it) fm = max4_abs(v[it], fm);
+        const float s = u2f(wave_max_u32(f2u(fm)));
+        if (lane == 0) scales[u] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        uint32_t *c4 = reinterpret_cast<uint32_t *>(codes) + (size_t)u * bq;
+        const uint32_t nq = quads_of(u);
+#pragma unroll
+        for (int g = 0; g < Q; g += G) {
+            v4f vv[G];
+            uint32_t cw[G];
+#pragma unroll
+            for (int it = 0; it < G; ++it) vv[it] = v[g + it];
+            encode_quads<true, G>(sr, vv, d, r, recip, cw);
+#pragma unroll
+            for (int it = 0; it < G; ++it) {
+                const uint32_t q = (g + it) * kWave + lane;
+                if (q < nq) stg_at<NT>(c4, q, cw[it]);
+            }
+        }
+    };
+    uint32_t u = (uint32_t)first_unit(WPW);
+    v4f a[Q], b[Q];
+    if (u < n_units) fetch(u, a);  // the first loads are in flight while the table is copied
+    sr = load_bucket_table(tab, lds, kWave * WPW);
+    if (!REMAP) sr.remap = nullptr;
+    __syncthreads();
+    // steady state as in k_encode_full: the next block's loads are issued unconditionally before the work on
+    // the current one
+    if (u < n_units) {
+        for (;;) {
+            uint32_t nx = u + n_waves;
+            if (!(nx < n_units)) {
+                process(u, a);
+                break;
+            }
+            fetch(nx, b);
+            process(u, a);
+            u = nx;
+            nx = u + n_waves;
+            if (!(nx < n_units)) {
+                process(u, b);
+                break;
+            }
+            fetch(nx, a);
+            process(u, b);
+            u = nx;
+        }
+    }
+}
+
 // Decompression with units that do not follow the blocks: unit u is quads [u Q 64, (u + 1) Q 64) of the array
 // (a quad = 4 consecutive elements; blocks are whole quads, bq of them, so a quad never straddles two blocks),
 // whatever the block length.  The host picks Q and NS with Q 64 <= (NS - 1) bq: a unit then touches at most NS

@@ -122,6 +122,9 @@ SHAPES = [  # (n, block)
     (5 * 2048 + 8, 2048), (4 * 3000, 3000), (3 * 2000 + 4, 2000), (2 * 3072 + 100, 3072), (3 * 1540, 1540),  # and in 2 or 3
     # blocks of whole quads that are not whole units: decompression walks units by position, up to 8 blocks per unit
     (500 * 40 + 3, 40), (300 * 100, 100), (70 * 200 + 1, 200), (900 * 36 + 2, 36), (33 * 588 + 7, 588), (40 * 340, 340),
+    # compression of blocks of whole quads up to 1024 elements: a wavefront per block, with and without a short last block
+    (500 * 40 + 4, 40), (64 * 200 + 8, 200), (9 * 1024 + 12, 1024), (100 * 12, 12), (21 * 600, 600), (2000 * 8, 8),
+    (3 * 132, 132), (1000 * 260 + 256, 260),
 ]
 
 
