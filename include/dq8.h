@@ -24,9 +24,10 @@
  *   - Any pointer alignment and any n / block are accepted.  The fast paths need
  *     16-byte aligned `x` / `out`, 4-byte aligned `codes`, and block % 4 == 0 (or a single
  *     block); anything else runs on slower paths with the same results.  Blocks of 4096
- *     elements are the fastest; other lengths come close (units follow the block; powers of
- *     two from 4 to 128 elements have kernels that pack many blocks into a wavefront), other
- *     lengths below 256 use a fraction of each wavefront.
+ *     elements are the fastest; other lengths come close (the units of work follow the block
+ *     or, where a block need not be held, the position in the array; powers of two from 4 to
+ *     128 elements have kernels that pack many blocks into a wavefront); other lengths below
+ *     256 use a fraction of each wavefront in the calls that compress.
  *   - Results are deterministic and independent of launch configuration: codes and scales
  *     are exact functions of the input, and the average adds workers in index order.
  *
