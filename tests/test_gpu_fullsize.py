@@ -2,10 +2,10 @@
 
 C3: the 61 100 840-element AlexNet-shaped gradient bucket, block 4096, dynamic tree: every
 code, scale and decoded value is compared with the oracle.
-C5: eight workers' buckets -> encode, fused decode-and-average, re-encode.  The oracle checks
-a sample of blocks end to end (its own encode of each worker's block, its own average of
-those codes, its own re-encode of that average); oracle inputs are the seeded tensors and
-the oracle's own outputs only.
+C5: eight workers' buckets -> encode, fused decode-and-average, re-encode: every element of
+every stage is compared with the oracle (its own encode of each worker's bucket, its own
+average of those codes, its own re-encode of that average); oracle inputs are the seeded
+tensors and the oracle's own outputs only.
 """
 import numpy as np
 import pytest
@@ -84,86 +84,74 @@ def test_config3_full_bucket_other_types(dq8, kind):
 
 @pytest.mark.parametrize("block", [8192, 9216, 16384])
 def test_config3_full_bucket_long_blocks(dq8, block):
-    """Blocks that a team holds in 8 to 16 quads per lane: every scale, and the codes of a sample of blocks
-    (the first ones, the ragged last one, 60 drawn ones), against the oracle."""
+    """Blocks that a team holds in 8 to 16 quads per lane: every scale and every code against the oracle."""
     x = workloads.bucket(3)
     xd = torch.from_numpy(x).cuda()
     print("C3 block %d: gpu encode" % block, flush=True)
     codes, scales = dq8.encode(KIND, xd, block)
+    out = dq8.decode(KIND, codes, scales, block)
     torch.cuda.synchronize()
-    bits_equal(scales, oracle.absmax(x, block), "scales at block %d" % block)
-    nb = oracle.dq8_oracle.n_blocks(x.size, block)
-    rng = np.random.Generator(np.random.PCG64(77 + block))
-    sample = sorted(set([0, 1, 2, nb - 2, nb - 1]) | set(rng.integers(0, nb, 60).tolist()))
-    got = codes.cpu().numpy()
-    for b in sample:
-        lo, hi = b * block, min((b + 1) * block, x.size)
-        want_codes, _ = oracle.encode(KIND, x[lo:hi], block)
-        assert got[lo:hi].tobytes() == want_codes.tobytes(), "codes of block %d at block length %d" % (b, block)
+    print("C3 block %d: oracle encode of the whole bucket" % block, flush=True)
+    want_codes, want_scales = oracle.encode(KIND, x, block)
+    bits_equal(scales, want_scales, "scales at block %d" % block)
+    bits_equal(codes, want_codes, "codes at block %d" % block)
+    bits_equal(out, oracle.decode(KIND, want_codes, want_scales, block), "decode at block %d" % block)
 
 
 def test_config5_aggregation_pipeline(dq8):
+    """C5 end to end on the full bucket, every element against the oracle: the eight workers' codes and scales,
+    the fp32 mean, the re-encoded mean (two calls and the one-call second round), and the shapes with a local
+    fp32 term.  Oracle inputs are the seeded tensors and the oracle's own outputs only."""
     K = workloads.C5_WORKERS
     n = workloads.C3_NUMEL
-    nb = (n + B - 1) // B
-    rng = np.random.Generator(np.random.PCG64(workloads.BASE_SEED + 5))
-    sample = np.unique(np.concatenate([rng.integers(0, nb, 160), [0, 1, nb - 2, nb - 1]]))
-    codes_d, scales_d, xs = [], [], []
+    codes_d, scales_d, codes_o, scales_o = [], [], [], []
+    x0 = None
     for w in range(K):
-        print("C5: worker %d generate + gpu encode" % w, flush=True)
+        print("C5: worker %d generate, gpu encode, oracle encode" % w, flush=True)
         x = workloads.bucket(5, worker=w)
         c, s = dq8.encode(KIND, torch.from_numpy(x).cuda(), B)
+        oc, os_ = oracle.encode(KIND, x, B)
+        bits_equal(c, oc, "C5 codes of worker %d" % w)
+        bits_equal(s, os_, "C5 scales of worker %d" % w)
         codes_d.append(c)
         scales_d.append(s)
-        xs.append([x[b * B:(b + 1) * B].copy() for b in sample])
+        codes_o.append(oc)
+        scales_o.append(os_)
+        if w == 0:
+            x0 = x
         del x
-    print("C5: gpu decode_accumulate_avg + re-encode", flush=True)
+    print("C5: gpu decode_accumulate_avg + re-encode, and the second round in one call", flush=True)
     mean = dq8.decode_accumulate_avg(KIND, codes_d, scales_d, B)
     rcodes, rscales = dq8.encode(KIND, mean, B)
-    print("C5: gpu decode_avg_encode in one call", flush=True)
     fcodes, fscales = dq8.decode_avg_encode(KIND, codes_d, scales_d, B)
     torch.cuda.synchronize()
-    # the single call must reproduce the two calls everywhere (and those are checked against the oracle below)
-    assert torch.equal(fcodes, rcodes) and fscales.cpu().numpy().tobytes() == rscales.cpu().numpy().tobytes()
-    del fcodes, fscales
-    print("C5: oracle on %d sampled blocks" % sample.size, flush=True)
-    mean_h, rcodes_h, rscales_h = mean.cpu().numpy(), rcodes.cpu().numpy(), rscales.cpu().numpy()
-    codes_h = [c.cpu().numpy() for c in codes_d]
-    scales_h = [s.cpu().numpy() for s in scales_d]
-    for i, b in enumerate(sample):
-        lo, hi = b * B, min((b + 1) * B, n)
-        oc, os_ = [], []
-        for w in range(K):
-            c, s = oracle.encode(KIND, xs[w][i], B)
-            assert codes_h[w][lo:hi].tobytes() == c.tobytes(), ("codes", w, b)
-            assert scales_h[w][b:b + 1].tobytes() == s.tobytes(), ("scales", w, b)
-            oc.append(c)
-            os_.append(s)
-        m = oracle.decode_accumulate_avg(KIND, oc, os_, B)
-        assert mean_h[lo:hi].tobytes() == m.tobytes(), ("mean", b)
-        rc, rs = oracle.encode(KIND, m, B)
-        assert rcodes_h[lo:hi].tobytes() == rc.tobytes() and rscales_h[b:b + 1].tobytes() == rs.tobytes(), ("re-encode", b)
+    print("C5: oracle average and re-encode of all %d elements" % n, flush=True)
+    want_mean = oracle.decode_accumulate_avg(KIND, codes_o, scales_o, B)
+    bits_equal(mean, want_mean, "C5 mean")
+    want_rc, want_rs = oracle.encode(KIND, want_mean, B)
+    bits_equal(rscales, want_rs, "C5 scales of the re-encoded mean")
+    bits_equal(rcodes, want_rc, "C5 codes of the re-encoded mean")
+    bits_equal(fscales, want_rs, "C5 scales of the one-call second round")
+    bits_equal(fcodes, want_rc, "C5 codes of the one-call second round")
+    # extra: the oracle's own one-call composition agrees with its two steps
+    oc1, os1 = oracle.decode_avg_encode(KIND, codes_o, scales_o, B)
+    assert oc1.tobytes() == want_rc.tobytes() and os1.tobytes() == want_rs.tobytes()
     # whole-array properties: the mean never exceeds the mean of the scales, signs of re-encoded codes follow it
-    bound = np.repeat(np.mean(np.stack(scales_h).astype(np.float64), axis=0), B)[:n]
-    assert np.all(np.abs(mean_h) <= bound * (1 + 1e-6))
-    assert np.array_equal((rcodes_h >> 7).astype(bool), np.signbit(mean_h))
-    del mean, mean_h, rcodes, rcodes_h
+    bound = np.repeat(np.mean(np.stack(scales_o).astype(np.float64), axis=0), B)[:n]
+    assert np.all(np.abs(want_mean) <= bound * (1 + 1e-6))
+    assert np.array_equal((want_rc >> 7).astype(bool), np.signbit(want_mean))
+    del mean, rcodes, fcodes, want_mean, want_rc, oc1, bound
     # the shapes with a local fp32 term that bench.py times: 8 workers + local into fp32, and 7 workers + local
     # averaged and compressed in one call (one GPU's share of the second round on an 8-GPU node)
-    print("C5: local-term variants", flush=True)
-    local = torch.from_numpy(workloads.bucket(5, worker=0)).cuda()
+    print("C5: local-term variants, all elements", flush=True)
+    local = torch.from_numpy(x0).cuda()
     mean_l = dq8.decode_accumulate_avg(KIND, codes_d, scales_d, B, local=local)
     fc7, fs7 = dq8.decode_avg_encode(KIND, codes_d[:7], scales_d[:7], B, local=local)
     torch.cuda.synchronize()
-    mean_l_h, fc7_h, fs7_h = mean_l.cpu().numpy(), fc7.cpu().numpy(), fs7.cpu().numpy()
-    for i, b in enumerate(sample):
-        lo, hi = b * B, min((b + 1) * B, n)
-        oc = [codes_h[w][lo:hi] for w in range(K)]
-        os_ = [scales_h[w][b:b + 1] for w in range(K)]
-        m = oracle.decode_accumulate_avg(KIND, oc, os_, B, local=xs[0][i])
-        assert mean_l_h[lo:hi].tobytes() == m.tobytes(), ("mean with local term", b)
-        c7, s7 = oracle.decode_avg_encode(KIND, oc[:7], os_[:7], B, local=xs[0][i])
-        assert fc7_h[lo:hi].tobytes() == c7.tobytes() and fs7_h[b:b + 1].tobytes() == s7.tobytes(), ("7 + local", b)
+    bits_equal(mean_l, oracle.decode_accumulate_avg(KIND, codes_o, scales_o, B, local=x0), "C5 mean with local term")
+    c7, s7 = oracle.decode_avg_encode(KIND, codes_o[:7], scales_o[:7], B, local=x0)
+    bits_equal(fs7, s7, "C5 scales of 7 workers + local")
+    bits_equal(fc7, c7, "C5 codes of 7 workers + local")
 
 
 def test_error_statistics_of_a_25_million_sample(dq8):
