@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdq8.so")
 SOURCES = ["dq8.hip", "dq8_tables.cpp"]
-HEADERS = ["dq8_internal.h", "dq8_tables.hpp", "dq8_device.hpp", "dq8_kernels_codec.hpp", "dq8_kernels_avg.hpp",
+HEADERS = ["dq8_internal.h", "dq8_tables.hpp", "dq8_device.hpp", "dq8_plan.hpp", "dq8_units.hpp", "dq8_kernels_codec.hpp", "dq8_kernels_avg.hpp",
            "dq8_kernels_avg_encode.hpp", "dq8_kernels_stats.hpp", "dq8_kernels_small.hpp", os.path.join(ROOT, "include", "dq8.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -54,6 +54,19 @@ def build(force=True, verbose=False, extra=()):
     return LIB
 
 
+def build_tunable(out=None, verbose=False):
+    """The same library with changeable launch shapes (-DDQ8_TUNABLE), for experiments: libdq8_tunable.so."""
+    out = out or os.path.join(HERE, "libdq8_tunable.so")
+    cmd = command(out, ["-DDQ8_TUNABLE"])
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return out
+
+
 if __name__ == "__main__":
-    build(force=True, verbose=True, extra=sys.argv[1:])
-    print(LIB)
+    if sys.argv[1:] == ["--tunable"]:
+        print(build_tunable(verbose=True))
+    else:
+        build(force=True, verbose=True, extra=sys.argv[1:])
+        print(LIB)

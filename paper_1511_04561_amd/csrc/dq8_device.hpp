@@ -7,6 +7,7 @@
 
 #include "dq8.h"
 #include "dq8_tables.hpp"
+#include "dq8_units.hpp"
 
 namespace {
 
@@ -20,11 +21,6 @@ using dq8::kNBucketOff;
 using dq8::kNearWindow;
 using dq8::kTableWords;
 
-constexpr int kWave = 64;
-constexpr int kWavesPerWg = 4;
-constexpr int kWg = kWave * kWavesPerWg;
-constexpr int kUnit = 4096;                      // elements per unit
-constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
 constexpr int kKinds = 4;
 constexpr int kLutCopies = 64;                   // one copy of the decode table per lane
 constexpr int kTeamSlots = 8;                    // LDS words for the cross-wave maximum (2 phases x 4 waves)
@@ -117,47 +113,6 @@ __device__ __forceinline__ float max4_abs(v4f v, float m)
     float a = __builtin_fmaxf(__builtin_fabsf(v.x), __builtin_fabsf(v.y));
     float b = __builtin_fmaxf(__builtin_fabsf(v.z), __builtin_fabsf(v.w));
     return __builtin_fmaxf(m, __builtin_fmaxf(a, b));
-}
-
-// Geometry of unit u.  All values are wave-uniform.
-struct Unit {
-    size_t block;   // scale index
-    size_t start;   // first element
-    uint32_t len;   // 1..kUnit
-};
-
-// min(v, U) of a 64-bit count as 32 bits, U a power of two.  Written with a shift and a compare
-// against zero so that it stays on the scalar unit: a 64-bit ordered compare of uniform values
-// is done on the vector unit, and the compiler has been seen to drop the copy of such a result
-// into the scalar condition bit when a branch on the same result follows, leaving a select
-// that reads a stale condition (wrong unit lengths, accesses past the end of the arrays).
-template <int U>
-__device__ __forceinline__ uint32_t cap_to_unit(size_t v)
-{
-    static_assert(U > 0 && (U & (U - 1)) == 0, "unit sizes are powers of two");
-    return (v >> __builtin_ctz(U)) != 0 ? (uint32_t)U : (uint32_t)v;
-}
-
-template <int U>
-__device__ __forceinline__ Unit unit_of(size_t u, size_t n, size_t B, size_t nb, size_t upb)
-{
-    Unit r;
-    size_t c;
-    if (upb == 1) {
-        r.block = u;
-        c = 0;
-    } else if (nb == 1) {
-        r.block = 0;
-        c = u;
-    } else {
-        r.block = u / upb;
-        c = u - r.block * upb;
-    }
-    const size_t off = c * (size_t)U;
-    r.start = r.block * B + off;
-    const uint32_t in_block = cap_to_unit<U>(B - off), in_array = cap_to_unit<U>(n - r.start);
-    r.len = in_block < in_array ? in_block : in_array;
-    return r;
 }
 
 // Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and
