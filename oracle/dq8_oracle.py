@@ -84,6 +84,12 @@ def _u8(a):
     return a.reshape(-1)
 
 
+def _non_negative(scales):
+    """A given scale stands for an absolute maximum or a power of ten (Sec. 3.1): finite, sign bit clear."""
+    if np.any(np.signbit(scales)) or not np.all(np.isfinite(scales)):
+        raise ValueError("given scales must be finite and >= 0 (sign bit clear)")
+
+
 def n_blocks(n, block):
     if n == 0:
         return 0
@@ -117,6 +123,7 @@ def encode(kind, x, block=0, scales=None):
         scales = _f32(scales).copy()
         if scales.size != n_blocks(x.size, block):
             raise ValueError("scales has %d entries, want %d" % (scales.size, n_blocks(x.size, block)))
+        _non_negative(scales)
     else:
         scales = np.empty(n_blocks(x.size, block), dtype=np.float32)
     codes = np.empty(x.size, dtype=np.uint8)
@@ -193,6 +200,7 @@ def error_stats(kind, x, block=0, scales=None):
         scales = _f32(scales).copy()
         if scales.size != nb:
             raise ValueError("scales has %d entries, want %d" % (scales.size, nb))
+        _non_negative(scales)
     else:
         scales = np.empty(nb, dtype=np.float32)
     stats = np.zeros((nb, 4), dtype=np.float64)

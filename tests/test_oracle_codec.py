@@ -494,3 +494,17 @@ def test_results_do_not_depend_on_thread_count():
     b = oracle.encode(oracle.DYNAMIC_TREE, x, 4096)
     oracle.set_threads(1)
     assert np.array_equal(a[0], b[0]) and a[1].tobytes() == b[1].tobytes()
+
+
+def test_given_scales_must_be_non_negative_and_finite():
+    """A given scale stands for an absolute maximum or a decade (Sec. 3.1): the HIP library takes the sign bit of a
+    code from x, which is the sign of x / scale only for such scales, so the oracle's front end refuses the rest
+    instead of letting the two sides disagree silently.  A zero scale (either sign bit clear) means no division."""
+    x = np.array([0.5, -0.25, 0.0], np.float32)
+    for bad in (-2.0, -0.0, np.inf, np.nan):
+        with pytest.raises(ValueError):
+            oracle.encode(oracle.DYNAMIC_TREE, x, 0, scales=np.array([bad], np.float32))
+        with pytest.raises(ValueError):
+            oracle.error_stats(oracle.DYNAMIC_TREE, x, 0, scales=np.array([bad], np.float32))
+    codes, _ = oracle.encode(oracle.DYNAMIC_TREE, x, 0, scales=np.array([0.0], np.float32))
+    assert codes[2] == 0 and codes[1] >> 7 == 1
