@@ -20,7 +20,9 @@
  *     dq8_init() beforehand where that must not happen (e.g. before stream capture).
  *   - Every function returns DQ8_OK or an error code and never throws or aborts.  After an
  *     error dq8_last_error() describes it.  n == 0 is DQ8_OK and launches nothing.
- *   - Inputs must be finite.  With DQ8_SCALES_GIVEN the quotient x / scale must be finite.
+ *   - Inputs must be finite.  With DQ8_SCALES_GIVEN every scale must be finite and >= 0 (a zero
+ *     scale means "do not divide") and the quotient x / scale must be finite; the sign bit of a
+ *     code is taken from x, which is the sign of the quotient only for such scales.
  *   - Any pointer alignment and any n / block are accepted.  The fast paths need
  *     16-byte aligned `x` / `out`, 4-byte aligned `codes`, and block % 4 == 0 (or a single
  *     block); anything else runs on slower paths with the same results.  Blocks of 4096
@@ -30,6 +32,12 @@
  *     256 use a fraction of each wavefront in the calls that compress.
  *   - Results are deterministic and independent of launch configuration: codes and scales
  *     are exact functions of the input, and the average adds workers in index order.
+ *   - Calls may be made from several threads at once; the library shares only immutable tables.
+ *   - DQ8_DEBUG=1 in the environment (read once, at the first launch of the process) makes every
+ *     call wait for the stream after each kernel it launches and check the device's error
+ *     state, so that a failing kernel is reported by the call that launched it (status
+ *     DQ8_ERR_DEVICE, text in dq8_last_error()).  Calls are then synchronous; do not use it on a
+ *     stream that is being captured into a graph.
  *
  * Code layout: bit 7 of a code is the sign, bits 6..0 index the 128 magnitudes in
  * ascending order.  This is this library's own layout; the paper's figure of the bit

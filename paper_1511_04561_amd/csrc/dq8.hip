@@ -31,11 +31,13 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
 #include "dq8.h"
 #include "dq8_internal.h"
+#include "dq8_plan.hpp"
 #include "dq8_tables.hpp"
 
 #include "dq8_device.hpp"
@@ -161,88 +163,14 @@ struct Tuning {
     int copy_q = 2;
     int copy_wpc = 8;
 };
+// The shipped library has fixed launch shapes: nothing mutable is shared between calls, so calls from several
+// threads need no lock.  A build with -DDQ8_TUNABLE (experiments only) makes them changeable through
+// dq8_internal_tune(), which is not synchronised with calls in flight on other threads.
+#ifdef DQ8_TUNABLE
 Tuning g_tune;
-
-// Elements per scale block: `block` as the caller passed it, the whole array for 0 or a longer block.
-size_t block_length(size_t n, size_t block) { return (block == 0 || block > n) ? n : block; }
-
-// Unit for the kernels in which units are pieces of a block: starting from *quads per lane, the largest
-// power of two of them whose unit (quads * 256 elements) is no longer than a block, at least one; every
-// halving doubles *waves_per_cu (up to 32) so that the bytes in flight per compute unit stay the same.
-void fit_unit_to_block(size_t block_len, int *quads, int *waves_per_cu)
-{
-    while (*quads > 1 && (size_t)*quads * 4 * kWave > block_len) {
-        *quads >>= 1;
-        *waves_per_cu = *waves_per_cu * 2 > 32 ? 32 : *waves_per_cu * 2;
-    }
-}
-
-// Workers per chunk for the decode-and-average kernel that takes any number of workers a chunk at a time: the
-// size from 3 to 8 with the fewest empty places in the last chunk (an empty place repeats a load), the largest
-// such size; fewer than 3 workers are one chunk; K = 0 (the local term alone) has no chunks at all.
-int chunk_size(int K)
-{
-    if (K < 3) return K < 1 ? 1 : K;
-    int best = 3;
-    for (int c = 3, waste = DQ8_MAX_K; c <= 8; ++c) {
-        const int w = (K + c - 1) / c * c - K;
-        if (w <= waste) {
-            waste = w;
-            best = c;
-        }
-    }
-    return best;
-}
-
-// Unit for the kernels that hold a whole block in registers: the smallest power of two of elements
-// between 256 and 4096 that holds a block (4096 for longer blocks).
-size_t holding_unit(size_t block_len)
-{
-    size_t unit = 256;
-    while (unit < block_len && unit < (size_t)kUnit) unit <<= 1;
-    return unit;
-}
-
-// The longest block that dq8_encode holds in a team's registers (maximum and quantisation from one read of x).
-constexpr size_t kLongestHeldBlock = 16384;
-
-// Elements per unit for compression: the smallest power of two that holds a block, up to 4096 when the scales
-// are given and up to 16384 when the kernel computes them.
-size_t encode_unit(size_t block_len, bool fused)
-{
-    if (fused && block_len > (size_t)kUnit && block_len <= kLongestHeldBlock) return block_len <= 8192 ? 8192 : 16384;
-    return holding_unit(block_len);
-}
-
-struct Plan {
-    size_t B, nb, upb, n_units, n_teams;
-    unsigned grid;
-};
-
-// Units, and a grid in which every team (wpb wavefronts) walks the same number of them.
-Plan make_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, int waves_per_wg = kWavesPerWg,
-               size_t unit = kUnit)
-{
-    Plan p;
-    p.B = block_length(n, block);
-    p.nb = (n + p.B - 1) / p.B;
-    p.upb = (p.B + unit - 1) / unit;
-    if (p.nb == 1) {
-        p.n_units = (n + unit - 1) / unit;
-    } else {
-        size_t last = n - (p.nb - 1) * p.B;  // the last block may be short
-        p.n_units = (p.nb - 1) * p.upb + (last + unit - 1) / unit;
-    }
-    size_t max_teams = (size_t)cus * (size_t)waves_per_cu / (size_t)wpb;
-    if (max_teams < 1) max_teams = 1;
-    size_t per_team = (p.n_units + max_teams - 1) / max_teams;
-    size_t teams = (p.n_units + per_team - 1) / per_team;
-    size_t teams_per_wg = (size_t)waves_per_wg / wpb;
-    size_t grid = (teams + teams_per_wg - 1) / teams_per_wg;
-    p.grid = (unsigned)grid;
-    p.n_teams = grid * teams_per_wg;
-    return p;
-}
+#else
+const Tuning g_tune{};
+#endif
 
 bool overlaps(const void *a, size_t na, const void *b, size_t nb)
 {
@@ -256,46 +184,30 @@ int check_kind(int kind)
     return DQ8_OK;
 }
 
-int after_launch(const char *what)
+// DQ8_DEBUG=1 in the environment (read once, at the first launch): every launch is followed by a wait for the
+// stream and a check of the error state, so that a failing kernel is reported by the call that launched it.
+bool debug_sync()
+{
+    static const bool on = [] {
+        const char *v = std::getenv("DQ8_DEBUG");
+        return v && v[0] != '\0' && std::strcmp(v, "0") != 0;
+    }();
+    return on;
+}
+
+int after_launch(const char *what, hipStream_t stream)
 {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(DQ8_ERR_DEVICE, "launch of %s failed: %s", what, hipGetErrorString(e));
+    if (debug_sync()) {
+        e = hipStreamSynchronize(stream);
+        if (e == hipSuccess) e = hipGetLastError();
+        if (e != hipSuccess) return fail(DQ8_ERR_DEVICE, "%s failed on the device: %s", what, hipGetErrorString(e));
+    }
     return DQ8_OK;
 }
 
 // ---- blocks of 4 .. 128 elements (powers of two): kernels that pack many blocks into a wavefront's unit
-
-constexpr int kSmallQ = 4;                          // quads per lane
-constexpr size_t kSmallUnit = kSmallQ * 4 * kWave;  // 1024 elements
-
-// Quads per block for those kernels, 0 when the block length does not qualify.  Blocks of 256 to 1024
-// elements (one, two or four whole rows of a unit) qualify in the kernels that have to hold a block, up to
-// the length from which the general kernel for that call is at least as fast: `longest`.
-int small_block_lanes(size_t n, size_t block_len, size_t longest = 128)
-{
-    if (block_len < 4 || block_len > longest || (block_len & (block_len - 1)) != 0 || block_len >= n) return 0;
-    return (int)(block_len / 4);
-}
-
-struct SmallPlan {
-    size_t n_units = 0, n_waves = 0, done = 0;  // whole units, wavefronts in the grid, elements they cover
-    unsigned grid = 0;
-};
-
-// Whole leading units of the array on `waves_per_cu` wavefronts per compute unit, `wpw` per workgroup.
-SmallPlan make_small_plan(size_t n, int cus, int waves_per_cu, int wpw)
-{
-    SmallPlan p;
-    p.n_units = n / kSmallUnit;
-    if (p.n_units == 0) return p;
-    size_t waves = (size_t)cus * (size_t)waves_per_cu;
-    const size_t per = (p.n_units + waves - 1) / waves;
-    waves = (p.n_units + per - 1) / per;
-    p.grid = (unsigned)((waves + wpw - 1) / wpw);
-    p.n_waves = (size_t)p.grid * wpw;
-    p.done = p.n_units * kSmallUnit;
-    return p;
-}
 
 #define DQ8_SMALL_G(lanes, CALL) \
     switch (lanes) {             \
@@ -332,7 +244,7 @@ int small_absmax(const DeviceState &st, const float *x, size_t n, size_t block_l
     DQ8_SMALL_G(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
-    return after_launch("k_small_absmax");
+    return after_launch("k_small_absmax", stream);
 }
 
 int small_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block_len, float *scales, uint8_t *codes,
@@ -355,7 +267,7 @@ int small_encode(const DeviceState &st, int kind, const float *x, size_t n, size
     DQ8_SMALL_G256(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
-    return after_launch("k_small_encode");
+    return after_launch("k_small_encode", stream);
 }
 
 int small_decode(const DeviceState &st, int kind, const uint8_t *codes, const float *scales, size_t n, size_t block_len,
@@ -372,7 +284,7 @@ int small_decode(const DeviceState &st, int kind, const uint8_t *codes, const fl
     DQ8_SMALL_G(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
-    return after_launch("k_small_decode");
+    return after_launch("k_small_decode", stream);
 }
 
 int small_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n, size_t block_len,
@@ -391,7 +303,7 @@ int small_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, cons
     DQ8_SMALL_G(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
-    return after_launch("k_small_avg");
+    return after_launch("k_small_avg", stream);
 }
 
 int small_avg_encode(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
@@ -412,7 +324,7 @@ int small_avg_encode(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     DQ8_SMALL_G256(lanes, DQ8_CALL)
 #undef DQ8_CALL
     *done = p.done;
-    return after_launch("k_small_avg_encode");
+    return after_launch("k_small_avg_encode", stream);
 }
 
 // The worker pointers advanced by `done` elements (`done` a multiple of the block length).
@@ -464,7 +376,7 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
     if (p.upb > 1) {
         unsigned g = (unsigned)((p.nb + 255) / 256);
         hipLaunchKernelGGL(k_fill_zero, dim3(g), dim3(256), 0, stream, scales, p.nb);
-        int rc = after_launch("k_fill_zero");
+        int rc = after_launch("k_fill_zero", stream);
         if (rc) return rc;
         per_wave = (p.n_units + p.n_teams - 1) / p.n_teams;
     }
@@ -486,7 +398,7 @@ int launch_absmax(const DeviceState &st, const float *x, size_t n, size_t block,
     }
 #undef DQ8_AMAX_Q
 #undef DQ8_AMAX
-    return after_launch("k_absmax");
+    return after_launch("k_absmax", stream);
 }
 
 int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, size_t block, float *scales, uint8_t *codes,
@@ -527,7 +439,7 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
             DQ8_ENC_FULL(false, false);
         }
 #undef DQ8_ENC_FULL
-        return after_launch("k_encode_full");
+        return after_launch("k_encode_full", stream);
     }
     // Blocks of 4097 .. 16384 elements in whole quads, aligned buffers: the team holds a block in 8, 12 or 16
     // quads per lane.
@@ -559,7 +471,7 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
         default: DQ8_ENC_WAVE(8) break;
         }
 #undef DQ8_ENC_WAVE
-        return after_launch("k_encode_wave");
+        return after_launch("k_encode_wave", stream);
     }
     const bool long_block = unit > (size_t)kUnit;
     // blocks of 1537 .. 3072 elements too: 2 or 3 quads per lane (2 to 7 % faster than a wavefront per block there)
@@ -593,7 +505,7 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
             DQ8_ENC_LONG(16)
         }
 #undef DQ8_ENC_LONG
-        return after_launch("k_encode_long");
+        return after_launch("k_encode_long", stream);
     }
 #define DQ8_ENC(WPB, QL, FUSED, FD)                                                                               \
     hipLaunchKernelGGL((k_encode<WPB, QL, 1, FUSED, FD>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, \
@@ -632,7 +544,7 @@ int launch_encode(const DeviceState &st, int kind, const float *x, size_t n, siz
     }
 #undef DQ8_ENC_F
 #undef DQ8_ENC
-    return after_launch("k_encode");
+    return after_launch("k_encode", stream);
 }
 
 // Error statistics of compress-then-decompress into stats[4 nb] (and means[2] when not NULL).
@@ -644,17 +556,17 @@ int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n
     const size_t zero_words = 8 * p.nb;  // 4 binary64 zeros per block
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, stream,
                        reinterpret_cast<float *>(stats), zero_words);
-    int rc = after_launch("k_fill_zero");
+    int rc = after_launch("k_fill_zero", stream);
     if (rc) return rc;
     const size_t per_wave = (p.n_units + p.n_teams - 1) / p.n_teams;
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = (256 + (size_t)st.search_words[kind]) * sizeof(uint32_t);
     hipLaunchKernelGGL((k_error_stats<Q>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, p.upb, p.n_units,
                        per_wave, scales, stats);
-    rc = after_launch("k_error_stats");
+    rc = after_launch("k_error_stats", stream);
     if (rc || !means) return rc;
     hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kMeansThreads), 0, stream, stats, p.nb, n, means);
-    return after_launch("k_error_means");
+    return after_launch("k_error_means", stream);
 }
 
 int launch_decode(const DeviceState &st, int kind, const uint8_t *codes, const float *scales, size_t n, size_t block,
@@ -708,7 +620,7 @@ int launch_decode(const DeviceState &st, int kind, const uint8_t *codes, const f
         }
 #undef DQ8_DEC_FLAT
 #undef DQ8_DEC_FLAT_N
-        return after_launch("k_decode_flat");
+        return after_launch("k_decode_flat", stream);
     }
 #define DQ8_DEC(Q, WPW, RG)                                                                                          \
     hipLaunchKernelGGL((k_decode<Q, 2, WPW, RG>), dim3(p.grid), dim3(kWave * WPW), 0, stream, tab, codes, scales, n, p.B, \
@@ -734,7 +646,7 @@ int launch_decode(const DeviceState &st, int kind, const uint8_t *codes, const f
     }
 #undef DQ8_DEC_R
 #undef DQ8_DEC
-    return after_launch("k_decode");
+    return after_launch("k_decode", stream);
 }
 
 // Copies and checks the K (codes, scales) pairs of a call; `out` / `out_bytes` is a buffer the
@@ -853,7 +765,7 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
         default: DQ8_TEAM_MULTI(8) break;
         }
 #undef DQ8_TEAM_MULTI
-        return after_launch("k_avg_team");
+        return after_launch("k_avg_team", stream);
     }
     switch (K) {
     case 1: DQ8_TEAM_3(1) break;
@@ -872,7 +784,7 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #undef DQ8_TEAM_T
 #undef DQ8_TEAM
 #undef DQ8_TEAM_M
-    return after_launch("k_avg_team");
+    return after_launch("k_avg_team", stream);
 }
 
 // Average-then-compress for blocks of 4097 .. kLongestHeldBlock elements: a workgroup per block.
@@ -898,7 +810,7 @@ int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     default: DQ8_AVG_LONG(8, 4); break;
     }
 #undef DQ8_AVG_LONG
-    return after_launch("k_avg_long");
+    return after_launch("k_avg_long", stream);
 }
 
 int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
@@ -941,7 +853,7 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     }
 #undef DQ8_BLK_R
 #undef DQ8_BLK
-    return after_launch("k_avg_block");
+    return after_launch("k_avg_block", stream);
 }
 
 // K-way decode-and-average (optional local term) of whole aligned units with a power-of-two number of them
@@ -1007,7 +919,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
             }
 #undef DQ8_AVGW
             *launched = true;
-            return after_launch("k_decode_avg_full");
+            return after_launch("k_decode_avg_full", stream);
         }
     }
     if (K < 1 || K > 8 || g_tune.avg_chunk_all) {
@@ -1038,7 +950,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
             default: DQ8_CHUNK_F(8, 8, true); break;
             }
             *launched = true;
-            return after_launch("k_decode_avg_chunks");
+            return after_launch("k_decode_avg_chunks", stream);
         }
 #define DQ8_CHUNK_W(CH)       \
     if (cw == 8) {            \
@@ -1060,7 +972,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #undef DQ8_CHUNK
 #undef DQ8_CHUNK_F
         *launched = true;
-        return after_launch("k_decode_avg_chunks");
+        return after_launch("k_decode_avg_chunks", stream);
     }
     // Wavefronts per compute unit: four with 8 workers' code words in flight per lane; more with fewer workers
     // (measured per K; avg_lean_wpc scales all of them).
@@ -1097,7 +1009,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #undef DQ8_AVGF_L
 #undef DQ8_AVGF
         *launched = true;
-        return after_launch("k_decode_avg_flat");
+        return after_launch("k_decode_avg_flat", stream);
     }
     size_t waves = (size_t)st.cus * (size_t)(kWavesForK[K] * g_tune.avg_lean_wpc / 4);
     if (waves > n_full) waves = n_full;
@@ -1140,7 +1052,7 @@ int launch_avg_full(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #undef DQ8_AVGL_L
 #undef DQ8_AVGL
     *launched = true;
-    return after_launch("k_decode_avg_full");
+    return after_launch("k_decode_avg_full", stream);
 }
 
 // K-way decode-and-average into an fp32 array with the general kernels.
@@ -1197,7 +1109,7 @@ int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int
 #undef DQ8_AVG_Q
 #undef DQ8_AVG_W
 #undef DQ8_AVG
-    return after_launch("k_decode_avg");
+    return after_launch("k_decode_avg", stream);
 }
 
 }  // namespace
@@ -1514,6 +1426,10 @@ int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb
 int dq8_internal_tune(const char *key, int value)
 {
     if (!key) return fail(DQ8_ERR_NULL, "dq8_internal_tune: key is NULL");
+#ifndef DQ8_TUNABLE
+    (void)value;
+    return fail(DQ8_ERR_ARG, "dq8_internal_tune: this build has fixed launch shapes (compile with -DDQ8_TUNABLE)");
+#else
     struct { const char *name; int *slot; int lo, hi; } keys[] = {
         {"amax_nt", &g_tune.amax_nt, 0, 1}, 
         {"avg_lean", &g_tune.avg_lean, 0, 1}, {"avg_lean_q", &g_tune.avg_lean_q, 2, 4},
@@ -1530,6 +1446,7 @@ int dq8_internal_tune(const char *key, int value)
             return DQ8_OK;
         }
     return fail(DQ8_ERR_ARG, "dq8_internal_tune: unknown key %s", key);
+#endif
 }
 
 int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
@@ -1559,7 +1476,7 @@ int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
     }
 #undef DQ8_COPY_Q
 #undef DQ8_COPY
-    return after_launch("k_copy");
+    return after_launch("k_copy", stream);
 }
 
 static int host_search(int kind, Search *sr)

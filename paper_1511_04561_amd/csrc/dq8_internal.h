@@ -44,7 +44,9 @@ int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_n
 int dq8_internal_encode_host(int kind, const float *x, size_t n, float scale, int use_reciprocal, uint8_t *codes,
                              uint64_t *n_exact);
 
-// Changes a launch-shape parameter (experiments only; results never depend on them).
+// Changes a launch-shape parameter (experiments only; results never depend on them).  Works only in a
+// library compiled with -DDQ8_TUNABLE, and is not synchronised with calls in flight on other threads; the
+// shipped library has constant launch shapes and returns DQ8_ERR_ARG here.
 int dq8_internal_tune(const char *key, int value);
 
 // Copies n floats device to device with the codec kernels' access pattern (bandwidth and

@@ -14,7 +14,8 @@ SCALES_GIVEN = 1
 MAX_K = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdq8.so")
+# DQ8_LIBRARY names another build of the same library (e.g. one compiled with -DDQ8_TUNABLE for experiments).
+LIB_PATH = os.environ.get("DQ8_LIBRARY") or os.path.join(_HERE, "libdq8.so")
 _lib = None
 
 
@@ -49,10 +50,6 @@ def lib():
         L.dq8_model_speedup.restype = ci
         L.dq8_model_penalty.restype = ci
         L.dq8_last_error.restype = ctypes.c_char_p
-        L.dq8_internal_copy.argtypes = [vp, vp, sz, vp]
-        L.dq8_internal_copy.restype = ci
-        L.dq8_internal_tune.argtypes = [ctypes.c_char_p, ci]
-        L.dq8_internal_tune.restype = ci
         _lib = L
     return _lib
 
@@ -268,20 +265,3 @@ def model_penalty(transfer_ms, compute_ms):
     out = ctypes.c_double()
     _check(lib().dq8_model_penalty(arr(*transfer_ms), arr(*compute_ms), n, ctypes.byref(out)), "dq8_model_penalty")
     return out.value
-
-
-def calibration_copy(dst, src):
-    """Plain fp32 device copy with the kernels' access pattern (bandwidth / counter calibration only)."""
-    src = _dev(src, torch.float32, "src")
-    dst = _dev(dst, torch.float32, "dst")
-    if dst.numel() < src.numel():
-        raise ValueError("dst too small")
-    with _on(src.device):
-        _check(lib().dq8_internal_copy(dst.data_ptr(), src.data_ptr(), src.numel(), _stream()), "dq8_internal_copy")
-    return dst
-
-
-def tune(**kw):
-    """Changes launch-shape parameters of the kernels (experiments only; results never depend on them)."""
-    for k, v in kw.items():
-        _check(lib().dq8_internal_tune(k.encode(), int(v)), "dq8_internal_tune(%s)" % k)

@@ -694,3 +694,48 @@ def test_calls_from_several_threads_on_their_own_streams(dq8):
         th.join(timeout=100)
     assert not any(th.is_alive() for th in threads), "a thread did not finish"
     assert errors == []
+
+
+def test_debug_switch_waits_after_every_launch(dq8):
+    """DQ8_DEBUG=1 is read once per process, so the round trip runs in a process of its own: every call waits for
+    its kernels and checks the device's error state; results are the oracle's bits, and the work of a call is
+    finished when the call returns (the outputs are read without any synchronisation in between)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    script = r"""
+import sys
+sys.path.insert(0, %r)
+import numpy as np, torch, oracle
+from paper_1511_04561_amd import dq8, workloads
+n, B = 40 * 4096 + 77, 4096
+x = workloads.tensor(5, 2, worker=3, limit=n)
+stream = torch.cuda.Stream()
+with torch.cuda.stream(stream):
+    xd = torch.from_numpy(x).cuda()
+    stream.synchronize()
+    for kind in (0, 3):
+        codes, scales = dq8.encode(kind, xd, B)
+        done = stream.query()          # nothing may be pending on the stream once the call has returned
+        out = dq8.decode(kind, codes, scales, B)
+        done = done and stream.query()
+        mean = dq8.decode_accumulate_avg(kind, [codes, codes, codes], [scales, scales, scales], B)
+        done = done and stream.query()
+        fc, fs = dq8.decode_avg_encode(kind, [codes, codes, codes], [scales, scales, scales], B)
+        done = done and stream.query()
+        stats, means = dq8.error_stats(kind, xd, B)
+        done = done and stream.query()
+        assert done, "a call returned before its kernels had finished"
+        wc, ws = oracle.encode(kind, x, B)
+        assert codes.cpu().numpy().tobytes() == wc.tobytes() and scales.cpu().numpy().tobytes() == ws.tobytes()
+        assert out.cpu().numpy().tobytes() == oracle.decode(kind, wc, ws, B).tobytes()
+        wm = oracle.decode_accumulate_avg(kind, [wc] * 3, [ws] * 3, B)
+        assert mean.cpu().numpy().tobytes() == wm.tobytes()
+        oc, os_ = oracle.encode(kind, wm, B)
+        assert fc.cpu().numpy().tobytes() == oc.tobytes() and fs.cpu().numpy().tobytes() == os_.tobytes()
+        assert stats.cpu().numpy()[:, 2].tobytes() == oracle.error_stats(kind, x, B)[0][:, 2].tobytes()
+print("debug round trip ok")
+""" % root
+    env = dict(os.environ, DQ8_DEBUG="1")
+    p = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0 and "debug round trip ok" in p.stdout, p.stdout[-2000:] + p.stderr[-4000:]
