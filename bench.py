@@ -17,7 +17,7 @@ for the average, the mean that was written two steps earlier for the re-compress
 anything that either of the two calls before it read or wrote, and whatever a call reads was last touched
 more than 1 GB of traffic ago, so the 256 MB last-level cache cannot serve any of it.
 
-Order of a run: untimed clock-settling steps (groups of ten until two consecutive groups agree within
+Order of a run: untimed clock-settling steps (groups of ten until three consecutive groups agree within
 1 %; their number is reported), W untimed warm-up steps, exactly K timed steps between two
 synchronisations.  value = fp32 bytes the five calls consume or produce (4 bytes x n each) per second over
 the timed region.
@@ -256,22 +256,22 @@ def run_default(args, torch, dq8, internal, workloads):
         for _, f in bk.step_calls(i):
             f()
 
-    # ---- clock settling (untimed): groups of ten steps until two consecutive groups agree within 1 %
-    settle_groups, prev, settled_ms = 0, None, None
+    # ---- clock settling (untimed): groups of ten steps until the last three groups agree within 1 %
+    settle_groups, recent, settled_ms = 0, [], None
     it = 0
-    while settle_groups < 60:
+    while settle_groups < args.max_settle_groups:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(10):
             step(it)
             it += 1
         torch.cuda.synchronize()
-        cur = (time.perf_counter() - t0) / 10 * 1e3
+        recent = (recent + [(time.perf_counter() - t0) / 10 * 1e3])[-3:]
         settle_groups += 1
-        if prev is not None and abs(cur - prev) <= 0.01 * prev:
-            settled_ms = cur
+        if len(recent) == 3 and max(recent) - min(recent) <= 0.01 * min(recent):
+            settled_ms = recent[-1]
             break
-        prev = cur
+    prev = recent[-1] if recent else None
     # ---- timed region: W warm-up steps, then exactly K steps between synchronisations
     for i in range(args.warmup):
         step(it + i)
@@ -321,7 +321,7 @@ def run_default(args, torch, dq8, internal, workloads):
         "kernels": kernels,
         "kernel_timing": "median of %d groups of %d consecutive launches between HIP events" % (GROUPS, launches),
         "settle": {"steps": 10 * settle_groups, "settled": settled_ms is not None,
-                   "last_ms_per_step": round(settled_ms if settled_ms is not None else prev, 4)},
+                   "last_ms_per_step": None if prev is None else round(settled_ms if settled_ms is not None else prev, 4)},
         "device": device_info(),
         "copy_kernel_GBps": round(copy_gbps, 1),
     }
@@ -434,6 +434,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-settle-groups", type=int, default=60,
+                    help="upper limit of the untimed clock-settling phase, in groups of ten steps (0: none, e.g. under a profiler)")
     ap.add_argument("--only", default=None, help="time only this call in the per-kernel pass (profiling aid)")
     ap.add_argument("--sweep", nargs="?", const="blocks,workers,configs", default=None,
                     help="print one JSON line per (block length | worker count | small configuration) instead of the bench line")

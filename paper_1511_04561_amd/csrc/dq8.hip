@@ -74,8 +74,8 @@ struct DeviceState {
     bool ready = false;
     uint32_t *tables = nullptr;  // device address of g_tables on this device
     int cus = 0;
-    bool has_remap[kKinds] = {false, false, false, false};  // the type needs the rank-to-code table
-    uint32_t search_words[kKinds] = {0, 0, 0, 0};  // LDS words of a type's search tables (buckets + rank-to-code)
+    bool has_remap[kKinds] = {false, false, false, false};  // code bytes of the type can carry marks (fix_marked_codes)
+    uint32_t search_words[kKinds] = {0, 0, 0, 0};  // LDS words of a type's bucket table
 };
 
 std::mutex g_mu;
@@ -95,8 +95,8 @@ int device_state(DeviceState **out)
             int rc = dq8::build_tables(k, &t);
             if (rc) return fail(DQ8_ERR_KIND, "table construction failed for kind %d (status %d)", k, rc);
             dq8::pack_tables(t, image[k]);
-            st.has_remap[k] = t.has_remap;
-            st.search_words[k] = t.n_bucket + (t.has_remap ? (uint32_t)kRemapWords : 0u);
+            st.has_remap[k] = t.has_marks;
+            st.search_words[k] = t.n_bucket;
         }
         void *sym = nullptr;
         DQ8_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(g_tables)));
@@ -552,18 +552,33 @@ int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n
                        double *stats, double *means, hipStream_t stream)
 {
     constexpr int Q = 4;
-    Plan p = make_plan(n, block, st.cus, 16, 1, kWavesPerWg, (size_t)Q * 4 * kWave);
-    const size_t zero_words = 8 * p.nb;  // 4 binary64 zeros per block
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, stream,
-                       reinterpret_cast<float *>(stats), zero_words);
-    int rc = after_launch("k_fill_zero", stream);
-    if (rc) return rc;
-    const size_t per_wave = (p.n_units + p.n_teams - 1) / p.n_teams;
+    constexpr int kWavesPerCu = 16;  // two workgroups of eight
+    Plan p = make_plan(n, block, st.cus, kWavesPerCu, 1, kStatsWaves, (size_t)Q * 4 * kWave);
+    const size_t n_waves = (size_t)p.grid * kStatsWaves;
+    // Wavefronts own whole blocks when there is at least one block for each of them and a block is at most 64 units
+    // (then no wavefront's share of the work is far from the average); otherwise they share blocks through atomics
+    // on zeroed rows.
+    const size_t all_waves = (size_t)st.cus * kWavesPerCu;
+    const bool own = p.upb <= 64 && p.nb >= all_waves;
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = (256 + (size_t)st.search_words[kind]) * sizeof(uint32_t);
-    hipLaunchKernelGGL((k_error_stats<Q>), dim3(p.grid), dim3(kWg), lds, stream, tab, x, n, p.B, p.nb, p.upb, p.n_units,
-                       per_wave, scales, stats);
-    rc = after_launch("k_error_stats", stream);
+    const size_t lds = (size_t)st.search_words[kind] * sizeof(uint32_t);
+    int rc;
+    if (own) {
+        const unsigned grid = (unsigned)(all_waves / kStatsWaves);
+        hipLaunchKernelGGL((k_error_stats<Q, true>), dim3(grid), dim3(kStatsWg), lds, stream, tab, x, n, p.B, p.nb, p.upb,
+                           p.n_units, (size_t)0, all_waves, scales, stats);
+        rc = after_launch("k_error_stats", stream);
+    } else {
+        const size_t zero_words = 8 * p.nb;  // 4 binary64 zeros per block
+        hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, stream,
+                           reinterpret_cast<float *>(stats), zero_words);
+        rc = after_launch("k_fill_zero", stream);
+        if (rc) return rc;
+        const size_t per_wave = (p.n_units + n_waves - 1) / n_waves;
+        hipLaunchKernelGGL((k_error_stats<Q, false>), dim3(p.grid), dim3(kStatsWg), lds, stream, tab, x, n, p.B, p.nb, p.upb,
+                           p.n_units, per_wave, n_waves, scales, stats);
+        rc = after_launch("k_error_stats", stream);
+    }
     if (rc || !means) return rc;
     hipLaunchKernelGGL(k_error_means, dim3(1), dim3(kMeansThreads), 0, stream, stats, p.nb, n, means);
     return after_launch("k_error_means", stream);
@@ -1484,10 +1499,8 @@ static int host_search(int kind, Search *sr)
     int rc = check_kind(kind);
     if (rc) return rc;
     static thread_local dq8::Tables t;
-    static thread_local uint32_t remap[kRemapWords];
     if (dq8::build_tables(kind, &t)) return fail(DQ8_ERR_KIND, "table construction failed for kind %d", kind);
-    for (int r = 0; r < kRemapWords; ++r) remap[r] = t.canon[r];
-    *sr = make_search(t.bucket, t.lo_key, t.n_bucket, t.has_remap ? remap : nullptr);
+    *sr = make_search(t.bucket, t.lo_key, t.n_bucket, t.has_marks);
     return DQ8_OK;
 }
 
@@ -1506,13 +1519,17 @@ int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_n
     for (uint32_t bits = 0; bits <= 0x7F800000u; ++bits) {
         while (j < n_thr && thr_bits[j] <= bits) ++j;
         const float pos = u2f(bits), neg = u2f(bits | 0x80000000u);
-        const uint32_t sp = search_sum(sr, pos), sn = search_sum(sr, neg);
         const uint32_t want = t.canon[j];
-        bad += code_of(sr, sp, pos) != want;
-        bad += code_of(sr, sn, neg) != (want | 0x80u);
-        // every value within kNearWindow steps of a threshold must raise the proximity flag
+        // the lookup for a correctly rounded quotient is right for every value
+        bad += code_of(sr, search_sum_exact(sr, pos), pos) != want;
+        bad += code_of(sr, search_sum_exact(sr, neg), neg) != (want | 0x80u);
+        // the lookup for a product x * fl(1 / s) is right wherever it does not raise the proximity flag,
+        const uint32_t sp = search_sum(sr, pos), sn = search_sum(sr, neg);
+        if (near_key(sp) > 2 * kNearWindow) bad += code_of(sr, sp, pos) != want;
+        if (near_key(sn) > 2 * kNearWindow) bad += code_of(sr, sn, neg) != (want | 0x80u);
+        // and every value within kNearWindow steps of a threshold raises it
         bool close = (j < n_thr && thr_bits[j] - bits <= kNearWindow) || (j > 0 && bits - thr_bits[j - 1] <= kNearWindow);
-        if (close && near_key(sp) > 2 * kNearWindow) ++missed;
+        if (close && (near_key(sp) > 2 * kNearWindow || near_key(sn) > 2 * kNearWindow)) ++missed;
     }
     if (mismatches) *mismatches = bad;
     if (missed_near) *missed_near = missed;

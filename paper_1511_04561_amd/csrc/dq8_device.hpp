@@ -12,9 +12,7 @@
 namespace {
 
 using dq8::kBucketOff;
-using dq8::kHasRemapOff;
-using dq8::kRemapOff;
-using dq8::kRemapWords;
+using dq8::kHasMarksOff;
 using dq8::kCbOff;
 using dq8::kLoKeyOff;
 using dq8::kNBucketOff;
@@ -115,32 +113,33 @@ __device__ __forceinline__ float max4_abs(v4f v, float m)
     return __builtin_fmaxf(m, __builtin_fmaxf(a, b));
 }
 
-// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and
-// for a data type with repeated values the table that turns a rank into its code.
+// Search state for the encoder (see dq8_tables.hpp): bucket table plus the clamp range, and whether
+// code bytes of this data type can carry the mark of a step of 3 between codes.
 struct Search {
     const uint32_t *bucket;  // LDS on the device
-    const uint32_t *remap;   // NULL when every rank is its own code
+    bool marks;              // code bytes have to pass through fix_marked_codes
     uint32_t lo_key;         // key of the first bucket
     float lo_f, hi_f;        // clamp range as binary32 values (bit patterns lo_bits, hi_bits)
 };
 
 __host__ __device__ __forceinline__ Search make_search(const uint32_t *bucket, uint32_t lo_key, uint32_t n_bucket,
-                                                       const uint32_t *remap = nullptr)
+                                                       bool marks = false)
 {
     Search s;
     s.bucket = bucket;
-    s.remap = remap;
+    s.marks = marks;
     s.lo_key = lo_key;
     s.lo_f = u2f((lo_key << 16) + 0x8000u);
     s.hi_f = u2f(((lo_key + n_bucket - 1) << 16) + 0x8000u);
     return s;
 }
 
-// sum >> 16 = rank of the nearest table value (the number of thresholds <= |xn|), which is its
-// magnitude field except for a type with a rank-to-code table (see finish_sum); the low half of
-// sum measures the distance to the threshold of the bucket.  Non-negative binary32 values order like their bit patterns,
-// so the clamp is done on the value.
-__host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn)
+// Lookup of a = bits(|xn|) clamped into the table's range.  Byte 2 of the result (bits 16..23) is the code field
+// of rank #{ T - W <= a } (T the thresholds, W = kNearWindow; possibly marked, see fix_marked_codes); its low half
+// is small (is_near) whenever a lies within W steps of a threshold.  Non-negative binary32 values order like their
+// bit patterns, so the clamp is done on the value.  SHIFT = W looks up a - W instead: the exact rank #{ T <= a }.
+template <uint32_t SHIFT>
+__host__ __device__ __forceinline__ uint32_t table_sum(const Search &s, float xn)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     const float c = __builtin_amdgcn_fmed3f(__builtin_fabsf(xn), s.lo_f, s.hi_f);
@@ -149,52 +148,64 @@ __host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float x
     c = c >= s.lo_f ? c : s.lo_f;  // also takes NaN to the low end; inputs are finite anyway
     c = c <= s.hi_f ? c : s.hi_f;
 #endif
-    const uint32_t a = f2u(c);  // the low 16 bits of lo_base are zero: subtracting it only moves the key
+    const uint32_t a = f2u(c) - SHIFT;  // the clamp range is the middle of a bucket: a - W stays inside the table
     return s.bucket[(a >> 16) - s.lo_key] + (a & 0xFFFFu);
 }
 
-// Rank to magnitude field in bits 16..22, for the types where the two differ.  Kept out of
-// search_sum so that an encoder takes this (wavefront-uniform) branch once per group of sums.
-__host__ __device__ __forceinline__ uint32_t finish_sum(const Search &s, uint32_t sum) { return s.remap[sum >> 16] << 16; }
+// For a quotient taken as x * fl(1 / s): right unless is_near(sum) says that a threshold is within W steps.
+__host__ __device__ __forceinline__ uint32_t search_sum(const Search &s, float xn) { return table_sum<0>(s, xn); }
 
-// (sum + W) mod 2^16 <= 2 W  <=>  |xn| is within W binary32 steps of a threshold or a bucket edge.
-__host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return (sum + kNearWindow) & 0xFFFFu; }
+// For a correctly rounded quotient: always right.
+__host__ __device__ __forceinline__ uint32_t search_sum_exact(const Search &s, float xn) { return table_sum<kNearWindow>(s, xn); }
 
-// Code = magnitude index, bit 7 = sign bit of the input (the divisor is positive).
-__host__ __device__ __forceinline__ uint32_t code_from(uint32_t sum, float x) { return (sum >> 16) | ((f2u(x) >> 24) & 0x80u); }
+// Distance measure of a search_sum result: values up to 2 W mean "within W steps of a threshold (or just past
+// the start of a bucket)".
+__host__ __device__ __forceinline__ uint32_t near_key(uint32_t sum) { return sum & 0xFFFFu; }
 
-__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, uint32_t sum, float x)
+// Up to four code bytes in one word.  A byte with bit 7 set comes from a bucket whose threshold separates code
+// 16 E + 15 from code 16 (E + 1) + 2 (the two fields in between repeat smaller values and are never emitted):
+// its low seven bits are 16 E + 15 when the value lies below the threshold and 16 (E + 1) when the carry of the
+// search has happened.  Clearing the mark and setting bit 1 of the bytes whose bit 0 is clear gives the codes.
+// Bytes without the mark pass unchanged.
+__host__ __device__ __forceinline__ uint32_t fix_marked_codes(uint32_t m)
 {
-    if (s.remap) sum = finish_sum(s, sum);
-    return code_from(sum, x);
+    const uint32_t marked = (m >> 7) & 0x01010101u;  // bit 0 of every marked byte
+    const uint32_t carried = marked & ~m;            // ... whose own bit 0 is clear
+    return (m & 0x7F7F7F7Fu) | (carried << 1);
 }
 
-__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_of(s, search_sum(s, x / d), x); }
+// Code = code field (byte 2 of sum), bit 7 = sign bit of the input (the divisor is not negative).
+__host__ __device__ __forceinline__ uint32_t code_of(const Search &s, uint32_t sum, float x)
+{
+    uint32_t m = (sum >> 16) & 0xFFu;
+    if (s.marks) m = fix_marked_codes(m);
+    return m | ((f2u(x) >> 24) & 0x80u);
+}
 
-// Four codes in one word: byte i = magnitude index of sum i (its byte 2) with the sign bit of
+__host__ __device__ __forceinline__ uint32_t code_exact(const Search &s, float x, float d) { return code_of(s, search_sum_exact(s, x / d), x); }
+
+// Four codes in one word: byte i = code field of sum i (its byte 2) with the sign bit of
 // x i (top bit of its byte 3).  v_perm_b32 gathers the bytes: selector byte 0..3 picks a byte
 // of the second operand, 4..7 of the first, 0x0C gives zero.
 __device__ __forceinline__ uint32_t pack_codes(const Search &sr, uint32_t s0, uint32_t s1, uint32_t s2, uint32_t s3, v4f v)
 {
-    if (sr.remap) {
-        s0 = finish_sum(sr, s0);
-        s1 = finish_sum(sr, s1);
-        s2 = finish_sum(sr, s2);
-        s3 = finish_sum(sr, s3);
-    }
     const uint32_t m01 = __builtin_amdgcn_perm(s1, s0, 0x0C0C0602u);
     const uint32_t m23 = __builtin_amdgcn_perm(s3, s2, 0x06020C0Cu);
     const uint32_t g01 = __builtin_amdgcn_perm(f2u(v.y), f2u(v.x), 0x0C0C0703u);
     const uint32_t g23 = __builtin_amdgcn_perm(f2u(v.w), f2u(v.z), 0x07030C0Cu);
-    return ((g01 | g23) & 0x80808080u) | m01 | m23;
+    uint32_t m = m01 | m23;
+    if (sr.marks) m = fix_marked_codes(m);
+    return ((g01 | g23) & 0x80808080u) | m;
 }
 
 // A scale qualifies for the reciprocal path when 1/d and every product x * (1/d) that can
-// reach a threshold are normal numbers: 2^-100 <= d <= 2^100.
+// reach a threshold are normal numbers: 2^-98 <= d <= 2^100.  (The lower end leaves room for two things: a
+// reciprocal that is scaled by up to 2^-5 more, and values below the normal range, |x| < 2^-126, whose quotient
+// is then below 2^-28, under the smallest threshold of every data type by a quarter of its value.)
 __host__ __device__ __forceinline__ bool reciprocal_ok(float d)
 {
     uint32_t b = f2u(d);
-    return b >= 0x0D800000u && b <= 0x71800000u;
+    return b >= 0x0E800000u && b <= 0x71800000u;
 }
 
 // Four codes packed into one word.  With `recip` the quotients are first taken as x * r with
@@ -213,42 +224,93 @@ __device__ __forceinline__ uint32_t encode_quad(const Search &sr, v4f v, float d
         k0 = k0 < k2 ? k0 : k2;
         if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(sr, s0, s1, s2, s3, v);
     }
-    return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
+    return pack_codes(sr, search_sum_exact(sr, v.x / d), search_sum_exact(sr, v.y / d), search_sum_exact(sr, v.z / d), search_sum_exact(sr, v.w / d), v);
 }
 
 // Q quads at once: all 4 Q table lookups of the reciprocal path are issued before the first result is
-// used, so their latencies overlap; then each quad is checked, and redone with true divisions, on its own.
+// used, so their latencies overlap.  One test covers all of them; only when some lane of the wavefront has a
+// value next to a threshold (about one group in five) is each quad checked, and redone with true divisions, on
+// its own.
+// The values to compress are v * pre, with pre = 1 or a power of two 2^-k, k <= 5, that the caller has not
+// multiplied in: the products v * pre are exact scalings for every result in the normal range, so
+// v * (pre * r) is the same number as (v * pre) * r and one multiplication per element is saved; results below
+// the normal range lie under every threshold (see reciprocal_ok) and get rank 0 either way.  Sign bits come
+// from v, which has the sign of v * pre.
 template <bool FASTDIV, int Q>
-__device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q], float d, float r, bool recip,
+__device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q], float pre, float d, float r, bool recip,
                                              uint32_t (&cw)[Q])
 {
     if (FASTDIV && recip) {
-        uint32_t s[Q][4];
+        const float rp = r * pre;  // exact: r is within [2^-100, 2^98]
+        uint32_t s[Q][4], k[Q];
 #pragma unroll
         for (int it = 0; it < Q; ++it) {
-            s[it][0] = search_sum(sr, v[it].x * r);
-            s[it][1] = search_sum(sr, v[it].y * r);
-            s[it][2] = search_sum(sr, v[it].z * r);
-            s[it][3] = search_sum(sr, v[it].w * r);
+            s[it][0] = search_sum(sr, v[it].x * rp);
+            s[it][1] = search_sum(sr, v[it].y * rp);
+            s[it][2] = search_sum(sr, v[it].z * rp);
+            s[it][3] = search_sum(sr, v[it].w * rp);
         }
+        uint32_t all = 0xFFFFu;
 #pragma unroll
         for (int it = 0; it < Q; ++it) {
-            uint32_t k0 = near_key(s[it][0]), k1 = near_key(s[it][1]), k2 = near_key(s[it][2]), k3 = near_key(s[it][3]);
-            k0 = k0 < k1 ? k0 : k1;
-            k2 = k2 < k3 ? k2 : k3;
-            k0 = k0 < k2 ? k0 : k2;
-            if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) != 0) {
-                s[it][0] = search_sum(sr, v[it].x / d);
-                s[it][1] = search_sum(sr, v[it].y / d);
-                s[it][2] = search_sum(sr, v[it].z / d);
-                s[it][3] = search_sum(sr, v[it].w / d);
+            const uint32_t k01 = near_key(s[it][0]) < near_key(s[it][1]) ? near_key(s[it][0]) : near_key(s[it][1]);
+            const uint32_t k23 = near_key(s[it][2]) < near_key(s[it][3]) ? near_key(s[it][2]) : near_key(s[it][3]);
+            k[it] = k01 < k23 ? k01 : k23;
+            all = all < k[it] ? all : k[it];
+        }
+        if (__builtin_amdgcn_ballot_w64(all <= 2 * kNearWindow) != 0) {
+#pragma unroll
+            for (int it = 0; it < Q; ++it) {
+                if (__builtin_amdgcn_ballot_w64(k[it] <= 2 * kNearWindow) != 0) {
+                    s[it][0] = search_sum_exact(sr, (v[it].x * pre) / d);
+                    s[it][1] = search_sum_exact(sr, (v[it].y * pre) / d);
+                    s[it][2] = search_sum_exact(sr, (v[it].z * pre) / d);
+                    s[it][3] = search_sum_exact(sr, (v[it].w * pre) / d);
+                }
             }
-            cw[it] = pack_codes(sr, s[it][0], s[it][1], s[it][2], s[it][3], v[it]);
         }
+#pragma unroll
+        for (int it = 0; it < Q; ++it) cw[it] = pack_codes(sr, s[it][0], s[it][1], s[it][2], s[it][3], v[it]);
     } else {
 #pragma unroll
-        for (int it = 0; it < Q; ++it) cw[it] = encode_quad<false>(sr, v[it], d, r, recip);
+        for (int it = 0; it < Q; ++it) {
+            const v4f m = {v[it].x * pre, v[it].y * pre, v[it].z * pre, v[it].w * pre};
+            cw[it] = encode_quad<false>(sr, m, d, r, recip);
+        }
     }
+}
+
+template <bool FASTDIV, int Q>
+__device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q], float d, float r, bool recip, uint32_t (&cw)[Q])
+{
+    encode_quads<FASTDIV, Q>(sr, v, 1.0f, d, r, recip, cw);
+}
+
+// The sums of `terms` terms become means, and their largest magnitude is returned.  When the number of terms is a
+// power of two the division is a scaling by rk = 1 / terms, which commutes with the maximum and with everything
+// the compression does (see encode_quads): the sums are left as they are, *pre = rk, and the maximum is scaled
+// once (rounding is monotonic, so the scaled maximum is the maximum of the scaled values, also below the normal
+// range).  Otherwise every sum is divided and *pre = 1.
+template <int Q>
+__device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2, float rk, float fk, float *pre)
+{
+    float fm = 0.0f;
+    if (pow2) {
+#pragma unroll
+        for (int j = 0; j < Q; ++j) fm = max4_abs(acc[j], fm);
+        *pre = rk;
+        return fm * rk;
+    }
+#pragma unroll
+    for (int j = 0; j < Q; ++j) {
+        acc[j].x = acc[j].x / fk;
+        acc[j].y = acc[j].y / fk;
+        acc[j].z = acc[j].z / fk;
+        acc[j].w = acc[j].w / fk;
+        fm = max4_abs(acc[j], fm);
+    }
+    *pre = 1.0f;
+    return fm;
 }
 
 template <bool FASTDIV>
@@ -261,19 +323,13 @@ __device__ __forceinline__ uint32_t encode_one(const Search &sr, float x, float 
     return code_exact(sr, x, d);
 }
 
-// Copies the bucket table (and the rank-to-code table of a type that has one, right behind it)
-// to LDS with all `n_threads` threads of the workgroup; the caller synchronises the workgroup
-// before using it.
+// Copies the bucket table to LDS with all `n_threads` threads of the workgroup; the caller synchronises
+// the workgroup before using it.
 __device__ __forceinline__ Search load_bucket_table(const uint32_t *tab, uint32_t *lds, uint32_t n_threads = kWg)
 {
     const uint32_t nbk = tab[kNBucketOff];
     for (uint32_t i = threadIdx.x; i < nbk; i += n_threads) lds[i] = tab[kBucketOff + i];
-    const uint32_t *remap = nullptr;
-    if (tab[kHasRemapOff]) {
-        for (uint32_t i = threadIdx.x; i < (uint32_t)kRemapWords; i += n_threads) lds[nbk + i] = tab[kRemapOff + i];
-        remap = lds + nbk;
-    }
-    return make_search(lds, tab[kLoKeyOff], nbk, remap);
+    return make_search(lds, tab[kLoKeyOff], nbk, tab[kHasMarksOff] != 0);
 }
 
 // Decode table in LDS, one copy per lane: entry (code, lane) at byte address code * 256 +

@@ -33,9 +33,11 @@ int dq8_internal_chunk_size(int K);
 int dq8_internal_plan(size_t n, size_t block, int cus, int waves_per_cu, int wpb, size_t unit, size_t *out6);
 
 // Runs the kernels' code search (the same inline functions, compiled for the host) over every
-// non-negative finite binary32 bit pattern and +inf, and compares it with a count of the
-// thresholds that are <= the value.  *mismatches = number of disagreements; *missed_near =
-// number of values within the proximity window of a threshold that did not raise the flag.
+// non-negative finite binary32 bit pattern and +inf, and compares it with the code of the rank that a count
+// of the thresholds <= the value gives: the lookup for exact quotients on every value, the lookup for
+// reciprocal products on every value that does not raise the proximity flag.  *mismatches = number of
+// disagreements; *missed_near = number of values within the proximity window of a threshold that did not
+// raise the flag.
 int dq8_internal_check_search(int kind, uint64_t *mismatches, uint64_t *missed_near);
 
 // The encoder's per-element arithmetic on the host (same inline functions): codes of x[0..n)

@@ -104,12 +104,12 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                     add_w(wb, k + 1);
                 }
             }
+            if (pow2) {  // one test for the whole unit, not one per element
 #pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                acc[j].x = mean_of(acc[j].x);
-                acc[j].y = mean_of(acc[j].y);
-                acc[j].z = mean_of(acc[j].z);
-                acc[j].w = mean_of(acc[j].w);
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{acc[j].x * rk, acc[j].y * rk, acc[j].z * rk, acc[j].w * rk};
+            } else {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) acc[j] = v4f{acc[j].x / fk, acc[j].y / fk, acc[j].z / fk, acc[j].w / fk};
             }
             if (mean_out) {
                 v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
@@ -332,15 +332,8 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
                 for (int i = 0; i < NB - 1; ++i)
                     if (i < K) load_w(w[i], i, next);
             }
-            float fm = 0.0f;
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                acc[j].x = mean_of(acc[j].x);
-                acc[j].y = mean_of(acc[j].y);
-                acc[j].z = mean_of(acc[j].z);
-                acc[j].w = mean_of(acc[j].w);
-                fm = max4_abs(acc[j], fm);
-            }
+            float pre;  // what the sums still have to be multiplied by to be the means
+            const float fm = means_for_compression<Q>(acc, pow2, rk, fk, &pre);
             s = u2f(team_max(wave_max_u32(f2u(fm))));
             const float d = s == 0.0f ? 1.0f : s;
             const float r = 1.0f / d;
@@ -353,7 +346,7 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
                 uint32_t cw[G];
 #pragma unroll
                 for (int j = 0; j < G; ++j) vv[j] = acc[g + j];
-                encode_quads<true, G>(sr, vv, d, r, recip, cw);
+                encode_quads<true, G>(sr, vv, pre, d, r, recip, cw);
 #pragma unroll
                 for (int j = 0; j < G; ++j)
                     if ((g + j) * kLongTeam + tl < nq) stg<1>(c4 + (g + j) * kLongTeam + tl, cw[j]);
@@ -536,6 +529,7 @@ struct AvgTeam {
     {
         v4f acc[Q];
         uint32_t m = 0;
+        float pre = 1.0f;  // what the sums still have to be multiplied by to be the means
         if (STEADY || (sl.active && sl.fast)) {
             if (local) {  // not prefetched: the code words take the registers
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
@@ -602,16 +596,7 @@ struct AvgTeam {
                 __builtin_amdgcn_sched_barrier(0);
             }
           }
-            float fm = 0.0f;
-#pragma unroll
-            for (int j = 0; j < Q; ++j) {
-                acc[j].x = mean_of(acc[j].x);
-                acc[j].y = mean_of(acc[j].y);
-                acc[j].z = mean_of(acc[j].z);
-                acc[j].w = mean_of(acc[j].w);
-                fm = max4_abs(acc[j], fm);
-            }
-            m = f2u(fm);
+            m = f2u(means_for_compression<Q>(acc, pow2, rk, fk, &pre));
         } else {
             if (sl.active) {
                 for (uint32_t i = tl; i < sl.un.len; i += kWg) {
@@ -639,7 +624,7 @@ struct AvgTeam {
         if (STEADY || sl.fast) {
             uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + sl.un.start);
             uint32_t cw[Q];
-            encode_quads<FASTDIV, Q>(sr, acc, d, r, recip, cw);
+            encode_quads<FASTDIV, Q>(sr, acc, pre, d, r, recip, cw);
 #pragma unroll
             for (int j = 0; j < Q; ++j)
                 if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw[j]);
@@ -691,7 +676,7 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     load_lut(tab, lut);
     {
         e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWg * TEAMS);
-        if (!REMAP) e.sr.remap = nullptr;  // a type without a rank-to-code table: no test for one in the loop
+        e.sr.marks = REMAP;  // known at compile time: no test for marked code bytes in the loop
     }
     __syncthreads();
     // `steady` (even) leading iterations in which this and the next unit of every team are whole

@@ -263,7 +263,8 @@ __global__ __launch_bounds__(kWg) void k_encode(const uint32_t *__restrict__ tab
 // nothing else in the loop.  Block b starts at element 4096 b, x is 16-byte and codes 4-byte
 // aligned, so unit geometry is a multiplication and there is no slow path to branch around.
 // A ragged last block of tail_len elements is done by the last workgroup after its loop.
-// REMAP = false promises a type without a rank-to-code table: the test for one drops out of the loop.
+// REMAP says whether code bytes of the data type can carry marks (see fix_marked_codes): known at compile time,
+// so the test for it drops out of the loop.
 template <int NT, bool FASTDIV, bool REMAP>
 __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict__ tab, const float *__restrict__ x,
                                                     uint32_t n_full, uint32_t n_teams, uint32_t tail_len,
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(kWg) void k_encode_full(const uint32_t *__restrict_
     v4f a[Q], b[Q];
     if (u < n_full) fetch(u, a);  // the first loads are in flight while the table is copied
     sr = load_bucket_table(tab, lds + kTeamSlots);
-    if (!REMAP) sr.remap = nullptr;
+    sr.marks = REMAP;  // known at compile time: no test for marked code bytes in the loop
     __syncthreads();
     // Steady state: the fetch of the next block is unconditional and comes before the work on the
     // current one, so at the point where the current block's registers are first read the compiler
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(kWave * WPW) void k_encode_wave(const uint32_t *__r
     v4f a[Q], b[Q];
     if (u < n_units) fetch(u, a);  // the first loads are in flight while the table is copied
     sr = load_bucket_table(tab, lds, kWave * WPW);
-    if (!REMAP) sr.remap = nullptr;
+    sr.marks = REMAP;  // known at compile time: no test for marked code bytes in the loop
     __syncthreads();
     // steady state as in k_encode_full: the next block's loads are issued unconditionally before the work on
     // the current one
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(kWg) void k_encode_long(const uint32_t *__restrict_
     v4f a[Q], b[Q];
     if (u < n_units) fetch(u, a);  // the first loads are in flight while the table is copied
     sr = load_bucket_table(tab, lds + kTeamSlots);
-    if (!REMAP) sr.remap = nullptr;
+    sr.marks = REMAP;  // known at compile time: no test for marked code bytes in the loop
     __syncthreads();
     // steady state as in k_encode_full: the next block's loads are issued unconditionally before the work on
     // the current one

@@ -45,7 +45,7 @@ __device__ __forceinline__ uint32_t encode_quad_own_scale(const Search &sr, v4f 
     k0 = k0 < k2 ? k0 : k2;
     if (!reciprocal_ok(d)) k0 = 0;
     if (__builtin_amdgcn_ballot_w64(k0 <= 2 * kNearWindow) == 0) return pack_codes(sr, s0, s1, s2, s3, v);
-    return pack_codes(sr, search_sum(sr, v.x / d), search_sum(sr, v.y / d), search_sum(sr, v.z / d), search_sum(sr, v.w / d), v);
+    return pack_codes(sr, search_sum_exact(sr, v.x / d), search_sum_exact(sr, v.y / d), search_sum_exact(sr, v.z / d), search_sum_exact(sr, v.w / d), v);
 }
 
 // Index of the block that holds this lane's quad j of unit u.

@@ -101,7 +101,7 @@ int build_tables(int kind, Tables *t)
     // patterns); of several fields with one value the smallest is the code.
     float mag[128];
     uint32_t n_mag = 0;
-    t->has_remap = false;
+    t->has_marks = false;
     for (;;) {
         int best = -1;
         for (int j = 0; j < 128; ++j) {
@@ -111,7 +111,6 @@ int build_tables(int kind, Tables *t)
         if (best < 0) break;
         mag[n_mag] = t->cb[best];
         t->canon[n_mag] = (uint8_t)best;
-        if ((uint32_t)best != n_mag) t->has_remap = true;
         ++n_mag;
     }
     for (uint32_t r = n_mag; r < 128; ++r) t->canon[r] = t->canon[n_mag - 1];
@@ -133,12 +132,16 @@ int build_tables(int kind, Tables *t)
     // and a threshold close to a bucket edge has a threshold-free neighbour bucket.
     for (int j = 1; j < n_thr; ++j)
         if (f2u(t->thr[j]) - f2u(t->thr[j - 1]) <= 0x10000u + 2 * kNearWindow) return 5;
-    uint32_t lo_key = (f2u(t->thr[0]) >> 16);
+    // the table is built from the thresholds moved down by the proximity window (see dq8_tables.hpp)
+    uint32_t moved[127];
+    for (int j = 0; j < n_thr; ++j) moved[j] = f2u(t->thr[j]) - kNearWindow;
+    uint32_t lo_key = (moved[0] >> 16);
     if (lo_key == 0) return 5;
     lo_key -= 1;  // one bucket that lies entirely below the first threshold
-    const uint32_t hi_key = (f2u(t->thr[n_thr - 1]) >> 16) + 1;  // one bucket entirely above the last threshold
+    // one bucket entirely above the last threshold and its window
+    const uint32_t hi_key = ((f2u(t->thr[n_thr - 1]) + kNearWindow) >> 16) + 1;
     uint32_t nb = hi_key - lo_key + 1;
-    if (nb > (uint32_t)(kRemapOff - kBucketOff)) return 5;
+    if (nb > (uint32_t)kBucketCapacity) return 5;
     t->lo_key = lo_key;
     t->n_bucket = nb;
     int j = 0;  // next threshold not yet passed
@@ -146,14 +149,25 @@ int build_tables(int kind, Tables *t)
         uint32_t first = key << 16, last = first | 0xFFFFu;
         uint32_t base = (uint32_t)j, tlow = 0x10000u;
         int inside = 0;
-        while (j < n_thr && f2u(t->thr[j]) <= last) {
-            if (f2u(t->thr[j]) < first) return 5;  // cannot happen: thresholds ascend
-            tlow = f2u(t->thr[j]) & 0xFFFFu;
+        while (j < n_thr && moved[j] <= last) {
+            if (moved[j] < first) return 5;  // cannot happen: thresholds ascend
+            tlow = moved[j] & 0xFFFFu;
             ++inside;
             ++j;
         }
         if (inside > 1) return 5;  // two thresholds in one bucket: scheme not applicable
-        t->bucket[key - lo_key] = (base << 16) + (0x10000u - tlow);
+        // the code field of rank `base`; the carry of a bucket with a threshold must lead to the code of the next rank
+        uint32_t field = t->canon[base];
+        if (inside == 1) {
+            const uint32_t next = t->canon[base + 1];
+            if (next == field + 3 && (field & 15u) == 15u) {
+                field |= 0x80u;  // the mark: see fix_marked_codes
+                t->has_marks = true;
+            } else if (next != field + 1) {
+                return 5;  // a step between codes that neither the carry nor the mark can make
+            }
+        }
+        t->bucket[key - lo_key] = (field << 16) + (0x10000u - tlow);
     }
     if (j != n_thr) return 5;
     return 0;
@@ -165,9 +179,8 @@ void pack_tables(const Tables &t, uint32_t *words)
     for (int c = 0; c < 256; ++c) words[kCbOff + c] = f2u(t.cb[c]);
     words[kLoKeyOff] = t.lo_key;
     words[kNBucketOff] = t.n_bucket;
-    words[kHasRemapOff] = t.has_remap ? 1u : 0u;
+    words[kHasMarksOff] = t.has_marks ? 1u : 0u;
     for (uint32_t i = 0; i < t.n_bucket; ++i) words[kBucketOff + i] = t.bucket[i];
-    for (int r = 0; r < kRemapWords; ++r) words[kRemapOff + r] = t.canon[r];
 }
 
 }  // namespace dq8

@@ -30,7 +30,7 @@ static void check_tables()
         CHECK(rc == 0, "kind %d status %d", kind, rc);
         std::vector<uint32_t> words(dq8::kTableWords);  // exactly sized: an overrun is an address error
         dq8::pack_tables(*t, words.data());
-        CHECK(words[dq8::kNBucketOff] == t->n_bucket && t->n_bucket <= (uint32_t)(dq8::kRemapOff - dq8::kBucketOff),
+        CHECK(words[dq8::kNBucketOff] == t->n_bucket && t->n_bucket <= (uint32_t)dq8::kBucketCapacity,
               "kind %d bucket count %u", kind, t->n_bucket);
         CHECK(t->n_mag >= 2 && t->n_mag <= 128, "kind %d magnitudes %u", kind, t->n_mag);
         for (uint32_t r = 1; r < t->n_mag; ++r) CHECK(t->cb[t->canon[r]] > t->cb[t->canon[r - 1]], "kind %d rank %u", kind, r);
