@@ -92,18 +92,12 @@ def algorithmic_bytes(n, nb, K=K_WORKERS):
     }
 
 
-def device_info():
-    """Name, compute units and clocks of the GPU as the runtime reports them."""
+def device_info(internal):
+    """Name, memory, compute units and peak clocks of the GPU as the runtime reports them."""
     import torch
     p = torch.cuda.get_device_properties(0)
-    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
-    for key in ("clock_rate", "memory_clock_rate"):
-        if hasattr(p, key):
-            info[key + "_MHz"] = round(getattr(p, key) / 1000.0, 1)
-    try:  # current clocks as the management library sees them, where it is reachable
-        info["sclk_MHz"] = torch.cuda.clock_rate()
-    except Exception:
-        pass
+    info = {"name": p.name, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
+    info.update(internal.device_info())
     return info
 
 
@@ -322,7 +316,7 @@ def run_default(args, torch, dq8, internal, workloads):
         "kernel_timing": "median of %d groups of %d consecutive launches between HIP events" % (GROUPS, launches),
         "settle": {"steps": 10 * settle_groups, "settled": settled_ms is not None,
                    "last_ms_per_step": None if prev is None else round(settled_ms if settled_ms is not None else prev, 4)},
-        "device": device_info(),
+        "device": device_info(internal),
         "copy_kernel_GBps": round(copy_gbps, 1),
     }
     if not args.no_cpu_baseline:

@@ -13,6 +13,8 @@ def _lib():
         L.dq8_internal_copy.restype = ci
         L.dq8_internal_tune.argtypes = [ctypes.c_char_p, ci]
         L.dq8_internal_tune.restype = ci
+        L.dq8_internal_device_info.argtypes = [ctypes.POINTER(ci)]
+        L.dq8_internal_device_info.restype = ci
         L._dq8_internal_bound = True
     return L
 
@@ -33,3 +35,11 @@ def tune(**kw):
     """Changes launch-shape parameters (only in a library built with -DDQ8_TUNABLE; results never depend on them)."""
     for k, v in kw.items():
         dq8._check(_lib().dq8_internal_tune(k.encode(), int(v)), "dq8_internal_tune(%s)" % k)
+
+
+def device_info():
+    """Compute units, peak clocks (MHz), memory bus width (bits) and L2 size (bytes) of the current device."""
+    out = (ctypes.c_int * 5)()
+    dq8._check(_lib().dq8_internal_device_info(out), "dq8_internal_device_info")
+    return {"compute_units": out[0], "peak_engine_clock_MHz": out[1] / 1000.0, "peak_memory_clock_MHz": out[2] / 1000.0,
+            "memory_bus_bits": out[3], "l2_bytes": out[4]}

@@ -552,7 +552,7 @@ int launch_error_stats(const DeviceState &st, int kind, const float *x, size_t n
                        double *stats, double *means, hipStream_t stream)
 {
     constexpr int Q = 4;
-    constexpr int kWavesPerCu = 16;  // two workgroups of eight
+    constexpr int kWavesPerCu = 2 * kStatsWaves;  // two workgroups
     Plan p = make_plan(n, block, st.cus, kWavesPerCu, 1, kStatsWaves, (size_t)Q * 4 * kWave);
     const size_t n_waves = (size_t)p.grid * kStatsWaves;
     // Wavefronts own whole blocks when there is at least one block for each of them and a block is at most 64 units
@@ -1492,6 +1492,18 @@ int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream)
 #undef DQ8_COPY_Q
 #undef DQ8_COPY
     return after_launch("k_copy", stream);
+}
+
+int dq8_internal_device_info(int *out5)
+{
+    if (!out5) return fail(DQ8_ERR_NULL, "dq8_internal_device_info: out5 is NULL");
+    int dev = -1;
+    DQ8_HIP(hipGetDevice(&dev));
+    const hipDeviceAttribute_t what[5] = {hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate,
+                                          hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth,
+                                          hipDeviceAttributeL2CacheSize};
+    for (int i = 0; i < 5; ++i) DQ8_HIP(hipDeviceGetAttribute(&out5[i], what[i], dev));
+    return DQ8_OK;
 }
 
 static int host_search(int kind, Search *sr)

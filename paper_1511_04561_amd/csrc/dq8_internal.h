@@ -55,6 +55,10 @@ int dq8_internal_tune(const char *key, int value);
 // counter calibration: exactly 4 bytes read and 4 written per element).
 int dq8_internal_copy(float *dst, const float *src, size_t n, void *hip_stream);
 
+// The current device as the runtime describes it: out5 = {compute units, peak engine clock in kHz, peak memory
+// clock in kHz, memory bus width in bits, L2 cache bytes} (for the benchmark's report).
+int dq8_internal_device_info(int *out5);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,7 +46,9 @@ __device__ __forceinline__ void load_magnitude_lut(const uint32_t *tab, float *l
     }
 }
 
-constexpr int kStatsWaves = 8;                  // wavefronts per workgroup: two workgroups (two tables) per compute unit
+// wavefronts per workgroup: two workgroups (two value tables) share a compute unit, six wavefronts per SIMD
+// (88.4 us with 8, 85.4 us with 12, 106 us with 16, where the registers no longer suffice)
+constexpr int kStatsWaves = 12;
 constexpr int kStatsWg = kStatsWaves * kWave;
 
 // Running statistics of one wavefront for the block it is in.
@@ -64,7 +66,7 @@ struct ErrorSums {
 // like their bit patterns); the two sums depend on the order only in their last bits.
 // Units are Q * 256 elements; the loads of a wavefront's next unit are issued before the current one is worked on.
 template <int Q, bool OWN>
-__global__ __launch_bounds__(kStatsWg) void k_error_stats(const uint32_t *__restrict__ tab, const float *__restrict__ x,
+__global__ __launch_bounds__(kStatsWg, kStatsWaves / 2) void k_error_stats(const uint32_t *__restrict__ tab, const float *__restrict__ x,
                                                          size_t n, size_t B, size_t nb, size_t upb, size_t n_units,
                                                          size_t per_wave, size_t n_waves,
                                                          const float *__restrict__ scales, double *__restrict__ stats)
