@@ -291,15 +291,26 @@ __device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q]
 // the compression does (see encode_quads): the sums are left as they are, *pre = rk, and the maximum is scaled
 // once (rounding is monotonic, so the scaled maximum is the maximum of the scaled values, also below the normal
 // range).  Otherwise every sum is divided and *pre = 1.
-template <int Q>
+// LEAVE_SCALING = false: the sums are multiplied by rk here and *pre = 1 (a kernel that is short of registers: a *pre
+// that is not a constant costs the compression about thirty of them).  One test per unit either way, not one per element.
+template <int Q, bool LEAVE_SCALING = true>
 __device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2, float rk, float fk, float *pre)
 {
     float fm = 0.0f;
-    if (pow2) {
+    if (pow2 && LEAVE_SCALING) {
 #pragma unroll
         for (int j = 0; j < Q; ++j) fm = max4_abs(acc[j], fm);
         *pre = rk;
         return fm * rk;
+    }
+    *pre = 1.0f;
+    if (pow2) {
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            acc[j] = v4f{acc[j].x * rk, acc[j].y * rk, acc[j].z * rk, acc[j].w * rk};
+            fm = max4_abs(acc[j], fm);
+        }
+        return fm;
     }
 #pragma unroll
     for (int j = 0; j < Q; ++j) {
@@ -309,7 +320,6 @@ __device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2,
         acc[j].w = acc[j].w / fk;
         fm = max4_abs(acc[j], fm);
     }
-    *pre = 1.0f;
     return fm;
 }
 

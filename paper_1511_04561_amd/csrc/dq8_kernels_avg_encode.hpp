@@ -2,6 +2,7 @@
 // again (the second round of the gradient exchange).
 #pragma once
 #include <type_traits>
+#include <utility>
 
 #include "dq8_device.hpp"
 
@@ -104,12 +105,14 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
                     add_w(wb, k + 1);
                 }
             }
-            if (pow2) {  // one test for the whole unit, not one per element
+            // (one test per element: with one test around all the multiplications and one around all the divisions
+            // the compiler interleaves them and spills a hundred registers in the 16-quad form of this kernel)
 #pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = v4f{acc[j].x * rk, acc[j].y * rk, acc[j].z * rk, acc[j].w * rk};
-            } else {
-#pragma unroll
-                for (int j = 0; j < Q; ++j) acc[j] = v4f{acc[j].x / fk, acc[j].y / fk, acc[j].z / fk, acc[j].w / fk};
+            for (int j = 0; j < Q; ++j) {
+                acc[j].x = mean_of(acc[j].x);
+                acc[j].y = mean_of(acc[j].y);
+                acc[j].z = mean_of(acc[j].z);
+                acc[j].w = mean_of(acc[j].w);
             }
             if (mean_out) {
                 v4f *o4 = reinterpret_cast<v4f *>(mean_out + un.start);
@@ -211,6 +214,13 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
 // and meets the same barriers.  A block of whole quads at aligned addresses stays in registers (a lane whose quad
 // lies past the end of the block loads the block's last quad instead and stores nothing); any other block goes
 // quad by quad or element by element and forms its means once for the maximum and once for the compression.
+// Calls f(first quad, G) for the groups 0, 1, ... of G quads each, in order.
+template <int G, typename F, int... I>
+__device__ __forceinline__ void encode_groups(F &f, std::integer_sequence<int, I...>)
+{
+    ((f(std::integral_constant<int, I * G>{}, std::integral_constant<int, G>{}), __builtin_amdgcn_sched_barrier(0)), ...);
+}
+
 constexpr int kLongWaves = 8;                  // wavefronts per block in k_avg_long
 constexpr int kLongTeam = kLongWaves * kWave;  // its threads
 constexpr int kLongSlots = 2 * kLongWaves;     // LDS words for the maxima (two phases)
@@ -332,8 +342,8 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
                 for (int i = 0; i < NB - 1; ++i)
                     if (i < K) load_w(w[i], i, next);
             }
-            float pre;  // what the sums still have to be multiplied by to be the means
-            const float fm = means_for_compression<Q>(acc, pow2, rk, fk, &pre);
+            float pre;  // what the sums still have to be multiplied by to be the means: 1 here (registers)
+            const float fm = means_for_compression<Q, false>(acc, pow2, rk, fk, &pre);
             s = u2f(team_max(wave_max_u32(f2u(fm))));
             const float d = s == 0.0f ? 1.0f : s;
             const float r = 1.0f / d;
@@ -351,10 +361,12 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
                 for (int j = 0; j < G; ++j)
                     if ((g + j) * kLongTeam + tl < nq) stg<1>(c4 + (g + j) * kLongTeam + tl, cw[j]);
             };
-            if constexpr (Q >= 4) encode_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
-            if constexpr (Q >= 8) encode_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
-            if constexpr (Q % 4 != 0)
-                encode_group(std::integral_constant<int, Q / 4 * 4>{}, std::integral_constant<int, Q % 4>{});
+            // groups of four quads, of two where a lane holds seven or eight (the sums of a group are all live at
+            // once; with larger groups two workgroups no longer fit a compute unit's registers), one group after the other
+            constexpr int G = Q >= 7 ? 2 : 4;
+            encode_groups<G>(encode_group, std::make_integer_sequence<int, Q / G>{});
+            if constexpr (Q % G != 0)
+                encode_group(std::integral_constant<int, Q / G * G>{}, std::integral_constant<int, Q % G>{});
         } else {
             // primed is false here: a block is only requested ahead when it is a fast one
             const bool aligned = [&] {
