@@ -276,6 +276,35 @@ def test_error_stats_shapes(dq8, kind):
     assert np.all(got == 0)
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_error_stats_when_wavefronts_own_whole_blocks(dq8, kind):
+    """With at least one block per resident wavefront (6144 on this GPU) and blocks of at most 64 units, a wavefront
+    owns whole blocks: plain stores into rows that were never zeroed, a fixed order of summation.  Blocks of one
+    element (every column exact), blocks shorter than a unit, of one unit, of three units with a short last one, of
+    four units; a ragged last block; a misaligned input; and the same bits from two launches."""
+    rng = np.random.Generator(np.random.PCG64(5300 + kind))
+    n = 7001
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-10, 3, n))).astype(np.float32)
+    x[::13] = 0.0
+    want, _ = oracle.error_stats(kind, x, 1)
+    stats, _ = dq8.error_stats(kind, dev(x), 1)
+    same_bits(stats.reshape(-1), want.reshape(-1), "per-element error statistics, owned blocks")
+    for i, (nb, block, tail) in enumerate([(6200, 100, 37), (6150, 1024, 500), (6145, 3000, 8), (6144, 4096, 808)]):
+        n = nb * block + tail
+        x = (rng.standard_normal(n) * np.exp(rng.uniform(-6, 0, n))).astype(np.float32)
+        x[::17] = 0.0
+        check_error_stats(dq8, kind, x, block, tag="owned%d" % i)
+        if i == 3 and kind == 0:
+            a, ma = dq8.error_stats(kind, dev(x), block)
+            b, mb = dq8.error_stats(kind, dev(x), block)
+            assert torch.equal(a, b) and torch.equal(ma, mb), "owned blocks are summed in a fixed order"
+            want, _ = oracle.error_stats(kind, x, block)
+            got, _ = dq8.error_stats(kind, dev(x, 1), block)  # input one element off a 16-byte boundary
+            got = got.cpu().numpy()
+            assert got[:, 2:].tobytes() == want[:, 2:].tobytes()
+            assert np.allclose(got[:, :2], want[:, :2], rtol=1e-12, atol=0)
+
+
 def test_error_stats_of_the_table_2_samples(dq8):
     """Sec. 3.4: samples from U(0,1) and normal distributions; static-exponent types with a decade as scale."""
     rng = np.random.Generator(np.random.PCG64(5200))
