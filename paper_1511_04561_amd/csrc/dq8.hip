@@ -812,18 +812,35 @@ int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     if (teams > nb) teams = nb;
     const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
     const size_t lds = ((size_t)st.search_words[kind] + kLongSlots) * sizeof(uint32_t);
-#define DQ8_AVG_LONG(QL, NB)                                                                                             \
-    hipLaunchKernelGGL((k_avg_long<QL, NB, 2>), dim3((unsigned)teams), dim3(kLongTeam), lds, stream, tab, wp, K, local, n, \
-                       B, nb, (uint32_t)teams, scales_out, codes_out)
-    // quads per lane that hold the block in a workgroup of 512 threads, four sets of code words in flight
-    switch ((int)((B + 4 * kLongTeam - 1) / (4 * kLongTeam))) {
-    case 3: DQ8_AVG_LONG(3, 8); break;
-    case 4: DQ8_AVG_LONG(4, 8); break;
-    case 5: DQ8_AVG_LONG(5, 6); break;
-    case 6: DQ8_AVG_LONG(6, 6); break;
-    case 7: DQ8_AVG_LONG(7, 4); break;
-    default: DQ8_AVG_LONG(8, 4); break;
+    // The register path needs 32-bit accesses to the codes and 128-bit ones to local at every block start.
+    bool aligned = K >= 1 && (nb == 1 || (B & 3) == 0) && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
+#define DQ8_AVG_LONG(QL, NB, KT)                                                                                              \
+    hipLaunchKernelGGL((k_avg_long<QL, NB, 2, KT>), dim3((unsigned)teams), dim3(kLongTeam), lds, stream, tab, wp, K, local, n, \
+                       B, nb, (uint32_t)teams, (uint32_t)aligned, scales_out, codes_out)
+    // Quads per lane that hold the block in a workgroup of 512 threads.  The worker counts of 2, 4 and 8 devices
+    // (with or without a local term) have kernels of their own, with one set of code words per worker where the
+    // registers allow (up to four quads per lane) and four sets otherwise; any other number of workers takes the
+    // kernel that reads the count at run time, with four sets (it pads the count to a multiple of four).
+    const int ql = (int)((B + 4 * kLongTeam - 1) / (4 * kLongTeam));
+#define DQ8_AVG_LONG_Q(NB_SHORT, NB_LONG, KT)            \
+    switch (ql) {                                        \
+    case 3: DQ8_AVG_LONG(3, NB_SHORT, KT); break;        \
+    case 4: DQ8_AVG_LONG(4, NB_SHORT, KT); break;        \
+    case 5: DQ8_AVG_LONG(5, NB_LONG, KT); break;         \
+    case 6: DQ8_AVG_LONG(6, NB_LONG, KT); break;         \
+    case 7: DQ8_AVG_LONG(7, NB_LONG, KT); break;         \
+    default: DQ8_AVG_LONG(8, NB_LONG, KT); break;        \
     }
+    switch (K) {
+    case 2: DQ8_AVG_LONG_Q(2, 2, 2) break;
+    case 3: DQ8_AVG_LONG_Q(3, 3, 3) break;
+    case 4: DQ8_AVG_LONG_Q(4, 4, 4) break;
+    case 7: DQ8_AVG_LONG_Q(7, 4, 7) break;
+    case 8: DQ8_AVG_LONG_Q(8, 4, 8) break;
+    default: DQ8_AVG_LONG_Q(4, 4, 0) break;
+    }
+#undef DQ8_AVG_LONG_Q
 #undef DQ8_AVG_LONG
     return after_launch("k_avg_long", stream);
 }

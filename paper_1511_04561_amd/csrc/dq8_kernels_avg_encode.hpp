@@ -207,13 +207,28 @@ __global__ __launch_bounds__(kWave * WPW, WPW / 2) void k_avg_block(const uint32
 
 // Average-then-compress for scale blocks of 4097 .. 16384 elements: the scheme of k_avg_block with a workgroup of
 // eight wavefronts per block (two such workgroups share a compute unit: each holds the 64 KiB decode table).
-// Every lane holds QL quads of running sums (quad it * 512 + t of the block for thread t), the workers are added
-// one after the other while the next workers' code words are in flight, and the block maximum of the means is a
-// wave reduction plus one LDS exchange between the eight wavefronts.  Blocks are handed
-// out by position (block b to workgroup b mod n_teams), so every wavefront of a workgroup walks the same blocks
-// and meets the same barriers.  A block of whole quads at aligned addresses stays in registers (a lane whose quad
-// lies past the end of the block loads the block's last quad instead and stores nothing); any other block goes
-// quad by quad or element by element and forms its means once for the maximum and once for the compression.
+// Every lane holds QL quads of running sums (quad it * 512 + t of the block for thread t) and the block maximum of
+// the means is a wave reduction plus one LDS exchange between the eight wavefronts.  Blocks are handed out by
+// position (block b to workgroup b mod n_teams), so every wavefront of a workgroup walks the same blocks and meets
+// the same barriers.
+//
+// The workgroup's work is one sequence of (block, worker) pairs: all workers of its first block, then all workers
+// of its second block, and so on.  NB register sets of code words rotate over that sequence: the pair that is
+// being added uses one set and the NB - 1 pairs after it are in flight, across the end of a block as well, so
+// the loads for the next block travel while the maximum is exchanged and the means are compressed.  Every step
+// issues exactly one set of loads and consumes exactly one, with no branch around either: the compiler then
+// knows how many loads are outstanding at every point and waits for the oldest set only.  For that
+//  - the number of workers is padded to a multiple of NB: a place without a worker repeats worker K - 1 (a hit in
+//    the cache) and is added with scale 0 (the product is a zero, and adding a zero to a sum that started at +0
+//    leaves it unchanged);
+//  - the worker's scale for the block is loaded with its code words, one more load of the set (requested at the
+//    start of a block it would be the wavefront's youngest load, and waiting for it would drain everything);
+//  - a place past the workgroup's last block repeats its last block (valid memory, result unused);
+//  - a lane whose quad lies past the end of a block loads the block's last quad and stores nothing.
+// `aligned` (from the host): every buffer allows 32-bit accesses to the codes and 128-bit ones to local at
+// every block start, and there is at least one worker.  Then every block of whole quads takes this path (all
+// but perhaps the array's last block); any other block goes quad by quad or element by element and forms its
+// means once for the maximum and once for the compression.
 // Calls f(first quad, G) for the groups 0, 1, ... of G quads each, in order.
 template <int G, typename F, int... I>
 __device__ __forceinline__ void encode_groups(F &f, std::integer_sequence<int, I...>)
@@ -225,16 +240,17 @@ constexpr int kLongWaves = 8;                  // wavefronts per block in k_avg_
 constexpr int kLongTeam = kLongWaves * kWave;  // its threads
 constexpr int kLongSlots = 2 * kLongWaves;     // LDS words for the maxima (two phases)
 
-template <int QL, int NB, int NT>
-__global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+template <int QL, int NB, int NT, int KT>
+__global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restrict__ tab, WorkerPtrs p, int K_rt,
                                                  const float *__restrict__ local, size_t n, size_t B, size_t nb,
-                                                 uint32_t n_teams, float *__restrict__ scales_out,
+                                                 uint32_t n_teams, uint32_t aligned, float *__restrict__ scales_out,
                                                  uint8_t *__restrict__ codes_out)
 {
     static_assert(NB >= 2, "at least two sets of code words");
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t dyn_lds[];  // kLongSlots words for the maxima, then the bucket table
     constexpr int Q = QL;
+    const int K = KT > 0 ? KT : K_rt;  // KT > 0: the number of workers is known at compile time
     const int terms = K + (local ? 1 : 0);
     const float fk = (float)terms;
     const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
@@ -259,43 +275,37 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
         return (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
     };
     auto length_of = [&](size_t blk) { return (uint32_t)(n - blk * B < B ? n - blk * B : B); };
-    // A block of whole quads whose addresses allow 128-bit accesses to local and 32-bit ones to the codes.
-    auto is_fast = [&](size_t blk) {
-        const size_t start = blk * B;
-        const uint32_t len = length_of(blk);
-        bool ok = len >= 4 && (len & 3) == 0 && ((uintptr_t)(codes_out + start) & 3) == 0;
-        for (int k = 0; k < K; ++k) ok = ok && (((uintptr_t)(p.codes[k] + start) & 3) == 0);
-        if (local) ok = ok && (((uintptr_t)(local + start) & 15) == 0);
-        return ok;
-    };
-    // NB sets of code words: worker k of a block uses set k mod NB, and the sets of the NB - 1 workers after the
-    // one being added are in flight, also across the end of a block (the first NB - 1 workers of the workgroup's
-    // next block are requested before the maximum and the compression of the current one).
-    uint32_t w[NB][Q];
-    // Worker k's code words of block blk (a fast one); a quad past its end is the block's last quad.
-    auto load_w = [&](uint32_t(&ww)[Q], int k, size_t blk) {
-        const uint32_t nq = length_of(blk) >> 2, last = nq - 1;
-        const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + blk * B);
+    // Blocks 0 .. n_stream - 1 take the register path: all of them when the array's last block is whole quads.
+    const uint32_t last_len = length_of(nb - 1);
+    const size_t n_stream = !aligned ? 0 : ((last_len >= 4 && (last_len & 3) == 0) ? nb : nb - 1);
+    if (blockIdx.x < n_stream) {
+        const int Kp = (K + NB - 1) / NB * NB;  // places per block
+        uint32_t w[NB][Q];                      // the sets of code words
+        float scv[NB];                          // and the scale that belongs to each
+        // Requests place `place` of block b: scale and code words of worker `place`, or of the last worker again.
+        auto request = [&](uint32_t(&ww)[Q], float &sc, size_t b, int place) {
+            const int worker = place < K ? place : K - 1;
+            const uint32_t last = (length_of(b) >> 2) - 1;
+            sc = ldg<0>(p.scales[worker] + b);
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[worker] + b * B);
 #pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            const uint32_t i = j * kLongTeam + tl;
-            ww[j] = ldg_at<NT>(c4, i < last ? i : last);
-        }
-    };
-    bool primed = false;  // the sets hold the first NB - 1 workers of the coming block
-    for (size_t blk = blockIdx.x; blk < nb; blk += n_teams) {
-        const size_t start = blk * B;
-        const uint32_t len = length_of(blk);
-        float s;
-        if (is_fast(blk)) {
-            const uint32_t nq = len >> 2, last = nq - 1;
-            if (!primed) {
-#pragma unroll
-                for (int i = 0; i < NB - 1; ++i)
-                    if (i < K) load_w(w[i], i, blk);
+            for (int j = 0; j < Q; ++j) {
+                const uint32_t i = j * kLongTeam + tl;
+                ww[j] = ldg_at<NT>(c4, i < last ? i : last);
             }
+        };
+        // (one set after the other, as in the loop below: the waits there are counted for the worse of the two orders)
+#pragma unroll
+        for (int i = 0; i < NB - 1; ++i) {
+            request(w[i], scv[i], blockIdx.x, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (size_t blk = blockIdx.x; blk < n_stream; blk += n_teams) {
+            const size_t start = blk * B;
+            const size_t next = blk + n_teams < n_stream ? blk + n_teams : blk;  // after the last block: this one again
+            const uint32_t nq = length_of(blk) >> 2, last = nq - 1;
             v4f acc[Q];
-            if (local) {
+            if (local) {  // not requested ahead: the sums are still in use when the code words of this block set out
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + start);
 #pragma unroll
                 for (int j = 0; j < Q; ++j) {
@@ -313,8 +323,7 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
 #pragma unroll
                 for (int j = 0; j < Q; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
             }
-            auto add_w = [&](const uint32_t(&ww)[Q], int k) {
-                const float sk = p.scales[k][blk];
+            auto add_w = [&](const uint32_t(&ww)[Q], float sk) {
 #pragma unroll
                 for (int j = 0; j < Q; ++j) {
                     acc[j].x = acc[j].x + lut_at<0>(lut, ww[j], lane4) * sk;
@@ -326,25 +335,27 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
 #pragma unroll
                 for (int j = 0; j < Q; ++j) asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
             };
-            for (int k = 0; k < K; k += NB) {
+            // One round: NB steps, each requesting the place NB - 1 ahead (in the next block once this block's places
+            // are all requested) and adding the oldest set.
+            auto round = [&](int k) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
-                    if (k + i < K) {
-                        if (k + i + NB - 1 < K) load_w(w[(i + NB - 1) % NB], k + i + NB - 1, blk);
-                        add_w(w[i], k + i);
-                    }
+                    const int ahead = k + i + NB - 1;
+                    const bool wraps = ahead >= Kp;
+                    request(w[(i + NB - 1) % NB], scv[(i + NB - 1) % NB], wraps ? next : blk, wraps ? ahead - Kp : ahead);
+                    add_w(w[i], k + i < K ? scv[i] : 0.0f);
                 }
-            }
-            const size_t next = blk + n_teams;
-            primed = next < nb && is_fast(next);
-            if (primed) {
+            };
+            if constexpr (KT > 0) {
 #pragma unroll
-                for (int i = 0; i < NB - 1; ++i)
-                    if (i < K) load_w(w[i], i, next);
+                for (int k = 0; k < (KT + NB - 1) / NB * NB; k += NB) round(k);
+            } else {
+                for (int k = 0; k < Kp; k += NB) round(k);
             }
             float pre;  // what the sums still have to be multiplied by to be the means: 1 here (registers)
             const float fm = means_for_compression<Q, false>(acc, pow2, rk, fk, &pre);
-            s = u2f(team_max(wave_max_u32(f2u(fm))));
+            const float s = u2f(team_max(wave_max_u32(f2u(fm))));
+            if (tl == 0) scales_out[blk] = s;
             const float d = s == 0.0f ? 1.0f : s;
             const float r = 1.0f / d;
             const bool recip = reciprocal_ok(d);
@@ -367,62 +378,67 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
             encode_groups<G>(encode_group, std::make_integer_sequence<int, Q / G>{});
             if constexpr (Q % G != 0)
                 encode_group(std::integral_constant<int, Q / G * G>{}, std::integral_constant<int, Q % G>{});
-        } else {
-            // primed is false here: a block is only requested ahead when it is a fast one
-            const bool aligned = [&] {
-                bool ok = ((uintptr_t)(codes_out + start) & 3) == 0;
-                for (int k = 0; k < K; ++k) ok = ok && (((uintptr_t)(p.codes[k] + start) & 3) == 0);
-                if (local) ok = ok && (((uintptr_t)(local + start) & 15) == 0);
-                return ok;
-            }();
-            const uint32_t nq = aligned ? len >> 2 : 0;
-            const uint32_t done = nq << 2;
-            auto mean_at = [&](uint32_t i) {
-                float a = 0.0f;
-                if (local) a = a + local[start + i];
-                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
-                return mean_of(a);
-            };
-            auto mean_quad = [&](uint32_t q) {
-                v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (local) {
-                    const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + start) + q);
-                    a.x = a.x + l.x;
-                    a.y = a.y + l.y;
-                    a.z = a.z + l.z;
-                    a.w = a.w + l.w;
-                }
-                for (int k = 0; k < K; ++k) {
-                    const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + start) + q);
-                    const float sk = p.scales[k][blk];
-                    a.x = a.x + lut_at<0>(lut, ww, lane4) * sk;
-                    a.y = a.y + lut_at<1>(lut, ww, lane4) * sk;
-                    a.z = a.z + lut_at<2>(lut, ww, lane4) * sk;
-                    a.w = a.w + lut_at<3>(lut, ww, lane4) * sk;
-                }
-                a.x = mean_of(a.x);
-                a.y = mean_of(a.y);
-                a.z = mean_of(a.z);
-                a.w = mean_of(a.w);
-                return a;
-            };
-            float fm = 0.0f;
-            for (uint32_t q = tl; q < nq; q += kLongTeam) fm = max4_abs(mean_quad(q), fm);
-            uint32_t m = f2u(fm);
-            for (uint32_t i = done + tl; i < len; i += kLongTeam) {
-                const uint32_t a = abs_bits(mean_at(i));
-                m = m > a ? m : a;
-            }
-            s = u2f(team_max(wave_max_u32(m)));
-            const float d = s == 0.0f ? 1.0f : s;
-            const float r = 1.0f / d;
-            const bool recip = reciprocal_ok(d);
-            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + start);
-            for (uint32_t q = tl; q < nq; q += kLongTeam) stg<1>(c4 + q, encode_quad<true>(sr, mean_quad(q), d, r, recip));
-            for (uint32_t i = done + tl; i < len; i += kLongTeam)
-                codes_out[start + i] = (uint8_t)encode_one<true>(sr, mean_at(i), d, r, recip);
         }
+    }
+    // The blocks that are not on the register path: all of them without `aligned`, else at most the array's last one.
+    const size_t slow_first = aligned ? nb - 1 : 0;
+    for (size_t blk = slow_first + (blockIdx.x + n_teams - slow_first % n_teams) % n_teams; blk < nb; blk += n_teams) {
+        if (blk < n_stream) continue;
+        const size_t start = blk * B;
+        const uint32_t len = length_of(blk);
+        const bool quads_ok = [&] {
+            bool ok = ((uintptr_t)(codes_out + start) & 3) == 0;
+            for (int k = 0; k < K; ++k) ok = ok && (((uintptr_t)(p.codes[k] + start) & 3) == 0);
+            if (local) ok = ok && (((uintptr_t)(local + start) & 15) == 0);
+            return ok;
+        }();
+        const uint32_t nq = quads_ok ? len >> 2 : 0;
+        const uint32_t done = nq << 2;
+        auto mean_at = [&](uint32_t i) {
+            float a = 0.0f;
+            if (local) a = a + local[start + i];
+            for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][start + i], lane4) * p.scales[k][blk];
+            return mean_of(a);
+        };
+        auto mean_quad = [&](uint32_t q) {
+            v4f a = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (local) {
+                const v4f l = ldg<NT>(reinterpret_cast<const v4f *>(local + start) + q);
+                a.x = a.x + l.x;
+                a.y = a.y + l.y;
+                a.z = a.z + l.z;
+                a.w = a.w + l.w;
+            }
+            for (int k = 0; k < K; ++k) {
+                const uint32_t ww = ldg<NT>(reinterpret_cast<const uint32_t *>(p.codes[k] + start) + q);
+                const float sk = p.scales[k][blk];
+                a.x = a.x + lut_at<0>(lut, ww, lane4) * sk;
+                a.y = a.y + lut_at<1>(lut, ww, lane4) * sk;
+                a.z = a.z + lut_at<2>(lut, ww, lane4) * sk;
+                a.w = a.w + lut_at<3>(lut, ww, lane4) * sk;
+            }
+            a.x = mean_of(a.x);
+            a.y = mean_of(a.y);
+            a.z = mean_of(a.z);
+            a.w = mean_of(a.w);
+            return a;
+        };
+        float fm = 0.0f;
+        for (uint32_t q = tl; q < nq; q += kLongTeam) fm = max4_abs(mean_quad(q), fm);
+        uint32_t m = f2u(fm);
+        for (uint32_t i = done + tl; i < len; i += kLongTeam) {
+            const uint32_t a = abs_bits(mean_at(i));
+            m = m > a ? m : a;
+        }
+        const float s = u2f(team_max(wave_max_u32(m)));
         if (tl == 0) scales_out[blk] = s;
+        const float d = s == 0.0f ? 1.0f : s;
+        const float r = 1.0f / d;
+        const bool recip = reciprocal_ok(d);
+        uint32_t *c4 = reinterpret_cast<uint32_t *>(codes_out + start);
+        for (uint32_t q = tl; q < nq; q += kLongTeam) stg<1>(c4 + q, encode_quad<true>(sr, mean_quad(q), d, r, recip));
+        for (uint32_t i = done + tl; i < len; i += kLongTeam)
+            codes_out[start + i] = (uint8_t)encode_one<true>(sr, mean_at(i), d, r, recip);
     }
 }
 

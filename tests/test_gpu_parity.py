@@ -520,6 +520,34 @@ def test_decode_avg_encode_long_blocks(dq8, kind, K, with_local):
         gs.check("avg->encode long scales")
 
 
+@pytest.mark.parametrize("kind,K,with_local,n,block", [
+    (0, 8, False, 1300 * 4100 + 52, 4100),   # a short last block of whole quads
+    (3, 5, True, 700 * 8192 + 8191, 8192),   # a last block that is not whole quads
+    (1, 13, False, 600 * 5000, 5000),        # more workers than register sets, a third of the lanes' last quads unused
+    (2, 3, False, 520 * 16384 + 12, 16384),  # fewer workers than register sets
+    (0, 1, True, 1100 * 6148, 6148),
+    (0, 7, True, 520 * 12288 + 8, 12288),    # one register set short of the workers, four sets rotate
+    (1, 4, False, 900 * 9216, 9216),
+    (2, 2, True, 530 * 7000, 7000),
+    (3, 7, False, 1400 * 4104 + 400, 4104)])
+def test_decode_avg_encode_long_blocks_several_per_workgroup(dq8, kind, K, with_local, n, block):
+    """More long blocks than workgroups: a workgroup walks several blocks and requests the next block's code words
+    while it finishes the current one."""
+    print("avg->encode long, many blocks kind=%d K=%d local=%d n=%d block=%d" % (kind, K, with_local, n, block), flush=True)
+    nb = oracle.dq8_oracle.n_blocks(n, block)
+    enc = [oracle.encode(kind, workloads.tensor(5, 12, worker=w, limit=n), block) for w in range(K)]
+    cl, sl = [e[0] for e in enc], [e[1] for e in enc]
+    local = workloads.tensor(5, 12, worker=9, limit=n) if with_local else None
+    want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)
+    gc, gs = Guarded(n, np.uint8), Guarded(nb, np.float32)
+    codes, scales = dq8.decode_avg_encode(kind, [dev(c) for c in cl], [dev(s) for s in sl], block,
+                                          local=None if local is None else dev(local), scales=gs.t, codes=gc.t)
+    same_bits(scales, want_scales, "avg->encode long scales")
+    same_bits(codes, want_codes, "avg->encode long codes")
+    gc.check("avg->encode long codes")
+    gs.check("avg->encode long scales")
+
+
 def test_average_order_is_worker_zero_first(dq8):
     c_pos, c_neg = np.full(5000, 127, np.uint8), np.full(5000, 255, np.uint8)
     big, small = np.array([1e8], np.float32), np.array([1.0], np.float32)
