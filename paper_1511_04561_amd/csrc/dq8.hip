@@ -681,6 +681,65 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
     return DQ8_OK;
 }
 
+// The worker counts for which teams of one, two or three wavefronts exist (blocks of up to 3072 elements).
+inline bool short_team_k(int K) { return K == 2 || K == 3 || K == 4 || K == 7 || K == 8; }
+
+// Average-then-compress for blocks of up to 3072 elements: teams of W = 1, 2 or 3 wavefronts, a block per team
+// (W x 1024 elements hold it), twelve wavefronts per workgroup and one workgroup per compute unit.
+int launch_avg_short_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
+                          size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
+{
+    const size_t Bq = block_length(n, block);
+    const int W = (int)((Bq + 1023) / 1024);
+    const bool ragged = Bq != (size_t)W * 1024;
+    const int teams = 12 / W;
+    Plan p = make_plan(n, block, st.cus, 12, W, 12, kUnit);
+    const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
+    // Iterations in which every team's current and next unit are whole aligned blocks.
+    uint32_t steady = 0;
+    bool aligned = !ragged && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
+    if (aligned) {
+        const size_t all_valid = (n / Bq) / p.n_teams;  // iterations in which every team has a whole unit
+        if (all_valid >= 2) steady = (uint32_t)((all_valid - 1) & ~(size_t)1);
+    }
+    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
+    const size_t lds = ((size_t)st.search_words[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
+#define DQ8_SHORT(KT, RM, RG, WW)                                                                                          \
+    hipLaunchKernelGGL((k_avg_team<KT, 1, true, 12 / WW, RM, RG, false, WW>), dim3(p.grid), dim3(kWave * 12), lds, stream, tab, \
+                       wp, K, local, n, p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
+#define DQ8_SHORT_RG(KT, RM, WW)       \
+    if (ragged) {                      \
+        DQ8_SHORT(KT, RM, true, WW);   \
+    } else {                           \
+        DQ8_SHORT(KT, RM, false, WW);  \
+    }
+#define DQ8_SHORT_W(KT, RM)                      \
+    switch (W) {                                 \
+    case 1: DQ8_SHORT_RG(KT, RM, 1) break;       \
+    case 2: DQ8_SHORT_RG(KT, RM, 2) break;       \
+    default: DQ8_SHORT_RG(KT, RM, 3) break;      \
+    }
+#define DQ8_SHORT_K(KT)              \
+    if (st.has_remap[kind]) {        \
+        DQ8_SHORT_W(KT, true)        \
+    } else {                         \
+        DQ8_SHORT_W(KT, false)       \
+    }
+    switch (K) {
+    case 2: DQ8_SHORT_K(2) break;
+    case 3: DQ8_SHORT_K(3) break;
+    case 4: DQ8_SHORT_K(4) break;
+    case 7: DQ8_SHORT_K(7) break;
+    default: DQ8_SHORT_K(8) break;
+    }
+#undef DQ8_SHORT_K
+#undef DQ8_SHORT_W
+#undef DQ8_SHORT_RG
+#undef DQ8_SHORT
+    return after_launch("k_avg_team", stream);
+}
+
 // Average-then-compress for up to 8 workers: teams of four wavefronts; two teams per workgroup and two
 // workgroups per compute unit (128 registers per lane), or three teams in one workgroup per compute
 // unit (170 registers per lane).
@@ -688,6 +747,7 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
                     size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
     const size_t Bq = block_length(n, block);
+    if (Bq <= 3 * 1024 && short_team_k(K)) return launch_avg_short_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
     const bool tuned_k = K == 2 || K == 4 || K == 8;  // the worker counts with a variant for 2 teams
     // Teams per workgroup: 3; 4 when each team has few code words in flight (up to `avg_teams4_upto` workers);
@@ -854,6 +914,9 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     // blocks that need a 4096-element unit with up to 8 workers, or exactly 4096 elements with more: the team kernel
     if (codes_out && !mean_out && K >= 1 && (K <= 8 || Bq == (size_t)kUnit) && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
+    // blocks of 513 .. 2048 elements with a worker count that has kernels for shorter teams
+    if (codes_out && !mean_out && g_tune.avg_team && Bq > 512 && Bq < n && short_team_k(K))
+        return launch_avg_short_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const int ql = (int)(unit / (size_t)(4 * kWave));
     // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave
     const bool ragged = Bq < n && Bq % unit != 0;  // blocks end inside units
@@ -1327,7 +1390,8 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (Bq > (size_t)kUnit) return launch_avg_long(*st, kind, wp, K, local, n, block, out_scales, out_codes, stream);
     size_t done = 0;
-    rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
+    // (blocks of 1024 elements: a wavefront per block is faster where that kernel exists for the worker count)
+    if (!(Bq == 1024 && short_team_k(K) && g_tune.avg_team)) rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
     if (rc || done == n) return rc;
     if (done) {  // the rest starts on a block boundary
         wp = advance_workers(wp, K, done, Bq);

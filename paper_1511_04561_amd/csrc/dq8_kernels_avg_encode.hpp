@@ -442,9 +442,9 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
     }
 }
 
-// The same average-then-compress round for up to eight workers (K fixed at compile time) at full speed.  A team of four
-// wavefronts owns a unit of 4096 elements (one scale block): every lane holds four quads of
-// running sums and K x 4 code words.  The code words are one register set that is refilled
+// The same average-then-compress round for up to eight workers (K fixed at compile time) at full speed.  A team of W
+// wavefronts (four unless the blocks are shorter) owns a unit of W x 1024 elements (one scale block): every lane
+// holds four quads of running sums and K x 4 code words.  The code words are one register set that is refilled
 // in place: as soon as worker k's words of the current unit have been decoded and added, the
 // loads of worker k's words of the team's next unit are issued into the same registers, so
 // loads are in flight all through the reduction to the block maximum (wave reduction, then one
@@ -452,14 +452,17 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
 // TEAMS teams share a workgroup and its tables; the workgroup barrier that separates the
 // exchange of the maxima from their use is executed by every wavefront the same number of
 // times (`iters`), whether or not its team still has a unit.
-// RAGGED = true (chosen by the host for blocks shorter than 4096): a unit of fewer whole aligned quads
+// RAGGED = true (chosen by the host for blocks shorter than the unit): a unit of fewer whole aligned quads
 // takes the register path as well.
 // MULTI = true: more workers than KT, taken KT at a time in `passes` passes over the same registers; a
 // place of the last pass that has no worker repeats worker K - 1 with scale 0 (the product is a zero, and
 // adding a zero leaves a sum that started at +0 unchanged).  K is then a run-time value.
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED, bool MULTI>
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool RAGGED, bool MULTI, int W>
 struct AvgTeam {
-    static constexpr int Q = kUnitQuads / kWavesPerWg;  // 4 quads per lane
+    static_assert(W >= 1 && W <= kWavesPerWg, "a team is one to four wavefronts");
+    static constexpr int Q = 4;               // quads per lane
+    static constexpr int kTeam = W * kWave;   // threads per team
+    static constexpr int kTeamUnit = Q * 4 * kTeam;  // elements per unit
 
     const WorkerPtrs &p;  // the kernel's argument itself: a copy would have to live in scratch memory to be indexed
     const float *local;
@@ -507,7 +510,7 @@ struct AvgTeam {
         if (!sl.active) return;
         sl.un = unit_of<kUnit>(u, n, B, nb, 1);
         // whole aligned quads: a short unit takes the register path too (see load_worker)
-        bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == kUnit) &&
+        bool f = (RAGGED ? (sl.un.len >= 4 && (sl.un.len & 3) == 0) : sl.un.len == (uint32_t)kTeamUnit) &&
                  (((uintptr_t)(codes_out + sl.un.start) & 3) == 0);
         if (MULTI) {
             for (int k = 0; k < K; ++k) f = f && (((uintptr_t)(p.codes[k] + sl.un.start) & 3) == 0);
@@ -519,13 +522,13 @@ struct AvgTeam {
         sl.fast = f;
     }
 
-    // This lane's j-th quad of the unit; WHOLE promises a unit of 4096 elements, otherwise a quad past the
+    // This lane's j-th quad of the unit; WHOLE promises a whole unit, otherwise a quad past the
     // end of a shorter unit becomes the unit's last one (an unconditional load of valid memory whose result
     // is not stored and cannot change the maximum).
     template <bool WHOLE>
     __device__ __forceinline__ uint32_t quad_of(const Slot &sl, int j) const
     {
-        const uint32_t i = j * kWg + tl;
+        const uint32_t i = j * kTeam + tl;
         if (WHOLE || !RAGGED) return i;
         const uint32_t last = (sl.un.len >> 2) - 1;
         return i < last ? i : last;
@@ -627,7 +630,7 @@ struct AvgTeam {
             m = f2u(means_for_compression<Q>(acc, pow2, rk, fk, &pre));
         } else {
             if (sl.active) {
-                for (uint32_t i = tl; i < sl.un.len; i += kWg) {
+                for (uint32_t i = tl; i < sl.un.len; i += kTeam) {
                     const uint32_t a = abs_bits(mean_at(sl.un, i));
                     m = m > a ? m : a;
                 }
@@ -638,9 +641,14 @@ struct AvgTeam {
         uint32_t *sp = slots + (phase * TEAMS + team) * kWavesPerWg;
         if (lane == 0) sp[wv] = m;
         __syncthreads();
-        {
+        if constexpr (W == 4) {
             const uint32_t a = sp[0] > sp[1] ? sp[0] : sp[1], b = sp[2] > sp[3] ? sp[2] : sp[3];
             m = (uint32_t)__builtin_amdgcn_readfirstlane((int)(a > b ? a : b));
+        } else {
+            uint32_t a = sp[0];
+#pragma unroll
+            for (int i = 1; i < W; ++i) a = a > sp[i] ? a : sp[i];
+            m = (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
         }
         phase ^= 1;  // the other half of the slots next time: one barrier per unit is enough
         if (!STEADY && !sl.active) return;
@@ -655,16 +663,16 @@ struct AvgTeam {
             encode_quads<FASTDIV, Q>(sr, acc, pre, d, r, recip, cw);
 #pragma unroll
             for (int j = 0; j < Q; ++j)
-                if (STEADY || !RAGGED || j * kWg + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kWg + tl, cw[j]);
+                if (STEADY || !RAGGED || j * kTeam + tl < (sl.un.len >> 2)) stg<1>(c4 + j * kTeam + tl, cw[j]);
         } else {
-            for (uint32_t i = tl; i < sl.un.len; i += kWg)
+            for (uint32_t i = tl; i < sl.un.len; i += kTeam)
                 codes_out[sl.un.start + i] = (uint8_t)encode_one<FASTDIV>(sr, mean_at(sl.un, i), d, r, recip);
         }
     }
 };
 
-template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED, bool MULTI>
-__global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
+template <int KT, int NT, bool FASTDIV, int TEAMS, bool REMAP, bool RAGGED, bool MULTI, int W = kWavesPerWg>
+__global__ __launch_bounds__(kWave * W * TEAMS, W * TEAMS == 12 ? 3 : 4) void k_avg_team(const uint32_t *__restrict__ tab, WorkerPtrs p,
                                                             int K_rt, const float *__restrict__ local, size_t n, size_t B,
                                                             size_t nb,
                                                             size_t n_units, size_t n_teams, uint32_t iters, uint32_t steady,
@@ -673,7 +681,8 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     __shared__ __align__(256) float lut[256 * kLutCopies];
     extern __shared__ uint32_t dyn_lds[];  // 2 phases x TEAMS x 4 maxima, then the bucket table
     constexpr int kSlots = 2 * TEAMS * kWavesPerWg;
-    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED, MULTI>;
+    static_assert(W * TEAMS % 4 == 0, "whole wavefronts per SIMD");
+    using Avg = AvgTeam<KT, NT, FASTDIV, TEAMS, RAGGED, MULTI, W>;
     Avg e(p);
     e.local = local;
     e.scales_out = scales_out;
@@ -687,9 +696,9 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     e.lane = threadIdx.x & 63;
     e.lane4 = e.lane * 4;
     const uint32_t wave = wave_in_wg();
-    e.team = wave / kWavesPerWg;
-    e.wv = wave % kWavesPerWg;
-    e.tl = threadIdx.x & (kWg - 1);  // lane within the team
+    e.team = wave / W;
+    e.wv = wave % W;
+    e.tl = (W & (W - 1)) == 0 ? threadIdx.x & (W * kWave - 1) : threadIdx.x - e.team * (W * kWave);  // thread within the team
     e.phase = 0;
     e.K = MULTI ? K_rt : KT;
     e.passes = (e.K + KT - 1) / KT;
@@ -703,7 +712,7 @@ __global__ __launch_bounds__(kWg * TEAMS, TEAMS == 3 ? 3 : 4) void k_avg_team(co
     e.load_all(a);  // the first loads are in flight while the tables are copied
     load_lut(tab, lut);
     {
-        e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWg * TEAMS);
+        e.sr = load_bucket_table(tab, dyn_lds + kSlots, kWave * W * TEAMS);
         e.sr.marks = REMAP;  // known at compile time: no test for marked code bytes in the loop
     }
     __syncthreads();

@@ -529,11 +529,16 @@ def test_decode_avg_encode_long_blocks(dq8, kind, K, with_local):
     (0, 7, True, 520 * 12288 + 8, 12288),    # one register set short of the workers, four sets rotate
     (1, 4, False, 900 * 9216, 9216),
     (2, 2, True, 530 * 7000, 7000),
-    (3, 7, False, 1400 * 4104 + 400, 4104)])
-def test_decode_avg_encode_long_blocks_several_per_workgroup(dq8, kind, K, with_local, n, block):
-    """More long blocks than workgroups: a workgroup walks several blocks and requests the next block's code words
-    while it finishes the current one."""
-    print("avg->encode long, many blocks kind=%d K=%d local=%d n=%d block=%d" % (kind, K, with_local, n, block), flush=True)
+    (3, 7, False, 1400 * 4104 + 400, 4104),
+    # blocks of 513 .. 3072 elements: teams of one, two or three wavefronts, more blocks than teams
+    (0, 8, False, 7000 * 1024 + 500, 1024), (3, 8, False, 3300 * 2048, 2048), (1, 8, True, 2500 * 3000 + 8, 3000),
+    (2, 8, False, 7100 * 1000 + 3, 1000), (0, 8, False, 2300 * 3072 + 1, 3072), (0, 8, False, 4000 * 1600, 1600),
+    (1, 4, False, 3200 * 2048 + 100, 2048), (2, 2, True, 7000 * 1000, 1000), (3, 3, False, 2400 * 3000 + 4, 3000),
+    (0, 7, True, 6500 * 1024, 1024)])
+def test_decode_avg_encode_several_blocks_per_team(dq8, kind, K, with_local, n, block):
+    """More blocks than workgroups (long blocks) or teams of wavefronts (shorter ones): each walks several blocks and
+    requests the next block's code words while it finishes the current one."""
+    print("avg->encode, many blocks kind=%d K=%d local=%d n=%d block=%d" % (kind, K, with_local, n, block), flush=True)
     nb = oracle.dq8_oracle.n_blocks(n, block)
     enc = [oracle.encode(kind, workloads.tensor(5, 12, worker=w, limit=n), block) for w in range(K)]
     cl, sl = [e[0] for e in enc], [e[1] for e in enc]
