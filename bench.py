@@ -417,8 +417,24 @@ def sweep_configs(torch, dq8, internal, workloads):
             launches = max(copies, 20)
             for call, f, alg in (("encode", enc_pass, enc_bytes), ("decode", dec_pass, dec_bytes)):
                 ms = event_time_ms(torch, f, launches, groups=3)
-                sweep_line(sweep="configs", config=label, kind=names[kind], call=call, tensors=len(host), elements=n_total,
-                           block=block, copies=copies, calls_per_pass=len(host), **rates(alg, ms, n_total, copy_gbps))
+                sweep_line(sweep="configs", config=label, kind=names[kind], call=call, launch="calls", tensors=len(host),
+                           elements=n_total, block=block, copies=copies, calls_per_pass=len(host),
+                           **rates(alg, ms, n_total, copy_gbps))
+                # the same pass recorded once per copy as a HIP graph and replayed: one launch from the host per pass
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                graphs = []
+                for r in range(copies):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        f(r)
+                    graphs.append(g)
+                torch.cuda.synchronize()
+                ms = event_time_ms(torch, lambda i: graphs[i % copies].replay(), launches, groups=3)
+                sweep_line(sweep="configs", config=label, kind=names[kind], call=call, launch="graph", tensors=len(host),
+                           elements=n_total, block=block, copies=copies, calls_per_pass=len(host),
+                           **rates(alg, ms, n_total, copy_gbps))
+                del graphs
         del xs, cs, ss, outs
 
 
