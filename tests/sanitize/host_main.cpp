@@ -92,6 +92,19 @@ static void check_plans()
             check_units<1024>(n, b);
             check_units<4096>(n, b);
         }
+    // teams of one to four wavefronts (twelve wavefronts per workgroup), a block of up to W x 1024 elements per team
+    for (int W = 1; W <= 4; ++W)
+        for (size_t b : {(size_t)(W * 1024), (size_t)(W * 1024 - 24), (size_t)((W - 1) * 1024 + 4)})
+            for (size_t n : {b, 5 * b + 3, (size_t)61100840, two32 + 12305}) {
+                const Plan p = make_plan(n, b, 256, 12, W, 12, kUnit);
+                CHECK(p.upb == 1 && p.n_units == p.nb, "team plan: n %zu block %zu", n, b);
+                CHECK(p.n_teams == (size_t)p.grid * (size_t)(12 / W) && p.n_teams <= (size_t)256 * 12 / W + 12, "team plan: n %zu block %zu W %d", n, b, W);
+                const size_t per = (p.n_units + p.n_teams - 1) / p.n_teams;
+                CHECK((per - 1) * p.n_teams < p.n_units, "team plan: %zu units on %zu teams", p.n_units, p.n_teams);
+                const Unit un = unit_of<kUnit>(p.nb - 1, n, p.B, p.nb, 1);
+                CHECK(un.block == p.nb - 1 && un.start == (p.nb - 1) * b && un.start + un.len == n && un.len <= (uint32_t)(W * 1024),
+                      "team plan: last unit of n %zu block %zu", n, b);
+            }
     for (int K = 0; K <= DQ8_MAX_K; ++K) {
         const int c = chunk_size(K);
         CHECK(c >= 1 && c <= 8, "chunk of %d workers: %d", K, c);
