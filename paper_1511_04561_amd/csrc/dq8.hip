@@ -681,8 +681,10 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
     return DQ8_OK;
 }
 
-// The worker counts for which teams of one, two or three wavefronts exist (blocks of up to 3072 elements).
-inline bool short_team_k(int K) { return K == 2 || K == 3 || K == 4 || K == 7 || K == 8; }
+// Whether a block of Bq <= 3072 elements goes to teams of one, two or three wavefronts: up to eight workers; a single
+// worker only with three wavefronts (with one worker's code words in flight per team the sixteen wavefronts per compute
+// unit of the wave-per-block kernels do better on the shorter blocks: 53 against 61 us at block 1000).
+inline bool short_team_k(int K, size_t Bq) { return K >= (Bq > 2048 ? 1 : 2) && K <= 8; }
 
 // Average-then-compress for blocks of up to 3072 elements: teams of W = 1, 2 or 3 wavefronts, a block per team
 // (W x 1024 elements hold it), twelve wavefronts per workgroup and one workgroup per compute unit.
@@ -727,9 +729,12 @@ int launch_avg_short_team(const DeviceState &st, int kind, const WorkerPtrs &wp,
         DQ8_SHORT_W(KT, false)       \
     }
     switch (K) {
+    case 1: DQ8_SHORT_K(1) break;
     case 2: DQ8_SHORT_K(2) break;
     case 3: DQ8_SHORT_K(3) break;
     case 4: DQ8_SHORT_K(4) break;
+    case 5: DQ8_SHORT_K(5) break;
+    case 6: DQ8_SHORT_K(6) break;
     case 7: DQ8_SHORT_K(7) break;
     default: DQ8_SHORT_K(8) break;
     }
@@ -747,7 +752,7 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
                     size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
     const size_t Bq = block_length(n, block);
-    if (Bq <= 3 * 1024 && short_team_k(K)) return launch_avg_short_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
+    if (Bq <= 3 * 1024 && short_team_k(K, Bq)) return launch_avg_short_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const bool ragged = Bq != (size_t)kUnit;  // shorter blocks: the variant whose register path takes short units
     const bool tuned_k = K == 2 || K == 4 || K == 8;  // the worker counts with a variant for 2 teams
     // Teams per workgroup: 3; 4 when each team has few code words in flight (up to `avg_teams4_upto` workers);
@@ -878,10 +883,10 @@ int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
 #define DQ8_AVG_LONG(QL, NB, KT)                                                                                              \
     hipLaunchKernelGGL((k_avg_long<QL, NB, 2, KT>), dim3((unsigned)teams), dim3(kLongTeam), lds, stream, tab, wp, K, local, n, \
                        B, nb, (uint32_t)teams, (uint32_t)aligned, scales_out, codes_out)
-    // Quads per lane that hold the block in a workgroup of 512 threads.  The worker counts of 2, 4 and 8 devices
-    // (with or without a local term) have kernels of their own, with one set of code words per worker where the
-    // registers allow (up to four quads per lane) and four sets otherwise; any other number of workers takes the
-    // kernel that reads the count at run time, with four sets (it pads the count to a multiple of four).
+    // Quads per lane that hold the block in a workgroup of 512 threads.  Up to eight workers have kernels of their
+    // own, with one set of code words per worker where the registers allow (up to four quads per lane) and three or
+    // four sets otherwise; more workers take the kernel that reads the count at run time, with four sets (it pads
+    // the count to a multiple of four).
     const int ql = (int)((B + 4 * kLongTeam - 1) / (4 * kLongTeam));
 #define DQ8_AVG_LONG_Q(NB_SHORT, NB_LONG, KT)            \
     switch (ql) {                                        \
@@ -893,9 +898,12 @@ int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     default: DQ8_AVG_LONG(8, NB_LONG, KT); break;        \
     }
     switch (K) {
+    case 1: DQ8_AVG_LONG_Q(2, 2, 1) break;
     case 2: DQ8_AVG_LONG_Q(2, 2, 2) break;
     case 3: DQ8_AVG_LONG_Q(3, 3, 3) break;
     case 4: DQ8_AVG_LONG_Q(4, 4, 4) break;
+    case 5: DQ8_AVG_LONG_Q(5, 3, 5) break;
+    case 6: DQ8_AVG_LONG_Q(6, 3, 6) break;
     case 7: DQ8_AVG_LONG_Q(7, 4, 7) break;
     case 8: DQ8_AVG_LONG_Q(8, 4, 8) break;
     default: DQ8_AVG_LONG_Q(4, 4, 0) break;
@@ -915,7 +923,7 @@ int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int 
     if (codes_out && !mean_out && K >= 1 && (K <= 8 || Bq == (size_t)kUnit) && g_tune.avg_team && unit == (size_t)kUnit)
         return launch_avg_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     // blocks of 513 .. 2048 elements with a worker count that has kernels for shorter teams
-    if (codes_out && !mean_out && g_tune.avg_team && Bq > 512 && Bq < n && short_team_k(K))
+    if (codes_out && !mean_out && g_tune.avg_team && Bq > 512 && Bq < n && short_team_k(K, Bq))
         return launch_avg_short_team(st, kind, wp, K, local, n, block, scales_out, codes_out, stream);
     const int ql = (int)(unit / (size_t)(4 * kWave));
     // whole 4096-element units with short ends need the 170 registers per lane that six wavefronts leave
@@ -1391,7 +1399,7 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
     if (Bq > (size_t)kUnit) return launch_avg_long(*st, kind, wp, K, local, n, block, out_scales, out_codes, stream);
     size_t done = 0;
     // (blocks of 1024 elements: a wavefront per block is faster where that kernel exists for the worker count)
-    if (!(Bq == 1024 && short_team_k(K) && g_tune.avg_team)) rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
+    if (!(Bq == 1024 && short_team_k(K, Bq) && g_tune.avg_team)) rc = small_avg_encode(*st, kind, wp, K, local, n, Bq, out_scales, out_codes, stream, &done);
     if (rc || done == n) return rc;
     if (done) {  // the rest starts on a block boundary
         wp = advance_workers(wp, K, done, Bq);

@@ -534,7 +534,8 @@ def test_decode_avg_encode_long_blocks(dq8, kind, K, with_local):
     (0, 8, False, 7000 * 1024 + 500, 1024), (3, 8, False, 3300 * 2048, 2048), (1, 8, True, 2500 * 3000 + 8, 3000),
     (2, 8, False, 7100 * 1000 + 3, 1000), (0, 8, False, 2300 * 3072 + 1, 3072), (0, 8, False, 4000 * 1600, 1600),
     (1, 4, False, 3200 * 2048 + 100, 2048), (2, 2, True, 7000 * 1000, 1000), (3, 3, False, 2400 * 3000 + 4, 3000),
-    (0, 7, True, 6500 * 1024, 1024)])
+    (0, 7, True, 6500 * 1024, 1024), (0, 1, False, 7000 * 1024, 1024), (3, 5, True, 3300 * 2000, 2000),
+    (1, 6, False, 2400 * 3072, 3072), (2, 6, False, 600 * 10000, 10000)])
 def test_decode_avg_encode_several_blocks_per_team(dq8, kind, K, with_local, n, block):
     """More blocks than workgroups (long blocks) or teams of wavefronts (shorter ones): each walks several blocks and
     requests the next block's code words while it finishes the current one."""
