@@ -8,6 +8,7 @@
 #include "dq8.h"
 #include "dq8_tables.hpp"
 #include "dq8_units.hpp"
+#include "dq8_arith.hpp"
 
 namespace {
 
@@ -290,11 +291,13 @@ __device__ __forceinline__ void encode_quads(const Search &sr, const v4f (&v)[Q]
 // power of two the division is a scaling by rk = 1 / terms, which commutes with the maximum and with everything
 // the compression does (see encode_quads): the sums are left as they are, *pre = rk, and the maximum is scaled
 // once (rounding is monotonic, so the scaled maximum is the maximum of the scaled values, also below the normal
-// range).  Otherwise every sum is divided and *pre = 1.
+// range).  Otherwise every sum is divided and *pre = 1: with the three instructions of divide_by_count when the
+// caller knows that the sums are 0 or in its range (`in_range`: no local term and every worker's scale for the block
+// passes scale_keeps_sums_in_range), with the division proper when not.
 // LEAVE_SCALING = false: the sums are multiplied by rk here and *pre = 1 (a kernel that is short of registers: a *pre
 // that is not a constant costs the compression about thirty of them).  One test per unit either way, not one per element.
 template <int Q, bool LEAVE_SCALING = true>
-__device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2, float rk, float fk, float *pre)
+__device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2, float rk, float fk, float *pre, bool in_range = false)
 {
     float fm = 0.0f;
     if (pow2 && LEAVE_SCALING) {
@@ -308,6 +311,17 @@ __device__ __forceinline__ float means_for_compression(v4f (&acc)[Q], bool pow2,
 #pragma unroll
         for (int j = 0; j < Q; ++j) {
             acc[j] = v4f{acc[j].x * rk, acc[j].y * rk, acc[j].z * rk, acc[j].w * rk};
+            fm = max4_abs(acc[j], fm);
+        }
+        return fm;
+    }
+    if (in_range) {
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            acc[j].x = divide_by_count(acc[j].x, fk, rk);
+            acc[j].y = divide_by_count(acc[j].y, fk, rk);
+            acc[j].z = divide_by_count(acc[j].z, fk, rk);
+            acc[j].w = divide_by_count(acc[j].w, fk, rk);
             fm = max4_abs(acc[j], fm);
         }
         return fm;

@@ -337,13 +337,17 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
             };
             // One round: NB steps, each requesting the place NB - 1 ahead (in the next block once this block's places
             // are all requested) and adding the oldest set.
+            bool in_range = !pow2 && !local;  // the sums are going to be divided and are 0 or where divide_by_count holds
             auto round = [&](int k) {
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
                     const int ahead = k + i + NB - 1;
                     const bool wraps = ahead >= Kp;
                     request(w[(i + NB - 1) % NB], scv[(i + NB - 1) % NB], wraps ? next : blk, wraps ? ahead - Kp : ahead);
-                    add_w(w[i], k + i < K ? scv[i] : 0.0f);
+                    // the scale is the same in every lane: to a scalar register, and its range test on the scalar unit
+                    const uint32_t sb = k + i < K ? (uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(scv[i])) : 0u;
+                    if (in_range) in_range = scale_keeps_sums_in_range(sb);
+                    add_w(w[i], u2f(sb));
                 }
             };
             if constexpr (KT > 0) {
@@ -353,7 +357,7 @@ __global__ __launch_bounds__(kLongTeam) void k_avg_long(const uint32_t *__restri
                 for (int k = 0; k < Kp; k += NB) round(k);
             }
             float pre;  // what the sums still have to be multiplied by to be the means: 1 here (registers)
-            const float fm = means_for_compression<Q, false>(acc, pow2, rk, fk, &pre);
+            const float fm = means_for_compression<Q, false>(acc, pow2, rk, fk, &pre, in_range);
             const float s = u2f(team_max(wave_max_u32(f2u(fm))));
             if (tl == 0) scales_out[blk] = s;
             const float d = s == 0.0f ? 1.0f : s;
@@ -561,6 +565,9 @@ struct AvgTeam {
         v4f acc[Q];
         uint32_t m = 0;
         float pre = 1.0f;  // what the sums still have to be multiplied by to be the means
+        // whether the sums are 0 or where divide_by_count holds (see scale_keeps_sums_in_range); only asked for when
+        // the sums are going to be divided
+        bool in_range = !pow2 && !local;
         if (STEADY || (sl.active && sl.fast)) {
             if (local) {  // not prefetched: the code words take the registers
                 const v4f *l4 = reinterpret_cast<const v4f *>(local + sl.un.start);
@@ -586,6 +593,10 @@ struct AvgTeam {
                 const int worker = empty ? K - 1 : base + k;
                 const float sv = p.scales[worker][sl.un.block];
                 sc[k] = u2f((uint32_t)__builtin_amdgcn_readfirstlane((int)f2u(empty ? 0.0f : sv)));
+            }
+            if (in_range) {  // (never with a power-of-two number of terms: nothing of this on that path)
+#pragma unroll
+                for (int k = 0; k < KT; ++k) in_range = in_range && scale_keeps_sums_in_range(f2u(sc[k]));
             }
             // The table lookups run one worker ahead of the sums: worker k + 1's sixteen lookups are issued
             // before worker k's values are multiplied and added, so the LDS latency of one worker hides behind
@@ -627,7 +638,7 @@ struct AvgTeam {
                 __builtin_amdgcn_sched_barrier(0);
             }
           }
-            m = f2u(means_for_compression<Q>(acc, pow2, rk, fk, &pre));
+            m = f2u(means_for_compression<Q>(acc, pow2, rk, fk, &pre, in_range));
         } else {
             if (sl.active) {
                 for (uint32_t i = tl; i < sl.un.len; i += kTeam) {

@@ -424,6 +424,7 @@ def test_decode_avg_encode(dq8, kind, K, with_local):
                     sl[k][0] = 0.0
             for k in range(K):
                 sl[k][1] = np.float32(1e-42)
+                sl[k][2] = np.float32(2.0 ** 110) if k % 2 else np.float32(2.0 ** 101)  # sums far above the usual range
             if with_local:
                 local[4096:8192] = np.float32(3e-43)
         want_codes, want_scales = oracle.decode_avg_encode(kind, cl, sl, block, local=local)

@@ -214,6 +214,23 @@ def test_division_by_a_power_of_two_equals_the_product_with_its_reciprocal():
         assert np.array_equal(q.view(np.uint32), m.view(np.uint32)), K
 
 
+def test_division_by_any_other_worker_count_in_three_instructions(tmp_path):
+    """A number of terms that is not a power of two: the kernels form a * fl(1/count), its exact remainder and one
+    correction instead of the division (csrc/dq8_arith.hpp).  The same function, compiled for the host, equals the
+    correctly rounded quotient for every significand, both signs, every count 3 .. 33 and binades across the range
+    that the kernels' test of the scales allows."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("needs g++")
+    exe = str(tmp_path / "division_main")
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(ROOT, "paper_1511_04561_amd", "csrc"), "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "sanitize", "division_main.cpp"), "-o", exe])
+    p = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert p.returncode == 0 and "division checks ok" in p.stdout, p.stdout[-2000:]
+
+
 @pytest.mark.parametrize("kind", KINDS)
 def test_reciprocal_path_matches_the_oracle_around_every_threshold(L, kind):
     """Inputs built so that x / s lands on, and next to, every decision point, for awkward scales."""
