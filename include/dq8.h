@@ -135,6 +135,27 @@ int dq8_decode(int kind, const uint8_t *codes, const float *scales, size_t n, si
                float *out, void *hip_stream);
 
 /*
+ * The same three steps for a set of matrices of any sizes laid out back to back in one array, each normalised
+ * by its own absolute maximum (Sec. 3.1, last paragraph: the maximum is taken per matrix), in one call for
+ * the whole set instead of one call per matrix (a gradient set of many small tensors is otherwise bound by
+ * the cost of the calls).
+ * bounds: DEVICE array of n_seg + 1 element offsets (read), bounds[0] = 0 <= bounds[1] <= ... <=
+ * bounds[n_seg] = n; segment i is elements [bounds[i], bounds[i + 1]) and has scale scales[i]; an empty
+ * segment gets scale +0.  1 <= n_seg <= DQ8_MAX_SEGMENTS.  The results are those of dq8_absmax / dq8_encode /
+ * dq8_decode with block == 0 on every segment by itself.  The offsets are read on the device only: entries
+ * beyond n count as n, and offsets that do not ascend give meaningless values, but no access outside the n
+ * elements of the arrays and the n_seg scales.  flags as in dq8_encode.  Arrays as in the calls above, with
+ * n_seg scales; outputs must not overlap inputs or each other.
+ */
+#define DQ8_MAX_SEGMENTS 4095
+int dq8_absmax_segments(const float *x, size_t n, const uint64_t *bounds, size_t n_seg, float *scales,
+                        void *hip_stream);
+int dq8_encode_segments(int kind, const float *x, size_t n, const uint64_t *bounds, size_t n_seg, float *scales,
+                        uint8_t *codes, unsigned flags, void *hip_stream);
+int dq8_decode_segments(int kind, const uint8_t *codes, const float *scales, size_t n, const uint64_t *bounds,
+                        size_t n_seg, float *out, void *hip_stream);
+
+/*
  * Decompress K workers' buffers and average them (Sec. 2.1: data parallelism averages the
  * exchanged gradients) in one pass:
  *   acc = +0;  for k = 0 .. K-1 in this order: acc = acc + table[codes[k][i]] * scales[k][b];

@@ -9,12 +9,15 @@ from .dq8_oracle import (  # noqa: F401
     MANTISSA,
     STATIC_TREE,
     absmax,
+    absmax_segments,
     build,
     codebook,
     decode,
     decode_accumulate_avg,
     decode_avg_encode,
+    decode_segments,
     encode,
+    encode_segments,
     error_stats,
     set_threads,
 )

@@ -141,6 +141,55 @@ def decode(kind, codes, scales, block=0):
     return out
 
 
+def _segments(n, bounds):
+    b = np.asarray(bounds, dtype=np.int64)
+    if b.ndim != 1 or b.size < 2 or b[0] != 0 or b[-1] != n or np.any(np.diff(b) < 0):
+        raise ValueError("bounds must ascend from 0 to n")
+    return b
+
+
+def absmax_segments(x, bounds):
+    """Sec. 3.1, last paragraph, for matrices laid out back to back: every segment [bounds[i], bounds[i + 1]) by
+    itself with one scale (block 0); an empty segment has scale +0."""
+    x = _f32(x)
+    b = _segments(x.size, bounds)
+    scales = np.zeros(b.size - 1, dtype=np.float32)
+    for i in range(b.size - 1):
+        if b[i + 1] > b[i]:
+            scales[i] = absmax(x[b[i]:b[i + 1]], 0)[0]
+    return scales
+
+
+def encode_segments(kind, x, bounds, scales=None):
+    """encode() of every segment by itself with one scale each.  Returns (codes, scales)."""
+    x = _f32(x)
+    b = _segments(x.size, bounds)
+    given = scales is not None
+    out_scales = _f32(scales).copy() if given else np.zeros(b.size - 1, dtype=np.float32)
+    if out_scales.size != b.size - 1:
+        raise ValueError("scales has %d entries, want %d" % (out_scales.size, b.size - 1))
+    codes = np.empty(x.size, dtype=np.uint8)
+    for i in range(b.size - 1):
+        if b[i + 1] > b[i]:
+            c, s = encode(kind, x[b[i]:b[i + 1]], 0, scales=out_scales[i:i + 1] if given else None)
+            codes[b[i]:b[i + 1]] = c
+            out_scales[i] = s[0]
+    return codes, out_scales
+
+
+def decode_segments(kind, codes, scales, bounds):
+    """decode() of every segment by itself with its scale."""
+    codes, scales = _u8(codes), _f32(scales)
+    b = _segments(codes.size, bounds)
+    if scales.size != b.size - 1:
+        raise ValueError("scales has %d entries, want %d" % (scales.size, b.size - 1))
+    out = np.empty(codes.size, dtype=np.float32)
+    for i in range(b.size - 1):
+        if b[i + 1] > b[i]:
+            out[b[i]:b[i + 1]] = decode(kind, codes[b[i]:b[i + 1]], scales[i:i + 1], 0)
+    return out
+
+
 def _workers(codes_list, scales_list, block, n=None):
     K = len(codes_list)
     if K != len(scales_list):

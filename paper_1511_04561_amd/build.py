@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdq8.so")
 SOURCES = ["dq8.hip", "dq8_tables.cpp"]
 HEADERS = ["dq8_internal.h", "dq8_tables.hpp", "dq8_device.hpp", "dq8_plan.hpp", "dq8_units.hpp", "dq8_arith.hpp", "dq8_kernels_codec.hpp", "dq8_kernels_avg.hpp",
-           "dq8_kernels_avg_encode.hpp", "dq8_kernels_stats.hpp", "dq8_kernels_small.hpp", os.path.join(ROOT, "include", "dq8.h")]
+           "dq8_kernels_avg_encode.hpp", "dq8_kernels_stats.hpp", "dq8_kernels_small.hpp", "dq8_kernels_segments.hpp", os.path.join(ROOT, "include", "dq8.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-unknown-cuda-version"]

@@ -45,6 +45,7 @@
 #include "dq8_kernels_avg_encode.hpp"
 #include "dq8_kernels_codec.hpp"
 #include "dq8_kernels_small.hpp"
+#include "dq8_kernels_segments.hpp"
 #include "dq8_kernels_stats.hpp"
 
 namespace {
@@ -1238,6 +1239,47 @@ int dq8_init(void)
     return device_state(&st);
 }
 
+// ---- segments: tensors back to back in one array, one scale each
+
+struct SegPlan {
+    size_t n_units, n_waves, lds;
+    unsigned grid;
+};
+
+// Units of kSegUnit elements on up to `waves_per_cu` wavefronts per compute unit, kSegWaves per workgroup.
+SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu)
+{
+    SegPlan p;
+    p.n_units = (n + kSegUnit - 1) / kSegUnit;
+    size_t waves = (size_t)st.cus * (size_t)waves_per_cu;
+    if (waves > p.n_units) waves = p.n_units;
+    p.grid = (unsigned)((waves + kSegWaves - 1) / kSegWaves);
+    p.n_waves = (size_t)p.grid * kSegWaves;
+    p.lds = (n_seg + 1) * sizeof(uint64_t);
+    return p;
+}
+
+int check_segments(const char *who, size_t n, const uint64_t *bounds, size_t n_seg)
+{
+    if (!bounds) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    if (n_seg < 1 || n_seg > (size_t)kSegMax) return fail(DQ8_ERR_ARG, "%s: %zu segments outside 1..%d", who, n_seg, kSegMax);
+    if (n > (SIZE_MAX >> 3)) return fail(DQ8_ERR_ARG, "%s: n too large", who);
+    return DQ8_OK;
+}
+
+int launch_segment_absmax(const DeviceState &st, const float *x, size_t n, const uint64_t *bounds, size_t n_seg,
+                          float *scales, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, scales, n_seg);
+    int rc = after_launch("k_fill_zero", stream);
+    if (rc) return rc;
+    const SegPlan p = make_segment_plan(st, n, n_seg, 32);
+    const uint32_t aligned = ((uintptr_t)x & 15) == 0;
+    hipLaunchKernelGGL(k_seg_absmax, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, x, n, bounds, (uint32_t)n_seg,
+                       p.n_units, p.n_waves, aligned, scales);
+    return after_launch("k_seg_absmax", stream);
+}
+
 int dq8_absmax(const float *x, size_t n, size_t block, float *scales, void *hip_stream)
 {
     if (n == 0) return DQ8_OK;
@@ -1409,6 +1451,80 @@ int dq8_decode_avg_encode(int kind, const uint8_t *const *codes, const float *co
         n -= done;
     }
     return launch_avg_block(*st, kind, wp, K, local, n, block, nullptr, out_scales, out_codes, stream);
+}
+
+int dq8_absmax_segments(const float *x, size_t n, const uint64_t *bounds, size_t n_seg, float *scales, void *hip_stream)
+{
+    static const char who[] = "dq8_absmax_segments";
+    if (n == 0) return DQ8_OK;
+    if (!x || !scales) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    int rc = check_segments(who, n, bounds, n_seg);
+    if (rc) return rc;
+    if (overlaps(x, n * 4, scales, n_seg * 4) || overlaps(bounds, (n_seg + 1) * 8, scales, n_seg * 4))
+        return fail(DQ8_ERR_ARG, "%s: buffers overlap", who);
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    return launch_segment_absmax(*st, x, n, bounds, n_seg, scales, static_cast<hipStream_t>(hip_stream));
+}
+
+int dq8_encode_segments(int kind, const float *x, size_t n, const uint64_t *bounds, size_t n_seg, float *scales,
+                        uint8_t *codes, unsigned flags, void *hip_stream)
+{
+    static const char who[] = "dq8_encode_segments";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (flags & ~DQ8_SCALES_GIVEN) return fail(DQ8_ERR_ARG, "%s: unknown flags 0x%x", who, flags);
+    if (n == 0) return DQ8_OK;
+    if (!x || !scales || !codes) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    rc = check_segments(who, n, bounds, n_seg);
+    if (rc) return rc;
+    if (overlaps(x, n * 4, codes, n) || overlaps(x, n * 4, scales, n_seg * 4) || overlaps(codes, n, scales, n_seg * 4) ||
+        overlaps(bounds, (n_seg + 1) * 8, codes, n) || overlaps(bounds, (n_seg + 1) * 8, scales, n_seg * 4))
+        return fail(DQ8_ERR_ARG, "%s: buffers overlap", who);
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!(flags & DQ8_SCALES_GIVEN)) {
+        rc = launch_segment_absmax(*st, x, n, bounds, n_seg, scales, stream);
+        if (rc) return rc;
+    }
+    SegPlan p = make_segment_plan(*st, n, n_seg, 32);
+    p.lds += (size_t)st->search_words[kind] * sizeof(uint32_t);
+    const uint32_t aligned = (((uintptr_t)x & 15) | ((uintptr_t)codes & 3)) == 0;
+    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
+    if (st->has_remap[kind])
+        hipLaunchKernelGGL((k_seg_encode<true>), dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, tab, x, n, bounds,
+                           (uint32_t)n_seg, p.n_units, p.n_waves, aligned, scales, codes);
+    else
+        hipLaunchKernelGGL((k_seg_encode<false>), dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, tab, x, n, bounds,
+                           (uint32_t)n_seg, p.n_units, p.n_waves, aligned, scales, codes);
+    return after_launch("k_seg_encode", stream);
+}
+
+int dq8_decode_segments(int kind, const uint8_t *codes, const float *scales, size_t n, const uint64_t *bounds, size_t n_seg,
+                        float *out, void *hip_stream)
+{
+    static const char who[] = "dq8_decode_segments";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (n == 0) return DQ8_OK;
+    if (!codes || !scales || !out) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    rc = check_segments(who, n, bounds, n_seg);
+    if (rc) return rc;
+    if (overlaps(out, n * 4, codes, n) || overlaps(out, n * 4, scales, n_seg * 4) || overlaps(out, n * 4, bounds, (n_seg + 1) * 8))
+        return fail(DQ8_ERR_ARG, "%s: out overlaps an input", who);
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const SegPlan p = make_segment_plan(*st, n, n_seg, 16);
+    const uint32_t aligned = (((uintptr_t)out & 15) | ((uintptr_t)codes & 3)) == 0;
+    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
+    hipLaunchKernelGGL(k_seg_decode, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, tab, codes, scales, n, bounds,
+                       (uint32_t)n_seg, p.n_units, p.n_waves, aligned, out);
+    return after_launch("k_seg_decode", stream);
 }
 
 int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *scales, unsigned flags, double *stats,

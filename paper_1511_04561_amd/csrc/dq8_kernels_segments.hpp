@@ -1,0 +1,235 @@
+// dq8 kernels for an array cut into segments of any lengths (tensors laid out back to back), one scale per
+// segment: the paper's per-matrix maximum (Sec. 3.1, last paragraph) for a whole set of matrices in one launch
+// instead of one call per matrix.
+//
+// bounds[0 .. n_seg] are element offsets, bounds[i] <= bounds[i + 1], segment i = [bounds[i], bounds[i + 1]).
+// A workgroup copies them to LDS, every entry clamped to n, so that nothing the array holds can lead an access
+// outside [0, n): the kernels walk the array in units of 1024 elements by position, and the segment of an
+// element is looked up, never the elements of a segment.  Entries that do not ascend give meaningless
+// results inside the arrays.
+// A wavefront takes a unit at a time.  The segment of the unit's first element comes from two votes over
+// the bounds (64 evenly spaced ones, then the 64 of the stretch the first vote names).  A unit that lies inside
+// one segment and is a whole aligned unit takes the register path of the other kernels with that segment's
+// scale; any other unit (a segment ends inside it, the end of the array, misaligned arrays) gives every lane
+// sixteen consecutive elements: one binary search for the first, then a step to the next segment whenever an
+// element reaches the next bound.
+#pragma once
+#include "dq8_device.hpp"
+
+namespace {
+
+constexpr int kSegMax = DQ8_MAX_SEGMENTS;           // segments per call: the bounds fit 32 KiB of LDS
+constexpr int kSegQ = 4;                            // quads per lane
+constexpr int kSegUnit = kSegQ * 4 * kWave;         // 1024 elements per unit
+constexpr int kSegRun = kSegUnit / kWave;           // 16 consecutive elements per lane on the slow path
+constexpr int kSegWaves = 16;                       // wavefronts per workgroup
+
+// Copies bounds[0 .. n_seg] to LDS, clamped to n.  The caller synchronises the workgroup.
+__device__ __forceinline__ void load_bounds(const uint64_t *__restrict__ bounds, uint32_t n_seg, size_t n, uint64_t *lds)
+{
+    for (uint32_t i = threadIdx.x; i <= n_seg; i += blockDim.x) {
+        const uint64_t b = bounds[i];
+        lds[i] = b < (uint64_t)n ? b : (uint64_t)n;
+    }
+}
+
+// The last segment whose first element is at or before element v (the same v in every lane), at most
+// n_seg - 1: two votes of the wavefront.
+__device__ __forceinline__ uint32_t segment_of_uniform(const uint64_t *lds, uint32_t n_seg, uint64_t v, uint32_t lane)
+{
+    const uint32_t stride = (n_seg + kWave) / kWave;  // ceil((n_seg + 1) / 64), at most 64
+    uint32_t i = lane * stride;
+    i = i < n_seg ? i : n_seg;
+    const uint32_t c1 = (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(lds[i] <= v && lane * stride <= n_seg));
+    const uint32_t base = (c1 ? c1 - 1 : 0) * stride;
+    uint32_t j = base + lane;
+    const bool in = lane < stride && j <= n_seg;
+    j = j < n_seg ? j : n_seg;
+    const uint32_t c2 = (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(in && lds[j] <= v));
+    const uint32_t s = base + (c2 ? c2 - 1 : 0);
+    return s < n_seg - 1 ? s : n_seg - 1;
+}
+
+// The same for a v of the lane's own: binary search.
+__device__ __forceinline__ uint32_t segment_of_lane(const uint64_t *lds, uint32_t n_seg, uint64_t v)
+{
+    uint32_t lo = 0, hi = n_seg;  // the answer is in [lo, hi)
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (lds[mid] <= v)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+// Geometry of unit u and what it needs: its first element, its length, the segment of its first element and
+// whether that segment holds the whole unit.
+struct SegUnit {
+    size_t start;
+    uint32_t len, seg;
+    bool single;
+};
+
+__device__ __forceinline__ SegUnit open_segment_unit(const uint64_t *lds, uint32_t n_seg, size_t n, size_t u, uint32_t lane)
+{
+    SegUnit q;
+    q.start = u * (size_t)kSegUnit;
+    q.len = cap_to_unit<kSegUnit>(n - q.start);
+    q.seg = segment_of_uniform(lds, n_seg, q.start, lane);
+    // (the last segment takes whatever lies beyond its end: bounds[n_seg] is n for well-formed bounds)
+    q.single = q.seg == n_seg - 1 || lds[q.seg + 1] >= q.start + q.len;
+    return q;
+}
+
+// Slow path: calls f(element index, segment) for the lane's run of up to sixteen consecutive elements of the unit.
+template <typename F>
+__device__ __forceinline__ void for_each_in_run(const uint64_t *lds, uint32_t n_seg, const SegUnit &q, uint32_t lane, F f)
+{
+    const uint32_t first = lane * kSegRun;
+    if (first >= q.len) return;
+    const uint32_t count = q.len - first < (uint32_t)kSegRun ? q.len - first : (uint32_t)kSegRun;
+    const size_t i0 = q.start + first;
+    uint32_t seg = q.single ? q.seg : segment_of_lane(lds, n_seg, i0);
+    uint64_t next = seg + 1 < n_seg ? lds[seg + 1] : ~(uint64_t)0;  // the last segment has no end
+    for (uint32_t i = 0; i < count; ++i) {
+        const size_t idx = i0 + i;
+        while (idx >= next) {  // empty segments are stepped over
+            ++seg;
+            next = seg + 1 < n_seg ? lds[seg + 1] : ~(uint64_t)0;
+        }
+        f(idx, seg);
+    }
+}
+
+// Maxima of the segments into zeroed scales (non-negative binary32 numbers order like their bit patterns, so
+// the pieces of a segment merge with an integer atomic max).
+__global__ __launch_bounds__(kWave * kSegWaves) void k_seg_absmax(const float *__restrict__ x, size_t n,
+                                                                  const uint64_t *__restrict__ bounds, uint32_t n_seg,
+                                                                  size_t n_units, size_t n_waves, uint32_t aligned,
+                                                                  float *__restrict__ scales)
+{
+    extern __shared__ uint64_t seg_lds[];
+    const uint32_t lane = threadIdx.x & 63;
+    load_bounds(bounds, n_seg, n, seg_lds);
+    __syncthreads();
+    unsigned int *sc = reinterpret_cast<unsigned int *>(scales);
+    for (size_t u = first_unit(kSegWaves); u < n_units; u += n_waves) {
+        const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
+        if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+            const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
+            float fm = 0.0f;
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j) fm = max4_abs(ldg<1>(p4 + j * kWave + lane), fm);
+            const uint32_t m = wave_max_u32(f2u(fm));
+            if (lane == 0 && m != 0) atomicMax(sc + q.seg, m);
+        } else {
+            uint32_t run = 0, run_seg = 0;
+            for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                if (seg != run_seg) {
+                    if (run != 0) atomicMax(sc + run_seg, run);
+                    run = 0;
+                    run_seg = seg;
+                }
+                const uint32_t a = abs_bits(x[idx]);
+                run = run > a ? run : a;
+            });
+            if (run != 0) atomicMax(sc + run_seg, run);
+        }
+    }
+}
+
+// Compression with the segments' scales (computed by k_seg_absmax or handed in).
+template <bool REMAP>
+__global__ __launch_bounds__(kWave * kSegWaves) void k_seg_encode(const uint32_t *__restrict__ tab, const float *__restrict__ x,
+                                                                  size_t n, const uint64_t *__restrict__ bounds, uint32_t n_seg,
+                                                                  size_t n_units, size_t n_waves, uint32_t aligned,
+                                                                  const float *__restrict__ scales, uint8_t *__restrict__ codes)
+{
+    extern __shared__ uint64_t seg_lds[];  // the bounds (n_seg + 1 entries, rounded up to an even count of words), then the search table
+    const uint32_t lane = threadIdx.x & 63;
+    load_bounds(bounds, n_seg, n, seg_lds);
+    Search sr = load_bucket_table(tab, reinterpret_cast<uint32_t *>(seg_lds + n_seg + 1), kWave * kSegWaves);
+    sr.marks = REMAP;
+    __syncthreads();
+    for (size_t u = first_unit(kSegWaves); u < n_units; u += n_waves) {
+        const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
+        if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+            const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
+            v4f v[kSegQ];
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j) v[j] = ldg<1>(p4 + j * kWave + lane);
+            const float s = scales[q.seg];
+            const float d = s == 0.0f ? 1.0f : s;
+            const float r = 1.0f / d;
+            const bool recip = reciprocal_ok(d);
+            uint32_t cw[kSegQ];
+            encode_quads<true, kSegQ>(sr, v, d, r, recip, cw);
+            uint32_t *c4 = reinterpret_cast<uint32_t *>(codes + q.start);
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j) stg<1>(c4 + j * kWave + lane, cw[j]);
+        } else {
+            uint32_t cur = ~0u;
+            float d = 1.0f, r = 1.0f;
+            bool recip = true;
+            for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                if (seg != cur) {
+                    cur = seg;
+                    const float s = scales[seg];
+                    d = s == 0.0f ? 1.0f : s;
+                    r = 1.0f / d;
+                    recip = reciprocal_ok(d);
+                }
+                codes[idx] = (uint8_t)encode_one<false>(sr, x[idx], d, r, recip);
+            });
+        }
+    }
+}
+
+// Decompression with the segments' scales.
+__global__ __launch_bounds__(kWave * kSegWaves) void k_seg_decode(const uint32_t *__restrict__ tab, const uint8_t *__restrict__ codes,
+                                                                  const float *__restrict__ scales, size_t n,
+                                                                  const uint64_t *__restrict__ bounds, uint32_t n_seg,
+                                                                  size_t n_units, size_t n_waves, uint32_t aligned,
+                                                                  float *__restrict__ out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint64_t seg_lds[];
+    const uint32_t lane = threadIdx.x & 63, lane4 = lane * 4;
+    load_bounds(bounds, n_seg, n, seg_lds);
+    load_lut(tab, lut);
+    __syncthreads();
+    for (size_t u = first_unit(kSegWaves); u < n_units; u += n_waves) {
+        const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
+        if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+            const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes + q.start);
+            uint32_t w[kSegQ];
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j) w[j] = ldg<1>(c4 + j * kWave + lane);
+            const float s = scales[q.seg];
+            v4f *o4 = reinterpret_cast<v4f *>(out + q.start);
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j) {
+                v4f r;
+                r.x = lut_at<0>(lut, w[j], lane4) * s;
+                r.y = lut_at<1>(lut, w[j], lane4) * s;
+                r.z = lut_at<2>(lut, w[j], lane4) * s;
+                r.w = lut_at<3>(lut, w[j], lane4) * s;
+                stg<2>(o4 + j * kWave + lane, r);
+            }
+        } else {
+            uint32_t cur = ~0u;
+            float s = 0.0f;
+            for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                if (seg != cur) {
+                    cur = seg;
+                    s = scales[seg];
+                }
+                out[idx] = lut_code(lut, codes[idx], lane4) * s;
+            });
+        }
+    }
+}
+
+}  // namespace

@@ -41,8 +41,12 @@ def lib():
         L.dq8_decode_accumulate_avg_local.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp]
         L.dq8_decode_avg_encode.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, sz, vp, vp, vp]
         L.dq8_error_stats.argtypes = [ci, vp, sz, sz, vp, ctypes.c_uint, vp, vp, vp]
+        L.dq8_absmax_segments.argtypes = [vp, sz, vp, sz, vp, vp]
+        L.dq8_encode_segments.argtypes = [ci, vp, sz, vp, sz, vp, vp, ctypes.c_uint, vp]
+        L.dq8_decode_segments.argtypes = [ci, vp, vp, sz, vp, sz, vp, vp]
         for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg,
-                  L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode):
+                  L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode, L.dq8_absmax_segments, L.dq8_encode_segments,
+                  L.dq8_decode_segments):
             f.restype = ci
         dbl = ctypes.c_double
         L.dq8_model_speedup.argtypes = [ci, dbl, dbl, dbl, ci, dbl, dbl, ctypes.POINTER(dbl)]
@@ -156,6 +160,70 @@ def decode(kind, codes, scales, block=0, out=None):
     with _on(codes.device):
         _check(lib().dq8_decode(int(kind), codes.data_ptr(), scales.data_ptr(), n, int(block), out.data_ptr(),
                                 _stream()), "dq8_decode")
+    return out
+
+
+MAX_SEGMENTS = 4095
+
+
+def _bounds(bounds, n):
+    """bounds: int64 device tensor of n_seg + 1 ascending element offsets from 0 to n (read by the kernels only)."""
+    b = _dev(bounds, torch.int64, "bounds")
+    if b.numel() < 2:
+        raise ValueError("bounds needs at least two entries")
+    return b, b.numel() - 1
+
+
+def absmax_segments(x, bounds, scales=None):
+    x = _dev(x, torch.float32, "x")
+    b, n_seg = _bounds(bounds, x.numel())
+    if scales is None:
+        scales = torch.empty(n_seg, dtype=torch.float32, device=x.device)
+    _dev(scales, torch.float32, "scales")
+    if scales.numel() < n_seg:
+        raise ValueError("scales too small")
+    with _on(x.device):
+        _check(lib().dq8_absmax_segments(x.data_ptr(), x.numel(), b.data_ptr(), n_seg, scales.data_ptr(), _stream()),
+               "dq8_absmax_segments")
+    return scales
+
+
+def encode_segments(kind, x, bounds, scales=None, codes=None, scales_given=False):
+    """Tensors back to back in x, one scale each.  Returns (codes, scales)."""
+    x = _dev(x, torch.float32, "x")
+    n = x.numel()
+    b, n_seg = _bounds(bounds, n)
+    if scales is None:
+        if scales_given:
+            raise ValueError("scales_given needs scales")
+        scales = torch.empty(n_seg, dtype=torch.float32, device=x.device)
+    if codes is None:
+        codes = torch.empty(n, dtype=torch.uint8, device=x.device)
+    _dev(scales, torch.float32, "scales")
+    _dev(codes, torch.uint8, "codes")
+    if scales.numel() < n_seg or codes.numel() < n:
+        raise ValueError("output buffers too small")
+    with _on(x.device):
+        _check(lib().dq8_encode_segments(int(kind), x.data_ptr(), n, b.data_ptr(), n_seg, scales.data_ptr(), codes.data_ptr(),
+                                         SCALES_GIVEN if scales_given else 0, _stream()), "dq8_encode_segments")
+    return codes, scales
+
+
+def decode_segments(kind, codes, scales, bounds, out=None):
+    codes = _dev(codes, torch.uint8, "codes")
+    scales = _dev(scales, torch.float32, "scales")
+    n = codes.numel()
+    b, n_seg = _bounds(bounds, n)
+    if scales.numel() < n_seg:
+        raise ValueError("scales too small")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _dev(out, torch.float32, "out")
+    if out.numel() < n:
+        raise ValueError("out too small")
+    with _on(codes.device):
+        _check(lib().dq8_decode_segments(int(kind), codes.data_ptr(), scales.data_ptr(), n, b.data_ptr(), n_seg, out.data_ptr(),
+                                         _stream()), "dq8_decode_segments")
     return out
 
 

@@ -803,3 +803,99 @@ print("debug round trip ok")
     env = dict(os.environ, DQ8_DEBUG="1")
     p = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=600)
     assert p.returncode == 0 and "debug round trip ok" in p.stdout, p.stdout[-2000:] + p.stderr[-4000:]
+
+
+# ---- tensors back to back in one array, one scale per tensor
+
+def bounds_dev(b):
+    return torch.from_numpy(np.asarray(b, dtype=np.int64)).cuda()
+
+
+def check_segments(dq8, kind, x, bounds, x_off=0, c_off=0, tag=""):
+    """absmax, encode (scales computed and handed in) and decode of a segmented array against the oracle's
+    per-segment results, with guard bands around every output."""
+    n, n_seg = x.size, len(bounds) - 1
+    print("segments %s kind=%d n=%d segments=%d x_off=%d c_off=%d" % (tag, kind, n, n_seg, x_off, c_off), flush=True)
+    want_codes, want_scales = oracle.encode_segments(kind, x, bounds)
+    want_out = oracle.decode_segments(kind, want_codes, want_scales, bounds)
+    b = bounds_dev(bounds)
+    xd = dev(x, x_off)
+    gs = Guarded(n_seg, np.float32)
+    dq8.absmax_segments(xd, b, scales=gs.t)
+    same_bits(gs.t, want_scales, "segment maxima " + tag)
+    gs.check("segment maxima " + tag)
+    gc, gs2 = Guarded(n, np.uint8, c_off), Guarded(n_seg, np.float32)
+    dq8.encode_segments(kind, xd, b, scales=gs2.t, codes=gc.t)
+    same_bits(gs2.t, want_scales, "segment scales " + tag)
+    same_bits(gc.t, want_codes, "segment codes " + tag)
+    gc.check("segment codes " + tag)
+    gs2.check("segment scales " + tag)
+    # scales handed in: twice the maxima (a power of two: the quotients halve exactly)
+    given = (2.0 * want_scales).astype(np.float32)
+    want_c2, _ = oracle.encode_segments(kind, x, bounds, scales=given)
+    gc2 = Guarded(n, np.uint8, c_off)
+    dq8.encode_segments(kind, xd, b, scales=dev(given), codes=gc2.t, scales_given=True)
+    same_bits(gc2.t, want_c2, "segment codes, scales given " + tag)
+    gc2.check("segment codes, scales given " + tag)
+    go = Guarded(n, np.float32, x_off)
+    dq8.decode_segments(kind, dev(want_codes, c_off), dev(want_scales), b, out=go.t)
+    same_bits(go.t, want_out, "segment decode " + tag)
+    go.check("segment decode " + tag)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_segments_of_the_gradient_sets(dq8, kind):
+    """The MLP's and the small convnet's gradient tensors back to back: one call for the whole set, results equal
+    to one call per tensor."""
+    for config in (1, 2):
+        parts = [t for _, t in workloads.tensors(config)]
+        bounds = np.concatenate([[0], np.cumsum([p.size for p in parts])])
+        check_segments(dq8, kind, np.concatenate(parts), bounds, tag="C%d" % config)
+
+
+def test_segments_edge_cases(dq8):
+    rng = np.random.Generator(np.random.PCG64(4242))
+    x = (rng.standard_normal(70000) * np.exp(rng.uniform(-6, 2, 70000))).astype(np.float32)
+    x[rng.random(70000) < 0.05] = 0.0
+    cases = [
+        ("one segment", [0, 70000]),
+        ("empty segments everywhere", [0, 0, 0, 5, 5, 1024, 1024, 1024, 2048, 30000, 30000, 70000, 70000]),
+        ("tiny segments", list(range(0, 200)) + [70000]),
+        ("ends inside quads and units", [0, 1, 3, 1023, 1025, 4097, 8190, 8193, 50001, 69999, 70000]),
+        ("whole units", list(range(0, 70000, 1024)) + [70000]),
+    ]
+    for tag, b in cases:
+        for kind in (0, 3):
+            check_segments(dq8, kind, x, b, tag=tag)
+    check_segments(dq8, 0, x, cases[3][1], x_off=1, c_off=3, tag="misaligned")
+    check_segments(dq8, 1, x[:7], [0, 2, 7], tag="seven elements")
+    zeros = np.zeros(5000, np.float32)
+    zeros[4000:] = -0.0
+    check_segments(dq8, 2, zeros, [0, 100, 4500, 5000], tag="all zero")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_segments_random(dq8, seed):
+    """Random cuts, among them the largest number of segments a call takes, over an array in which every wavefront
+    walks several units."""
+    rng = np.random.Generator(np.random.PCG64(5100 + seed))
+    n = int(rng.integers(1_200_000, 2_500_000))
+    n_seg = [4095, 1, 64, 700][seed]
+    cuts = np.sort(rng.integers(0, n + 1, n_seg - 1)) if seed != 2 else np.sort(rng.integers(0, n // 50, n_seg - 1))
+    bounds = np.concatenate([[0], cuts, [n]])
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-9, 2, n))).astype(np.float32)
+    check_segments(dq8, int(rng.integers(0, 4)), x, bounds, x_off=int(seed == 3), tag="random %d" % seed)
+
+
+def test_segment_calls_reject_bad_arguments(dq8):
+    x = torch.zeros(100, device="cuda")
+    with pytest.raises(dq8.Dq8Error, match="segments outside"):
+        dq8.encode_segments(0, x, bounds_dev(np.arange(4098) % 101))
+    with pytest.raises(ValueError):
+        dq8.encode_segments(0, x, bounds_dev([0]))
+    # offsets that do not ascend or lie beyond the array: no error is promised, but nothing outside the arrays is touched
+    gc, gs = Guarded(100, np.uint8), Guarded(4, np.float32)
+    dq8.encode_segments(0, dev(np.ones(100, np.float32)), bounds_dev([0, 90, 20, 10 ** 12, 100]), scales=gs.t, codes=gc.t)
+    torch.cuda.synchronize()
+    gc.check("malformed bounds")
+    gs.check("malformed bounds")
