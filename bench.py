@@ -35,6 +35,7 @@ per tensor), C2 (convnet gradients, one scale per tensor, three data types) and 
 per row) as per-tensor calls over enough copies of the configuration to exceed 1 GB.
 """
 import argparse
+import itertools
 import json
 import os
 import re
@@ -435,6 +436,37 @@ def sweep_configs(torch, dq8, internal, workloads):
                            elements=n_total, block=block, copies=copies, calls_per_pass=len(host),
                            **rates(alg, ms, n_total, copy_gbps))
                 del graphs
+            if block == 0:
+                # the whole configuration as one array with one scale per tensor: one call per pass
+                bounds = torch.tensor([0] + list(itertools.accumulate(t.size for t in host)), dtype=torch.int64, device="cuda")
+                fx = [torch.cat(x) for x in xs]
+                fc = [torch.empty(n_total, dtype=torch.uint8, device="cuda") for _ in range(copies)]
+                fs = [torch.empty(len(host), dtype=torch.float32, device="cuda") for _ in range(copies)]
+                fo = [torch.empty(n_total, dtype=torch.float32, device="cuda") for _ in range(copies)]
+                seg_enc = lambda i: dq8.encode_segments(kind, fx[i % copies], bounds, scales=fs[i % copies], codes=fc[i % copies])
+                seg_dec = lambda i: dq8.decode_segments(kind, fc[i % copies], fs[i % copies], bounds, out=fo[i % copies])
+                for r in range(copies):
+                    seg_enc(r)
+                torch.cuda.synchronize()
+                seg_bytes = 4 * len(host)
+                for call, f, alg in (("encode_segments", seg_enc, 9 * n_total + seg_bytes), ("decode_segments", seg_dec, 5 * n_total + seg_bytes)):
+                    ms = event_time_ms(torch, f, launches, groups=3)
+                    sweep_line(sweep="configs", config=label, kind=names[kind], call=call, launch="calls", tensors=len(host),
+                               elements=n_total, block=block, copies=copies, calls_per_pass=1, **rates(alg, ms, n_total, copy_gbps))
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    graphs = []
+                    for r in range(copies):
+                        g = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(g, stream=side):
+                            f(r)
+                        graphs.append(g)
+                    torch.cuda.synchronize()
+                    ms = event_time_ms(torch, lambda i: graphs[i % copies].replay(), launches, groups=3)
+                    sweep_line(sweep="configs", config=label, kind=names[kind], call=call, launch="graph", tensors=len(host),
+                               elements=n_total, block=block, copies=copies, calls_per_pass=1, **rates(alg, ms, n_total, copy_gbps))
+                    del graphs
+                del fx, fc, fs, fo
         del xs, cs, ss, outs
 
 

@@ -104,39 +104,66 @@ __device__ __forceinline__ void for_each_in_run(const uint64_t *lds, uint32_t n_
 }
 
 // Maxima of the segments into zeroed scales (non-negative binary32 numbers order like their bit patterns, so
-// the pieces of a segment merge with an integer atomic max).
+// the pieces of a segment merge with an integer atomic max).  The sixteen wavefronts of a workgroup take sixteen
+// consecutive units at a time and merge what they found through LDS first, so that a long segment costs one
+// atomic per sixteen units: thousands of atomics on one address take longer than reading the array.
 __global__ __launch_bounds__(kWave * kSegWaves) void k_seg_absmax(const float *__restrict__ x, size_t n,
                                                                   const uint64_t *__restrict__ bounds, uint32_t n_seg,
                                                                   size_t n_units, size_t n_waves, uint32_t aligned,
                                                                   float *__restrict__ scales)
 {
     extern __shared__ uint64_t seg_lds[];
-    const uint32_t lane = threadIdx.x & 63;
+    __shared__ uint32_t post_seg[kSegWaves], post_max[kSegWaves];
+    const uint32_t lane = threadIdx.x & 63, wave = wave_in_wg();
     load_bounds(bounds, n_seg, n, seg_lds);
     __syncthreads();
     unsigned int *sc = reinterpret_cast<unsigned int *>(scales);
-    for (size_t u = first_unit(kSegWaves); u < n_units; u += n_waves) {
-        const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
-        if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
-            float fm = 0.0f;
+    // every wavefront of the workgroup makes the same number of rounds (the barriers below)
+    for (size_t base = (size_t)blockIdx.x * kSegWaves; base < n_units; base += n_waves) {
+        const size_t u = base + wave;
+        uint32_t my_seg = ~0u, my_max = 0;  // what this wavefront's unit adds to one segment, if it is that simple
+        if (u < n_units) {
+            const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
+            if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+                const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
+                float fm = 0.0f;
 #pragma unroll
-            for (int j = 0; j < kSegQ; ++j) fm = max4_abs(ldg<1>(p4 + j * kWave + lane), fm);
-            const uint32_t m = wave_max_u32(f2u(fm));
-            if (lane == 0 && m != 0) atomicMax(sc + q.seg, m);
-        } else {
-            uint32_t run = 0, run_seg = 0;
-            for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
-                if (seg != run_seg) {
-                    if (run != 0) atomicMax(sc + run_seg, run);
-                    run = 0;
-                    run_seg = seg;
-                }
-                const uint32_t a = abs_bits(x[idx]);
-                run = run > a ? run : a;
-            });
-            if (run != 0) atomicMax(sc + run_seg, run);
+                for (int j = 0; j < kSegQ; ++j) fm = max4_abs(ldg<1>(p4 + j * kWave + lane), fm);
+                my_seg = q.seg;
+                my_max = wave_max_u32(f2u(fm));
+            } else {
+                uint32_t run = 0, run_seg = 0;
+                for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                    if (seg != run_seg) {
+                        if (run != 0) atomicMax(sc + run_seg, run);
+                        run = 0;
+                        run_seg = seg;
+                    }
+                    const uint32_t a = abs_bits(x[idx]);
+                    run = run > a ? run : a;
+                });
+                if (run != 0) atomicMax(sc + run_seg, run);
+            }
         }
+        if (lane == 0) {
+            post_seg[wave] = my_seg;
+            post_max[wave] = my_max;
+        }
+        __syncthreads();
+        if (wave == 0 && lane < (uint32_t)kSegWaves) {
+            // lane l speaks for the wavefronts that posted the same segment as wavefront l, if it is the first of them
+            const uint32_t s = post_seg[lane];
+            uint32_t m = 0;
+            bool first = true;
+            for (uint32_t j = 0; j < (uint32_t)kSegWaves; ++j) {
+                if (post_seg[j] == s) {
+                    if (j < lane) first = false;
+                    m = m > post_max[j] ? m : post_max[j];
+                }
+            }
+            if (first && s != ~0u && m != 0) atomicMax(sc + s, m);
+        }
+        __syncthreads();  // the posts are rewritten in the next round
     }
 }
 

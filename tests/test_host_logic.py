@@ -26,9 +26,9 @@ def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "dq8.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(dq8_[a-z0-9_]+)\s*\(", header)))
-    assert names == ["dq8_absmax", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
-                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_encode", "dq8_error_stats",
-                     "dq8_init",
+    assert names == ["dq8_absmax", "dq8_absmax_segments", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
+                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_decode_segments", "dq8_encode",
+                     "dq8_encode_segments", "dq8_error_stats", "dq8_init",
                      "dq8_last_error", "dq8_model_penalty", "dq8_model_speedup"]
     for n in names:
         assert hasattr(L, n), n
@@ -57,6 +57,24 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode(-1, p, p, n, z, p, None) == 2
     assert L.dq8_decode(0, p, None, n, z, p, None) == 1
     assert L.dq8_decode(0, None, None, z, z, None, None) == 0
+    # tensors back to back: the same checks, and the number of segments
+    one, many = ctypes.c_size_t(1), ctypes.c_size_t(4096)
+    q = np.zeros(64, np.float32).ctypes.data_as(ctypes.c_void_p)
+    r = np.zeros(64, np.uint8).ctypes.data_as(ctypes.c_void_p)
+    b = np.zeros(8, np.uint64).ctypes.data_as(ctypes.c_void_p)
+    assert L.dq8_absmax_segments(None, n, b, one, q, None) == 1
+    assert L.dq8_absmax_segments(p, n, None, one, q, None) == 1
+    assert L.dq8_absmax_segments(p, n, b, z, q, None) == 3 and b"segments" in L.dq8_last_error()
+    assert L.dq8_absmax_segments(p, n, b, many, q, None) == 3
+    assert L.dq8_absmax_segments(None, z, None, z, None, None) == 0
+    assert L.dq8_encode_segments(9, p, n, b, one, q, r, 0, None) == 2
+    assert L.dq8_encode_segments(0, p, n, b, one, q, r, 2, None) == 3  # unknown flag
+    assert L.dq8_encode_segments(0, p, n, b, one, p, r, 0, None) == 3 and b"overlap" in L.dq8_last_error()
+    assert L.dq8_encode_segments(0, p, n, b, many, q, r, 0, None) == 3
+    assert L.dq8_decode_segments(4, r, q, n, b, one, p, None) == 2
+    assert L.dq8_decode_segments(0, r, q, n, None, one, p, None) == 1
+    assert L.dq8_decode_segments(0, r, p, n, b, one, p, None) == 3  # out overlaps the scales
+    assert L.dq8_decode_segments(0, None, None, z, None, z, None, None) == 0
     arr = (ctypes.c_void_p * 2)(p, p)
     assert L.dq8_decode_accumulate_avg(0, arr, arr, 0, n, z, p, None) == 3
     assert L.dq8_decode_accumulate_avg(0, arr, arr, 33, n, z, p, None) == 3
