@@ -1242,17 +1242,23 @@ int dq8_init(void)
 // ---- segments: tensors back to back in one array, one scale each
 
 struct SegPlan {
-    size_t n_units, n_waves, lds;
+    size_t n_units, n_items, n_waves, lds;
+    uint32_t group;
     unsigned grid;
 };
 
 // Units of kSegUnit elements on up to `waves_per_cu` wavefronts per compute unit, kSegWaves per workgroup.
-SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu)
+// grouped (the maxima): an item of work is four units when a workgroup per compute unit still gets two items or more
+// per wavefront, else one unit (short arrays: as many wavefronts as there are units).
+SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu, bool grouped = false)
 {
     SegPlan p;
     p.n_units = (n + kSegUnit - 1) / kSegUnit;
     size_t waves = (size_t)st.cus * (size_t)waves_per_cu;
-    if (waves > p.n_units) waves = p.n_units;
+    p.group = grouped && p.n_units >= (size_t)st.cus * kSegWaves * 8 ? 4u : 1u;
+    if (p.group == 4) waves = (size_t)st.cus * kSegWaves;
+    p.n_items = (p.n_units + p.group - 1) / p.group;
+    if (waves > p.n_items) waves = p.n_items;
     p.grid = (unsigned)((waves + kSegWaves - 1) / kSegWaves);
     p.n_waves = (size_t)p.grid * kSegWaves;
     p.lds = (n_seg + 1) * sizeof(uint64_t);
@@ -1273,10 +1279,10 @@ int launch_segment_absmax(const DeviceState &st, const float *x, size_t n, const
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, scales, n_seg);
     int rc = after_launch("k_fill_zero", stream);
     if (rc) return rc;
-    const SegPlan p = make_segment_plan(st, n, n_seg, 32);
+    const SegPlan p = make_segment_plan(st, n, n_seg, 32, true);
     const uint32_t aligned = ((uintptr_t)x & 15) == 0;
     hipLaunchKernelGGL(k_seg_absmax, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, x, n, bounds, (uint32_t)n_seg,
-                       p.n_units, p.n_waves, aligned, scales);
+                       p.n_units, p.n_items, p.n_waves, p.group, aligned, scales);
     return after_launch("k_seg_absmax", stream);
 }
 

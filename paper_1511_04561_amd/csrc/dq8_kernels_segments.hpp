@@ -103,14 +103,43 @@ __device__ __forceinline__ void for_each_in_run(const uint64_t *lds, uint32_t n_
     }
 }
 
+// An item of work is `group` consecutive units, 1 or 4 (the host takes 4 when that still leaves every wavefront of
+// the chip several items).  Four units that lie inside one segment and are whole and aligned are taken at once,
+// sixteen quads per lane with all their loads in flight together; otherwise each unit of the item by itself.
+struct SegItem {
+    size_t first_unit;   // of the item
+    uint32_t units;      // that exist
+    bool whole;          // the four-unit register path applies
+    uint32_t seg;        // then: the segment
+};
+
+__device__ __forceinline__ SegItem open_segment_item(const uint64_t *lds, uint32_t n_seg, size_t n, size_t n_units, size_t item,
+                                                     uint32_t group, uint32_t aligned, uint32_t lane)
+{
+    SegItem it;
+    it.first_unit = item * group;
+    const size_t left = n_units - it.first_unit;
+    it.units = left < group ? (uint32_t)left : group;
+    it.whole = false;
+    it.seg = 0;
+    if (group == 4 && aligned) {
+        const size_t start = it.first_unit * (size_t)kSegUnit;
+        if (n - start >= (size_t)(4 * kSegUnit)) {
+            it.seg = segment_of_uniform(lds, n_seg, start, lane);
+            it.whole = it.seg == n_seg - 1 || lds[it.seg + 1] >= start + 4 * kSegUnit;
+        }
+    }
+    return it;
+}
+
 // Maxima of the segments into zeroed scales (non-negative binary32 numbers order like their bit patterns, so
 // the pieces of a segment merge with an integer atomic max).  The sixteen wavefronts of a workgroup take sixteen
-// consecutive units at a time and merge what they found through LDS first, so that a long segment costs one
-// atomic per sixteen units: thousands of atomics on one address take longer than reading the array.
+// consecutive items at a time and merge what they found through LDS first, so that a long segment costs one
+// atomic per sixteen items: thousands of atomics on one address take longer than reading the array.
 __global__ __launch_bounds__(kWave * kSegWaves) void k_seg_absmax(const float *__restrict__ x, size_t n,
                                                                   const uint64_t *__restrict__ bounds, uint32_t n_seg,
-                                                                  size_t n_units, size_t n_waves, uint32_t aligned,
-                                                                  float *__restrict__ scales)
+                                                                  size_t n_units, size_t n_items, size_t n_waves, uint32_t group,
+                                                                  uint32_t aligned, float *__restrict__ scales)
 {
     extern __shared__ uint64_t seg_lds[];
     __shared__ uint32_t post_seg[kSegWaves], post_max[kSegWaves];
@@ -119,30 +148,50 @@ __global__ __launch_bounds__(kWave * kSegWaves) void k_seg_absmax(const float *_
     __syncthreads();
     unsigned int *sc = reinterpret_cast<unsigned int *>(scales);
     // every wavefront of the workgroup makes the same number of rounds (the barriers below)
-    for (size_t base = (size_t)blockIdx.x * kSegWaves; base < n_units; base += n_waves) {
-        const size_t u = base + wave;
-        uint32_t my_seg = ~0u, my_max = 0;  // what this wavefront's unit adds to one segment, if it is that simple
-        if (u < n_units) {
-            const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
-            if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
-                const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
+    for (size_t base = (size_t)blockIdx.x * kSegWaves; base < n_items; base += n_waves) {
+        const size_t item = base + wave;
+        uint32_t my_seg = ~0u, my_max = 0;  // what this wavefront's item adds to one segment, if it is that simple
+        if (item < n_items) {
+            const SegItem it = open_segment_item(seg_lds, n_seg, n, n_units, item, group, aligned, lane);
+            if (it.whole) {
+                const v4f *p4 = reinterpret_cast<const v4f *>(x + it.first_unit * (size_t)kSegUnit);
+                v4f v[4 * kSegQ];
+#pragma unroll
+                for (int j = 0; j < 4 * kSegQ; ++j) v[j] = ldg<1>(p4 + j * kWave + lane);
                 float fm = 0.0f;
 #pragma unroll
-                for (int j = 0; j < kSegQ; ++j) fm = max4_abs(ldg<1>(p4 + j * kWave + lane), fm);
-                my_seg = q.seg;
+                for (int j = 0; j < 4 * kSegQ; ++j) fm = max4_abs(v[j], fm);
+                my_seg = it.seg;
                 my_max = wave_max_u32(f2u(fm));
             } else {
-                uint32_t run = 0, run_seg = 0;
-                for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
-                    if (seg != run_seg) {
+                for (uint32_t r = 0; r < it.units; ++r) {
+                    const SegUnit q = open_segment_unit(seg_lds, n_seg, n, it.first_unit + r, lane);
+                    if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+                        const v4f *p4 = reinterpret_cast<const v4f *>(x + q.start);
+                        float fm = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < kSegQ; ++j) fm = max4_abs(ldg<1>(p4 + j * kWave + lane), fm);
+                        const uint32_t m = wave_max_u32(f2u(fm));
+                        if (group == 1) {  // the item is this unit: merged with the workgroup's other items below
+                            my_seg = q.seg;
+                            my_max = m;
+                        } else if (lane == 0 && m != 0) {
+                            atomicMax(sc + q.seg, m);
+                        }
+                    } else {
+                        uint32_t run = 0, run_seg = 0;
+                        for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                            if (seg != run_seg) {
+                                if (run != 0) atomicMax(sc + run_seg, run);
+                                run = 0;
+                                run_seg = seg;
+                            }
+                            const uint32_t a = abs_bits(x[idx]);
+                            run = run > a ? run : a;
+                        });
                         if (run != 0) atomicMax(sc + run_seg, run);
-                        run = 0;
-                        run_seg = seg;
                     }
-                    const uint32_t a = abs_bits(x[idx]);
-                    run = run > a ? run : a;
-                });
-                if (run != 0) atomicMax(sc + run_seg, run);
+                }
             }
         }
         if (lane == 0) {
