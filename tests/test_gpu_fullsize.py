@@ -321,3 +321,29 @@ def test_more_than_two_to_the_32_elements(dq8):
         wc2, ws2 = oracle.encode(KIND, want, 0)
         assert fc[lo:hi].cpu().numpy().tobytes() == wc2.tobytes() and fs[b:b + 1].cpu().numpy().tobytes() == ws2.tobytes(), \
             "compressed mean of block %d (5000)" % b
+    del out, mean, fc, fs, codes, scales, scales2
+    # the same array as four matrices back to back, one of them across element 2^32 and one of 4 G elements
+    two32 = 1 << 32
+    bounds = [0, 3 * B + 5, two32 - 1000, two32 + 9000, n]
+    bd = torch.tensor(bounds, dtype=torch.int64, device="cuda")
+    codes, scales = dq8.encode_segments(KIND, x, bd)
+    amax = dq8.absmax_segments(x, bd)
+    out = dq8.decode_segments(KIND, codes, scales, bd)
+    torch.cuda.synchronize()
+    print("2^32+: segments done", flush=True)
+    assert torch.equal(amax, scales)
+    sc = scales.cpu().numpy()
+    for i in (0, 2, 3):  # the matrices the oracle takes whole
+        lo, hi = bounds[i], bounds[i + 1]
+        wc, ws = oracle.encode(KIND, x[lo:hi].cpu().numpy(), 0)
+        assert sc[i:i + 1].tobytes() == ws.tobytes(), "scale of matrix %d" % i
+        assert codes[lo:hi].cpu().numpy().tobytes() == wc.tobytes(), "codes of matrix %d" % i
+        assert out[lo:hi].cpu().numpy().tobytes() == oracle.decode(KIND, wc, ws, 0).tobytes(), "decoded matrix %d" % i
+    lo, hi = bounds[1], bounds[2]
+    big_max = max(float(x[a:min(hi, a + step)].abs().max()) for a in range(lo, hi, step))  # torch's own reduction
+    assert float(sc[1]) == big_max
+    for a in [lo, lo + 1019, hi - 4096] + [int(v) for v in rng.integers(lo, hi - 4096, 20)]:
+        xs = x[a:a + 4096].cpu().numpy()
+        wc, _ = oracle.encode(KIND, xs, 0, scales=sc[1:2])
+        assert codes[a:a + 4096].cpu().numpy().tobytes() == wc.tobytes(), "codes at %d of the long matrix" % a
+        assert out[a:a + 4096].cpu().numpy().tobytes() == oracle.decode(KIND, wc, sc[1:2], 0).tobytes(), "decoded at %d" % a

@@ -141,3 +141,41 @@ def test_per_tensor_passes_recorded_in_a_graph(dq8):
                 want_c, want_s = oracle.encode(kind, h, 0)
                 assert bits(c) == want_c.tobytes() and bits(s) == want_s.tobytes()
                 assert bits(o) == oracle.decode(kind, want_c, want_s, 0).tobytes()
+
+
+def test_segment_calls_recorded_in_a_graph(dq8):
+    """The MLP's gradient set as one array with one scale per tensor: compression (zero fill, maxima, codes) and
+    decompression recorded once and replayed on new gradients."""
+    sizes = [t.size for _, t in workloads.tensors(1)]
+    bounds = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    n = int(bounds[-1])
+    bd = torch.from_numpy(bounds).cuda()
+    x = torch.zeros(n, dtype=torch.float32, device="cuda")
+    codes = torch.empty(n, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(len(sizes), dtype=torch.float32, device="cuda")
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+
+    def calls():
+        dq8.encode_segments(0, x, bd, scales=scales, codes=codes)
+        dq8.decode_segments(0, codes, scales, bd, out=out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for rep in range(1, 4):
+        host = np.concatenate([t for _, t in workloads.tensors(1, worker=rep)])
+        x.copy_(torch.from_numpy(host))
+        scales.fill_(7.0)  # the maxima are merged into zeroed scales: the zero fill has to be part of every replay
+        codes.fill_(0xEE)
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_c, want_s = oracle.encode_segments(0, host, bounds)
+        assert bits(scales) == want_s.tobytes() and bits(codes) == want_c.tobytes()
+        assert bits(out) == oracle.decode_segments(0, want_c, want_s, bounds).tobytes()
