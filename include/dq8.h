@@ -154,6 +154,12 @@ int dq8_encode_segments(int kind, const float *x, size_t n, const uint64_t *boun
                         uint8_t *codes, unsigned flags, void *hip_stream);
 int dq8_decode_segments(int kind, const uint8_t *codes, const float *scales, size_t n, const uint64_t *bounds,
                         size_t n_seg, float *out, void *hip_stream);
+/* The K-way average of dq8_decode_accumulate_avg (Sec. 2.1) with the same segments: scales[k][i] is worker k's scale of
+ * segment i.  local: NULL, or the caller's own n floats as the first term of every sum (Sec. 3.4), divisor K + 1 and
+ * K >= 0 then; 1 <= K <= DQ8_MAX_K otherwise.  codes, scales: HOST arrays of K device pointers, as there. */
+int dq8_decode_accumulate_avg_segments(int kind, const uint8_t *const *codes, const float *const *scales, int K,
+                                       const float *local, size_t n, const uint64_t *bounds, size_t n_seg, float *out,
+                                       void *hip_stream);
 
 /*
  * Decompress K workers' buffers and average them (Sec. 2.1: data parallelism averages the

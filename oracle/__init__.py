@@ -14,6 +14,7 @@ from .dq8_oracle import (  # noqa: F401
     codebook,
     decode,
     decode_accumulate_avg,
+    decode_accumulate_avg_segments,
     decode_avg_encode,
     decode_segments,
     encode,

@@ -190,6 +190,19 @@ def decode_segments(kind, codes, scales, bounds):
     return out
 
 
+def decode_accumulate_avg_segments(kind, codes_list, scales_list, bounds, local=None):
+    """decode_accumulate_avg() of every segment by itself, scales_list[k][i] = worker k's scale of segment i."""
+    n = _f32(local).size if local is not None else _u8(codes_list[0]).size
+    b = _segments(n, bounds)
+    out = np.empty(n, dtype=np.float32)
+    for i in range(b.size - 1):
+        lo, hi = b[i], b[i + 1]
+        if hi > lo:
+            out[lo:hi] = decode_accumulate_avg(kind, [_u8(c)[lo:hi] for c in codes_list], [_f32(s)[i:i + 1] for s in scales_list], 0,
+                                               local=None if local is None else _f32(local)[lo:hi])
+    return out
+
+
 def _workers(codes_list, scales_list, block, n=None):
     K = len(codes_list)
     if K != len(scales_list):

@@ -1533,6 +1533,37 @@ int dq8_decode_segments(int kind, const uint8_t *codes, const float *scales, siz
     return after_launch("k_seg_decode", stream);
 }
 
+int dq8_decode_accumulate_avg_segments(int kind, const uint8_t *const *codes, const float *const *scales, int K,
+                                       const float *local, size_t n, const uint64_t *bounds, size_t n_seg, float *out,
+                                       void *hip_stream)
+{
+    static const char who[] = "dq8_decode_accumulate_avg_segments";
+    int rc = check_kind(kind);
+    if (rc) return rc;
+    if (K < (local ? 0 : 1) || K > DQ8_MAX_K)
+        return fail(DQ8_ERR_ARG, "%s: K = %d outside %d..%d", who, K, local ? 0 : 1, DQ8_MAX_K);
+    if (n == 0) return DQ8_OK;
+    if (!out) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
+    rc = check_segments(who, n, bounds, n_seg);
+    if (rc) return rc;
+    if (overlaps(out, n * 4, bounds, (n_seg + 1) * 8)) return fail(DQ8_ERR_ARG, "%s: out overlaps the offsets", who);
+    if (local && overlaps(out, n * 4, local, n * 4)) return fail(DQ8_ERR_ARG, "%s: out overlaps local", who);
+    WorkerPtrs wp;
+    rc = gather_workers(who, codes, scales, K, n, n_seg, out, n * 4, &wp);
+    if (rc) return rc;
+    DeviceState *st;
+    rc = device_state(&st);
+    if (rc) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const SegPlan p = make_segment_plan(*st, n, n_seg, 16);
+    bool aligned = ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
+    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
+    const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
+    hipLaunchKernelGGL(k_seg_avg, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, tab, wp, K, local, n, bounds,
+                       (uint32_t)n_seg, p.n_units, p.n_waves, (uint32_t)aligned, out);
+    return after_launch("k_seg_avg", stream);
+}
+
 int dq8_error_stats(int kind, const float *x, size_t n, size_t block, float *scales, unsigned flags, double *stats,
                     double *means, void *hip_stream)
 {

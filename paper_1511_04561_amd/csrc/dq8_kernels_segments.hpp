@@ -308,4 +308,80 @@ __global__ __launch_bounds__(kWave * kSegWaves) void k_seg_decode(const uint32_t
     }
 }
 
+// Decompression of K workers' buffers and their average (optionally with a local fp32 array as the first term)
+// with the segments' scales: the ordered sum of the other averaging kernels (product and sum rounded separately,
+// workers in index order, then the division by the number of terms), any number of workers, four at a time in
+// flight on the register path.
+__global__ __launch_bounds__(kWave * kSegWaves) void k_seg_avg(const uint32_t *__restrict__ tab, WorkerPtrs p, int K,
+                                                               const float *__restrict__ local, size_t n,
+                                                               const uint64_t *__restrict__ bounds, uint32_t n_seg,
+                                                               size_t n_units, size_t n_waves, uint32_t aligned,
+                                                               float *__restrict__ out)
+{
+    __shared__ __align__(256) float lut[256 * kLutCopies];
+    extern __shared__ uint64_t seg_lds[];
+    const uint32_t lane = threadIdx.x & 63, lane4 = lane * 4;
+    const int terms = K + (local ? 1 : 0);
+    const float fk = (float)terms;
+    const bool pow2 = (terms & (terms - 1)) == 0;  // then acc * (1 / terms) equals acc / terms exactly
+    const float rk = 1.0f / fk;
+    auto mean_of = [&](float acc) { return pow2 ? acc * rk : acc / fk; };
+    load_bounds(bounds, n_seg, n, seg_lds);
+    load_lut(tab, lut);
+    __syncthreads();
+    constexpr int kAhead = 4;  // workers whose code words are requested together
+    for (size_t u = first_unit(kSegWaves); u < n_units; u += n_waves) {
+        const SegUnit q = open_segment_unit(seg_lds, n_seg, n, u, lane);
+        if (q.single && q.len == (uint32_t)kSegUnit && aligned) {
+            v4f acc[kSegQ];
+            if (local) {  // the sum starts at +0: a local -0 becomes +0
+                const v4f *l4 = reinterpret_cast<const v4f *>(local + q.start);
+#pragma unroll
+                for (int j = 0; j < kSegQ; ++j) {
+                    const v4f l = ldg<1>(l4 + j * kWave + lane);
+                    acc[j] = v4f{0.0f + l.x, 0.0f + l.y, 0.0f + l.z, 0.0f + l.w};
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < kSegQ; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            for (int k0 = 0; k0 < K; k0 += kAhead) {
+                uint32_t w[kAhead][kSegQ];
+                float sc[kAhead];
+#pragma unroll
+                for (int c = 0; c < kAhead; ++c) {
+                    const int k = k0 + c < K ? k0 + c : K - 1;  // a place past the last worker repeats it and is not added
+                    const uint32_t *c4 = reinterpret_cast<const uint32_t *>(p.codes[k] + q.start);
+                    sc[c] = p.scales[k][q.seg];
+#pragma unroll
+                    for (int j = 0; j < kSegQ; ++j) w[c][j] = ldg<1>(c4 + j * kWave + lane);
+                }
+#pragma unroll
+                for (int c = 0; c < kAhead; ++c) {
+                    if (k0 + c < K) {
+#pragma unroll
+                        for (int j = 0; j < kSegQ; ++j) {
+                            acc[j].x = acc[j].x + lut_at<0>(lut, w[c][j], lane4) * sc[c];
+                            acc[j].y = acc[j].y + lut_at<1>(lut, w[c][j], lane4) * sc[c];
+                            acc[j].z = acc[j].z + lut_at<2>(lut, w[c][j], lane4) * sc[c];
+                            acc[j].w = acc[j].w + lut_at<3>(lut, w[c][j], lane4) * sc[c];
+                        }
+                    }
+                }
+            }
+            v4f *o4 = reinterpret_cast<v4f *>(out + q.start);
+#pragma unroll
+            for (int j = 0; j < kSegQ; ++j)
+                stg<2>(o4 + j * kWave + lane, v4f{mean_of(acc[j].x), mean_of(acc[j].y), mean_of(acc[j].z), mean_of(acc[j].w)});
+        } else {
+            for_each_in_run(seg_lds, n_seg, q, lane, [&](size_t idx, uint32_t seg) {
+                float a = 0.0f;
+                if (local) a = a + local[idx];
+                for (int k = 0; k < K; ++k) a = a + lut_code(lut, p.codes[k][idx], lane4) * p.scales[k][seg];
+                out[idx] = mean_of(a);
+            });
+        }
+    }
+}
+
 }  // namespace

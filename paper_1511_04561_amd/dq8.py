@@ -44,9 +44,10 @@ def lib():
         L.dq8_absmax_segments.argtypes = [vp, sz, vp, sz, vp, vp]
         L.dq8_encode_segments.argtypes = [ci, vp, sz, vp, sz, vp, vp, ctypes.c_uint, vp]
         L.dq8_decode_segments.argtypes = [ci, vp, vp, sz, vp, sz, vp, vp]
+        L.dq8_decode_accumulate_avg_segments.argtypes = [ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ci, vp, sz, vp, sz, vp, vp]
         for f in (L.dq8_codebook, L.dq8_init, L.dq8_absmax, L.dq8_encode, L.dq8_decode, L.dq8_decode_accumulate_avg,
                   L.dq8_decode_accumulate_avg_local, L.dq8_decode_avg_encode, L.dq8_absmax_segments, L.dq8_encode_segments,
-                  L.dq8_decode_segments):
+                  L.dq8_decode_segments, L.dq8_decode_accumulate_avg_segments):
             f.restype = ci
         dbl = ctypes.c_double
         L.dq8_model_speedup.argtypes = [ci, dbl, dbl, dbl, ci, dbl, dbl, ctypes.POINTER(dbl)]
@@ -263,6 +264,34 @@ def decode_accumulate_avg(kind, codes_list, scales_list, block=0, out=None, loca
         else:
             _check(lib().dq8_decode_accumulate_avg_local(int(kind), cp, sp, K, local.data_ptr(), n, int(block),
                                                          out.data_ptr(), _stream()), "dq8_decode_accumulate_avg_local")
+    return out
+
+
+def decode_accumulate_avg_segments(kind, codes_list, scales_list, bounds, out=None, local=None):
+    """Mean of the K decoded buffers of tensors back to back, one scale per tensor and worker."""
+    if local is not None:
+        _dev(local, torch.float32, "local")
+    K = len(codes_list)
+    if K != len(scales_list) or (K == 0 and local is None):
+        raise ValueError("need as many scale arrays as code arrays, and at least one worker or local")
+    n = local.numel() if local is not None else codes_list[0].numel()
+    b, n_seg = _bounds(bounds, n)
+    for c, s in zip(codes_list, scales_list):
+        _dev(c, torch.uint8, "codes")
+        _dev(s, torch.float32, "scales")
+        if c.numel() != n or s.numel() < n_seg:
+            raise ValueError("worker buffers differ in size")
+    cp = (ctypes.c_void_p * max(K, 1))(*[c.data_ptr() for c in codes_list])
+    sp = (ctypes.c_void_p * max(K, 1))(*[s.data_ptr() for s in scales_list])
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=b.device)
+    _dev(out, torch.float32, "out")
+    if out.numel() < n:
+        raise ValueError("out too small")
+    with _on(out.device):
+        _check(lib().dq8_decode_accumulate_avg_segments(int(kind), cp, sp, K, None if local is None else local.data_ptr(), n,
+                                                        b.data_ptr(), n_seg, out.data_ptr(), _stream()),
+               "dq8_decode_accumulate_avg_segments")
     return out
 
 

@@ -899,3 +899,27 @@ def test_segment_calls_reject_bad_arguments(dq8):
     torch.cuda.synchronize()
     gc.check("malformed bounds")
     gs.check("malformed bounds")
+
+
+@pytest.mark.parametrize("kind,K,with_local", [(0, 1, False), (0, 8, False), (1, 3, True), (2, 7, False), (3, 5, True),
+                                               (0, 0, True), (0, 32, False)])
+def test_average_of_segments(dq8, kind, K, with_local):
+    """K workers' codes of tensors back to back, one scale per tensor and worker (the convnet's gradient set and an
+    array cut at awkward places), averaged in one call: equal to the average of every tensor by itself."""
+    rng = np.random.Generator(np.random.PCG64(6100 + 10 * K + kind))
+    sizes = [t.size for _, t in workloads.tensors(2)]
+    layouts = [(np.concatenate([[0], np.cumsum(sizes)]), 0, "C2"),
+               (np.array([0, 0, 3, 1023, 1025, 4097, 9000, 9000, 20001, 33333]), 0, "awkward"),
+               (np.array([0, 5000, 12000]), 1, "misaligned")]
+    for bounds, off, tag in layouts:
+        n, n_seg = int(bounds[-1]), len(bounds) - 1
+        print("segment average %s kind=%d K=%d local=%d n=%d" % (tag, kind, K, with_local, n), flush=True)
+        cl = [rng.integers(0, 256, n).astype(np.uint8) for _ in range(K)]
+        sl = [np.exp(rng.uniform(-8, 8, n_seg)).astype(np.float32) for _ in range(K)]
+        local = (rng.standard_normal(n) * np.exp(rng.uniform(-8, 8, n))).astype(np.float32) if with_local else None
+        want = oracle.decode_accumulate_avg_segments(kind, cl, sl, bounds, local=local)
+        go = Guarded(n, np.float32, off)
+        dq8.decode_accumulate_avg_segments(kind, [dev(c, off) for c in cl], [dev(s) for s in sl], bounds_dev(bounds), out=go.t,
+                                           local=None if local is None else dev(local, off))
+        same_bits(go.t, want, "segment average " + tag)
+        go.check("segment average " + tag)

@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(L):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = sorted(set(re.findall(r"\b(dq8_[a-z0-9_]+)\s*\(", header)))
     assert names == ["dq8_absmax", "dq8_absmax_segments", "dq8_codebook", "dq8_decode", "dq8_decode_accumulate_avg",
-                     "dq8_decode_accumulate_avg_local", "dq8_decode_avg_encode", "dq8_decode_segments", "dq8_encode",
+                     "dq8_decode_accumulate_avg_local", "dq8_decode_accumulate_avg_segments", "dq8_decode_avg_encode", "dq8_decode_segments", "dq8_encode",
                      "dq8_encode_segments", "dq8_error_stats", "dq8_init",
                      "dq8_last_error", "dq8_model_penalty", "dq8_model_speedup"]
     for n in names:
@@ -75,6 +75,13 @@ def test_argument_errors_need_no_device(L):
     assert L.dq8_decode_segments(0, r, q, n, None, one, p, None) == 1
     assert L.dq8_decode_segments(0, r, p, n, b, one, p, None) == 3  # out overlaps the scales
     assert L.dq8_decode_segments(0, None, None, z, None, z, None, None) == 0
+    two = (ctypes.c_void_p * 2)(r, r)
+    twos = (ctypes.c_void_p * 2)(q, q)
+    assert L.dq8_decode_accumulate_avg_segments(0, two, twos, 0, None, n, b, one, p, None) == 3  # no worker and no local
+    assert L.dq8_decode_accumulate_avg_segments(0, two, twos, 33, None, n, b, one, p, None) == 3
+    assert L.dq8_decode_accumulate_avg_segments(0, two, twos, 2, None, n, None, one, p, None) == 1
+    assert L.dq8_decode_accumulate_avg_segments(0, two, twos, 2, None, n, b, one, q, None) == 3  # out overlaps a worker's scales
+    assert L.dq8_decode_accumulate_avg_segments(0, two, twos, 2, None, z, None, z, None, None) == 0
     arr = (ctypes.c_void_p * 2)(p, p)
     assert L.dq8_decode_accumulate_avg(0, arr, arr, 0, n, z, p, None) == 3
     assert L.dq8_decode_accumulate_avg(0, arr, arr, 33, n, z, p, None) == 3
