@@ -508,3 +508,34 @@ def test_given_scales_must_be_non_negative_and_finite():
             oracle.error_stats(oracle.DYNAMIC_TREE, x, 0, scales=np.array([bad], np.float32))
     codes, _ = oracle.encode(oracle.DYNAMIC_TREE, x, 0, scales=np.array([0.0], np.float32))
     assert codes[2] == 0 and codes[1] >> 7 == 1
+
+
+def test_segment_functions_are_the_per_array_functions_on_every_segment():
+    """Tensors back to back with one scale each: nothing but the pinned functions with block 0 applied to every
+    segment, an empty segment's scale being +0; offsets have to ascend from 0 to n."""
+    rng = np.random.Generator(np.random.PCG64(31))
+    x = (rng.standard_normal(3000) * np.exp(rng.uniform(-5, 2, 3000))).astype(np.float32)
+    bounds = [0, 7, 7, 1000, 1003, 3000]
+    for kind in (0, 1, 2, 3):
+        codes, scales = oracle.encode_segments(kind, x, bounds)
+        out = oracle.decode_segments(kind, codes, scales, bounds)
+        assert scales.tobytes() == oracle.absmax_segments(x, bounds).tobytes()
+        assert scales[1] == 0.0 and not np.signbit(scales[1])
+        for i, (lo, hi) in enumerate(zip(bounds[:-1], bounds[1:])):
+            if hi == lo:
+                continue
+            c, s = oracle.encode(kind, x[lo:hi], 0)
+            assert codes[lo:hi].tobytes() == c.tobytes() and scales[i] == s[0] == np.abs(x[lo:hi]).max()
+            assert out[lo:hi].tobytes() == oracle.decode(kind, c, s, 0).tobytes()
+        given = (scales * np.float32(4.0)).astype(np.float32)
+        c2, s2 = oracle.encode_segments(kind, x, bounds, scales=given)
+        assert s2.tobytes() == given.tobytes()
+        assert c2[7:1000].tobytes() == oracle.encode(kind, x[7:1000], 0, scales=given[2:3])[0].tobytes()
+        cl = [rng.integers(0, 256, 3000).astype(np.uint8) for _ in range(3)]
+        sl = [np.exp(rng.uniform(-3, 3, 5)).astype(np.float32) for _ in range(3)]
+        mean = oracle.decode_accumulate_avg_segments(kind, cl, sl, bounds, local=x)
+        want = oracle.decode_accumulate_avg(kind, [c[1003:] for c in cl], [s[4:5] for s in sl], 0, local=x[1003:])
+        assert mean[1003:].tobytes() == want.tobytes()
+    for bad in ([0, 10, 5, 3000], [1, 3000], [0, 2999], [0]):
+        with pytest.raises(ValueError):
+            oracle.encode_segments(0, x, bad)
