@@ -32,7 +32,9 @@ counters of an earlier run of this script, not measured in this run).
 --sweep prints one JSON line per measurement instead (not part of `value`): every call at other block
 lengths and worker counts on the same bucket, and the small configurations C1 (MLP gradients, one scale
 per tensor), C2 (convnet gradients, one scale per tensor, three data types) and C4 (activations, one scale
-per row) as per-tensor calls over enough copies of the configuration to exceed 1 GB.
+per row) as per-tensor calls over enough copies of the configuration to exceed 1 GB, each pass also recorded into
+a HIP graph and replayed, and C1 / C2 also as one array with one call for all tensors (dq8_encode_segments,
+dq8_decode_segments).
 """
 import argparse
 import itertools
