@@ -469,6 +469,23 @@ def sweep_configs(torch, dq8, internal, workloads):
                                elements=n_total, block=block, copies=copies, calls_per_pass=1, **rates(alg, ms, n_total, copy_gbps))
                     del graphs
                 del fx, fc, fs, fo
+            else:
+                # rows of one length: the matrices back to back are one array with that block length, one call per pass
+                fx = [torch.cat(x) for x in xs]
+                fc = [torch.empty(n_total, dtype=torch.uint8, device="cuda") for _ in range(copies)]
+                fs = [torch.empty(dq8.n_blocks(n_total, block), dtype=torch.float32, device="cuda") for _ in range(copies)]
+                fo = [torch.empty(n_total, dtype=torch.float32, device="cuda") for _ in range(copies)]
+                one_enc = lambda i: dq8.encode(kind, fx[i % copies], block, scales=fs[i % copies], codes=fc[i % copies])
+                one_dec = lambda i: dq8.decode(kind, fc[i % copies], fs[i % copies], block, out=fo[i % copies])
+                for r in range(copies):
+                    one_enc(r)
+                torch.cuda.synchronize()
+                alg = 5 * n_total + 4 * dq8.n_blocks(n_total, block)
+                for call, f in (("encode, one array", one_enc), ("decode, one array", one_dec)):
+                    ms = event_time_ms(torch, f, launches, groups=3)
+                    sweep_line(sweep="configs", config=label, kind=names[kind], call=call, launch="calls", tensors=len(host),
+                               elements=n_total, block=block, copies=copies, calls_per_pass=1, **rates(alg, ms, n_total, copy_gbps))
+                del fx, fc, fs, fo
         del xs, cs, ss, outs
 
 
