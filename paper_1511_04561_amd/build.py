@@ -13,8 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdq8.so")
-SOURCES = ["dq8.hip", "dq8_tables.cpp"]
-HEADERS = ["dq8_internal.h", "dq8_tables.hpp", "dq8_device.hpp", "dq8_plan.hpp", "dq8_units.hpp", "dq8_arith.hpp", "dq8_kernels_codec.hpp", "dq8_kernels_avg.hpp",
+SOURCES = ["dq8.hip", "dq8_avg_short.hip", "dq8_avg_long.hip", "dq8_tables.cpp"]
+HEADERS = ["dq8_internal.h", "dq8_launch.hpp", "dq8_tables.hpp", "dq8_device.hpp", "dq8_plan.hpp", "dq8_units.hpp", "dq8_arith.hpp", "dq8_kernels_codec.hpp", "dq8_kernels_avg.hpp",
            "dq8_kernels_avg_encode.hpp", "dq8_kernels_stats.hpp", "dq8_kernels_small.hpp", "dq8_kernels_segments.hpp", os.path.join(ROOT, "include", "dq8.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -41,15 +41,41 @@ def stale():
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+def _compile_and_link(out, extra=(), verbose=False):
+    """Every source to an object file, all at once, then one link: the translation units are independent."""
+    import shutil
+    import tempfile
+    tmpdir = tempfile.mkdtemp(prefix="dq8_build_")
+    try:
+        flags = [f for f in FLAGS if f != "-shared"]
+        jobs = []
+        for src in SOURCES:
+            obj = os.path.join(tmpdir, src + ".o")
+            cmd = [hipcc()] + flags + list(extra) + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, src),
+                                                    "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            jobs.append((cmd, obj, subprocess.Popen(cmd)))
+        for cmd, obj, proc in jobs:
+            if proc.wait() != 0:
+                for _, _, other in jobs:
+                    if other.poll() is None:
+                        other.kill()
+                raise subprocess.CalledProcessError(proc.returncode, cmd)
+        link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + [obj for _, obj, _ in jobs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.check_call(link)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
+
+
 def build(force=True, verbose=False, extra=()):
     """Compiles the library; with force=False only when it is missing or older than a source."""
     if not force and not stale():
         return LIB
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = command(tmp, extra)
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    _compile_and_link(tmp, extra, verbose)
     os.replace(tmp, LIB)
     return LIB
 
@@ -57,10 +83,7 @@ def build(force=True, verbose=False, extra=()):
 def build_tunable(out=None, verbose=False):
     """The same library with changeable launch shapes (-DDQ8_TUNABLE), for experiments: libdq8_tunable.so."""
     out = out or os.path.join(HERE, "libdq8_tunable.so")
-    cmd = command(out, ["-DDQ8_TUNABLE"])
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    _compile_and_link(out, ["-DDQ8_TUNABLE"], verbose)
     return out
 
 

@@ -37,6 +37,7 @@
 
 #include "dq8.h"
 #include "dq8_internal.h"
+#include "dq8_launch.hpp"
 #include "dq8_plan.hpp"
 #include "dq8_tables.hpp"
 
@@ -687,63 +688,12 @@ int gather_workers(const char *who, const uint8_t *const *codes, const float *co
 // unit of the wave-per-block kernels do better on the shorter blocks: 53 against 61 us at block 1000).
 inline bool short_team_k(int K, size_t Bq) { return K >= (Bq > 2048 ? 1 : 2) && K <= 8; }
 
-// Average-then-compress for blocks of up to 3072 elements: teams of W = 1, 2 or 3 wavefronts, a block per team
-// (W x 1024 elements hold it), twelve wavefronts per workgroup and one workgroup per compute unit.
+// Average-then-compress for blocks of up to 3072 elements: teams of W = 1, 2 or 3 wavefronts (dq8_avg_short.hip).
 int launch_avg_short_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                           size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
-    const size_t Bq = block_length(n, block);
-    const int W = (int)((Bq + 1023) / 1024);
-    const bool ragged = Bq != (size_t)W * 1024;
-    const int teams = 12 / W;
-    Plan p = make_plan(n, block, st.cus, 12, W, 12, kUnit);
-    const uint32_t iters = (uint32_t)((p.n_units + p.n_teams - 1) / p.n_teams);
-    // Iterations in which every team's current and next unit are whole aligned blocks.
-    uint32_t steady = 0;
-    bool aligned = !ragged && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
-    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
-    if (aligned) {
-        const size_t all_valid = (n / Bq) / p.n_teams;  // iterations in which every team has a whole unit
-        if (all_valid >= 2) steady = (uint32_t)((all_valid - 1) & ~(size_t)1);
-    }
-    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = ((size_t)st.search_words[kind] + 2 * teams * kWavesPerWg) * sizeof(uint32_t);
-#define DQ8_SHORT(KT, RM, RG, WW)                                                                                          \
-    hipLaunchKernelGGL((k_avg_team<KT, 1, true, 12 / WW, RM, RG, false, WW>), dim3(p.grid), dim3(kWave * 12), lds, stream, tab, \
-                       wp, K, local, n, p.B, p.nb, p.n_units, p.n_teams, iters, steady, scales_out, codes_out)
-#define DQ8_SHORT_RG(KT, RM, WW)       \
-    if (ragged) {                      \
-        DQ8_SHORT(KT, RM, true, WW);   \
-    } else {                           \
-        DQ8_SHORT(KT, RM, false, WW);  \
-    }
-#define DQ8_SHORT_W(KT, RM)                      \
-    switch (W) {                                 \
-    case 1: DQ8_SHORT_RG(KT, RM, 1) break;       \
-    case 2: DQ8_SHORT_RG(KT, RM, 2) break;       \
-    default: DQ8_SHORT_RG(KT, RM, 3) break;      \
-    }
-#define DQ8_SHORT_K(KT)              \
-    if (st.has_remap[kind]) {        \
-        DQ8_SHORT_W(KT, true)        \
-    } else {                         \
-        DQ8_SHORT_W(KT, false)       \
-    }
-    switch (K) {
-    case 1: DQ8_SHORT_K(1) break;
-    case 2: DQ8_SHORT_K(2) break;
-    case 3: DQ8_SHORT_K(3) break;
-    case 4: DQ8_SHORT_K(4) break;
-    case 5: DQ8_SHORT_K(5) break;
-    case 6: DQ8_SHORT_K(6) break;
-    case 7: DQ8_SHORT_K(7) break;
-    default: DQ8_SHORT_K(8) break;
-    }
-#undef DQ8_SHORT_K
-#undef DQ8_SHORT_W
-#undef DQ8_SHORT_RG
-#undef DQ8_SHORT
-    return after_launch("k_avg_team", stream);
+    return dq8::launch_avg_short_team_tu(st.cus, st.tables + (size_t)kind * kTableWords, st.search_words[kind], st.has_remap[kind],
+                                         wp.codes, wp.scales, K, local, n, block, scales_out, codes_out, stream);
 }
 
 // Average-then-compress for up to 8 workers: teams of four wavefronts; two teams per workgroup and two
@@ -868,50 +818,12 @@ int launch_avg_team(const DeviceState &st, int kind, const WorkerPtrs &wp, int K
     return after_launch("k_avg_team", stream);
 }
 
-// Average-then-compress for blocks of 4097 .. kLongestHeldBlock elements: a workgroup per block.
+// Average-then-compress for blocks of 4097 .. kLongestHeldBlock elements: a workgroup per block (dq8_avg_long.hip).
 int launch_avg_long(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
                     size_t block, float *scales_out, uint8_t *codes_out, hipStream_t stream)
 {
-    const size_t B = block_length(n, block);
-    const size_t nb = (n + B - 1) / B;
-    size_t teams = (size_t)st.cus * 2;  // two workgroups' tables fit the LDS of a compute unit
-    if (teams > nb) teams = nb;
-    const uint32_t *tab = st.tables + (size_t)kind * kTableWords;
-    const size_t lds = ((size_t)st.search_words[kind] + kLongSlots) * sizeof(uint32_t);
-    // The register path needs 32-bit accesses to the codes and 128-bit ones to local at every block start.
-    bool aligned = K >= 1 && (nb == 1 || (B & 3) == 0) && ((uintptr_t)codes_out & 3) == 0 && ((uintptr_t)local & 15) == 0;
-    for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
-#define DQ8_AVG_LONG(QL, NB, KT)                                                                                              \
-    hipLaunchKernelGGL((k_avg_long<QL, NB, 2, KT>), dim3((unsigned)teams), dim3(kLongTeam), lds, stream, tab, wp, K, local, n, \
-                       B, nb, (uint32_t)teams, (uint32_t)aligned, scales_out, codes_out)
-    // Quads per lane that hold the block in a workgroup of 512 threads.  Up to eight workers have kernels of their
-    // own, with one set of code words per worker where the registers allow (up to four quads per lane) and three or
-    // four sets otherwise; more workers take the kernel that reads the count at run time, with four sets (it pads
-    // the count to a multiple of four).
-    const int ql = (int)((B + 4 * kLongTeam - 1) / (4 * kLongTeam));
-#define DQ8_AVG_LONG_Q(NB_SHORT, NB_LONG, KT)            \
-    switch (ql) {                                        \
-    case 3: DQ8_AVG_LONG(3, NB_SHORT, KT); break;        \
-    case 4: DQ8_AVG_LONG(4, NB_SHORT, KT); break;        \
-    case 5: DQ8_AVG_LONG(5, NB_LONG, KT); break;         \
-    case 6: DQ8_AVG_LONG(6, NB_LONG, KT); break;         \
-    case 7: DQ8_AVG_LONG(7, NB_LONG, KT); break;         \
-    default: DQ8_AVG_LONG(8, NB_LONG, KT); break;        \
-    }
-    switch (K) {
-    case 1: DQ8_AVG_LONG_Q(2, 2, 1) break;
-    case 2: DQ8_AVG_LONG_Q(2, 2, 2) break;
-    case 3: DQ8_AVG_LONG_Q(3, 3, 3) break;
-    case 4: DQ8_AVG_LONG_Q(4, 4, 4) break;
-    case 5: DQ8_AVG_LONG_Q(5, 3, 5) break;
-    case 6: DQ8_AVG_LONG_Q(6, 3, 6) break;
-    case 7: DQ8_AVG_LONG_Q(7, 4, 7) break;
-    case 8: DQ8_AVG_LONG_Q(8, 4, 8) break;
-    default: DQ8_AVG_LONG_Q(4, 4, 0) break;
-    }
-#undef DQ8_AVG_LONG_Q
-#undef DQ8_AVG_LONG
-    return after_launch("k_avg_long", stream);
+    return dq8::launch_avg_long_tu(st.cus, st.tables + (size_t)kind * kTableWords, st.search_words[kind], wp.codes, wp.scales, K,
+                                   local, n, block, scales_out, codes_out, stream);
 }
 
 int launch_avg_block(const DeviceState &st, int kind, const WorkerPtrs &wp, int K, const float *local, size_t n,
@@ -1218,6 +1130,8 @@ int launch_decode_avg(const DeviceState &st, int kind, const WorkerPtrs &wp, int
 
 }  // namespace
 
+int dq8::after_launch_of(const char *what, hipStream_t stream) { return after_launch(what, stream); }
+
 extern "C" {
 
 const char *dq8_last_error(void) { return t_err; }
@@ -1241,6 +1155,8 @@ int dq8_init(void)
 
 // ---- segments: tensors back to back in one array, one scale each
 
+namespace {
+
 struct SegPlan {
     size_t n_units, n_items, n_waves, lds;
     uint32_t group;
@@ -1250,7 +1166,7 @@ struct SegPlan {
 // Units of kSegUnit elements on up to `waves_per_cu` wavefronts per compute unit, kSegWaves per workgroup.
 // grouped (the maxima): an item of work is four units when a workgroup per compute unit still gets two items or more
 // per wavefront, else one unit (short arrays: as many wavefronts as there are units).
-SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu, bool grouped = false)
+static SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu, bool grouped = false)
 {
     SegPlan p;
     p.n_units = (n + kSegUnit - 1) / kSegUnit;
@@ -1265,7 +1181,7 @@ SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int wav
     return p;
 }
 
-int check_segments(const char *who, size_t n, const uint64_t *bounds, size_t n_seg)
+static int check_segments(const char *who, size_t n, const uint64_t *bounds, size_t n_seg)
 {
     if (!bounds) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
     if (n_seg < 1 || n_seg > (size_t)kSegMax) return fail(DQ8_ERR_ARG, "%s: %zu segments outside 1..%d", who, n_seg, kSegMax);
@@ -1273,7 +1189,7 @@ int check_segments(const char *who, size_t n, const uint64_t *bounds, size_t n_s
     return DQ8_OK;
 }
 
-int launch_segment_absmax(const DeviceState &st, const float *x, size_t n, const uint64_t *bounds, size_t n_seg,
+static int launch_segment_absmax(const DeviceState &st, const float *x, size_t n, const uint64_t *bounds, size_t n_seg,
                           float *scales, hipStream_t stream)
 {
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, scales, n_seg);
@@ -1285,6 +1201,8 @@ int launch_segment_absmax(const DeviceState &st, const float *x, size_t n, const
                        p.n_units, p.n_items, p.n_waves, p.group, aligned, scales);
     return after_launch("k_seg_absmax", stream);
 }
+
+}  // namespace
 
 int dq8_absmax(const float *x, size_t n, size_t block, float *scales, void *hip_stream)
 {
