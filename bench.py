@@ -22,8 +22,9 @@ Order of a run: untimed clock-settling steps (groups of ten until three consecut
 synchronisations.  value = fp32 bytes the five calls consume or produce (4 bytes x n each) per second over
 the timed region.
 
-`kernels` times every call on its own: HIP events on the launch stream around max(K, 50) consecutive
-launches of that call over the same rotating buffers, median of five such groups.  It also holds calls that
+`kernels` times every call on its own: 200 untimed launches of that call (the clocks follow a change of load with a
+delay), then HIP events on the launch stream around max(K, 50) consecutive launches of it over the same rotating
+buffers, median of five such groups.  It also holds calls that
 are not part of a step (the one-call second round, the local fp32 term, the error statistics, the mantissa
 type).  `roofline` is for the call that takes the largest share of a step (the K-way decode-and-average);
 its `traffic` is the HBM traffic per launch recorded in profiles/hbm_traffic_bench_c5.md (rocprofv3
@@ -54,6 +55,9 @@ BLOCK = 4096
 K_WORKERS = 8
 N_SETS = 4
 GROUPS = 5        # per-kernel timing: median of this many groups of consecutive launches
+# untimed launches of a call before its timed groups: the clocks follow the load with a delay of tens of milliseconds, and a
+# call that keeps the vector units busy reads up to 10 % slow when it is timed right after calls that only move data
+PRIME = 200
 MIN_LAUNCHES = 50  # launches per group, at least
 
 TRAFFIC_PROFILE = os.path.join("profiles", "hbm_traffic_bench_c5.md")
@@ -296,7 +300,7 @@ def run_default(args, torch, dq8, internal, workloads):
     for idx, nm in enumerate(names):
         if args.only and nm != args.only:
             continue
-        ms = event_time_ms(torch, lambda i, idx=idx: all_calls(i)[idx][1](), launches)
+        ms = event_time_ms(torch, lambda i, idx=idx: all_calls(i)[idx][1](), launches, prime=PRIME)
         kernels[nm] = rates(alg[nm], ms, n, copy_gbps)
 
     dom = "decode_accumulate_avg" if "decode_accumulate_avg" in kernels else list(kernels)[0]
@@ -356,7 +360,7 @@ def sweep_bucket(what, torch, dq8, internal, workloads):
             if nm not in idx_name:
                 continue
             try:
-                ms = event_time_ms(torch, lambda i, idx=idx: calls_of(i)[idx][1](), SWEEP_LAUNCHES, groups=3)
+                ms = event_time_ms(torch, lambda i, idx=idx: calls_of(i)[idx][1](), SWEEP_LAUNCHES, groups=3, prime=PRIME)
             except dq8.Dq8Error as e:  # e.g. the one-call second round with a block too long to hold
                 sweep_line(sweep=sweep, block=block_label, K=K, call=nm, error=str(e))
                 continue
