@@ -480,6 +480,10 @@ def test_random_shapes_through_every_call(dq8, seed):
             gc.check("avg->encode " + tag)
             gs.check("avg->encode " + tag)
         check_error_stats(dq8, kind, x, block, tag=tag)
+        # the same array cut at random places, one scale per piece
+        n_seg = int(rng.integers(1, 40))
+        cuts = np.sort(rng.integers(0, n + 1, n_seg - 1))
+        check_segments(dq8, kind, x, np.concatenate([[0], cuts, [n]]), x_off=x_off, c_off=c_off, tag=tag)
 
 
 def test_decode_avg_encode_rejects_blocks_that_do_not_fit(dq8):
