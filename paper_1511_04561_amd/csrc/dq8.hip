@@ -1157,30 +1157,6 @@ int dq8_init(void)
 
 namespace {
 
-struct SegPlan {
-    size_t n_units, n_items, n_waves, lds;
-    uint32_t group;
-    unsigned grid;
-};
-
-// Units of kSegUnit elements on up to `waves_per_cu` wavefronts per compute unit, kSegWaves per workgroup.
-// grouped (the maxima): an item of work is four units when a workgroup per compute unit still gets two items or more
-// per wavefront, else one unit (short arrays: as many wavefronts as there are units).
-static SegPlan make_segment_plan(const DeviceState &st, size_t n, size_t n_seg, int waves_per_cu, bool grouped = false)
-{
-    SegPlan p;
-    p.n_units = (n + kSegUnit - 1) / kSegUnit;
-    size_t waves = (size_t)st.cus * (size_t)waves_per_cu;
-    p.group = grouped && p.n_units >= (size_t)st.cus * kSegWaves * 8 ? 4u : 1u;
-    if (p.group == 4) waves = (size_t)st.cus * kSegWaves;
-    p.n_items = (p.n_units + p.group - 1) / p.group;
-    if (waves > p.n_items) waves = p.n_items;
-    p.grid = (unsigned)((waves + kSegWaves - 1) / kSegWaves);
-    p.n_waves = (size_t)p.grid * kSegWaves;
-    p.lds = (n_seg + 1) * sizeof(uint64_t);
-    return p;
-}
-
 static int check_segments(const char *who, size_t n, const uint64_t *bounds, size_t n_seg)
 {
     if (!bounds) return fail(DQ8_ERR_NULL, "%s: NULL pointer", who);
@@ -1195,7 +1171,7 @@ static int launch_segment_absmax(const DeviceState &st, const float *x, size_t n
     hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream, scales, n_seg);
     int rc = after_launch("k_fill_zero", stream);
     if (rc) return rc;
-    const SegPlan p = make_segment_plan(st, n, n_seg, 32, true);
+    const SegPlan p = make_segment_plan(st.cus, n, n_seg, 32, true);
     const uint32_t aligned = ((uintptr_t)x & 15) == 0;
     hipLaunchKernelGGL(k_seg_absmax, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, x, n, bounds, (uint32_t)n_seg,
                        p.n_units, p.n_items, p.n_waves, p.group, aligned, scales);
@@ -1414,7 +1390,7 @@ int dq8_encode_segments(int kind, const float *x, size_t n, const uint64_t *boun
         rc = launch_segment_absmax(*st, x, n, bounds, n_seg, scales, stream);
         if (rc) return rc;
     }
-    SegPlan p = make_segment_plan(*st, n, n_seg, 32);
+    SegPlan p = make_segment_plan(st->cus, n, n_seg, 32);
     p.lds += (size_t)st->search_words[kind] * sizeof(uint32_t);
     const uint32_t aligned = (((uintptr_t)x & 15) | ((uintptr_t)codes & 3)) == 0;
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
@@ -1443,7 +1419,7 @@ int dq8_decode_segments(int kind, const uint8_t *codes, const float *scales, siz
     rc = device_state(&st);
     if (rc) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const SegPlan p = make_segment_plan(*st, n, n_seg, 16);
+    const SegPlan p = make_segment_plan(st->cus, n, n_seg, 16);
     const uint32_t aligned = (((uintptr_t)out & 15) | ((uintptr_t)codes & 3)) == 0;
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;
     hipLaunchKernelGGL(k_seg_decode, dim3(p.grid), dim3(kWave * kSegWaves), p.lds, stream, tab, codes, scales, n, bounds,
@@ -1473,7 +1449,7 @@ int dq8_decode_accumulate_avg_segments(int kind, const uint8_t *const *codes, co
     rc = device_state(&st);
     if (rc) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const SegPlan p = make_segment_plan(*st, n, n_seg, 16);
+    const SegPlan p = make_segment_plan(st->cus, n, n_seg, 16);
     bool aligned = ((uintptr_t)out & 15) == 0 && ((uintptr_t)local & 15) == 0;
     for (int k = 0; k < K; ++k) aligned = aligned && ((uintptr_t)wp.codes[k] & 3) == 0;
     const uint32_t *tab = st->tables + (size_t)kind * kTableWords;

@@ -19,10 +19,7 @@
 namespace {
 
 constexpr int kSegMax = DQ8_MAX_SEGMENTS;           // segments per call: the bounds fit 32 KiB of LDS
-constexpr int kSegQ = 4;                            // quads per lane
-constexpr int kSegUnit = kSegQ * 4 * kWave;         // 1024 elements per unit
 constexpr int kSegRun = kSegUnit / kWave;           // 16 consecutive elements per lane on the slow path
-constexpr int kSegWaves = 16;                       // wavefronts per workgroup
 
 // Copies bounds[0 .. n_seg] to LDS, clamped to n.  The caller synchronises the workgroup.
 __device__ __forceinline__ void load_bounds(const uint64_t *__restrict__ bounds, uint32_t n_seg, size_t n, uint64_t *lds)

@@ -125,4 +125,30 @@ inline SmallPlan make_small_plan(size_t n, int cus, int waves_per_cu, int wpw)
     return p;
 }
 
+// ---- tensors back to back, one scale each
+
+struct SegPlan {
+    size_t n_units, n_items, n_waves, lds;
+    uint32_t group;
+    unsigned grid;
+};
+
+// Units of kSegUnit elements on up to `waves_per_cu` wavefronts per compute unit, kSegWaves per workgroup.
+// grouped (the maxima): an item of work is four units when a workgroup per compute unit still gets two items or more
+// per wavefront, else one unit (short arrays: as many wavefronts as there are units).
+inline SegPlan make_segment_plan(int cus, size_t n, size_t n_seg, int waves_per_cu, bool grouped = false)
+{
+    SegPlan p;
+    p.n_units = (n + kSegUnit - 1) / kSegUnit;
+    size_t waves = (size_t)cus * (size_t)waves_per_cu;
+    p.group = grouped && p.n_units >= (size_t)cus * kSegWaves * 8 ? 4u : 1u;
+    if (p.group == 4) waves = (size_t)cus * kSegWaves;
+    p.n_items = (p.n_units + p.group - 1) / p.group;
+    if (waves > p.n_items) waves = p.n_items;
+    p.grid = (unsigned)((waves + kSegWaves - 1) / kSegWaves);
+    p.n_waves = (size_t)p.grid * kSegWaves;
+    p.lds = (n_seg + 1) * sizeof(uint64_t);
+    return p;
+}
+
 }  // namespace

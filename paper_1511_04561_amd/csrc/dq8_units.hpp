@@ -19,6 +19,11 @@ constexpr int kWg = kWave * kWavesPerWg;
 constexpr int kUnit = 4096;                      // elements per unit
 constexpr int kUnitQuads = kUnit / (4 * kWave);  // 16 quads per lane when one wave owns a unit
 
+// The kernels for tensors back to back with one scale each (segments) walk the array in units of their own.
+constexpr int kSegQ = 4;                     // quads per lane
+constexpr int kSegUnit = kSegQ * 4 * kWave;  // 1024 elements per unit
+constexpr int kSegWaves = 16;                // wavefronts per workgroup
+
 // Geometry of unit u.  All values are wave-uniform.
 struct Unit {
     size_t block;   // scale index

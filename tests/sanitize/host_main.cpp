@@ -105,6 +105,17 @@ static void check_plans()
                 CHECK(un.block == p.nb - 1 && un.start == (p.nb - 1) * b && un.start + un.len == n && un.len <= (uint32_t)(W * 1024),
                       "team plan: last unit of n %zu block %zu", n, b);
             }
+    // tensors back to back: units of 1024 elements, items of one or four units, sixteen wavefronts per workgroup
+    for (size_t n : {(size_t)1, (size_t)1023, (size_t)1024, (size_t)1025, (size_t)1863690, (size_t)61100840, two32 + 12305})
+        for (int wpc : {16, 32})
+            for (bool grouped : {false, true}) {
+                const SegPlan p = make_segment_plan(256, n, 17, wpc, grouped);
+                CHECK(p.n_units == (n + 1023) / 1024 && (p.group == 1 || (grouped && p.group == 4)), "segment plan of %zu", n);
+                CHECK(p.n_items * p.group >= p.n_units && (p.n_items - 1) * p.group < p.n_units, "segment plan of %zu: items", n);
+                CHECK(p.grid >= 1 && p.n_waves == (size_t)p.grid * kSegWaves && p.n_waves < p.n_items + kSegWaves, "segment plan of %zu: grid", n);
+                CHECK(p.n_waves <= (size_t)256 * 32 && p.lds == 18 * sizeof(uint64_t), "segment plan of %zu: size", n);
+                CHECK(p.group == 1 || p.n_items >= 2 * p.n_waves, "segment plan of %zu: too few items of four", n);
+            }
     for (int K = 0; K <= DQ8_MAX_K; ++K) {
         const int c = chunk_size(K);
         CHECK(c >= 1 && c <= 8, "chunk of %d workers: %d", K, c);
